@@ -1,0 +1,178 @@
+/*
+ * libspecdec -- the syntax-aligned speculative-decoding step on one MI355X (gfx950).
+ *
+ * One step (paper Section III-B, "Model Architecture"): at position t the base model's
+ * token for t+1 and the top-k tokens of every draft head (head i drafts t+i+1) form a fixed
+ * token tree; the base decoder verifies the whole tree in one forward pass (tree-masked
+ * attention over the KV cache); a drafted token is accepted only if it and every token
+ * before it is accepted (greedy decoding: equals the base arg-max given the tokens before
+ * it); the accepted run is cut back to the end of its last complete syntactic fragment (a
+ * token of the stop set, the paper's [FRAG] boundary, Section III-C); the longest such
+ * prefix is emitted and its key/value rows are committed to the cache.
+ *
+ * Conventions
+ *   - Every function returns SD_OK (0) or a negative sd_status. On error nothing has been
+ *     enqueued and no state has changed; sd_last_error() gives a message (thread-local).
+ *   - "dev" pointers are device memory owned by the caller (PyTorch allocates it) and are
+ *     only borrowed for the duration documented per call. "host" pointers are host memory.
+ *   - `stream` is a hipStream_t passed as void*. Calls that take a stream are asynchronous
+ *     on it; results are valid once the caller has synchronised the stream. A handle must
+ *     be used from one thread and one stream at a time.
+ *   - All weight matrices are row-major [out_features][in_features] (y = W x), bf16.
+ *   - Only dtype = SD_DTYPE_BF16 is implemented; head_dim must be 64 or 128; d_model and
+ *     d_ffn must be multiples of 16; n_medusa <= 15; topk <= 32; tree nodes <= 128.
+ */
+#ifndef SPECDEC_H
+#define SPECDEC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum sd_status {
+    SD_OK = 0,
+    SD_ERR_NULL = -1,      /* a required pointer was NULL                                   */
+    SD_ERR_SHAPE = -2,     /* configuration or sizes not supported / inconsistent           */
+    SD_ERR_BAD_TREE = -3,  /* tree_spec is not a valid candidate tree                       */
+    SD_ERR_KV_FULL = -4,   /* the step could overflow the cache; nothing was enqueued       */
+    SD_ERR_HIP = -5,       /* a HIP runtime call failed (text in sd_last_error)             */
+    SD_ERR_STATE = -6      /* call order violated (e.g. a step before any prefill)          */
+} sd_status;
+
+enum { SD_DTYPE_F32 = 0, SD_DTYPE_BF16 = 1 };
+/* What to keep when the accepted run holds no stop token at all: the paper only describes
+ * the case where a complete fragment exists inside the run (Section III-B).               */
+enum { SD_TRUNC_KEEP_ALL = 0, SD_TRUNC_KEEP_ONE = 1 };
+
+typedef struct sd_config {
+    int32_t n_layers, d_model, n_heads, head_dim, d_ffn, vocab;
+    int32_t n_medusa;        /* H: draft heads                                              */
+    int32_t topk;            /* k: candidates kept per head                                 */
+    int32_t dtype;           /* SD_DTYPE_*                                                  */
+    int32_t trunc_fallback;  /* SD_TRUNC_*                                                  */
+    float rope_theta, rms_eps;
+} sd_config;
+
+/* Device pointers to the caller's weights (bf16). Per-layer arrays are host arrays of
+ * n_layers (resp. n_medusa) device pointers. medusa_b may be NULL (no bias).
+ * wqkv stacks q, k, v along the output axis: [3*d_model][d_model].                         */
+typedef struct sd_weights {
+    const void* embed;              /* dev [vocab][d_model]                                  */
+    const void* lm_head;            /* dev [vocab][d_model]                                  */
+    const void* final_norm;         /* dev [d_model]                                         */
+    const void* const* attn_norm;   /* host[n_layers] -> dev [d_model]                       */
+    const void* const* wqkv;        /* host[n_layers] -> dev [3*d_model][d_model]            */
+    const void* const* wo;          /* host[n_layers] -> dev [d_model][d_model]              */
+    const void* const* ffn_norm;    /* host[n_layers] -> dev [d_model]                       */
+    const void* const* w_gate;      /* host[n_layers] -> dev [d_ffn][d_model]                */
+    const void* const* w_up;        /* host[n_layers] -> dev [d_ffn][d_model]                */
+    const void* const* w_down;      /* host[n_layers] -> dev [d_model][d_ffn]                */
+    const void* const* medusa_w;    /* host[n_medusa] -> dev [d_model][d_model]              */
+    const void* const* medusa_b;    /* host[n_medusa] -> dev [d_model], or NULL              */
+} sd_weights;
+
+typedef struct sd_model sd_model;
+typedef struct sd_kv sd_kv;
+typedef struct sd_tree sd_tree;
+
+/* ---- model ------------------------------------------------------------------------------
+ * sd_model_create copies every weight into a library-owned device arena, re-tiled so that one
+ * wavefront load instruction fetches one contiguous 1 KiB MFMA operand fragment. The
+ * caller's weight buffers are read on `stream` during this call only; the call synchronises
+ * the stream before returning, after which the caller may free them. `max_rows` is the
+ * largest batch * round_up(tree_nodes, 32) any later call will use (workspace is sized for
+ * it). Blocking; allocates device memory. */
+int sd_model_create(const sd_config* cfg, const sd_weights* w, int32_t max_rows, void* stream,
+                    sd_model** out);
+int sd_model_destroy(sd_model* m);
+
+/* ---- KV cache ---------------------------------------------------------------------------
+ * The cache lives in ONE caller-allocated device buffer of sd_kv_bytes(...) bytes; its
+ * internal tiling is private (keys and values are stored as ready-made MFMA fragments of
+ * 32 cache rows), use sd_kv_write_rows / sd_kv_read_rows to move rows in natural layout.
+ * `cap` = capacity in rows per sequence. A step needs kv_len + n_medusa + 1 <= cap (the
+ * tree's own keys/values live in a library-owned scratch, not in the cache).               */
+size_t sd_kv_bytes(const sd_config* cfg, int32_t batch, int32_t cap);
+int sd_kv_create(const sd_model* m, int32_t batch, int32_t cap, void* dev_buf, size_t bytes,
+                 sd_kv** out);
+int sd_kv_destroy(sd_kv* kv);
+/* Committed length per sequence -> host out_len[batch]. Synchronises `stream`.              */
+int sd_kv_len(sd_kv* kv, int32_t* out_len, void* stream);
+/* Set the committed length per sequence from host len[batch] (roll back after a step, or
+ * declare rows written by sd_kv_write_rows as committed). Rows beyond len are ignored.     */
+int sd_kv_set_len(sd_kv* kv, const int32_t* len, void* stream);
+/* Copy `nrows` rows starting at cache row `row0` of sequence `seq`, layer `layer`, between
+ * the cache and natural-layout device arrays k_rows / v_rows: bf16 [nrows][n_heads][head_dim].
+ * Keys are stored as given (they must already be rotated to their positions).              */
+int sd_kv_write_rows(sd_kv* kv, int32_t layer, int32_t seq, int32_t row0, int32_t nrows,
+                     const void* k_rows, const void* v_rows, void* stream);
+int sd_kv_read_rows(sd_kv* kv, int32_t layer, int32_t seq, int32_t row0, int32_t nrows,
+                    void* k_rows, void* v_rows, void* stream);
+/* Overwrite the carried draft state of every sequence: the base model's token for the next
+ * position (dev root_tok[batch]) and the heads' candidates (dev cand[batch][n_medusa][topk]).
+ * Used with synthetic caches, and to resynchronise a lock-step comparison.                 */
+int sd_kv_set_draft(sd_kv* kv, const int32_t* root_tok, const int32_t* cand, void* stream);
+/* Read the carried draft state back (same shapes, dev pointers).                           */
+int sd_kv_get_draft(sd_kv* kv, int32_t* root_tok, int32_t* cand, void* stream);
+
+/* ---- candidate tree ---------------------------------------------------------------------
+ * Host arrays of T entries: parent[0] = -1, parent[j] < j, depth[j] = depth[parent[j]] + 1
+ * <= n_medusa, rank[j] < topk, siblings have distinct ranks. Node j >= 1 carries head
+ * (depth[j]-1)'s candidate number rank[j]; node 0 carries the base model's token.
+ * The arrays are copied. Returns SD_ERR_BAD_TREE if any rule is broken.                    */
+int sd_tree_create(int32_t T, const int32_t* parent, const int32_t* depth, const int32_t* rank,
+                   int32_t n_medusa, int32_t topk, sd_tree** out);
+int sd_tree_destroy(sd_tree* t);
+
+/* ---- decoding ---------------------------------------------------------------------------*/
+/* Run the prompts through the base model (causal), commit their keys/values after the rows
+ * already committed, and draft from each prompt's last position. tokens: dev int32, the
+ * prompts back to back; lens: host [batch], each >= 1. kv_len + len must be <= cap.         */
+int sd_prefill(sd_model* m, sd_kv* kv, const int32_t* tokens, const int32_t* lens, void* stream);
+
+typedef struct sd_step_io {
+    int32_t* n_accept;         /* dev [batch]: tokens emitted by this step, 1..n_medusa+1     */
+    int32_t* tokens;           /* dev [batch][n_medusa+1]: emitted tokens, rest -1            */
+    int32_t* src_slots;        /* dev [batch][n_medusa+1]: tree node whose K/V row was
+                                  committed at cache row old_len + j, rest -1                 */
+    int32_t* n_accept_raw;     /* dev [batch] or NULL: accepted length before the cut         */
+    float* logits;             /* dev [batch][T][vocab] or NULL: base logits of every node    */
+    int32_t* argmax;           /* dev [batch][T] or NULL: base arg-max of every node          */
+    float* head_logits;        /* dev [batch][n_medusa][vocab] or NULL: draft-head logits at
+                                  the last kept node                                          */
+    const int32_t* forced_cand;/* dev [batch][n_medusa][topk] or NULL: use these candidates
+                                  instead of the carried ones (test / planted-draft hook)     */
+} sd_step_io;
+
+/* One speculative step for every sequence of `kv` (Section III-B). stop_mask: dev uint32
+ * words, bit (id % 32) of word (id / 32) set for syntactically significant token ids,
+ * ceil(vocab / 32) words. Needs a prior sd_prefill or sd_kv_set_draft.
+ * SD_ERR_KV_FULL if some sequence might exceed `cap` (judged from the lengths the host
+ * knows; call sd_kv_len to refresh them).                                                  */
+int sd_spec_step(sd_model* m, sd_kv* kv, const sd_tree* tree, const uint32_t* stop_mask,
+                 sd_step_io* io, void* stream);
+/* Plain next-token greedy decoding: a step whose tree is the root alone (the paper's NTP
+ * baseline, Section IV-B). Fills n_accept (=1), tokens, src_slots (=0); logits is
+ * [batch][1][vocab].                                                                       */
+int sd_greedy_step(sd_model* m, sd_kv* kv, sd_step_io* io, void* stream);
+
+/* ---- single stages, for per-kernel parity tests -------------------------------------------
+ * Acceptance + fragment cut alone (no forward): am dev [batch][T] = base arg-max per node,
+ * tok dev [batch][T] = node tokens. Writes n_accept, n_accept_raw, tokens, src_slots as in
+ * sd_step_io (token ids outside [0, vocab) are never stop tokens). Touches no cache.                                                   */
+int sd_verify_tree(const sd_tree* tree, int32_t batch, int32_t n_medusa, int32_t trunc_fallback,
+                   int32_t vocab, const int32_t* tok, const int32_t* am, const uint32_t* stop_mask,
+                   int32_t* n_accept, int32_t* n_accept_raw, int32_t* tokens, int32_t* src_slots,
+                   void* stream);
+
+const char* sd_last_error(void);
+/* Library version string; also proves the shared object loads without a GPU.              */
+const char* sd_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECDEC_H */

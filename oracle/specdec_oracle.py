@@ -34,7 +34,13 @@ Conventions (readings of points the paper leaves open):
     base model's own LM head;
   * a tree node's token depends only on (depth, rank): tok = cand[depth-1][rank];
   * the cut keeps the stop token itself; when the accepted run holds no stop token the
-    whole run is kept ("keep_all") or only its first token ("keep_one").
+    whole run is kept ("keep_all") or only its first token ("keep_one");
+  * precision: the paper loads its models in float16 (Section IV-A) and says nothing else.
+    Here a model's `dtype` names a STORAGE format, not an arithmetic: for "bf16" the weights,
+    the embeddings and every key/value row exist only as bfloat16 numbers (a K/V row is
+    rounded once, when it is produced, and that rounded row is what attention reads in the
+    same step and what is committed to the cache); everything computed in between is exact
+    up to float64 rounding. For "f32" nothing is rounded.
 """
 from __future__ import annotations
 
@@ -74,6 +80,15 @@ def rope(x: np.ndarray, pos: np.ndarray, theta: float) -> np.ndarray:
     s = np.sin(ang)[:, None, :]
     x1, x2 = x[..., :half], x[..., half:]
     return np.concatenate([x1 * c - x2 * s, x2 * c + x1 * s], axis=-1)
+
+
+def kv_storage(a: np.ndarray, dtype: str) -> np.ndarray:
+    """Round key/value rows to the cache's storage format (bfloat16: nearest, ties to even)."""
+    if dtype != "bf16":
+        return a
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).reshape(a.shape).astype(F64)
 
 
 def attention(q: np.ndarray, keys: np.ndarray, vals: np.ndarray, visible: np.ndarray) -> np.ndarray:
@@ -121,8 +136,8 @@ def forward_rows(weights, shape, tok, pos, visible, kv: KVCache):
         a = rmsnorm(x, _w(weights, f"l{l}.attn_norm"), shape.rms_eps)
         qkv = a @ _w(weights, f"l{l}.wqkv").T
         q = rope(qkv[:, :d].reshape(T, nh, hd), pos, shape.rope_theta)
-        k = rope(qkv[:, d:2 * d].reshape(T, nh, hd), pos, shape.rope_theta)
-        v = qkv[:, 2 * d:].reshape(T, nh, hd)
+        k = kv_storage(rope(qkv[:, d:2 * d].reshape(T, nh, hd), pos, shape.rope_theta), shape.dtype)
+        v = kv_storage(qkv[:, 2 * d:].reshape(T, nh, hd), shape.dtype)
         k_new[l], v_new[l] = k, v
         o = np.zeros((T, nh, hd), F64)
         for h in range(nh):

@@ -1,0 +1,11 @@
+"""MI355X-native speculative-decoding step (HIP kernels behind a C ABI) -- Python binding.
+
+The package is a thin ctypes wrapper over `libspecdec.so` (see include/specdec.h): argument
+marshalling only, every step of the path runs in the library's HIP kernels. PyTorch is used
+for device memory and streams. Importing the package does not load the library; the first
+call does, and fails loudly if it has not been built (`python -m paper_2503_14153_amd.build`).
+"""
+from .binding import (  # noqa: F401
+    KVCache, Model, SpecDecError, StepOutput, Tree, greedy_step, lib, lib_path, prefill, spec_step,
+    verify_tree, EXPORTED_SYMBOLS,
+)

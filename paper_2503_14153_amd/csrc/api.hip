@@ -1,0 +1,617 @@
+// Host side of libspecdec: handle management, argument validation, and the sequencing of the
+// kernels of one speculative step (paper Section III-B) on a caller-supplied HIP stream.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "sd_internal.h"
+
+// ------------------------------------------------------------------------------------------ errors
+static thread_local char g_err[512] = "";
+
+static int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+#define HIP_TRY(expr)                                                                              \
+    do {                                                                                           \
+        hipError_t e_ = (expr);                                                                    \
+        if (e_ != hipSuccess) return fail(SD_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_));     \
+    } while (0)
+
+extern "C" const char* sd_last_error(void) { return g_err; }
+extern "C" const char* sd_version(void) { return "libspecdec 0.1 (gfx950)"; }
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+static inline int pow2_blocks(int rows) {   // 32-row blocks, rounded up to 1, 2, 4 or 8
+    int mb = ceil_div(rows, 32), p = 1;
+    while (p < mb) p *= 2;
+    return p;
+}
+
+// ------------------------------------------------------------------------------------------ handles
+struct LayerW {
+    const void *attn_norm, *ffn_norm;       // bf16 [d]
+    const void *wqkv, *wo, *wgu, *wdown;    // packed fragments
+};
+
+struct sd_model {
+    sd_config cfg;
+    int max_rows, MBmax;
+    int KBd, KBf, Fpad, NBqkv, NBo, NBgu, NBv, Vpad, NBmed;
+    char* arena = nullptr;                   // packed weights
+    char* work = nullptr;                    // workspace
+    const void *embed, *lm_head, *final_norm, *medusa_w;
+    MedusaBias medusa_b;
+    std::vector<LayerW> layers;
+    // workspace
+    float *x, *part, *logits, *hlogits, *hf, *h_rows, *opart;
+    float2* mlpart;
+    void *xn, *attn_x, *act, *q, *kt, *vt;
+    RowTable rt;
+    int32_t *am, *g_parent, *g_depth, *g_rank;
+    uint32_t* zero_stop;
+    size_t part_floats;
+    int max_parts;
+};
+
+struct sd_kv {
+    const sd_model* m;
+    int B, cap, cap_blocks;
+    uint16_t* buf;
+    size_t layer_stride;                     // elements between layers, per K or V plane
+    uint16_t *kc, *vc;                       // plane bases
+    int32_t* state = nullptr;                // device: kv_len, n_old, root_tok, last_row, cand, io scratch
+    int32_t *kv_len, *n_old, *root_tok, *last_row, *cand, *i_nacc, *i_tokens, *i_slots;
+    std::vector<int32_t> len_hi;             // host upper bound of the committed lengths
+    bool has_draft = false;
+};
+
+struct sd_tree {
+    int T, Tp, H, topk;
+    int32_t* dev = nullptr;                  // parent | depth | rank
+    const int32_t *parent, *depth, *rank;
+};
+
+// ------------------------------------------------------------------------------------------ model
+static int check_config(const sd_config* c) {
+    if (c->dtype != SD_DTYPE_BF16) return fail(SD_ERR_SHAPE, "only dtype bf16 is implemented");
+    if (c->head_dim != 64 && c->head_dim != 128) return fail(SD_ERR_SHAPE, "head_dim must be 64 or 128");
+    if (c->n_layers < 1 || c->n_heads < 1 || c->vocab < 2) return fail(SD_ERR_SHAPE, "bad sizes");
+    if (c->d_model != c->n_heads * c->head_dim) return fail(SD_ERR_SHAPE, "d_model != n_heads * head_dim");
+    if (c->d_model % 32 || c->d_model > 8192) return fail(SD_ERR_SHAPE, "d_model must be a multiple of 32, <= 8192");
+    if (c->d_ffn % 16 || c->d_ffn < 16) return fail(SD_ERR_SHAPE, "d_ffn must be a multiple of 16");
+    if (c->n_medusa < 1 || c->n_medusa > SD_MAX_MEDUSA) return fail(SD_ERR_SHAPE, "n_medusa must be in 1..15");
+    if (c->topk < 1 || c->topk > 32 || c->topk > c->vocab) return fail(SD_ERR_SHAPE, "topk must be in 1..32");
+    if (c->trunc_fallback != SD_TRUNC_KEEP_ALL && c->trunc_fallback != SD_TRUNC_KEEP_ONE)
+        return fail(SD_ERR_SHAPE, "bad trunc_fallback");
+    if (!(c->rope_theta > 0.f) || !(c->rms_eps >= 0.f)) return fail(SD_ERR_SHAPE, "bad rope_theta / rms_eps");
+    return SD_OK;
+}
+
+extern "C" int sd_model_create(const sd_config* cfg, const sd_weights* w, int32_t max_rows, void* stream,
+                               sd_model** out) {
+    if (!cfg || !w || !out) return fail(SD_ERR_NULL, "sd_model_create: NULL argument");
+    *out = nullptr;
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    if (max_rows < 1 || max_rows > 256) return fail(SD_ERR_SHAPE, "max_rows must be in 1..256");
+    if (!w->embed || !w->lm_head || !w->final_norm || !w->attn_norm || !w->wqkv || !w->wo || !w->ffn_norm ||
+        !w->w_gate || !w->w_up || !w->w_down || !w->medusa_w)
+        return fail(SD_ERR_NULL, "sd_model_create: NULL weight pointer");
+    const int L = cfg->n_layers, d = cfg->d_model, F = cfg->d_ffn, V = cfg->vocab, H = cfg->n_medusa;
+    for (int l = 0; l < L; ++l)
+        if (!w->attn_norm[l] || !w->wqkv[l] || !w->wo[l] || !w->ffn_norm[l] || !w->w_gate[l] || !w->w_up[l] ||
+            !w->w_down[l])
+            return fail(SD_ERR_NULL, "sd_model_create: NULL weight pointer in layer %d", l);
+    for (int i = 0; i < H; ++i)
+        if (!w->medusa_w[i]) return fail(SD_ERR_NULL, "sd_model_create: NULL draft-head weight %d", i);
+
+    hipStream_t s = (hipStream_t)stream;
+    sd_model* m = new (std::nothrow) sd_model();
+    if (!m) return fail(SD_ERR_HIP, "out of host memory");
+    m->cfg = *cfg;
+    m->max_rows = max_rows;
+    m->MBmax = pow2_blocks(max_rows);
+    m->KBd = d / 16;
+    m->KBf = F / 16;
+    m->Fpad = (int)align_up(F, 32);
+    m->NBqkv = 3 * d / 32;
+    m->NBo = d / 32;
+    m->NBgu = 2 * m->Fpad / 32;
+    m->NBv = ceil_div(V, 32);
+    m->Vpad = m->NBv * 32;
+    m->NBmed = H * d / 32;
+
+    // ---- arena of packed weights
+    const size_t frag = 1024;    // bytes per fragment
+    size_t sz = 0;
+    auto take = [&](size_t bytes) { size_t o = sz; sz = align_up(sz + bytes, 256); return o; };
+    size_t o_embed = take((size_t)V * d * 2), o_lm = take((size_t)m->NBv * m->KBd * frag), o_fn = take((size_t)d * 2);
+    size_t o_med = take((size_t)m->NBmed * m->KBd * frag);
+    std::vector<size_t> o_mb(H), o_an(L), o_qkv(L), o_o(L), o_ffn(L), o_gu(L), o_dn(L);
+    for (int i = 0; i < H; ++i) o_mb[i] = take((size_t)d * 2);
+    for (int l = 0; l < L; ++l) {
+        o_an[l] = take((size_t)d * 2);
+        o_qkv[l] = take((size_t)m->NBqkv * m->KBd * frag);
+        o_o[l] = take((size_t)m->NBo * m->KBd * frag);
+        o_ffn[l] = take((size_t)d * 2);
+        o_gu[l] = take((size_t)m->NBgu * m->KBd * frag);
+        o_dn[l] = take((size_t)m->NBo * m->KBf * frag);
+    }
+    hipError_t e = hipMalloc((void**)&m->arena, sz);
+    if (e != hipSuccess) { delete m; return fail(SD_ERR_HIP, "hipMalloc(%zu) for weights: %s", sz, hipGetErrorString(e)); }
+    char* A = m->arena;
+    auto copy = [&](size_t off, const void* src, size_t bytes) {
+        return hipMemcpyAsync(A + off, src, bytes, hipMemcpyDeviceToDevice, s);
+    };
+    e = copy(o_embed, w->embed, (size_t)V * d * 2);
+    if (e == hipSuccess) e = copy(o_fn, w->final_norm, (size_t)d * 2);
+    if (e != hipSuccess) { hipFree(m->arena); delete m; return fail(SD_ERR_HIP, "weight copy: %s", hipGetErrorString(e)); }
+    m->embed = A + o_embed;
+    m->final_norm = A + o_fn;
+    launch_pack_weight(w->lm_head, A + o_lm, V, d, 0, m->KBd, s);
+    m->lm_head = A + o_lm;
+    for (int i = 0; i < H; ++i) {
+        launch_pack_weight(w->medusa_w[i], A + o_med, d, d, i * (d / 32), m->KBd, s);
+        if (w->medusa_b && w->medusa_b[i]) {
+            copy(o_mb[i], w->medusa_b[i], (size_t)d * 2);
+            m->medusa_b.p[i] = (const uint16_t*)(A + o_mb[i]);
+        } else {
+            m->medusa_b.p[i] = nullptr;
+        }
+    }
+    m->medusa_w = A + o_med;
+    m->layers.resize(L);
+    for (int l = 0; l < L; ++l) {
+        LayerW& lw = m->layers[l];
+        copy(o_an[l], w->attn_norm[l], (size_t)d * 2);
+        copy(o_ffn[l], w->ffn_norm[l], (size_t)d * 2);
+        launch_pack_weight(w->wqkv[l], A + o_qkv[l], 3 * d, d, 0, m->KBd, s);
+        launch_pack_weight(w->wo[l], A + o_o[l], d, d, 0, m->KBd, s);
+        launch_pack_weight(w->w_gate[l], A + o_gu[l], F, d, 0, m->KBd, s);
+        launch_pack_weight(w->w_up[l], A + o_gu[l], F, d, m->Fpad / 32, m->KBd, s);
+        launch_pack_weight(w->w_down[l], A + o_dn[l], d, F, 0, m->KBf, s);
+        lw.attn_norm = A + o_an[l];
+        lw.ffn_norm = A + o_ffn[l];
+        lw.wqkv = A + o_qkv[l];
+        lw.wo = A + o_o[l];
+        lw.wgu = A + o_gu[l];
+        lw.wdown = A + o_dn[l];
+    }
+
+    // ---- workspace
+    const int Mp = m->MBmax * 32, nh = cfg->n_heads, hd = cfg->head_dim;
+    const int ld_max = std::max(std::max(3 * d, 2 * m->Fpad), H * d);
+    size_t pf = 0;
+    for (int mb = 1; mb <= m->MBmax; mb *= 2) {
+        int kbs[2] = {m->KBd, m->KBf};
+        int nbs[4] = {m->NBqkv, m->NBo, m->NBgu, m->NBmed};
+        for (int kb : kbs)
+            for (int nb : nbs) pf = std::max(pf, (size_t)gemm_choose_split(mb, kb, nb) * (mb * 32) * (size_t)nb * 32);
+    }
+    (void)ld_max;
+    m->part_floats = pf;
+    m->max_parts = 65;
+    const int HBp = pow2_blocks(H * SD_MAX_BATCH > 256 ? 256 : H * SD_MAX_BATCH) * 32;
+    size_t wz = 0;
+    auto wtake = [&](size_t bytes) { size_t o = wz; wz = align_up(wz + bytes, 256); return o; };
+    size_t w_x = wtake((size_t)Mp * d * 4), w_part = wtake(pf * 4), w_logits = wtake((size_t)Mp * m->Vpad * 4);
+    size_t w_hlog = wtake((size_t)HBp * m->Vpad * 4), w_hf = wtake((size_t)Mp * d * 4);
+    size_t w_hrows = wtake((size_t)SD_MAX_BATCH * d * 4);
+    size_t w_opart = wtake((size_t)Mp * nh * m->max_parts * hd * 4), w_ml = wtake((size_t)Mp * nh * m->max_parts * 8);
+    size_t w_xn = wtake((size_t)std::max(Mp, HBp) * d * 4), w_attn = wtake((size_t)Mp * d * 4);
+    size_t w_act = wtake((size_t)Mp * F * 4), w_q = wtake((size_t)Mp * d * 4);
+    size_t w_kt = wtake((size_t)L * Mp * d * 2), w_vt = wtake((size_t)L * Mp * d * 2);
+    size_t w_tok = wtake((size_t)Mp * 4), w_pos = wtake((size_t)Mp * 4), w_anc = wtake((size_t)Mp * SD_ANC_WORDS * 4);
+    size_t w_cs = wtake((size_t)Mp * (hd / 2) * 8), w_am = wtake((size_t)Mp * 4), w_g = wtake(3 * 4);
+    size_t w_zs = wtake((size_t)ceil_div(V, 32) * 4);
+    e = hipMalloc((void**)&m->work, wz);
+    if (e != hipSuccess) {
+        hipFree(m->arena);
+        delete m;
+        return fail(SD_ERR_HIP, "hipMalloc(%zu) for workspace: %s", wz, hipGetErrorString(e));
+    }
+    hipMemsetAsync(m->work, 0, wz, s);
+    char* Wk = m->work;
+    m->x = (float*)(Wk + w_x); m->part = (float*)(Wk + w_part); m->logits = (float*)(Wk + w_logits);
+    m->hlogits = (float*)(Wk + w_hlog); m->hf = (float*)(Wk + w_hf); m->h_rows = (float*)(Wk + w_hrows);
+    m->opart = (float*)(Wk + w_opart); m->mlpart = (float2*)(Wk + w_ml);
+    m->xn = Wk + w_xn; m->attn_x = Wk + w_attn; m->act = Wk + w_act; m->q = Wk + w_q;
+    m->kt = Wk + w_kt; m->vt = Wk + w_vt;
+    m->rt.tok = (int32_t*)(Wk + w_tok); m->rt.pos = (int32_t*)(Wk + w_pos); m->rt.anc = (uint32_t*)(Wk + w_anc);
+    m->rt.cs = (float2*)(Wk + w_cs);
+    m->am = (int32_t*)(Wk + w_am);
+    m->g_parent = (int32_t*)(Wk + w_g); m->g_depth = m->g_parent + 1; m->g_rank = m->g_parent + 2;
+    m->zero_stop = (uint32_t*)(Wk + w_zs);
+    launch_fill_i32(m->g_parent, -1, 1, s);
+    e = hipStreamSynchronize(s);
+    if (e == hipSuccess) e = hipGetLastError();
+    if (e != hipSuccess) {
+        hipFree(m->arena); hipFree(m->work); delete m;
+        return fail(SD_ERR_HIP, "weight packing failed: %s", hipGetErrorString(e));
+    }
+    *out = m;
+    return SD_OK;
+}
+
+extern "C" int sd_model_destroy(sd_model* m) {
+    if (!m) return SD_OK;
+    hipFree(m->arena);
+    hipFree(m->work);
+    delete m;
+    return SD_OK;
+}
+
+// ------------------------------------------------------------------------------------------ KV cache
+extern "C" size_t sd_kv_bytes(const sd_config* cfg, int32_t batch, int32_t cap) {
+    if (!cfg || batch < 1 || cap < 1) return 0;
+    size_t blocks = (size_t)ceil_div(cap, 32);
+    return (size_t)cfg->n_layers * 2 * batch * cfg->n_heads * blocks * 32 * cfg->head_dim * 2;
+}
+
+extern "C" int sd_kv_create(const sd_model* m, int32_t batch, int32_t cap, void* dev_buf, size_t bytes, sd_kv** out) {
+    if (!m || !dev_buf || !out) return fail(SD_ERR_NULL, "sd_kv_create: NULL argument");
+    *out = nullptr;
+    if (batch < 1 || batch > SD_MAX_BATCH) return fail(SD_ERR_SHAPE, "batch must be in 1..%d", SD_MAX_BATCH);
+    if (batch * m->cfg.n_medusa > 256) return fail(SD_ERR_SHAPE, "batch * n_medusa must be <= 256");
+    if (cap < m->cfg.n_medusa + 2) return fail(SD_ERR_SHAPE, "cap too small");
+    if (bytes < sd_kv_bytes(&m->cfg, batch, cap)) return fail(SD_ERR_SHAPE, "KV buffer too small");
+    if (((uintptr_t)dev_buf) & 15) return fail(SD_ERR_SHAPE, "KV buffer must be 16-byte aligned");
+    sd_kv* kv = new (std::nothrow) sd_kv();
+    if (!kv) return fail(SD_ERR_HIP, "out of host memory");
+    kv->m = m;
+    kv->B = batch;
+    kv->cap = cap;
+    kv->cap_blocks = ceil_div(cap, 32);
+    kv->buf = (uint16_t*)dev_buf;
+    kv->layer_stride = (size_t)batch * m->cfg.n_heads * kv->cap_blocks * 32 * m->cfg.head_dim;
+    kv->kc = kv->buf;
+    kv->vc = kv->buf + (size_t)m->cfg.n_layers * kv->layer_stride;
+    const int H = m->cfg.n_medusa, k = m->cfg.topk;
+    const int W = std::max(H + 1, SD_MAX_TREE);
+    size_t n = (size_t)batch * (4 + H * k + 1 + 2 * W);
+    hipError_t e = hipMalloc((void**)&kv->state, n * 4);
+    if (e != hipSuccess) { delete kv; return fail(SD_ERR_HIP, "hipMalloc state: %s", hipGetErrorString(e)); }
+    e = hipMemset(kv->state, 0, n * 4);
+    if (e != hipSuccess) { hipFree(kv->state); delete kv; return fail(SD_ERR_HIP, "hipMemset: %s", hipGetErrorString(e)); }
+    int32_t* p = kv->state;
+    kv->kv_len = p; p += batch;
+    kv->n_old = p; p += batch;
+    kv->root_tok = p; p += batch;
+    kv->last_row = p; p += batch;
+    kv->cand = p; p += (size_t)batch * H * k;
+    kv->i_nacc = p; p += batch;
+    kv->i_tokens = p; p += (size_t)batch * W;
+    kv->i_slots = p;
+    kv->len_hi.assign(batch, 0);
+    *out = kv;
+    return SD_OK;
+}
+
+extern "C" int sd_kv_destroy(sd_kv* kv) {
+    if (!kv) return SD_OK;
+    hipFree(kv->state);
+    delete kv;
+    return SD_OK;
+}
+
+extern "C" int sd_kv_len(sd_kv* kv, int32_t* out_len, void* stream) {
+    if (!kv || !out_len) return fail(SD_ERR_NULL, "sd_kv_len: NULL argument");
+    HIP_TRY(hipMemcpyAsync(out_len, kv->kv_len, kv->B * 4, hipMemcpyDeviceToHost, (hipStream_t)stream));
+    HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+    for (int b = 0; b < kv->B; ++b) kv->len_hi[b] = out_len[b];
+    return SD_OK;
+}
+
+extern "C" int sd_kv_set_len(sd_kv* kv, const int32_t* len, void* stream) {
+    if (!kv || !len) return fail(SD_ERR_NULL, "sd_kv_set_len: NULL argument");
+    for (int b = 0; b < kv->B; ++b)
+        if (len[b] < 0 || len[b] > kv->cap) return fail(SD_ERR_SHAPE, "sd_kv_set_len: length %d out of range", len[b]);
+    HIP_TRY(hipMemcpyAsync(kv->kv_len, len, kv->B * 4, hipMemcpyHostToDevice, (hipStream_t)stream));
+    HIP_TRY(hipStreamSynchronize((hipStream_t)stream));   // `len` may be a temporary of the caller
+    for (int b = 0; b < kv->B; ++b) kv->len_hi[b] = len[b];
+    return SD_OK;
+}
+
+static int kv_rows_common(sd_kv* kv, int layer, int seq, int row0, int nrows, void* k_rows, void* v_rows, int to_cache,
+                          void* stream) {
+    if (!kv || !k_rows || !v_rows) return fail(SD_ERR_NULL, "sd_kv_*_rows: NULL argument");
+    const sd_config& c = kv->m->cfg;
+    if (layer < 0 || layer >= c.n_layers || seq < 0 || seq >= kv->B || row0 < 0 || nrows < 0 || row0 + nrows > kv->cap)
+        return fail(SD_ERR_SHAPE, "sd_kv_*_rows: index out of range");
+    if (nrows == 0) return SD_OK;
+    size_t off = layer * kv->layer_stride + (size_t)seq * c.n_heads * kv->cap_blocks * 32 * c.head_dim;
+    launch_kv_rows(kv->kc + off, kv->vc + off, k_rows, v_rows, row0, nrows, c.n_heads, c.head_dim, kv->cap_blocks,
+                   to_cache, (hipStream_t)stream);
+    HIP_TRY(hipGetLastError());
+    return SD_OK;
+}
+extern "C" int sd_kv_write_rows(sd_kv* kv, int32_t layer, int32_t seq, int32_t row0, int32_t nrows, const void* k_rows,
+                                const void* v_rows, void* stream) {
+    return kv_rows_common(kv, layer, seq, row0, nrows, (void*)k_rows, (void*)v_rows, 1, stream);
+}
+extern "C" int sd_kv_read_rows(sd_kv* kv, int32_t layer, int32_t seq, int32_t row0, int32_t nrows, void* k_rows,
+                               void* v_rows, void* stream) {
+    return kv_rows_common(kv, layer, seq, row0, nrows, k_rows, v_rows, 0, stream);
+}
+
+extern "C" int sd_kv_set_draft(sd_kv* kv, const int32_t* root_tok, const int32_t* cand, void* stream) {
+    if (!kv || !root_tok || !cand) return fail(SD_ERR_NULL, "sd_kv_set_draft: NULL argument");
+    const sd_config& c = kv->m->cfg;
+    launch_copy_i32(root_tok, kv->root_tok, kv->B, (hipStream_t)stream);
+    launch_copy_i32(cand, kv->cand, kv->B * c.n_medusa * c.topk, (hipStream_t)stream);
+    HIP_TRY(hipGetLastError());
+    kv->has_draft = true;
+    return SD_OK;
+}
+extern "C" int sd_kv_get_draft(sd_kv* kv, int32_t* root_tok, int32_t* cand, void* stream) {
+    if (!kv || !root_tok || !cand) return fail(SD_ERR_NULL, "sd_kv_get_draft: NULL argument");
+    const sd_config& c = kv->m->cfg;
+    launch_copy_i32(kv->root_tok, root_tok, kv->B, (hipStream_t)stream);
+    launch_copy_i32(kv->cand, cand, kv->B * c.n_medusa * c.topk, (hipStream_t)stream);
+    HIP_TRY(hipGetLastError());
+    return SD_OK;
+}
+
+// ------------------------------------------------------------------------------------------ tree
+static int validate_tree(int T, const int32_t* parent, const int32_t* depth, const int32_t* rank, int H, int k) {
+    if (T < 1 || T > SD_MAX_TREE) return fail(SD_ERR_BAD_TREE, "tree must have 1..%d nodes", SD_MAX_TREE);
+    if (parent[0] != -1 || depth[0] != 0) return fail(SD_ERR_BAD_TREE, "node 0 must be the root (parent -1, depth 0)");
+    for (int j = 1; j < T; ++j) {
+        if (parent[j] < 0 || parent[j] >= j) return fail(SD_ERR_BAD_TREE, "node %d: parent must precede it", j);
+        if (depth[j] != depth[parent[j]] + 1) return fail(SD_ERR_BAD_TREE, "node %d: depth != parent's depth + 1", j);
+        if (depth[j] > H) return fail(SD_ERR_BAD_TREE, "node %d: depth %d exceeds the number of draft heads", j, depth[j]);
+        if (rank[j] < 0 || rank[j] >= k) return fail(SD_ERR_BAD_TREE, "node %d: rank out of range", j);
+        for (int i = 1; i < j; ++i)
+            if (parent[i] == parent[j] && rank[i] == rank[j])
+                return fail(SD_ERR_BAD_TREE, "nodes %d and %d: siblings with equal rank", i, j);
+    }
+    return SD_OK;
+}
+
+extern "C" int sd_tree_create(int32_t T, const int32_t* parent, const int32_t* depth, const int32_t* rank,
+                              int32_t n_medusa, int32_t topk, sd_tree** out) {
+    if (!parent || !depth || !rank || !out) return fail(SD_ERR_NULL, "sd_tree_create: NULL argument");
+    *out = nullptr;
+    if (n_medusa < 0 || n_medusa > SD_MAX_MEDUSA || topk < 1) return fail(SD_ERR_SHAPE, "bad n_medusa / topk");
+    int rc = validate_tree(T, parent, depth, rank, n_medusa, topk);
+    if (rc) return rc;
+    sd_tree* t = new (std::nothrow) sd_tree();
+    if (!t) return fail(SD_ERR_HIP, "out of host memory");
+    t->T = T;
+    t->Tp = ceil_div(T, 32) * 32;
+    t->H = n_medusa;
+    t->topk = topk;
+    hipError_t e = hipMalloc((void**)&t->dev, (size_t)3 * T * 4);
+    if (e == hipSuccess) e = hipMemcpy(t->dev, parent, (size_t)T * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(t->dev + T, depth, (size_t)T * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(t->dev + 2 * T, rank, (size_t)T * 4, hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        if (t->dev) hipFree(t->dev);
+        delete t;
+        return fail(SD_ERR_HIP, "tree upload: %s", hipGetErrorString(e));
+    }
+    t->parent = t->dev;
+    t->depth = t->dev + T;
+    t->rank = t->dev + 2 * T;
+    *out = t;
+    return SD_OK;
+}
+
+extern "C" int sd_tree_destroy(sd_tree* t) {
+    if (!t) return SD_OK;
+    hipFree(t->dev);
+    delete t;
+    return SD_OK;
+}
+
+// ------------------------------------------------------------------------------------------ forward
+// Layers 0..L-1 on the rows described by m->rt / m->x (B sequences of Tp rows each). Leaves the
+// last down-projection's partial sums in m->part (added by the caller's next norm).
+struct PartRef { int nsplit; size_t stride; int ld; };
+
+static PartRef run_gemm(sd_model* m, const void* Xp, const void* Wp, float* out, int MB, int KB, int NB, hipStream_t s) {
+    PartRef p;
+    p.ld = NB * 32;
+    p.nsplit = gemm_choose_split(MB, KB, NB);
+    p.stride = (size_t)MB * 32 * p.ld;
+    launch_gemm(Xp, Wp, out, MB, KB, NB, p.ld, p.nsplit, p.stride, s);
+    return p;
+}
+
+static void attn_geometry(const sd_model* m, int B, int Tp, int n_hi, int* nchunks, int* bpc) {
+    const int nblk = ceil_div(n_hi, 32);
+    const int TB = Tp / 32, TG = (TB % 2 == 0) ? TB / 2 : TB;
+    const int waves_per_chunk = B * m->cfg.n_heads * TG;
+    int want = ceil_div(2048, waves_per_chunk);
+    if (want > m->max_parts - 1) want = m->max_parts - 1;
+    if (want > ceil_div(nblk, 4)) want = ceil_div(nblk, 4);   // at least 128 cache rows per part
+    if (want < 1) { *nchunks = 0; *bpc = 1; return; }
+    *bpc = ceil_div(nblk, want);
+    *nchunks = ceil_div(nblk, *bpc);
+}
+
+static PartRef run_layers(sd_model* m, sd_kv* kv, int B, int Tp, int n_hi, hipStream_t s) {
+    const sd_config& c = m->cfg;
+    const int M = B * Tp, MB = pow2_blocks(M), d = c.d_model, nh = c.n_heads, hd = c.head_dim, TB = Tp / 32;
+    int nchunks, bpc;
+    attn_geometry(m, B, Tp, n_hi, &nchunks, &bpc);
+    PartRef prev = {0, 0, d};
+    const size_t t_stride = (size_t)B * nh * TB * 32 * hd;     // elements per layer of tree scratch
+    for (int l = 0; l < c.n_layers; ++l) {
+        const LayerW& lw = m->layers[l];
+        launch_norm_pack(m->x, m->part, prev.nsplit, prev.stride, prev.ld, lw.attn_norm, c.rms_eps, m->xn, nullptr, M, d,
+                         MB, nullptr, s);
+        PartRef pq = run_gemm(m, m->xn, lw.wqkv, m->part, MB, m->KBd, m->NBqkv, s);
+        uint16_t* kt = (uint16_t*)m->kt + l * t_stride;
+        uint16_t* vt = (uint16_t*)m->vt + l * t_stride;
+        launch_rope_kv(m->part, pq.nsplit, pq.stride, pq.ld, m->rt, m->q, kt, vt, B, Tp, nh, hd, s);
+        launch_tree_attn(m->q, kv->kc + l * kv->layer_stride, kv->vc + l * kv->layer_stride, kt, vt, kv->kv_len,
+                         m->rt.anc, m->opart, m->mlpart, B, nh, hd, Tp, kv->cap_blocks, nchunks, bpc, s);
+        launch_attn_merge(m->opart, m->mlpart, m->attn_x, B, nh, hd, Tp, nchunks + 1, MB, s);
+        PartRef po = run_gemm(m, m->attn_x, lw.wo, m->part, MB, m->KBd, m->NBo, s);
+        launch_norm_pack(m->x, m->part, po.nsplit, po.stride, po.ld, lw.ffn_norm, c.rms_eps, m->xn, nullptr, M, d, MB,
+                         nullptr, s);
+        PartRef pg = run_gemm(m, m->xn, lw.wgu, m->part, MB, m->KBd, m->NBgu, s);
+        launch_swiglu_pack(m->part, pg.nsplit, pg.stride, pg.ld, c.d_ffn, m->Fpad, m->act, M, MB, s);
+        prev = run_gemm(m, m->act, lw.wdown, m->part, MB, m->KBf, m->NBo, s);
+    }
+    return prev;
+}
+
+// final norm + LM head on all rows + arg-max of the first T rows of every sequence
+static void run_lm_head(sd_model* m, PartRef prev, int B, int T, int Tp, hipStream_t s) {
+    const sd_config& c = m->cfg;
+    const int M = B * Tp, MB = pow2_blocks(M);
+    launch_norm_pack(m->x, m->part, prev.nsplit, prev.stride, prev.ld, m->final_norm, c.rms_eps, m->xn, nullptr, M,
+                     c.d_model, MB, nullptr, s);
+    launch_gemm(m->xn, m->lm_head, m->logits, MB, m->KBd, m->NBv, m->Vpad, 1, 0, s);
+    launch_argmax(m->logits, m->Vpad, c.vocab, m->am, B, T, Tp, s);
+}
+
+// draft heads at row last_row[b] of every sequence -> cand (sequences in seq_mask only)
+static void run_draft_heads(sd_model* m, sd_kv* kv, int B, uint32_t seq_mask, float* head_logits_out, hipStream_t s) {
+    const sd_config& c = m->cfg;
+    const int d = c.d_model, H = c.n_medusa;
+    launch_norm_pack(m->x, nullptr, 0, 0, 0, m->final_norm, c.rms_eps, m->xn, m->h_rows, B, d, 1, kv->last_row, s);
+    PartRef pm = run_gemm(m, m->xn, m->medusa_w, m->part, 1, m->KBd, m->NBmed, s);
+    const int MBh = pow2_blocks(H * B);
+    launch_medusa_act(m->part, pm.nsplit, pm.stride, pm.ld, m->h_rows, m->medusa_b, B, H, d, m->xn, MBh, s);
+    launch_gemm(m->xn, m->lm_head, m->hlogits, MBh, m->KBd, m->NBv, m->Vpad, 1, 0, s);
+    launch_topk(m->hlogits, m->Vpad, c.vocab, c.topk, kv->cand, B, H, seq_mask, s);
+    if (head_logits_out) launch_copy_head_logits(m->hlogits, m->Vpad, head_logits_out, c.vocab, B, H, s);
+}
+
+// ------------------------------------------------------------------------------------------ prefill
+extern "C" int sd_prefill(sd_model* m, sd_kv* kv, const int32_t* tokens, const int32_t* lens, void* stream) {
+    if (!m || !kv || !tokens || !lens) return fail(SD_ERR_NULL, "sd_prefill: NULL argument");
+    if (kv->m != m) return fail(SD_ERR_STATE, "sd_prefill: cache belongs to another model");
+    const sd_config& c = m->cfg;
+    const int B = kv->B;
+    hipStream_t s = (hipStream_t)stream;
+    int Tp = (m->max_rows / B) / 32 * 32;
+    if (Tp > SD_MAX_TREE) Tp = SD_MAX_TREE;
+    if (Tp > 64) Tp = 64;
+    if (Tp < 32) return fail(SD_ERR_SHAPE, "sd_prefill: max_rows %d too small for batch %d", m->max_rows, B);
+    int maxlen = 0;
+    for (int b = 0; b < B; ++b) {
+        if (lens[b] < 1) return fail(SD_ERR_SHAPE, "sd_prefill: every prompt needs at least one token");
+        if (kv->len_hi[b] + lens[b] > kv->cap) return fail(SD_ERR_KV_FULL, "sd_prefill: sequence %d does not fit", b);
+        maxlen = std::max(maxlen, lens[b]);
+    }
+    std::vector<int> start(B), done(B, 0);
+    for (int b = 0, o = 0; b < B; ++b) { start[b] = o; o += lens[b]; }
+    for (int pos = 0; pos < maxlen; pos += Tp) {
+        ChainArgs ca;
+        memset(&ca, 0, sizeof(ca));
+        uint32_t fin = 0;
+        int n_hi = 0;
+        for (int b = 0; b < B; ++b) {
+            int left = lens[b] - pos;
+            ca.len[b] = left <= 0 ? 0 : std::min(left, Tp);
+            ca.off[b] = start[b] + pos;
+            if (left > 0 && left <= Tp) fin |= 1u << b;
+            n_hi = std::max(n_hi, kv->len_hi[b]);
+        }
+        launch_build_rows_chain(m->rt, tokens, ca, kv->kv_len, B, Tp, c.head_dim, c.rope_theta, m->embed, c.d_model,
+                                c.vocab, m->x, s);
+        PartRef prev = run_layers(m, kv, B, Tp, n_hi, s);
+        launch_prefill_commit_setup(ca, B, Tp, kv->i_slots, kv->i_nacc, kv->n_old, kv->kv_len, kv->last_row, s);
+        launch_kv_commit(m->kt, m->vt, kv->kc, kv->vc, kv->i_slots, kv->i_nacc, kv->n_old, c.n_layers, B, c.n_heads,
+                         c.head_dim, Tp / 32, kv->cap_blocks, Tp, Tp, s);
+        for (int b = 0; b < B; ++b) kv->len_hi[b] += ca.len[b];
+        if (fin) {
+            run_lm_head(m, prev, B, Tp, Tp, s);
+            launch_pick_root(m->am, kv->last_row, kv->root_tok, B, fin, s);
+            run_draft_heads(m, kv, B, fin, nullptr, s);
+        }
+    }
+    HIP_TRY(hipGetLastError());
+    kv->has_draft = true;
+    return SD_OK;
+}
+
+// ------------------------------------------------------------------------------------------ steps
+static int step_common(sd_model* m, sd_kv* kv, const int32_t* parent, const int32_t* depth, const int32_t* rank, int T,
+                       int Tp, const uint32_t* stop_mask, sd_step_io* io, hipStream_t s, const char* who) {
+    const sd_config& c = m->cfg;
+    const int B = kv->B, H = c.n_medusa;
+    if (kv->m != m) return fail(SD_ERR_STATE, "%s: cache belongs to another model", who);
+    if (!kv->has_draft) return fail(SD_ERR_STATE, "%s: no draft state (call sd_prefill or sd_kv_set_draft first)", who);
+    if (pow2_blocks(B * Tp) > m->MBmax)
+        return fail(SD_ERR_SHAPE, "%s: %d rows exceed the model's max_rows", who, B * Tp);
+    int n_hi = 0;
+    for (int b = 0; b < B; ++b) {
+        if (kv->len_hi[b] + H + 1 > kv->cap)
+            return fail(SD_ERR_KV_FULL, "%s: sequence %d may exceed the cache (len <= %d, cap %d)", who, b,
+                        kv->len_hi[b], kv->cap);
+        n_hi = std::max(n_hi, kv->len_hi[b]);
+    }
+    int32_t* n_accept = io->n_accept ? io->n_accept : kv->i_nacc;
+    int32_t* tokens = io->tokens ? io->tokens : kv->i_tokens;
+    int32_t* slots = io->src_slots ? io->src_slots : kv->i_slots;
+
+    const int32_t* cand = io->forced_cand ? io->forced_cand : kv->cand;
+    launch_build_rows_tree(m->rt, parent, depth, rank, kv->root_tok, cand, kv->kv_len, B, T, Tp, H, c.topk, c.head_dim,
+                           c.rope_theta, m->embed, c.d_model, c.vocab, m->x, s);
+    PartRef prev = run_layers(m, kv, B, Tp, n_hi, s);
+    run_lm_head(m, prev, B, T, Tp, s);
+    if (io->logits) launch_copy_logits(m->logits, m->Vpad, io->logits, c.vocab, B, T, Tp, s);
+    if (io->argmax) launch_copy_rows_i32(m->am, io->argmax, B, T, Tp, s);
+    VerifyArgs va;
+    va.parent = parent; va.depth = depth; va.T = T; va.H = H; va.fallback = c.trunc_fallback;
+    va.src_stride = Tp; va.Tp = Tp; va.V = c.vocab;
+    va.tok = m->rt.tok; va.am = m->am; va.stop_mask = stop_mask;
+    va.n_accept = n_accept; va.n_accept_raw = io->n_accept_raw; va.tokens = tokens; va.src_slots = slots;
+    va.kv_len = kv->kv_len; va.n_old = kv->n_old; va.root_tok = kv->root_tok; va.last_row = kv->last_row;
+    launch_verify(va, B, s);
+    launch_kv_commit(m->kt, m->vt, kv->kc, kv->vc, slots, n_accept, kv->n_old, c.n_layers, B, c.n_heads, c.head_dim,
+                     Tp / 32, kv->cap_blocks, H + 1, H + 1, s);
+    run_draft_heads(m, kv, B, 0xffffffffu, io->head_logits, s);
+    HIP_TRY(hipGetLastError());
+    for (int b = 0; b < B; ++b) kv->len_hi[b] += (T == 1) ? 1 : H + 1;
+    return SD_OK;
+}
+
+extern "C" int sd_spec_step(sd_model* m, sd_kv* kv, const sd_tree* tree, const uint32_t* stop_mask, sd_step_io* io,
+                            void* stream) {
+    if (!m || !kv || !tree || !stop_mask || !io) return fail(SD_ERR_NULL, "sd_spec_step: NULL argument");
+    if (tree->H != m->cfg.n_medusa || tree->topk != m->cfg.topk)
+        return fail(SD_ERR_BAD_TREE, "sd_spec_step: tree was built for %d heads / top-%d", tree->H, tree->topk);
+    return step_common(m, kv, tree->parent, tree->depth, tree->rank, tree->T, tree->Tp, stop_mask, io,
+                       (hipStream_t)stream, "sd_spec_step");
+}
+
+extern "C" int sd_greedy_step(sd_model* m, sd_kv* kv, sd_step_io* io, void* stream) {
+    if (!m || !kv || !io) return fail(SD_ERR_NULL, "sd_greedy_step: NULL argument");
+    return step_common(m, kv, m->g_parent, m->g_depth, m->g_rank, 1, 32, m->zero_stop, io, (hipStream_t)stream,
+                       "sd_greedy_step");
+}
+
+extern "C" int sd_verify_tree(const sd_tree* tree, int32_t batch, int32_t n_medusa, int32_t trunc_fallback,
+                              int32_t vocab, const int32_t* tok, const int32_t* am, const uint32_t* stop_mask,
+                              int32_t* n_accept, int32_t* n_accept_raw, int32_t* tokens, int32_t* src_slots,
+                              void* stream) {
+    if (!tree || !tok || !am || !stop_mask || !n_accept || !tokens || !src_slots)
+        return fail(SD_ERR_NULL, "sd_verify_tree: NULL argument");
+    if (batch < 1 || batch > 65535) return fail(SD_ERR_SHAPE, "sd_verify_tree: bad batch");
+    if (n_medusa != tree->H) return fail(SD_ERR_BAD_TREE, "sd_verify_tree: tree was built for %d heads", tree->H);
+    if (trunc_fallback != SD_TRUNC_KEEP_ALL && trunc_fallback != SD_TRUNC_KEEP_ONE)
+        return fail(SD_ERR_SHAPE, "sd_verify_tree: bad trunc_fallback");
+    VerifyArgs va;
+    memset(&va, 0, sizeof(va));
+    va.parent = tree->parent; va.depth = tree->depth; va.T = tree->T; va.H = tree->H; va.fallback = trunc_fallback;
+    va.src_stride = tree->T; va.Tp = tree->Tp; va.V = vocab;
+    va.tok = tok; va.am = am; va.stop_mask = stop_mask;
+    va.n_accept = n_accept; va.n_accept_raw = n_accept_raw; va.tokens = tokens; va.src_slots = src_slots;
+    launch_verify(va, batch, (hipStream_t)stream);
+    HIP_TRY(hipGetLastError());
+    return SD_OK;
+}

@@ -1,0 +1,303 @@
+// Integer stages of the step: arg-max / top-k over the vocabulary, greedy acceptance with
+// the fragment cut (paper Section III-B), and the commit of the accepted K/V rows.
+#include "sd_internal.h"
+
+#define NEG_INF (-__builtin_inff())
+
+// "better" = larger value, ties to the lower index
+static __device__ inline bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
+
+static __device__ inline void wave_best(float& v, int& i) {
+    for (int o = 32; o > 0; o >>= 1) {
+        float ov = __shfl_xor(v, o);
+        int oi = __shfl_xor(i, o);
+        if (better(ov, oi, v, i)) { v = ov; i = oi; }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Row-wise arg-max over V columns (lowest id on ties). One workgroup per row.
+__global__ __launch_bounds__(256) void k_argmax(const float* __restrict__ logits, int ld, int V, int32_t* __restrict__ am,
+                                                int T, int Tp) {
+    const int b = blockIdx.x / T, j = blockIdx.x % T;
+    const int m = b * Tp + j;
+    const float* row = logits + (size_t)m * ld;
+    float bv = NEG_INF;
+    int bi = 0x7fffffff;
+    for (int i = threadIdx.x * 4; i < V; i += 256 * 4) {
+        float4 f = *(const float4*)(row + i);
+        float vals[4] = {f.x, f.y, f.z, f.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (i + e < V && better(vals[e], i + e, bv, bi)) { bv = vals[e]; bi = i + e; }
+    }
+    wave_best(bv, bi);
+    __shared__ float sv[4];
+    __shared__ int si[4];
+    if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 4; ++w)
+            if (better(sv[w], si[w], bv, bi)) { bv = sv[w]; bi = si[w]; }
+        am[m] = bi;
+    }
+}
+
+void launch_argmax(const float* logits, int ld, int V, int32_t* am, int B, int T, int Tp, hipStream_t s) {
+    hipLaunchKernelGGL(k_argmax, dim3(B * T), dim3(256), 0, s, logits, ld, V, am, T, Tp);
+}
+
+// ------------------------------------------------------------------------------------------
+// Per-row top-k (descending logit, ties to the lower id): k selection rounds; an element is
+// still eligible in a round iff it sorts after the previously selected one.
+__global__ __launch_bounds__(256) void k_topk(const float* __restrict__ logits, int ld, int V, int k,
+                                              int32_t* __restrict__ out, int B, int H, uint32_t seq_mask) {
+    const int r = blockIdx.x;                 // row r = head i * B + sequence b
+    const int i = r / B, b = r % B;
+    if (!((seq_mask >> b) & 1u)) return;
+    const float* row = logits + (size_t)r * ld;
+    __shared__ float sv[4];
+    __shared__ int si[4];
+    __shared__ float lastv;
+    __shared__ int lasti;
+    float pv = __builtin_inff();
+    int pi = -1;
+    for (int round = 0; round < k; ++round) {
+        float bv = NEG_INF;
+        int bi = 0x7fffffff;
+        for (int c = threadIdx.x; c < V; c += 256) {
+            float v = row[c];
+            bool eligible = v < pv || (v == pv && c > pi);
+            if (eligible && better(v, c, bv, bi)) { bv = v; bi = c; }
+        }
+        wave_best(bv, bi);
+        if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            for (int w = 1; w < 4; ++w)
+                if (better(sv[w], si[w], bv, bi)) { bv = sv[w]; bi = si[w]; }
+            lastv = bv;
+            lasti = bi;
+            out[((size_t)b * H + i) * k + round] = bi;
+        }
+        __syncthreads();
+        pv = lastv;
+        pi = lasti;
+    }
+}
+
+void launch_topk(const float* logits, int ld, int V, int k, int32_t* out, int B, int H, uint32_t seq_mask,
+                 hipStream_t s) {
+    hipLaunchKernelGGL(k_topk, dim3(B * H), dim3(256), 0, s, logits, ld, V, k, out, B, H, seq_mask);
+}
+
+// ------------------------------------------------------------------------------------------
+// Greedy acceptance + fragment cut. One workgroup of SD_MAX_TREE threads per sequence, thread
+// j = tree node j.
+//   match[j]  = tok[j] == am[parent[j]]                     (root: true)
+//   ok[j]     = match holds on every node of j's root path  (prefix-closed acceptance): with
+//               the per-wave ballots of `match` gathered into a T-bit mask, ok[j] is one
+//               AND of j's ancestor bitset with the complement of that mask
+//   best      = deepest ok node (lowest index on equal depth), by wavefront reduction
+//   chain     = best's ancestor bitset; node j of the chain sits at chain index depth[j]
+//   cut       = 1 + largest chain index whose token is in the stop set; without any stop
+//               token: whole chain (keep_all) or 1 (keep_one)
+__global__ __launch_bounds__(SD_MAX_TREE) void k_verify(VerifyArgs a) {
+    const int b = blockIdx.x, j = threadIdx.x, T = a.T, H = a.H;
+    const bool valid = j < T;
+    const int32_t* tok = a.tok + (size_t)b * a.src_stride;
+    const int32_t* am = a.am + (size_t)b * a.src_stride;
+    __shared__ unsigned long long matchw[2], bestanc[2];
+    __shared__ int wkey[2], stopmax[2];
+    int dj = 0, tj = 0, pj = -1;
+    unsigned long long anc[2] = {0ull, 0ull};
+    bool match = false;
+    if (valid) {
+        dj = a.depth[j];
+        pj = a.parent[j];
+        tj = tok[j];
+        match = (j == 0) || (tj == am[pj]);
+        for (int i = j, guard = 0; i >= 0 && guard <= H; i = a.parent[i], ++guard) anc[i >> 6] |= 1ull << (i & 63);
+    }
+    unsigned long long bal = __ballot(match);
+    if ((j & 63) == 0) matchw[j >> 6] = bal;
+    __syncthreads();
+    const bool ok = valid && ((anc[0] & ~matchw[0]) | (anc[1] & ~matchw[1])) == 0ull;
+    // deepest accepted node, lowest index on ties: maximise depth * 256 + (255 - j)
+    int key = ok ? dj * 256 + (255 - j) : -1;
+    for (int o = 32; o > 0; o >>= 1) key = max(key, __shfl_xor(key, o));
+    if ((j & 63) == 0) wkey[j >> 6] = key;
+    __syncthreads();
+    key = max(wkey[0], wkey[1]);
+    const int best = 255 - (key & 255);
+    const int n_raw = (key >> 8) + 1;
+    if (j == best) { bestanc[0] = anc[0]; bestanc[1] = anc[1]; }
+    __syncthreads();
+    const bool on_chain = valid && ((bestanc[j >> 6] >> (j & 63)) & 1ull);
+    const bool is_stop = on_chain && tj >= 0 && tj < a.V && ((a.stop_mask[tj >> 5] >> (tj & 31)) & 1u);
+    int sm = is_stop ? dj : -1;
+    for (int o = 32; o > 0; o >>= 1) sm = max(sm, __shfl_xor(sm, o));
+    if ((j & 63) == 0) stopmax[j >> 6] = sm;
+    __syncthreads();
+    sm = max(stopmax[0], stopmax[1]);
+    const int n_acc = sm >= 0 ? sm + 1 : (a.fallback == SD_TRUNC_KEEP_ALL ? n_raw : 1);
+    const int W = H + 1;
+    if (on_chain && dj < n_acc) {
+        a.tokens[(size_t)b * W + dj] = tj;
+        a.src_slots[(size_t)b * W + dj] = j;
+        if (dj == n_acc - 1) {
+            if (a.root_tok) a.root_tok[b] = am[j];
+            if (a.last_row) a.last_row[b] = b * a.Tp + j;
+        }
+    }
+    if (j >= n_acc && j < W) {
+        a.tokens[(size_t)b * W + j] = -1;
+        a.src_slots[(size_t)b * W + j] = -1;
+    }
+    if (j == 0) {
+        a.n_accept[b] = n_acc;
+        if (a.n_accept_raw) a.n_accept_raw[b] = n_raw;
+        if (a.kv_len) {
+            int n = a.kv_len[b];
+            a.n_old[b] = n;
+            a.kv_len[b] = n + n_acc;
+        }
+    }
+}
+
+void launch_verify(const VerifyArgs& a, int B, hipStream_t s) {
+    hipLaunchKernelGGL(k_verify, dim3(B), dim3(SD_MAX_TREE), 0, s, a);
+}
+
+// ------------------------------------------------------------------------------------------
+// Commit the kept nodes' K/V rows: tree-scratch row src_slots[j] -> cache row n_old + j, for
+// every layer and head. A kept node at chain index j was rotated for position n_old + j
+// already (depth = chain index), so this is a pure copy.
+// grid: x = head, y = j (0..H), z = layer * B + b; hd threads.
+__global__ void k_kv_commit(const uint16_t* __restrict__ kt, const uint16_t* __restrict__ vt, uint16_t* __restrict__ kc,
+                            uint16_t* __restrict__ vc, const int32_t* __restrict__ src_slots,
+                            const int32_t* __restrict__ n_accept, const int32_t* __restrict__ n_old, int B, int nh,
+                            int hd, int TB, int cap_blocks, int W, size_t layer_stride_t, size_t layer_stride_c) {
+    const int h = blockIdx.x, j = blockIdx.y, l = blockIdx.z / B, b = blockIdx.z % B, e = threadIdx.x;
+    if (j >= n_accept[b]) return;
+    const int src = src_slots[(size_t)b * W + j];
+    const int dst = n_old[b] + j;
+    const size_t toff = l * layer_stride_t + ((size_t)b * nh + h) * TB * (32 * hd);
+    const size_t coff = l * layer_stride_c + ((size_t)b * nh + h) * cap_blocks * (32 * hd);
+    vc[coff + vblk_index(dst, e, hd)] = vt[toff + vblk_index(src, e, hd)];
+    if (e < hd / 8) {
+        const uint4* s4 = (const uint4*)(kt + toff + kblk_index(src, e * 8, hd));
+        uint4* d4 = (uint4*)(kc + coff + kblk_index(dst, e * 8, hd));
+        *d4 = *s4;
+    }
+}
+
+void launch_kv_commit(const void* kt_all, const void* vt_all, void* kc_all, void* vc_all, const int32_t* src_slots,
+                      const int32_t* n_accept, const int32_t* n_old, int L, int B, int nh, int hd, int TB,
+                      int cap_blocks, int rows, int W, hipStream_t s) {
+    size_t lst = (size_t)B * nh * TB * 32 * hd, lsc = (size_t)B * nh * cap_blocks * 32 * hd;
+    hipLaunchKernelGGL(k_kv_commit, dim3(nh, rows, L * B), dim3(hd), 0, s, (const uint16_t*)kt_all,
+                       (const uint16_t*)vt_all, (uint16_t*)kc_all, (uint16_t*)vc_all, src_slots, n_accept, n_old, B, nh,
+                       hd, TB, cap_blocks, W, lst, lsc);
+}
+
+// ------------------------------------------------------------------------------------------
+// Natural-layout rows [nrows][nh][hd] <-> one sequence's cache blocks of one layer.
+__global__ void k_kv_rows(uint16_t* __restrict__ kc, uint16_t* __restrict__ vc, uint16_t* __restrict__ k_rows,
+                          uint16_t* __restrict__ v_rows, int row0, int nh, int hd, int cap_blocks, int to_cache) {
+    const int r = blockIdx.x, h = blockIdx.y, e = threadIdx.x;
+    const size_t nat = ((size_t)r * nh + h) * hd + e;
+    const size_t hoff = (size_t)h * cap_blocks * (32 * hd);
+    const size_t ki = hoff + kblk_index(row0 + r, e, hd), vi = hoff + vblk_index(row0 + r, e, hd);
+    if (to_cache) {
+        kc[ki] = k_rows[nat];
+        vc[vi] = v_rows[nat];
+    } else {
+        k_rows[nat] = kc[ki];
+        v_rows[nat] = vc[vi];
+    }
+}
+
+void launch_kv_rows(void* kc, void* vc, void* k_rows, void* v_rows, int row0, int nrows, int nh, int hd,
+                    int cap_blocks, int to_cache, hipStream_t s) {
+    hipLaunchKernelGGL(k_kv_rows, dim3(nrows, nh), dim3(hd), 0, s, (uint16_t*)kc, (uint16_t*)vc, (uint16_t*)k_rows,
+                       (uint16_t*)v_rows, row0, nh, hd, cap_blocks, to_cache);
+}
+
+// ------------------------------------------------------------------------------------------
+// Small copies out of the padded internal buffers into the caller's dense outputs.
+__global__ void k_copy_logits(const float* __restrict__ src, int ld, float* __restrict__ dst, int V, int T, int Tp) {
+    const int b = blockIdx.y / T, j = blockIdx.y % T;
+    const float* s = src + (size_t)(b * Tp + j) * ld;
+    float* d = dst + (size_t)(b * T + j) * V;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < V; i += gridDim.x * blockDim.x) d[i] = s[i];
+}
+void launch_copy_logits(const float* src, int ld, float* dst, int V, int B, int T, int Tp, hipStream_t s) {
+    hipLaunchKernelGGL(k_copy_logits, dim3(16, B * T), dim3(256), 0, s, src, ld, dst, V, T, Tp);
+}
+
+__global__ void k_copy_rows_i32(const int32_t* __restrict__ src, int32_t* __restrict__ dst, int B, int T, int Tp) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < B * T) dst[i] = src[(i / T) * Tp + i % T];
+}
+void launch_copy_rows_i32(const int32_t* src, int32_t* dst, int B, int T, int Tp, hipStream_t s) {
+    hipLaunchKernelGGL(k_copy_rows_i32, dim3((B * T + 255) / 256), dim3(256), 0, s, src, dst, B, T, Tp);
+}
+
+// head logits: internal row (i*B + b) -> dst [b][i][V]
+__global__ void k_copy_head_logits(const float* __restrict__ src, int ld, float* __restrict__ dst, int V, int B, int H) {
+    const int r = blockIdx.y, i = r / B, b = r % B;
+    const float* s = src + (size_t)r * ld;
+    float* d = dst + ((size_t)b * H + i) * V;
+    for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < V; c += gridDim.x * blockDim.x) d[c] = s[c];
+}
+void launch_copy_head_logits(const float* src, int ld, float* dst, int V, int B, int H, hipStream_t s) {
+    hipLaunchKernelGGL(k_copy_head_logits, dim3(16, B * H), dim3(256), 0, s, src, ld, dst, V, B, H);
+}
+
+__global__ void k_fill_i32(int32_t* p, int32_t v, int n) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+void launch_fill_i32(int32_t* p, int32_t v, int n, hipStream_t s) {
+    hipLaunchKernelGGL(k_fill_i32, dim3((n + 255) / 256), dim3(256), 0, s, p, v, n);
+}
+
+__global__ void k_copy_i32(const int32_t* __restrict__ src, int32_t* __restrict__ dst, int n) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = src[i];
+}
+void launch_copy_i32(const int32_t* src, int32_t* dst, int n, hipStream_t s) {
+    hipLaunchKernelGGL(k_copy_i32, dim3((n + 255) / 256), dim3(256), 0, s, src, dst, n);
+}
+
+// Prompt chunks commit every row: slots are the identity, the count is the chunk length.
+__global__ void k_prefill_commit_setup(ChainArgs ca, int B, int Tp, int32_t* __restrict__ src_slots,
+                                       int32_t* __restrict__ n_accept, int32_t* __restrict__ n_old,
+                                       int32_t* __restrict__ kv_len, int32_t* __restrict__ last_row) {
+    const int b = blockIdx.x, j = threadIdx.x;
+    if (j < Tp) src_slots[(size_t)b * Tp + j] = j;
+    if (j == 0) {
+        int n = kv_len[b];
+        n_old[b] = n;
+        n_accept[b] = ca.len[b];
+        kv_len[b] = n + ca.len[b];
+        if (ca.len[b] > 0) last_row[b] = b * Tp + ca.len[b] - 1;
+    }
+}
+void launch_prefill_commit_setup(const ChainArgs& ca, int B, int Tp, int32_t* src_slots, int32_t* n_accept,
+                                 int32_t* n_old, int32_t* kv_len, int32_t* last_row, hipStream_t s) {
+    hipLaunchKernelGGL(k_prefill_commit_setup, dim3(B), dim3(SD_MAX_TREE), 0, s, ca, B, Tp, src_slots, n_accept, n_old,
+                       kv_len, last_row);
+}
+
+// root_tok[b] = arg-max at the last prompt row, for the sequences whose prompt just ended
+__global__ void k_pick_root(const int32_t* __restrict__ am, const int32_t* __restrict__ last_row,
+                            int32_t* __restrict__ root_tok, int B, uint32_t seq_mask) {
+    int b = threadIdx.x;
+    if (b < B && ((seq_mask >> b) & 1u)) root_tok[b] = am[last_row[b]];
+}
+void launch_pick_root(const int32_t* am, const int32_t* last_row, int32_t* root_tok, int B, uint32_t seq_mask,
+                      hipStream_t s) {
+    hipLaunchKernelGGL(k_pick_root, dim3(1), dim3(SD_MAX_BATCH), 0, s, am, last_row, root_tok, B, seq_mask);
+}

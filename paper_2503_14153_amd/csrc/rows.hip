@@ -1,0 +1,294 @@
+// Row-wise kernels of the verifying pass: tree assembly + embedding, RMSNorm, rotary embedding
+// with the tree K/V write, SwiGLU, and the draft-head activation. They sit between the
+// weight-streaming GEMMs, reduce the GEMMs' split partial sums, and emit the next GEMM's
+// operand directly in MFMA fragment order (bf16), so no separate conversion pass exists.
+#include "sd_internal.h"
+
+static __device__ inline float bf16_bits_to_float(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+// ------------------------------------------------------------------------------------------
+// Rotary angle table entry, in float64 so that positions up to ~17k lose nothing.
+static __device__ inline float2 rope_cs(int pos, int i, int hd, float theta) {
+    double inv = pow((double)theta, -2.0 * (double)i / (double)hd);
+    double s, c;
+    sincos((double)pos * inv, &s, &c);
+    return make_float2((float)c, (float)s);
+}
+
+static __device__ inline void embed_row(const uint16_t* __restrict__ embed, int tok, int d, float* __restrict__ xrow,
+                                        bool valid) {
+    const uint16_t* e = embed + (size_t)tok * d;
+    for (int i = threadIdx.x; i < d; i += blockDim.x) xrow[i] = valid ? bf16_bits_to_float(e[i]) : 0.f;
+}
+
+// Tree assembly (paper Section III-B): node 0 = the base model's token, node j >= 1 = the
+// candidate number rank[j] of head depth[j]-1; position = committed length + depth; a node
+// attends its ancestors and itself.  One workgroup per row.
+__global__ void k_build_rows_tree(RowTable rt, const int32_t* __restrict__ parent, const int32_t* __restrict__ depth,
+                                  const int32_t* __restrict__ rank, const int32_t* __restrict__ root_tok,
+                                  const int32_t* __restrict__ cand, const int32_t* __restrict__ kv_len, int T, int Tp,
+                                  int H, int topk, int hd, float theta, const uint16_t* __restrict__ embed, int d,
+                                  int V, float* __restrict__ x) {
+    const int m = blockIdx.x, b = m / Tp, j = m % Tp;
+    const bool valid = j < T;
+    int tok = 0, pos = kv_len[b];
+    uint32_t a[SD_ANC_WORDS] = {0, 0, 0, 0};
+    if (valid) {
+        int dj = depth[j];
+        tok = (j == 0) ? root_tok[b] : cand[((size_t)b * H + (dj - 1)) * topk + rank[j]];
+        tok = min(max(tok, 0), V - 1);               // a bad candidate id must not become a bad address
+        pos += dj;
+        for (int i = j, guard = 0; i >= 0 && guard <= H; i = parent[i], ++guard) a[i >> 5] |= 1u << (i & 31);
+    } else {
+        a[j >> 5] |= 1u << (j & 31);
+    }
+    if (threadIdx.x == 0) {
+        rt.tok[m] = tok;
+        rt.pos[m] = pos;
+        for (int w = 0; w < SD_ANC_WORDS; ++w) rt.anc[(size_t)m * SD_ANC_WORDS + w] = a[w];
+    }
+    for (int i = threadIdx.x; i < hd / 2; i += blockDim.x) rt.cs[(size_t)m * (hd / 2) + i] = rope_cs(pos, i, hd, theta);
+    embed_row(embed, tok, d, x + (size_t)m * d, valid);
+}
+
+void launch_build_rows_tree(RowTable rt, const int32_t* parent, const int32_t* depth, const int32_t* rank,
+                            const int32_t* root_tok, const int32_t* cand, const int32_t* kv_len, int B, int T, int Tp,
+                            int H, int topk, int hd, float theta, const void* embed, int d, int V, float* x, hipStream_t s) {
+    hipLaunchKernelGGL(k_build_rows_tree, dim3(B * Tp), dim3(256), 0, s, rt, parent, depth, rank, root_tok, cand,
+                       kv_len, T, Tp, H, topk, hd, theta, (const uint16_t*)embed, d, V, x);
+}
+
+// Prompt chunk as a chain: row j of sequence b is prompt token off[b] + j at position
+// committed length + j and attends rows 0..j of the chunk.
+__global__ void k_build_rows_chain(RowTable rt, const int32_t* __restrict__ tokens, ChainArgs ca,
+                                   const int32_t* __restrict__ kv_len, int Tp, int hd, float theta,
+                                   const uint16_t* __restrict__ embed, int d, int V, float* __restrict__ x) {
+    const int m = blockIdx.x, b = m / Tp, j = m % Tp;
+    const bool valid = j < ca.len[b];
+    int tok = valid ? min(max(tokens[ca.off[b] + j], 0), V - 1) : 0;
+    int pos = kv_len[b] + (valid ? j : 0);
+    uint32_t a[SD_ANC_WORDS] = {0, 0, 0, 0};
+    if (valid) {
+        for (int w = 0; w < SD_ANC_WORDS; ++w) {
+            int hi = j - 32 * w;
+            a[w] = hi >= 31 ? 0xffffffffu : (hi < 0 ? 0u : ((2u << hi) - 1u));
+        }
+    } else {
+        a[j >> 5] |= 1u << (j & 31);
+    }
+    if (threadIdx.x == 0) {
+        rt.tok[m] = tok;
+        rt.pos[m] = pos;
+        for (int w = 0; w < SD_ANC_WORDS; ++w) rt.anc[(size_t)m * SD_ANC_WORDS + w] = a[w];
+    }
+    for (int i = threadIdx.x; i < hd / 2; i += blockDim.x) rt.cs[(size_t)m * (hd / 2) + i] = rope_cs(pos, i, hd, theta);
+    embed_row(embed, tok, d, x + (size_t)m * d, valid);
+}
+
+void launch_build_rows_chain(RowTable rt, const int32_t* tokens, const ChainArgs& ca, const int32_t* kv_len, int B,
+                             int Tp, int hd, float theta, const void* embed, int d, int V, float* x, hipStream_t s) {
+    hipLaunchKernelGGL(k_build_rows_chain, dim3(B * Tp), dim3(256), 0, s, rt, tokens, ca, kv_len, Tp, hd, theta,
+                       (const uint16_t*)embed, d, V, x);
+}
+
+// ------------------------------------------------------------------------------------------
+// x += sum of split partials (residual add of the previous projection), then
+// xn = x * rsqrt(mean(x^2) + eps) * gain, written as bf16 in fragment order.
+// One workgroup (256 threads) per row; a thread owns groups of 8 consecutive columns.
+#define NP_MAXG 4   // d <= 8 * 256 * NP_MAXG = 8192
+__global__ __launch_bounds__(256) void k_norm_pack(float* __restrict__ x, const float* __restrict__ part, int nsplit,
+                                                   size_t split_stride, int ldp, const uint16_t* __restrict__ gain,
+                                                   float eps, bf16x8* __restrict__ xn, float* __restrict__ hf, int d,
+                                                   int MB, const int32_t* __restrict__ gather) {
+    const int m = blockIdx.x;
+    const int src = gather ? gather[m] : m;
+    float* xr = x + (size_t)src * d;
+    const int ngroups = d >> 3;
+    float v[NP_MAXG][8];
+    float ss = 0.f;
+#pragma unroll
+    for (int gi = 0; gi < NP_MAXG; ++gi) {
+        int grp = gi * 256 + threadIdx.x;
+        if (grp < ngroups) {
+            float4 a = *(const float4*)(xr + grp * 8), c = *(const float4*)(xr + grp * 8 + 4);
+            float t[8] = {a.x, a.y, a.z, a.w, c.x, c.y, c.z, c.w};
+            for (int sp = 0; sp < nsplit; ++sp) {
+                const float* p = part + (size_t)sp * split_stride + (size_t)src * ldp + grp * 8;
+                float4 pa = *(const float4*)p, pc = *(const float4*)(p + 4);
+                t[0] += pa.x; t[1] += pa.y; t[2] += pa.z; t[3] += pa.w;
+                t[4] += pc.x; t[5] += pc.y; t[6] += pc.z; t[7] += pc.w;
+            }
+            if (nsplit > 0) {
+                *(float4*)(xr + grp * 8) = make_float4(t[0], t[1], t[2], t[3]);
+                *(float4*)(xr + grp * 8 + 4) = make_float4(t[4], t[5], t[6], t[7]);
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) { v[gi][i] = t[i]; ss += t[i] * t[i]; }
+        }
+    }
+    __shared__ float red[4];
+    for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    ss = red[0] + red[1] + red[2] + red[3];
+    const float r = rsqrtf(ss / (float)d + eps);
+#pragma unroll
+    for (int gi = 0; gi < NP_MAXG; ++gi) {
+        int grp = gi * 256 + threadIdx.x;
+        if (grp < ngroups) {
+            bf16x8 hi, lo;
+            float f[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) f[i] = v[gi][i] * r * bf16_bits_to_float(gain[grp * 8 + i]);
+            split_hilo(f, hi, lo);
+            const size_t u = xpack_index(m, grp * 8, MB) >> 3;
+            xn[u] = hi;
+            xn[u + XPART / 8] = lo;
+            if (hf) {
+                *(float4*)(hf + (size_t)m * d + grp * 8) = make_float4(f[0], f[1], f[2], f[3]);
+                *(float4*)(hf + (size_t)m * d + grp * 8 + 4) = make_float4(f[4], f[5], f[6], f[7]);
+            }
+        }
+    }
+}
+
+void launch_norm_pack(float* x, const float* part, int nsplit, size_t split_stride, int ldp, const void* gain,
+                      float eps, void* xn_packed, float* hf_out, int M, int d, int MB, const int32_t* gather,
+                      hipStream_t s) {
+    hipLaunchKernelGGL(k_norm_pack, dim3(M), dim3(256), 0, s, x, part, nsplit, split_stride, ldp,
+                       (const uint16_t*)gain, eps, (bf16x8*)xn_packed, hf_out, d, MB, gather);
+}
+
+// ------------------------------------------------------------------------------------------
+// Sum the QKV partials, rotate q and k to the row's position, and write q (fragment order),
+// k and v (tree scratch, block layouts). Thread (m, h, a) owns dims [8a, 8a+8) and their
+// rotary partners [hd/2 + 8a, +8).
+__global__ void k_rope_kv(const float* __restrict__ part, int nsplit, size_t split_stride, int ldp, RowTable rt,
+                          bf16x8* __restrict__ qp, uint16_t* __restrict__ kt, uint16_t* __restrict__ vt, int B, int Tp,
+                          int nh, int hd) {
+    const int na = hd / 16;
+    int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= B * Tp * nh * na) return;
+    const int a = idx % na, h = (idx / na) % nh, m = idx / (na * nh);
+    const int b = m / Tp, t = m % Tp, d = nh * hd, half = hd / 2;
+    float q1[8], q2[8], k1[8], k2[8], v1[8], v2[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) q1[i] = q2[i] = k1[i] = k2[i] = v1[i] = v2[i] = 0.f;
+    for (int sp = 0; sp < nsplit; ++sp) {
+        const float* p = part + (size_t)sp * split_stride + (size_t)m * ldp + h * hd + a * 8;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            q1[i] += p[i];            q2[i] += p[half + i];
+            k1[i] += p[d + i];        k2[i] += p[d + half + i];
+            v1[i] += p[2 * d + i];    v2[i] += p[2 * d + half + i];
+        }
+    }
+    bf16x8 ko1, ko2, qh1, ql1, qh2, ql2;
+    float r1[8], r2[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        float2 cs = rt.cs[(size_t)m * half + a * 8 + i];
+        r1[i] = q1[i] * cs.x - q2[i] * cs.y;
+        r2[i] = q2[i] * cs.x + q1[i] * cs.y;
+        ko1[i] = (__bf16)(k1[i] * cs.x - k2[i] * cs.y);
+        ko2[i] = (__bf16)(k2[i] * cs.x + k1[i] * cs.y);
+    }
+    split_hilo(r1, qh1, ql1);
+    split_hilo(r2, qh2, ql2);
+    // q: two-term expansion in fragment order; k, v: bf16, the cache's storage type
+    const int TB = Tp / 32;
+    size_t head_off = ((size_t)b * nh + h) * TB * (32 * hd);
+    size_t i1 = head_off + kblk_index(t, a * 8, hd), i2 = head_off + kblk_index(t, half + a * 8, hd);
+    size_t q1i = 2 * head_off + qblk_index(t, a * 8, hd), q2i = 2 * head_off + qblk_index(t, half + a * 8, hd);
+    qp[q1i >> 3] = qh1;
+    qp[(q1i >> 3) + 64] = ql1;
+    qp[q2i >> 3] = qh2;
+    qp[(q2i >> 3) + 64] = ql2;
+    ((bf16x8*)kt)[i1 >> 3] = ko1;
+    ((bf16x8*)kt)[i2 >> 3] = ko2;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        __bf16 w1 = (__bf16)v1[i], w2 = (__bf16)v2[i];
+        vt[head_off + vblk_index(t, a * 8 + i, hd)] = __builtin_bit_cast(uint16_t, w1);
+        vt[head_off + vblk_index(t, half + a * 8 + i, hd)] = __builtin_bit_cast(uint16_t, w2);
+    }
+}
+
+void launch_rope_kv(const float* part, int nsplit, size_t split_stride, int ldp, RowTable rt, void* q_packed, void* kt,
+                    void* vt, int B, int Tp, int nh, int hd, hipStream_t s) {
+    int total = B * Tp * nh * (hd / 16);
+    hipLaunchKernelGGL(k_rope_kv, dim3((total + 255) / 256), dim3(256), 0, s, part, nsplit, split_stride, ldp, rt,
+                       (bf16x8*)q_packed, (uint16_t*)kt, (uint16_t*)vt, B, Tp, nh, hd);
+}
+
+// ------------------------------------------------------------------------------------------
+// act = silu(gate) * up from the gate/up partials (gate in columns [0,F), up in [Fpad, Fpad+F)).
+__global__ void k_swiglu_pack(const float* __restrict__ part, int nsplit, size_t split_stride, int ldp, int F, int Fpad,
+                              bf16x8* __restrict__ act, int M, int MB) {
+    int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    int ng = F / 8;
+    if (idx >= M * ng) return;
+    int grp = idx % ng, m = idx / ng;
+    float gsum[8] = {0, 0, 0, 0, 0, 0, 0, 0}, usum[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int sp = 0; sp < nsplit; ++sp) {
+        const float* p = part + (size_t)sp * split_stride + (size_t)m * ldp + grp * 8;
+        float4 a = *(const float4*)p, c = *(const float4*)(p + 4);
+        float4 ua = *(const float4*)(p + Fpad), uc = *(const float4*)(p + Fpad + 4);
+        gsum[0] += a.x; gsum[1] += a.y; gsum[2] += a.z; gsum[3] += a.w;
+        gsum[4] += c.x; gsum[5] += c.y; gsum[6] += c.z; gsum[7] += c.w;
+        usum[0] += ua.x; usum[1] += ua.y; usum[2] += ua.z; usum[3] += ua.w;
+        usum[4] += uc.x; usum[5] += uc.y; usum[6] += uc.z; usum[7] += uc.w;
+    }
+    bf16x8 hi, lo;
+    float f[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) f[i] = gsum[i] / (1.f + __expf(-gsum[i])) * usum[i];
+    split_hilo(f, hi, lo);
+    const size_t u = xpack_index(m, grp * 8, MB) >> 3;
+    act[u] = hi;
+    act[u + XPART / 8] = lo;
+}
+
+void launch_swiglu_pack(const float* part, int nsplit, size_t split_stride, int ldp, int F, int Fpad, void* act_packed,
+                        int M, int MB, hipStream_t s) {
+    int total = M * (F / 8);
+    hipLaunchKernelGGL(k_swiglu_pack, dim3((total + 255) / 256), dim3(256), 0, s, part, nsplit, split_stride, ldp, F,
+                       Fpad, (bf16x8*)act_packed, M, MB);
+}
+
+// ------------------------------------------------------------------------------------------
+// Draft heads, activation stage: row (i, b) = h_b + silu(W_i h_b + bias_i), packed as the
+// operand of the shared LM-head GEMM. part columns [i*d, (i+1)*d) hold W_i h_b for row b.
+__global__ void k_medusa_act(const float* __restrict__ part, int nsplit, size_t split_stride, int ldp,
+                             const float* __restrict__ h_rows, MedusaBias bias, int B, int H, int d,
+                             bf16x8* __restrict__ xp, int MB) {
+    int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    int ng = d / 8;
+    if (idx >= H * B * ng) return;
+    int grp = idx % ng, b = (idx / ng) % B, i = idx / (ng * B);
+    float z[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int sp = 0; sp < nsplit; ++sp) {
+        const float* p = part + (size_t)sp * split_stride + (size_t)b * ldp + (size_t)i * d + grp * 8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) z[e] += p[e];
+    }
+    const uint16_t* bi = bias.p[i];
+    bf16x8 hi, lo;
+    float f[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        float zz = z[e] + (bi ? bf16_bits_to_float(bi[grp * 8 + e]) : 0.f);
+        f[e] = h_rows[(size_t)b * d + grp * 8 + e] + zz / (1.f + __expf(-zz));
+    }
+    split_hilo(f, hi, lo);
+    const size_t u = xpack_index(i * B + b, grp * 8, MB) >> 3;
+    xp[u] = hi;
+    xp[u + XPART / 8] = lo;
+}
+
+void launch_medusa_act(const float* part, int nsplit, size_t split_stride, int ldp, const float* h_rows,
+                       const MedusaBias& bias, int B, int H, int d, void* x_packed, int MB, hipStream_t s) {
+    int total = H * B * (d / 8);
+    hipLaunchKernelGGL(k_medusa_act, dim3((total + 255) / 256), dim3(256), 0, s, part, nsplit, split_stride, ldp,
+                       h_rows, bias, B, H, d, (bf16x8*)x_packed, MB);
+}

@@ -1,0 +1,137 @@
+// Internal declarations shared by the HIP translation units of libspecdec (gfx950 only).
+//
+// Memory layouts (all "fragment" layouts are chosen so that one wave64 load instruction of
+// 16 bytes per lane fetches one contiguous 1 KiB MFMA operand of v_mfma_f32_32x32x16_bf16:
+// lane l supplies row/column (l % 32) and the eight contraction elements g*8 .. g*8+7 with
+// g = l / 32):
+//
+//   packed activation  X[kb][mb][part][lane][8]  element (row m, col k): kb = k/16, mb = m/32,
+//                                            lane = m%32 + 32*((k/8)&1), slot = k%8;
+//                                            part 0 = bf16(x), part 1 = bf16(x - part 0): the
+//                                            activations enter the MFMAs as a two-term bf16
+//                                            expansion (about 16 mantissa bits), see gemm.hip
+//   packed weight      W[nb][kb][lane][8]    element (out n, in k):  nb = n/32, kb = k/16,
+//                                            lane = n%32 + 32*((k/8)&1), slot = k%8
+//   key block (32 rows of one head)          K[kk][lane][8]: row c, dim e: kk = e/16,
+//                                            lane = c%32 + 32*((e/8)&1), slot = e%8
+//   value block (32 rows of one head)        V[p][eb][lane][8]: row c, dim e: p = (c%32)/16,
+//                                            eb = e/32, lane = e%32 + 32*((c/4)&1),
+//                                            slot = 4*((c/8)&1) + c%4
+//     (the value rows are permuted inside a block so that the softmax probabilities, as they
+//      come out of the QK^T accumulator, are already the B operand of the PV product)
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/specdec.h"
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+#ifdef __HIPCC__
+// two-term bf16 expansion of eight floats: hi = bf16(f), lo = bf16(f - hi)
+static __device__ inline void split_hilo(const float (&f)[8], bf16x8& hi, bf16x8& lo) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        __bf16 h = (__bf16)f[i];
+        hi[i] = h;
+        lo[i] = (__bf16)(f[i] - (float)h);
+    }
+}
+#endif
+
+#define SD_MAX_TREE 128
+#define SD_ANC_WORDS 4
+
+// element index of (row m, col k) in part 0 of a packed activation; part 1 is XPART further
+#define XPART 512
+static __host__ __device__ inline size_t xpack_index(int m, int k, int MB) {
+    int kb = k >> 4, g = (k >> 3) & 1, s = k & 7, mb = m >> 5, r = m & 31;
+    return ((((size_t)kb * MB + mb) * 2 * 64) + (size_t)(r + 32 * g)) * 8 + s;
+}
+// same for a query block: Q[kk][part][lane][8] per 32 queries of one head
+static __host__ __device__ inline size_t qblk_index(int t, int e, int HD) {
+    int blk = t >> 5, r = t & 31, kk = e >> 4, g = (e >> 3) & 1, s = e & 7;
+    return (size_t)blk * (64 * HD) + ((size_t)(kk * 2 * 64 + r + 32 * g)) * 8 + s;
+}
+// offset (in elements) of (row c, dim e) inside a head's key blocks; HD = head_dim
+static __host__ __device__ inline size_t kblk_index(int c, int e, int HD) {
+    int blk = c >> 5, r = c & 31, kk = e >> 4, g = (e >> 3) & 1, s = e & 7;
+    return (size_t)blk * (32 * HD) + ((size_t)(kk * 64 + r + 32 * g)) * 8 + s;
+}
+static __host__ __device__ inline size_t vblk_index(int c, int e, int HD) {
+    int blk = c >> 5, cc = c & 31, p = cc >> 4, g = (cc >> 2) & 1, s = ((cc >> 3) & 1) * 4 + (cc & 3);
+    int eb = e >> 5, er = e & 31;
+    return (size_t)blk * (32 * HD) + ((size_t)((p * (HD / 32) + eb) * 64 + er + 32 * g)) * 8 + s;
+}
+
+// ---- per-call row table (device) -----------------------------------------------------------
+struct RowTable {
+    int32_t* tok;      // [M] token id of every row (0 for padding rows)
+    int32_t* pos;      // [M] position
+    uint32_t* anc;     // [M][SD_ANC_WORDS] bit i set: row may attend tree row i of its sequence
+    float2* cs;        // [M][head_dim/2] (cos, sin) of the rotary angle
+};
+
+#define SD_MAX_BATCH 32
+#define SD_MAX_MEDUSA 15
+struct ChainArgs { int32_t off[SD_MAX_BATCH]; int32_t len[SD_MAX_BATCH]; };
+struct MedusaBias { const uint16_t* p[SD_MAX_MEDUSA + 1]; };
+struct VerifyArgs {
+    const int32_t *parent, *depth;      // device tree tables [T]
+    int T, H, fallback, src_stride, Tp, V;
+    const int32_t *tok, *am;            // [B][src_stride]
+    const uint32_t* stop_mask;
+    int32_t *n_accept, *n_accept_raw, *tokens, *src_slots;   // outputs, [B] / [B][H+1]
+    int32_t *kv_len, *n_old, *root_tok, *last_row;           // carried state, may be NULL
+};
+
+// ---- launchers (defined in the kernel translation units) ----------------------------------
+// All take a stream; all sizes have been validated by the caller.
+void launch_pack_weight(const void* src, void* dst, int N, int K, int nb_offset, int KB, hipStream_t s);
+void launch_gemm(const void* Xp, const void* Wp, float* out, int MB, int KB, int NB, int ldo,
+                 int nsplit, size_t split_stride, hipStream_t s);
+int gemm_choose_split(int MB, int KB, int NB);
+
+void launch_build_rows_tree(RowTable rt, const int32_t* parent, const int32_t* depth, const int32_t* rank,
+                            const int32_t* root_tok, const int32_t* cand, const int32_t* kv_len,
+                            int B, int T, int Tp, int H, int topk, int hd, float theta,
+                            const void* embed, int d, int V, float* x, hipStream_t s);
+void launch_build_rows_chain(RowTable rt, const int32_t* tokens, const ChainArgs& ca, const int32_t* kv_len,
+                             int B, int Tp, int hd, float theta, const void* embed, int d, int V, float* x,
+                             hipStream_t s);
+void launch_norm_pack(float* x, const float* part, int nsplit, size_t split_stride, int ldp,
+                      const void* gain, float eps, void* xn_packed, float* hf_out,
+                      int M, int d, int MB, const int32_t* gather, hipStream_t s);
+void launch_rope_kv(const float* part, int nsplit, size_t split_stride, int ldp, RowTable rt,
+                    void* q_packed, void* kt, void* vt, int B, int Tp, int nh, int hd, hipStream_t s);
+void launch_tree_attn(const void* q_packed, const void* kc, const void* vc, const void* kt, const void* vt,
+                      const int32_t* kv_len, const uint32_t* anc, float* opart, float2* mlpart,
+                      int B, int nh, int hd, int Tp, int cap_blocks, int nchunks, int blocks_per_chunk,
+                      hipStream_t s);
+void launch_attn_merge(const float* opart, const float2* mlpart, void* x_packed, int B, int nh, int hd,
+                       int Tp, int nparts, int MB, hipStream_t s);
+void launch_swiglu_pack(const float* part, int nsplit, size_t split_stride, int ldp, int F, int Fpad,
+                        void* act_packed, int M, int MB, hipStream_t s);
+void launch_medusa_act(const float* part, int nsplit, size_t split_stride, int ldp, const float* h_rows,
+                       const MedusaBias& bias, int B, int H, int d, void* x_packed, int MB, hipStream_t s);
+void launch_argmax(const float* logits, int ld, int V, int32_t* am, int B, int T, int Tp, hipStream_t s);
+void launch_topk(const float* logits, int ld, int V, int k, int32_t* out, int B, int H, uint32_t seq_mask,
+                 hipStream_t s);
+void launch_pick_root(const int32_t* am, const int32_t* last_row, int32_t* root_tok, int B, uint32_t seq_mask,
+                      hipStream_t s);
+void launch_verify(const VerifyArgs& a, int B, hipStream_t s);
+void launch_kv_commit(const void* kt_all, const void* vt_all, void* kc_all, void* vc_all,
+                      const int32_t* src_slots, const int32_t* n_accept, const int32_t* n_old,
+                      int L, int B, int nh, int hd, int TB, int cap_blocks, int rows, int W, hipStream_t s);
+void launch_kv_rows(void* kc, void* vc, void* k_rows, void* v_rows, int row0, int nrows, int nh, int hd,
+                    int cap_blocks, int to_cache, hipStream_t s);
+void launch_copy_logits(const float* src, int ld, float* dst, int V, int B, int T, int Tp, hipStream_t s);
+void launch_copy_rows_i32(const int32_t* src, int32_t* dst, int B, int T, int Tp, hipStream_t s);
+void launch_copy_head_logits(const float* src, int ld, float* dst, int V, int B, int H, hipStream_t s);
+void launch_fill_i32(int32_t* p, int32_t v, int n, hipStream_t s);
+void launch_copy_i32(const int32_t* src, int32_t* dst, int n, hipStream_t s);
+void launch_prefill_commit_setup(const ChainArgs& ca, int B, int Tp, int32_t* src_slots, int32_t* n_accept,
+                                 int32_t* n_old, int32_t* kv_len, int32_t* last_row, hipStream_t s);

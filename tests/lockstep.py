@@ -1,0 +1,126 @@
+"""Lock-step comparison of the HIP path with the CPU oracle (helper for the GPU parity tests).
+
+Both sides get the same committed history and the same draft state at every step; each keeps
+its own KV cache. Floating-point outputs are compared within the stated tolerances; integer
+outputs must be bit-exact given the same arg-max, and the arg-max itself may differ only where
+the oracle's top-2 logit margin is below 1e-2 (counted and reported; the cache and draft state
+are then resynchronised from the oracle).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+
+import numpy as np
+import torch
+
+import paper_2503_14153_amd as sd
+from oracle import specdec_oracle as orc
+
+LOGIT_MAX_ABS = 2e-2      # max-abs error of the base logits
+LOGIT_REL = 1e-2          # Frobenius-norm relative error of the base logits
+NEAR_TIE = 1e-2           # oracle top-2 margin below which an arg-max flip is tolerated
+
+
+def weights_to_f64(weights: dict) -> dict:
+    """Widen once, so the oracle does not re-convert every matrix at every call."""
+    return {k: v.detach().cpu().double().numpy() for k, v in weights.items()}
+
+
+@dataclass
+class Report:
+    steps: int = 0
+    max_abs: float = 0.0
+    max_rel: float = 0.0
+    near_tie_flips: int = 0
+    cand_near_ties: int = 0
+    accepted: list = field(default_factory=list)
+    kv_max_abs: float = 0.0
+    head_max_abs: float = 0.0
+
+
+def check_logits(got: np.ndarray, want: np.ndarray, rep: Report, max_abs=LOGIT_MAX_ABS, rel=LOGIT_REL):
+    err = float(np.abs(got - want).max())
+    r = float(np.linalg.norm(got - want) / np.linalg.norm(want))
+    rep.max_abs, rep.max_rel = max(rep.max_abs, err), max(rep.max_rel, r)
+    assert err <= max_abs, f"logits max-abs error {err:.4g} > {max_abs}"
+    assert r <= rel, f"logits relative error {r:.4g} > {rel}"
+
+
+def check_cand(got: np.ndarray, want: np.ndarray, head_logits: np.ndarray, rep: Report):
+    """Top-k candidates: identical, except where the oracle's logits are within NEAR_TIE."""
+    for i in range(want.shape[0]):
+        for r in range(want.shape[1]):
+            if got[i, r] != want[i, r]:
+                gap = abs(head_logits[i, want[i, r]] - head_logits[i, got[i, r]])
+                assert gap < NEAR_TIE, f"head {i} rank {r}: got id {got[i, r]}, want {want[i, r]}, gap {gap:.4g}"
+                rep.cand_near_ties += 1
+
+
+def compare_kv_rows(kv: sd.KVCache, st: orc.DecodeState, shape, row0: int, row1: int, rep: Report, tol: float):
+    for layer in range(shape.n_layers):
+        k, v = kv.read_rows(layer, 0, row0, row1 - row0)
+        dk = np.abs(k.float().cpu().numpy() - st.kv.k[layer, row0:row1]).max()
+        dv = np.abs(v.float().cpu().numpy() - st.kv.v[layer, row0:row1]).max()
+        rep.kv_max_abs = max(rep.kv_max_abs, float(dk), float(dv))
+        assert dk <= tol and dv <= tol, f"layer {layer}: committed K/V rows differ by {max(dk, dv):.4g}"
+
+
+def resync_kv(kv: sd.KVCache, st: orc.DecodeState, shape, row0: int):
+    """Overwrite the GPU cache rows from row0 on with the oracle's and adopt its length."""
+    n = st.kv.n
+    if n > row0:
+        for layer in range(shape.n_layers):
+            k = torch.from_numpy(st.kv.k[layer, row0:n]).to(torch.bfloat16).cuda().contiguous()
+            v = torch.from_numpy(st.kv.v[layer, row0:n]).to(torch.bfloat16).cuda().contiguous()
+            kv.write_rows(layer, 0, row0, k, v)
+    kv.set_len([n])
+
+
+def lockstep_spec(model: sd.Model, kv: sd.KVCache, tree: sd.Tree, tree_np, stop_np: np.ndarray,
+                  stop_words: torch.Tensor, w64: dict, shape, st: orc.DecodeState, n_steps: int, fallback: str,
+                  cand_fn=None, kv_tol: float = 0.05, rep: Report | None = None) -> Report:
+    """Run n_steps speculative steps on both sides (batch 1). `cand_fn(st)` may edit the draft."""
+    rep = rep or Report()
+    parent, depth, rank = tree_np
+    for _ in range(n_steps):
+        cand = np.asarray(st.cand if cand_fn is None else cand_fn(st), dtype=np.int32)
+        n_old = st.kv.n
+        kv.set_draft([st.root_tok], cand[None])
+        out = sd.spec_step(model, kv, tree, stop_words, want_logits=True, want_argmax=True, want_head_logits=True)
+        rec = orc.spec_step(w64, shape, st, tree_np, stop_np, fallback, cand_override=cand)
+        torch.cuda.synchronize()
+        check_logits(out.logits[0].cpu().numpy().astype(np.float64), rec.logits, rep)
+        am = out.argmax[0].cpu().numpy()
+        flips = np.nonzero(am != rec.am)[0]
+        for j in flips:
+            assert rec.margin[j] < NEAR_TIE, f"arg-max differs at node {j} with oracle margin {rec.margin[j]:.4g}"
+        rep.near_tie_flips += len(flips)
+        # integer outputs: bit-exact against the oracle's rule applied to the arg-max the GPU saw
+        ok, chain = orc.greedy_accept(rec.tok, am, parent, depth)
+        n_acc = orc.fragment_cut([rec.tok[c] for c in chain], stop_np, fallback)
+        W = shape.n_medusa + 1
+        want_tok = np.full(W, -1, np.int32)
+        want_slot = np.full(W, -1, np.int32)
+        want_tok[:n_acc] = [rec.tok[c] for c in chain[:n_acc]]
+        want_slot[:n_acc] = chain[:n_acc]
+        assert int(out.n_accept[0]) == n_acc and int(out.n_accept_raw[0]) == len(chain)
+        assert np.array_equal(out.tokens[0].cpu().numpy(), want_tok)
+        assert np.array_equal(out.src_slots[0].cpu().numpy(), want_slot)
+        assert kv.len() == [n_old + n_acc]
+        rep.accepted.append(n_acc)
+        same_path = n_acc == rec.n_accept and chain[:n_acc] == list(rec.src_slots)
+        if same_path:
+            compare_kv_rows(kv, st, shape, n_old, n_old + n_acc, rep, kv_tol)
+            root, gcand = kv.get_draft()
+            last = rec.src_slots[-1]
+            if am[last] == rec.am[last]:
+                assert int(root[0]) == rec.next_root
+            hl = out.head_logits[0].cpu().numpy().astype(np.float64)
+            herr = float(np.abs(hl - rec.head_logits).max())
+            rep.head_max_abs = max(rep.head_max_abs, herr)
+            assert herr <= 2 * LOGIT_MAX_ABS, f"draft-head logits differ by {herr:.4g}"
+            check_cand(gcand[0].cpu().numpy(), rec.next_cand, rec.head_logits, rep)
+        else:
+            resync_kv(kv, st, shape, n_old)
+        rep.steps += 1
+    return rep

@@ -181,3 +181,27 @@ def test_medusa_head_block_matches_torch_formulation():
     cand = orc.medusa_candidates(w, shape, h.numpy())
     assert cand.shape == (shape.n_medusa, shape.topk)
     assert list(cand[1]) == list(torch.topk(torch.from_numpy(got[1]), shape.topk).indices.numpy())
+
+
+def test_kv_storage_rounding_is_torch_bfloat16_and_only_for_bf16():
+    a = RNG.standard_normal((7, 3, 16)) * np.array([1e-3, 1.0, 300.0])[None, :, None]
+    want = torch.from_numpy(a).float().bfloat16().double().numpy()
+    assert np.array_equal(orc.kv_storage(a, "bf16"), want)
+    assert orc.kv_storage(a, "f32") is a
+    ties = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8])          # exactly between two bf16 numbers
+    assert np.array_equal(orc.kv_storage(ties, "bf16"), [1.0, 1.0 + 2.0 ** -6])
+
+
+def test_bf16_storage_keeps_the_cache_path_consistent():
+    """With bf16 K/V storage the new rows a forward returns are exactly what attention used:
+    one pass over a prompt equals two passes through the committed (rounded) cache."""
+    import dataclasses
+    shape = dataclasses.replace(wl.preset("tiny").model, dtype="bf16")
+    w = wl.make_weights(shape)
+    prompt = wl.zipf_prompt(shape.vocab, 20)
+    kv = orc.KVCache.empty(shape, 32)
+    full, _, k_all, v_all = orc.forward_rows(w, shape, prompt, np.arange(20), np.tril(np.ones((20, 20), bool)), kv)
+    assert np.array_equal(k_all, orc.kv_storage(k_all, "bf16"))
+    kv.k[:, :12], kv.v[:, :12], kv.n = k_all[:, :12], v_all[:, :12], 12
+    part, _, _, _ = orc.forward_rows(w, shape, prompt[12:], np.arange(12, 20), np.tril(np.ones((8, 8), bool)), kv)
+    assert np.abs(part - full[12:]).max() < 1e-11
