@@ -1,0 +1,237 @@
+#!/usr/bin/env python3
+"""Benchmark of the speculative-decoding step on one MI355X.
+
+A "step" is one pass of the whole hot path (tree assembly, embedding, 32 decoder layers with
+tree-masked attention over the KV cache, LM head, greedy acceptance with the fragment cut, KV
+commit, draft heads + top-k) for one sequence with a 64-node candidate tree, on the
+CodeLlama-7b-shaped synthetic workload. Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+Timed loop = what a decoding loop does: launch a step, read back the committed length and the
+emitted tokens, choose the next step's planted draft candidates. Inputs (weights, cache,
+candidate table, stop mask) are resident in HBM before the timed region starts.
+"""
+from __future__ import annotations
+
+import argparse
+import dataclasses
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+# HBM bytes per GEMM launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, calibrated
+# against a copy kernel of known size (see profiles/); None until measured for this build.
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = None
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="7b", choices=["7b", "7b-long", "13b", "tiny"])
+    ap.add_argument("--layers", type=int, default=None, help="cut the depth (debugging only; result is labelled)")
+    ap.add_argument("--draft", default="planted", choices=["planted", "random"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-steps", type=int, default=32)
+    return ap.parse_args()
+
+
+def weight_bytes(m) -> float:
+    d, F, V, L, H = m.d_model, m.d_ffn, m.vocab, m.n_layers, m.n_medusa
+    # every projection once + LM head twice (tree rows, then the draft-head rows) + draft heads
+    return 2.0 * (L * (4 * d * d + 3 * d * F) + 2 * V * d + H * d * d)
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus {args.gpus} is not "
+              f"supported, run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import workload as wl
+    import paper_2503_14153_amd as sd
+
+    sd.lib()
+    torch.cuda.set_device(0)
+    W = wl.preset(args.workload, args.layers)
+    shape = dataclasses.replace(W.model, dtype="bf16")
+    T, H, k = W.tree_nodes, shape.n_medusa, shape.topk
+    prompt_len = W.prompt_len if args.workload != "7b-long" else W.prompt_len
+
+    # ---------------------------------------------------------------- inputs, resident in HBM
+    weights = wl.make_weights(shape, device="cuda")
+    cpu_keep = None
+    if not args.no_cpu_baseline:
+        names = ["embed", "lm_head", "final_norm"] + [f"medusa{i}.{x}" for i in range(H) for x in "wb"]
+        names += [n for n in weights if n.startswith("l0.") or n.startswith("l1.")]
+        cpu_keep = {n: weights[n].cpu() for n in names}
+    model = sd.Model(shape, weights, max_rows=max(64, ((T + 31) // 32) * 32))
+    del weights
+    torch.cuda.empty_cache()
+    kv = sd.KVCache(model, 1, W.kv_cap)
+    prompt = wl.zipf_prompt(shape.vocab, prompt_len)
+    stop = wl.stop_set(shape.vocab, W.stop_frac)
+    stop_words = torch.from_numpy(wl.pack_mask_words(stop).view(np.int32)).cuda()
+    tree_np = wl.default_tree(T, H, k)
+    tree = sd.Tree(*tree_np, H, k)
+
+    t0 = time.perf_counter()
+    sd.prefill(model, kv, torch.from_numpy(prompt).cuda(), [prompt_len])
+    torch.cuda.synchronize()
+    prefill_s = time.perf_counter() - t0
+    root0, cand0 = kv.get_draft()
+    root0, cand0 = root0.clone(), cand0.clone()
+
+    # ---------------------------------------------------------------- plain greedy on the same GPU
+    max_emit = W.kv_cap - prompt_len - (H + 1) - 1
+    n_truth = min(max_emit, (args.steps + args.warmup) * (H + 1) + H + 2)
+    gout = [sd.greedy_step(model, kv) for _ in range(4)]            # warm-up
+    torch.cuda.synchronize()
+    n_timed = min(128, n_truth - 4)
+    t0 = time.perf_counter()
+    for _ in range(n_timed):
+        gout.append(sd.greedy_step(model, kv))
+        kv.len()
+    greedy_s = time.perf_counter() - t0
+    for _ in range(n_truth - 4 - n_timed):
+        gout.append(sd.greedy_step(model, kv))
+    torch.cuda.synchronize()
+    truth = torch.stack([o.tokens[0, 0] for o in gout]).cpu().numpy()
+    del gout
+
+    # ---------------------------------------------------------------- planted-draft table
+    rng = np.random.default_rng(wl.SEEDS["force"])
+    p_depth = (0.9, 0.85, 0.8, 0.75, 0.7)[:H]
+    n_table = len(truth) - H
+    table = np.zeros((n_table, H, k), np.int32)
+    for e in range(n_table):
+        filler = (truth[e + 1: e + 1 + H, None] + 1 + np.arange(k)[None, :]) % shape.vocab   # never the true token
+        table[e] = wl.plant_drafts(filler, truth[e + 1: e + 1 + H], p_depth, rng) if args.draft == "planted" else filler
+    table_dev = torch.from_numpy(table).cuda()
+
+    def reset():
+        kv.set_len([prompt_len])
+        kv.set_draft(root0, cand0)
+
+    out = sd.StepOutput(
+        torch.empty(1, dtype=torch.int32, device="cuda"), torch.empty((1, H + 1), dtype=torch.int32, device="cuda"),
+        torch.empty((1, H + 1), dtype=torch.int32, device="cuda"), torch.empty(1, dtype=torch.int32, device="cuda"))
+    tok_host = torch.empty((1, H + 1), dtype=torch.int32).pin_memory()
+    state = {"e": 0, "emitted": 0, "diverged": 0, "resets": 0}
+
+    def run_steps(n):
+        for _ in range(n):
+            e = state["e"]
+            if e >= n_table or prompt_len + e + H + 1 > W.kv_cap - 1:
+                reset()
+                state["resets"] += 1
+                e = state["e"] = 0
+            sd.spec_step(model, kv, tree, stop_words, forced_cand=table_dev[e], out=out)
+            tok_host.copy_(out.tokens, non_blocking=True)
+            n_now = kv.len()[0]                     # synchronises the stream
+            n_acc = n_now - prompt_len - e
+            if not np.array_equal(tok_host[0, :n_acc].numpy(), truth[e: e + n_acc]):
+                state["diverged"] += 1              # an arg-max flipped between the two GPU runs
+                reset()
+                state["e"] = 0
+                continue
+            state["e"] = e + n_acc
+            state["emitted"] += n_acc
+
+    reset()
+    state["e"] = 0
+    run_steps(args.warmup)
+    torch.cuda.synchronize()
+    state["emitted"] = 0
+    t0 = time.perf_counter()
+    run_steps(args.steps)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    emitted = state["emitted"]
+    ms_per_step = elapsed / args.steps * 1e3
+
+    # ---------------------------------------------------------------- per-kernel timing (HIP events)
+    model.profile_begin(200000)
+    run_steps(args.profile_steps)
+    prof = model.profile_end()
+    g = prof["gemm"]
+    gemm_avg_us = g["ms"] / max(g["launches"], 1) * 1e3
+    gemm_gbs = g["bytes"] / max(g["ms"], 1e-9) / 1e6
+    a = prof["attn"]
+    attn_gbs = a["bytes"] / max(a["ms"], 1e-9) / 1e6
+
+    # ---------------------------------------------------------------- CPU oracle on a bounded sample
+    cpu = None
+    if cpu_keep is not None:
+        cpu = cpu_baseline(wl, shape, cpu_keep, T, tree_np, stop, n_cache=prompt_len)
+
+    kv_bytes = (prompt_len + state["e"] / 2) * 2.0 * shape.d_model * 2 * shape.n_layers
+    step_bytes = weight_bytes(shape) + kv_bytes
+    res = {
+        "metric": "verified_tree_tokens_per_s", "value": args.steps * T / elapsed, "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{W.name}: {shape.n_layers}-layer d={shape.d_model} Llama-shaped decoder, "
+                               f"{H} draft heads top-{k}, {T}-node tree, batch 1, Zipf prompt {prompt_len}, "
+                               f"KV cap {W.kv_cap}, 20% stop ids",
+                   "draft_mode": args.draft, "planted_accuracy_by_depth": list(p_depth) if args.draft == "planted" else None},
+        "accepted_tokens_per_s": emitted / elapsed, "mean_accepted_len": emitted / args.steps,
+        "greedy_tokens_per_s": n_timed / greedy_s, "speedup_vs_greedy": (emitted / elapsed) / (n_timed / greedy_s),
+        "prefill_tokens_per_s": prompt_len / prefill_s,
+        "step_hbm_frac": step_bytes / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9),
+        "diverged_resets": state["diverged"],
+        "roofline": {"kernel": "k_gemm_stream (weight-streaming MFMA GEMM, all projections)", "bound": "hbm",
+                     "achieved": gemm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gemm_gbs / HBM_PEAK_GBS,
+                     "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH, "avg_launch_us": gemm_avg_us,
+                     "launches_per_step": g["launches"] / args.profile_steps,
+                     "algorithmic_bytes_per_launch": g["bytes"] / max(g["launches"], 1)},
+        "attention": {"kernel": "k_tree_attn", "achieved_GBs": attn_gbs, "frac_hbm": attn_gbs / HBM_PEAK_GBS,
+                      "avg_launch_us": a["ms"] / max(a["launches"], 1) * 1e3},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(res))
+
+
+def cpu_baseline(wl, shape, cpu_keep, T, tree_np, stop, n_cache):
+    """Time the oracle's speculative step on the host, on a bounded sample of the workload."""
+    from threadpoolctl import threadpool_info
+    from oracle import specdec_oracle as orc
+
+    w64 = {n: t.double().numpy() for n, t in cpu_keep.items()}
+    times = {}
+    for L in (1, 2):
+        sh = shape.with_layers(L)
+        kv = orc.KVCache.empty(sh, n_cache + shape.n_medusa + 2)
+        for l in range(L):
+            dims = (n_cache, shape.n_heads, shape.head_dim)
+            kv.k[l, :n_cache] = wl.synthetic_kv_rows(wl.SEEDS["kvfill"], f"k{l}", dims, "bf16").double().numpy()
+            kv.v[l, :n_cache] = wl.synthetic_kv_rows(wl.SEEDS["kvfill"], f"v{l}", dims, "bf16").double().numpy()
+        kv.n = n_cache
+        cand = (np.arange(shape.n_medusa * shape.topk, dtype=np.int32).reshape(shape.n_medusa, shape.topk) * 7 + 3) % shape.vocab
+        st = orc.DecodeState(kv, root_tok=11, cand=cand)
+        t0 = time.perf_counter()
+        orc.spec_step(w64, sh, st, tree_np, stop)
+        times[L] = time.perf_counter() - t0
+    per_layer = max(times[2] - times[1], 1e-9)
+    rest = max(times[1] - per_layer, 0.0)
+    full = rest + shape.n_layers * per_layer
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    return {"value": T / full, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": f"one speculative step ({T}-node tree over a {n_cache}-row synthetic cache) timed at 1 and 2 "
+                      f"of the {shape.n_layers} layers (full width, LM head and draft heads included); "
+                      f"per-layer time {per_layer:.3f} s extrapolated to {shape.n_layers} layers: {full:.2f} s/step",
+            "seconds_measured": times[1] + times[2]}
+
+
+if __name__ == "__main__":
+    main()

@@ -168,6 +168,17 @@ int sd_verify_tree(const sd_tree* tree, int32_t batch, int32_t n_medusa, int32_t
                    int32_t* n_accept, int32_t* n_accept_raw, int32_t* tokens, int32_t* src_slots,
                    void* stream);
 
+/* ---- measurement ---------------------------------------------------------------------------
+ * Between sd_profile_begin and sd_profile_end every launch of the two bandwidth-bound kernel
+ * classes is bracketed by HIP events on the stream it is launched on (up to max_launches
+ * launches; later ones are not recorded). sd_profile_end synchronises `stream` and returns,
+ * per class (index 0 = weight-streaming GEMM, 1 = tree attention): the summed launch
+ * durations in ms, the number of launches, and the summed algorithmic bytes (GEMM: one read
+ * of the weight matrix; attention: one read of K and V of the committed rows, taken at the
+ * host's upper bound of the length, plus the tree rows). Arrays of 2 entries, host.        */
+int sd_profile_begin(sd_model* m, int32_t max_launches);
+int sd_profile_end(sd_model* m, void* stream, double* ms_total, int64_t* launches, double* bytes_total);
+
 const char* sd_last_error(void);
 /* Library version string; also proves the shared object loads without a GPU.              */
 const char* sd_version(void);

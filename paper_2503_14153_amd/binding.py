@@ -14,7 +14,7 @@ EXPORTED_SYMBOLS = [
     "sd_model_create", "sd_model_destroy", "sd_kv_bytes", "sd_kv_create", "sd_kv_destroy", "sd_kv_len",
     "sd_kv_set_len", "sd_kv_write_rows", "sd_kv_read_rows", "sd_kv_set_draft", "sd_kv_get_draft",
     "sd_tree_create", "sd_tree_destroy", "sd_prefill", "sd_spec_step", "sd_greedy_step", "sd_verify_tree",
-    "sd_last_error", "sd_version",
+    "sd_profile_begin", "sd_profile_end", "sd_last_error", "sd_version",
 ]
 
 SD_ERR = {-1: "SD_ERR_NULL", -2: "SD_ERR_SHAPE", -3: "SD_ERR_BAD_TREE", -4: "SD_ERR_KV_FULL", -5: "SD_ERR_HIP",
@@ -80,6 +80,9 @@ def lib() -> C.CDLL:
         L.sd_spec_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(_StepIO), C.c_void_p]
         L.sd_greedy_step.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(_StepIO), C.c_void_p]
         L.sd_verify_tree.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32] + [C.c_void_p] * 8
+        L.sd_profile_begin.argtypes = [C.c_void_p, C.c_int32]
+        L.sd_profile_end.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64),
+                                     C.POINTER(C.c_double)]
         _LIB = L
     return _LIB
 
@@ -131,6 +134,14 @@ class Model:
                      C.cast(mw, C.POINTER(C.c_void_p)), C.cast(mb, C.POINTER(C.c_void_p)))
         self.handle = C.c_void_p()
         _check(lib().sd_model_create(C.byref(self.cfg), C.byref(w), max_rows, _stream(), C.byref(self.handle)))
+
+    def profile_begin(self, max_launches: int = 65536):
+        _check(lib().sd_profile_begin(self.handle, max_launches))
+
+    def profile_end(self) -> dict:
+        ms, n, by = (C.c_double * 2)(), (C.c_int64 * 2)(), (C.c_double * 2)()
+        _check(lib().sd_profile_end(self.handle, _stream(), ms, n, by))
+        return {name: {"ms": ms[i], "launches": n[i], "bytes": by[i]} for i, name in enumerate(("gemm", "attn"))}
 
     def close(self):
         if getattr(self, "handle", None):

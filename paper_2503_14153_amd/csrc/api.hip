@@ -41,8 +41,20 @@ struct LayerW {
     const void *wqkv, *wo, *wgu, *wdown;    // packed fragments
 };
 
+// Optional per-launch timing of the two bandwidth-bound kernel classes with HIP events on the
+// caller's stream (sd_profile_begin / sd_profile_end).
+enum { PROF_GEMM = 0, PROF_ATTN = 1, PROF_CLASSES = 2 };
+struct Profile {
+    bool on = false;
+    std::vector<hipEvent_t> ev;              // pairs (start, stop)
+    std::vector<int> cls;                    // class of pair i
+    std::vector<double> bytes;               // algorithmic bytes of pair i
+    size_t used = 0;                         // pairs used
+};
+
 struct sd_model {
     sd_config cfg;
+    Profile prof;
     int max_rows, MBmax;
     int KBd, KBf, Fpad, NBqkv, NBo, NBgu, NBv, Vpad, NBmed;
     char* arena = nullptr;                   // packed weights
@@ -57,8 +69,16 @@ struct sd_model {
     RowTable rt;
     int32_t *am, *g_parent, *g_depth, *g_rank;
     uint32_t* zero_stop;
+    const void* zfrag;                       // 1 KiB of zeros
     size_t part_floats;
     int max_parts;
+    std::vector<GemmPlan> plans;             // one per (row blocks, K blocks, N blocks) in use
+    int32_t* plan_cnt = nullptr;             // device: the plans' per-group slot counts
+    const GemmPlan& plan(int MB, int KB, int NB) const {
+        for (const GemmPlan& p : plans)
+            if (p.MB == MB && p.KB == KB && p.NB == NB) return p;
+        return plans[0];                     // unreachable: every shape is planned at creation
+    }
 };
 
 struct sd_kv {
@@ -83,7 +103,7 @@ struct sd_tree {
 static int check_config(const sd_config* c) {
     if (c->dtype != SD_DTYPE_BF16) return fail(SD_ERR_SHAPE, "only dtype bf16 is implemented");
     if (c->head_dim != 64 && c->head_dim != 128) return fail(SD_ERR_SHAPE, "head_dim must be 64 or 128");
-    if (c->n_layers < 1 || c->n_heads < 1 || c->vocab < 2) return fail(SD_ERR_SHAPE, "bad sizes");
+    if (c->n_layers < 1 || c->n_heads < 1 || c->vocab < 2 || c->vocab > 163840) return fail(SD_ERR_SHAPE, "bad sizes");
     if (c->d_model != c->n_heads * c->head_dim) return fail(SD_ERR_SHAPE, "d_model != n_heads * head_dim");
     if (c->d_model % 32 || c->d_model > 8192) return fail(SD_ERR_SHAPE, "d_model must be a multiple of 32, <= 8192");
     if (c->d_ffn % 16 || c->d_ffn < 16) return fail(SD_ERR_SHAPE, "d_ffn must be a multiple of 16");
@@ -156,10 +176,10 @@ extern "C" int sd_model_create(const sd_config* cfg, const sd_weights* w, int32_
     if (e != hipSuccess) { hipFree(m->arena); delete m; return fail(SD_ERR_HIP, "weight copy: %s", hipGetErrorString(e)); }
     m->embed = A + o_embed;
     m->final_norm = A + o_fn;
-    launch_pack_weight(w->lm_head, A + o_lm, V, d, 0, m->KBd, s);
+    launch_pack_weight(w->lm_head, A + o_lm, V, d, 0, m->NBv, m->KBd, s);
     m->lm_head = A + o_lm;
     for (int i = 0; i < H; ++i) {
-        launch_pack_weight(w->medusa_w[i], A + o_med, d, d, i * (d / 32), m->KBd, s);
+        launch_pack_weight(w->medusa_w[i], A + o_med, d, d, i * (d / 32), m->NBmed, m->KBd, s);
         if (w->medusa_b && w->medusa_b[i]) {
             copy(o_mb[i], w->medusa_b[i], (size_t)d * 2);
             m->medusa_b.p[i] = (const uint16_t*)(A + o_mb[i]);
@@ -173,11 +193,11 @@ extern "C" int sd_model_create(const sd_config* cfg, const sd_weights* w, int32_
         LayerW& lw = m->layers[l];
         copy(o_an[l], w->attn_norm[l], (size_t)d * 2);
         copy(o_ffn[l], w->ffn_norm[l], (size_t)d * 2);
-        launch_pack_weight(w->wqkv[l], A + o_qkv[l], 3 * d, d, 0, m->KBd, s);
-        launch_pack_weight(w->wo[l], A + o_o[l], d, d, 0, m->KBd, s);
-        launch_pack_weight(w->w_gate[l], A + o_gu[l], F, d, 0, m->KBd, s);
-        launch_pack_weight(w->w_up[l], A + o_gu[l], F, d, m->Fpad / 32, m->KBd, s);
-        launch_pack_weight(w->w_down[l], A + o_dn[l], d, F, 0, m->KBf, s);
+        launch_pack_weight(w->wqkv[l], A + o_qkv[l], 3 * d, d, 0, m->NBqkv, m->KBd, s);
+        launch_pack_weight(w->wo[l], A + o_o[l], d, d, 0, m->NBo, m->KBd, s);
+        launch_pack_weight(w->w_gate[l], A + o_gu[l], F, d, 0, m->NBgu, m->KBd, s);
+        launch_pack_weight(w->w_up[l], A + o_gu[l], F, d, m->Fpad / 32, m->NBgu, m->KBd, s);
+        launch_pack_weight(w->w_down[l], A + o_dn[l], d, F, 0, m->NBo, m->KBf, s);
         lw.attn_norm = A + o_an[l];
         lw.ffn_norm = A + o_ffn[l];
         lw.wqkv = A + o_qkv[l];
@@ -189,12 +209,31 @@ extern "C" int sd_model_create(const sd_config* cfg, const sd_weights* w, int32_
     // ---- workspace
     const int Mp = m->MBmax * 32, nh = cfg->n_heads, hd = cfg->head_dim;
     const int ld_max = std::max(std::max(3 * d, 2 * m->Fpad), H * d);
+    // launch plans for every GEMM shape this model can issue
     size_t pf = 0;
-    for (int mb = 1; mb <= m->MBmax; mb *= 2) {
-        int kbs[2] = {m->KBd, m->KBf};
-        int nbs[4] = {m->NBqkv, m->NBo, m->NBgu, m->NBmed};
-        for (int kb : kbs)
-            for (int nb : nbs) pf = std::max(pf, (size_t)gemm_choose_split(mb, kb, nb) * (mb * 32) * (size_t)nb * 32);
+    std::vector<int32_t> cnt_all;
+    std::vector<size_t> cnt_off;
+    {
+        const int shapes[6][2] = {{m->KBd, m->NBqkv}, {m->KBd, m->NBo}, {m->KBd, m->NBgu},
+                                  {m->KBf, m->NBo},   {m->KBd, m->NBv}, {m->KBd, m->NBmed}};
+        for (int mb = 1; mb <= 8; mb *= 2)
+            for (int si = 0; si < 6; ++si) {
+                const int* sh = shapes[si];
+                // beyond MBmax only the LM head is used (draft-head rows); the draft-head
+                // projection itself always has one row block
+                if (mb > m->MBmax && si != 4) continue;
+                if (si == 5 && mb > 1) continue;
+                bool dup = false;
+                for (const GemmPlan& q : m->plans) dup |= q.MB == mb && q.KB == sh[0] && q.NB == sh[1];
+                if (dup) continue;
+                GemmPlan pl;
+                std::vector<int32_t> cnt((sh[1] + 7) / 8 + 1, 0);
+                gemm_plan_make(&pl, mb, sh[0], sh[1], cnt.data());
+                cnt_off.push_back(cnt_all.size());
+                cnt_all.insert(cnt_all.end(), cnt.begin(), cnt.end());
+                m->plans.push_back(pl);
+                pf = std::max(pf, (size_t)pl.slots * (mb * 32) * (size_t)sh[1] * 32);
+            }
     }
     (void)ld_max;
     m->part_floats = pf;
@@ -211,13 +250,19 @@ extern "C" int sd_model_create(const sd_config* cfg, const sd_weights* w, int32_
     size_t w_kt = wtake((size_t)L * Mp * d * 2), w_vt = wtake((size_t)L * Mp * d * 2);
     size_t w_tok = wtake((size_t)Mp * 4), w_pos = wtake((size_t)Mp * 4), w_anc = wtake((size_t)Mp * SD_ANC_WORDS * 4);
     size_t w_cs = wtake((size_t)Mp * (hd / 2) * 8), w_am = wtake((size_t)Mp * 4), w_g = wtake(3 * 4);
-    size_t w_zs = wtake((size_t)ceil_div(V, 32) * 4);
+    size_t w_zs = wtake((size_t)ceil_div(V, 32) * 4), w_zf = wtake(1024);
     e = hipMalloc((void**)&m->work, wz);
+    if (e == hipSuccess) e = hipMalloc((void**)&m->plan_cnt, cnt_all.size() * 4);
+    if (e == hipSuccess) e = hipMemcpy(m->plan_cnt, cnt_all.data(), cnt_all.size() * 4, hipMemcpyHostToDevice);
     if (e != hipSuccess) {
         hipFree(m->arena);
+        if (m->work) hipFree(m->work);
+        if (m->plan_cnt) hipFree(m->plan_cnt);
         delete m;
         return fail(SD_ERR_HIP, "hipMalloc(%zu) for workspace: %s", wz, hipGetErrorString(e));
     }
+    for (size_t i = 0; i < m->plans.size(); ++i)
+        if (m->plans[i].kind == 1) m->plans[i].cnt_dev = m->plan_cnt + cnt_off[i];
     hipMemsetAsync(m->work, 0, wz, s);
     char* Wk = m->work;
     m->x = (float*)(Wk + w_x); m->part = (float*)(Wk + w_part); m->logits = (float*)(Wk + w_logits);
@@ -230,21 +275,67 @@ extern "C" int sd_model_create(const sd_config* cfg, const sd_weights* w, int32_
     m->am = (int32_t*)(Wk + w_am);
     m->g_parent = (int32_t*)(Wk + w_g); m->g_depth = m->g_parent + 1; m->g_rank = m->g_parent + 2;
     m->zero_stop = (uint32_t*)(Wk + w_zs);
+    m->zfrag = Wk + w_zf;
     launch_fill_i32(m->g_parent, -1, 1, s);
     e = hipStreamSynchronize(s);
     if (e == hipSuccess) e = hipGetLastError();
     if (e != hipSuccess) {
-        hipFree(m->arena); hipFree(m->work); delete m;
+        hipFree(m->arena); hipFree(m->work); hipFree(m->plan_cnt); delete m;
         return fail(SD_ERR_HIP, "weight packing failed: %s", hipGetErrorString(e));
     }
     *out = m;
     return SD_OK;
 }
 
+static void prof_free(sd_model* m) {
+    for (hipEvent_t e : m->prof.ev) hipEventDestroy(e);
+    m->prof = Profile();
+}
+
+extern "C" int sd_profile_begin(sd_model* m, int32_t max_launches) {
+    if (!m) return fail(SD_ERR_NULL, "sd_profile_begin: NULL model");
+    if (max_launches < 1 || max_launches > (1 << 20)) return fail(SD_ERR_SHAPE, "sd_profile_begin: bad max_launches");
+    prof_free(m);
+    m->prof.ev.resize((size_t)max_launches * 2);
+    m->prof.cls.assign(max_launches, 0);
+    m->prof.bytes.assign(max_launches, 0.0);
+    for (size_t i = 0; i < m->prof.ev.size(); ++i) {
+        hipError_t e = hipEventCreate(&m->prof.ev[i]);
+        if (e != hipSuccess) {
+            m->prof.ev.resize(i);
+            prof_free(m);
+            return fail(SD_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(e));
+        }
+    }
+    m->prof.on = true;
+    return SD_OK;
+}
+
+extern "C" int sd_profile_end(sd_model* m, void* stream, double* ms_total, int64_t* launches, double* bytes_total) {
+    if (!m || !ms_total || !launches || !bytes_total) return fail(SD_ERR_NULL, "sd_profile_end: NULL argument");
+    if (!m->prof.on) return fail(SD_ERR_STATE, "sd_profile_end: profiling is not on");
+    hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+    if (e != hipSuccess) { prof_free(m); return fail(SD_ERR_HIP, "sync: %s", hipGetErrorString(e)); }
+    for (int c = 0; c < PROF_CLASSES; ++c) { ms_total[c] = 0.0; launches[c] = 0; bytes_total[c] = 0.0; }
+    for (size_t i = 0; i < m->prof.used; ++i) {
+        float ms = 0.f;
+        e = hipEventElapsedTime(&ms, m->prof.ev[2 * i], m->prof.ev[2 * i + 1]);
+        if (e != hipSuccess) { prof_free(m); return fail(SD_ERR_HIP, "hipEventElapsedTime: %s", hipGetErrorString(e)); }
+        int c = m->prof.cls[i];
+        ms_total[c] += ms;
+        launches[c] += 1;
+        bytes_total[c] += m->prof.bytes[i];
+    }
+    prof_free(m);
+    return SD_OK;
+}
+
 extern "C" int sd_model_destroy(sd_model* m) {
     if (!m) return SD_OK;
+    prof_free(m);
     hipFree(m->arena);
     hipFree(m->work);
+    hipFree(m->plan_cnt);
     delete m;
     return SD_OK;
 }
@@ -415,15 +506,26 @@ extern "C" int sd_tree_destroy(sd_tree* t) {
 // ------------------------------------------------------------------------------------------ forward
 // Layers 0..L-1 on the rows described by m->rt / m->x (B sequences of Tp rows each). Leaves the
 // last down-projection's partial sums in m->part (added by the caller's next norm).
-struct PartRef { int nsplit; size_t stride; int ld; };
+static int prof_start(sd_model* m, int cls, double bytes, hipStream_t s) {
+    Profile& p = m->prof;
+    if (!p.on || p.used * 2 + 1 >= p.ev.size()) return -1;
+    int i = (int)p.used++;
+    p.cls[i] = cls;
+    p.bytes[i] = bytes;
+    hipEventRecord(p.ev[2 * i], s);
+    return i;
+}
+static void prof_stop(sd_model* m, int i, hipStream_t s) {
+    if (i >= 0) hipEventRecord(m->prof.ev[2 * i + 1], s);
+}
 
-static PartRef run_gemm(sd_model* m, const void* Xp, const void* Wp, float* out, int MB, int KB, int NB, hipStream_t s) {
-    PartRef p;
-    p.ld = NB * 32;
-    p.nsplit = gemm_choose_split(MB, KB, NB);
-    p.stride = (size_t)MB * 32 * p.ld;
-    launch_gemm(Xp, Wp, out, MB, KB, NB, p.ld, p.nsplit, p.stride, s);
-    return p;
+// One weight-streaming GEMM; algorithmic bytes = one read of the (unpadded) weight matrix.
+static PartView run_gemm(sd_model* m, const void* Xp, const void* Wp, float* out, int MB, int KB, int NB, int n_real,
+                         hipStream_t s) {
+    int pi = prof_start(m, PROF_GEMM, (double)n_real * KB * 16 * 2, s);
+    PartView pv = launch_gemm(m->plan(MB, KB, NB), Xp, Wp, m->zfrag, out, s);
+    prof_stop(m, pi, s);
+    return pv;
 }
 
 static void attn_geometry(const sd_model* m, int B, int Tp, int n_hi, int* nchunks, int* bpc) {
@@ -438,41 +540,42 @@ static void attn_geometry(const sd_model* m, int B, int Tp, int n_hi, int* nchun
     *nchunks = ceil_div(nblk, *bpc);
 }
 
-static PartRef run_layers(sd_model* m, sd_kv* kv, int B, int Tp, int n_hi, hipStream_t s) {
+static PartView run_layers(sd_model* m, sd_kv* kv, int B, int Tp, int n_hi, hipStream_t s) {
     const sd_config& c = m->cfg;
     const int M = B * Tp, MB = pow2_blocks(M), d = c.d_model, nh = c.n_heads, hd = c.head_dim, TB = Tp / 32;
     int nchunks, bpc;
     attn_geometry(m, B, Tp, n_hi, &nchunks, &bpc);
-    PartRef prev = {0, 0, d};
+    PartView prev = {nullptr, 0, d, nullptr, 256, 0};
     const size_t t_stride = (size_t)B * nh * TB * 32 * hd;     // elements per layer of tree scratch
     for (int l = 0; l < c.n_layers; ++l) {
         const LayerW& lw = m->layers[l];
-        launch_norm_pack(m->x, m->part, prev.nsplit, prev.stride, prev.ld, lw.attn_norm, c.rms_eps, m->xn, nullptr, M, d,
-                         MB, nullptr, s);
-        PartRef pq = run_gemm(m, m->xn, lw.wqkv, m->part, MB, m->KBd, m->NBqkv, s);
+        launch_norm_pack(m->x, prev, lw.attn_norm, c.rms_eps, m->xn, nullptr, M, d, MB, nullptr, s);
+        PartView pq = run_gemm(m, m->xn, lw.wqkv, m->part, MB, m->KBd, m->NBqkv, 3 * d, s);
         uint16_t* kt = (uint16_t*)m->kt + l * t_stride;
         uint16_t* vt = (uint16_t*)m->vt + l * t_stride;
-        launch_rope_kv(m->part, pq.nsplit, pq.stride, pq.ld, m->rt, m->q, kt, vt, B, Tp, nh, hd, s);
+        launch_rope_kv(pq, m->rt, m->q, kt, vt, B, Tp, nh, hd, s);
+        // algorithmic bytes: one read of K and V of the committed rows (upper bound n_hi) + tree rows
+        int pa = prof_start(m, PROF_ATTN, (double)B * (n_hi + Tp) * 2.0 * d * 2.0, s);
         launch_tree_attn(m->q, kv->kc + l * kv->layer_stride, kv->vc + l * kv->layer_stride, kt, vt, kv->kv_len,
                          m->rt.anc, m->opart, m->mlpart, B, nh, hd, Tp, kv->cap_blocks, nchunks, bpc, s);
+        prof_stop(m, pa, s);
         launch_attn_merge(m->opart, m->mlpart, m->attn_x, B, nh, hd, Tp, nchunks + 1, MB, s);
-        PartRef po = run_gemm(m, m->attn_x, lw.wo, m->part, MB, m->KBd, m->NBo, s);
-        launch_norm_pack(m->x, m->part, po.nsplit, po.stride, po.ld, lw.ffn_norm, c.rms_eps, m->xn, nullptr, M, d, MB,
-                         nullptr, s);
-        PartRef pg = run_gemm(m, m->xn, lw.wgu, m->part, MB, m->KBd, m->NBgu, s);
-        launch_swiglu_pack(m->part, pg.nsplit, pg.stride, pg.ld, c.d_ffn, m->Fpad, m->act, M, MB, s);
-        prev = run_gemm(m, m->act, lw.wdown, m->part, MB, m->KBf, m->NBo, s);
+        PartView po = run_gemm(m, m->attn_x, lw.wo, m->part, MB, m->KBd, m->NBo, d, s);
+        launch_norm_pack(m->x, po, lw.ffn_norm, c.rms_eps, m->xn, nullptr, M, d, MB, nullptr, s);
+        PartView pg = run_gemm(m, m->xn, lw.wgu, m->part, MB, m->KBd, m->NBgu, 2 * c.d_ffn, s);
+        launch_swiglu_pack(pg, c.d_ffn, m->Fpad, m->act, M, MB, s);
+        prev = run_gemm(m, m->act, lw.wdown, m->part, MB, m->KBf, m->NBo, d, s);
     }
     return prev;
 }
 
 // final norm + LM head on all rows + arg-max of the first T rows of every sequence
-static void run_lm_head(sd_model* m, PartRef prev, int B, int T, int Tp, hipStream_t s) {
+static void run_lm_head(sd_model* m, PartView prev, int B, int T, int Tp, hipStream_t s) {
     const sd_config& c = m->cfg;
     const int M = B * Tp, MB = pow2_blocks(M);
-    launch_norm_pack(m->x, m->part, prev.nsplit, prev.stride, prev.ld, m->final_norm, c.rms_eps, m->xn, nullptr, M,
-                     c.d_model, MB, nullptr, s);
-    launch_gemm(m->xn, m->lm_head, m->logits, MB, m->KBd, m->NBv, m->Vpad, 1, 0, s);
+    launch_norm_pack(m->x, prev, m->final_norm, c.rms_eps, m->xn, nullptr, M, c.d_model, MB, nullptr, s);
+    PartView pl = run_gemm(m, m->xn, m->lm_head, m->part, MB, m->KBd, m->NBv, c.vocab, s);
+    launch_reduce_slots(pl, m->logits, M, s);
     launch_argmax(m->logits, m->Vpad, c.vocab, m->am, B, T, Tp, s);
 }
 
@@ -480,11 +583,13 @@ static void run_lm_head(sd_model* m, PartRef prev, int B, int T, int Tp, hipStre
 static void run_draft_heads(sd_model* m, sd_kv* kv, int B, uint32_t seq_mask, float* head_logits_out, hipStream_t s) {
     const sd_config& c = m->cfg;
     const int d = c.d_model, H = c.n_medusa;
-    launch_norm_pack(m->x, nullptr, 0, 0, 0, m->final_norm, c.rms_eps, m->xn, m->h_rows, B, d, 1, kv->last_row, s);
-    PartRef pm = run_gemm(m, m->xn, m->medusa_w, m->part, 1, m->KBd, m->NBmed, s);
+    const PartView none = {nullptr, 0, d, nullptr, 256, 0};
+    launch_norm_pack(m->x, none, m->final_norm, c.rms_eps, m->xn, m->h_rows, B, d, 1, kv->last_row, s);
+    PartView pm = run_gemm(m, m->xn, m->medusa_w, m->part, 1, m->KBd, m->NBmed, H * d, s);
     const int MBh = pow2_blocks(H * B);
-    launch_medusa_act(m->part, pm.nsplit, pm.stride, pm.ld, m->h_rows, m->medusa_b, B, H, d, m->xn, MBh, s);
-    launch_gemm(m->xn, m->lm_head, m->hlogits, MBh, m->KBd, m->NBv, m->Vpad, 1, 0, s);
+    launch_medusa_act(pm, m->h_rows, m->medusa_b, B, H, d, m->xn, MBh, s);
+    PartView pl = run_gemm(m, m->xn, m->lm_head, m->part, MBh, m->KBd, m->NBv, c.vocab, s);
+    launch_reduce_slots(pl, m->hlogits, H * B, s);
     launch_topk(m->hlogits, m->Vpad, c.vocab, c.topk, kv->cand, B, H, seq_mask, s);
     if (head_logits_out) launch_copy_head_logits(m->hlogits, m->Vpad, head_logits_out, c.vocab, B, H, s);
 }
@@ -522,7 +627,7 @@ extern "C" int sd_prefill(sd_model* m, sd_kv* kv, const int32_t* tokens, const i
         }
         launch_build_rows_chain(m->rt, tokens, ca, kv->kv_len, B, Tp, c.head_dim, c.rope_theta, m->embed, c.d_model,
                                 c.vocab, m->x, s);
-        PartRef prev = run_layers(m, kv, B, Tp, n_hi, s);
+        PartView prev = run_layers(m, kv, B, Tp, n_hi, s);
         launch_prefill_commit_setup(ca, B, Tp, kv->i_slots, kv->i_nacc, kv->n_old, kv->kv_len, kv->last_row, s);
         launch_kv_commit(m->kt, m->vt, kv->kc, kv->vc, kv->i_slots, kv->i_nacc, kv->n_old, c.n_layers, B, c.n_heads,
                          c.head_dim, Tp / 32, kv->cap_blocks, Tp, Tp, s);
@@ -561,7 +666,7 @@ static int step_common(sd_model* m, sd_kv* kv, const int32_t* parent, const int3
     const int32_t* cand = io->forced_cand ? io->forced_cand : kv->cand;
     launch_build_rows_tree(m->rt, parent, depth, rank, kv->root_tok, cand, kv->kv_len, B, T, Tp, H, c.topk, c.head_dim,
                            c.rope_theta, m->embed, c.d_model, c.vocab, m->x, s);
-    PartRef prev = run_layers(m, kv, B, Tp, n_hi, s);
+    PartView prev = run_layers(m, kv, B, Tp, n_hi, s);
     run_lm_head(m, prev, B, T, Tp, s);
     if (io->logits) launch_copy_logits(m->logits, m->Vpad, io->logits, c.vocab, B, T, Tp, s);
     if (io->argmax) launch_copy_rows_i32(m->am, io->argmax, B, T, Tp, s);

@@ -48,47 +48,69 @@ void launch_argmax(const float* logits, int ld, int V, int32_t* am, int B, int T
 }
 
 // ------------------------------------------------------------------------------------------
-// Per-row top-k (descending logit, ties to the lower id): k selection rounds; an element is
-// still eligible in a round iff it sorts after the previously selected one.
-__global__ __launch_bounds__(256) void k_topk(const float* __restrict__ logits, int ld, int V, int k,
-                                              int32_t* __restrict__ out, int B, int H, uint32_t seq_mask) {
+// Per-row top-k (descending logit, ties to the lower id). One workgroup of 1024 threads per
+// row keeps the whole row in registers (thread t owns ids t, t+1024, ...); each of the k
+// rounds is a thread-local scan plus one block-wide (value, id) reduction, after which the
+// owner retires the selected element.
+#define TOPK_THREADS 1024
+template <int NPT>
+__global__ __launch_bounds__(TOPK_THREADS) void k_topk(const float* __restrict__ logits, int ld, int V, int k,
+                                                       int32_t* __restrict__ out, int B, int H, uint32_t seq_mask) {
     const int r = blockIdx.x;                 // row r = head i * B + sequence b
     const int i = r / B, b = r % B;
     if (!((seq_mask >> b) & 1u)) return;
     const float* row = logits + (size_t)r * ld;
-    __shared__ float sv[4];
-    __shared__ int si[4];
-    __shared__ float lastv;
-    __shared__ int lasti;
-    float pv = __builtin_inff();
-    int pi = -1;
+    const int tid = threadIdx.x;
+    float v[NPT];
+#pragma unroll
+    for (int j = 0; j < NPT; ++j) {
+        int c = j * TOPK_THREADS + tid;
+        v[j] = c < V ? row[c] : NEG_INF;
+    }
+    __shared__ float sv[TOPK_THREADS / 64];
+    __shared__ int si[TOPK_THREADS / 64];
+    __shared__ int chosen;
     for (int round = 0; round < k; ++round) {
         float bv = NEG_INF;
         int bi = 0x7fffffff;
-        for (int c = threadIdx.x; c < V; c += 256) {
-            float v = row[c];
-            bool eligible = v < pv || (v == pv && c > pi);
-            if (eligible && better(v, c, bv, bi)) { bv = v; bi = c; }
+#pragma unroll
+        for (int j = 0; j < NPT; ++j) {       // ascending ids: strict > keeps the lowest id
+            int c = j * TOPK_THREADS + tid;
+            if (c < V && v[j] > bv) { bv = v[j]; bi = c; }
         }
         wave_best(bv, bi);
-        if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
+        if ((tid & 63) == 0) { sv[tid >> 6] = bv; si[tid >> 6] = bi; }
         __syncthreads();
-        if (threadIdx.x == 0) {
-            for (int w = 1; w < 4; ++w)
-                if (better(sv[w], si[w], bv, bi)) { bv = sv[w]; bi = si[w]; }
-            lastv = bv;
-            lasti = bi;
-            out[((size_t)b * H + i) * k + round] = bi;
+        if (tid < 64) {
+            float wv = tid < TOPK_THREADS / 64 ? sv[tid] : NEG_INF;
+            int wi = tid < TOPK_THREADS / 64 ? si[tid] : 0x7fffffff;
+            wave_best(wv, wi);
+            if (tid == 0) {
+                chosen = wi;
+                out[((size_t)b * H + i) * k + round] = wi;
+            }
         }
         __syncthreads();
-        pv = lastv;
-        pi = lasti;
+        const int ch = chosen;
+        if ((ch % TOPK_THREADS) == tid) {
+#pragma unroll
+            for (int j = 0; j < NPT; ++j)
+                if (j == ch / TOPK_THREADS) v[j] = NEG_INF;
+        }
     }
 }
 
 void launch_topk(const float* logits, int ld, int V, int k, int32_t* out, int B, int H, uint32_t seq_mask,
                  hipStream_t s) {
-    hipLaunchKernelGGL(k_topk, dim3(B * H), dim3(256), 0, s, logits, ld, V, k, out, B, H, seq_mask);
+    const int npt = (V + TOPK_THREADS - 1) / TOPK_THREADS;
+#define TOPK(N) hipLaunchKernelGGL((k_topk<N>), dim3(B * H), dim3(TOPK_THREADS), 0, s, logits, ld, V, k, out, B, H, seq_mask)
+    if (npt <= 1) TOPK(1);
+    else if (npt <= 4) TOPK(4);
+    else if (npt <= 16) TOPK(16);
+    else if (npt <= 32) TOPK(32);
+    else if (npt <= 64) TOPK(64);
+    else TOPK(160);          // vocabularies up to 163840 ids (validated at model creation)
+#undef TOPK
 }
 
 // ------------------------------------------------------------------------------------------

@@ -94,12 +94,13 @@ void launch_build_rows_chain(RowTable rt, const int32_t* tokens, const ChainArgs
 // ------------------------------------------------------------------------------------------
 // x += sum of split partials (residual add of the previous projection), then
 // xn = x * rsqrt(mean(x^2) + eps) * gain, written as bf16 in fragment order.
-// One workgroup (256 threads) per row; a thread owns groups of 8 consecutive columns.
-#define NP_MAXG 4   // d <= 8 * 256 * NP_MAXG = 8192
-__global__ __launch_bounds__(256) void k_norm_pack(float* __restrict__ x, const float* __restrict__ part, int nsplit,
-                                                   size_t split_stride, int ldp, const uint16_t* __restrict__ gain,
-                                                   float eps, bf16x8* __restrict__ xn, float* __restrict__ hf, int d,
-                                                   int MB, const int32_t* __restrict__ gather) {
+// One workgroup per row; a thread owns groups of 8 consecutive columns.
+#define NP_THREADS 512
+#define NP_MAXG 2   // d <= 8 * NP_THREADS * NP_MAXG = 8192
+__global__ __launch_bounds__(NP_THREADS) void k_norm_pack(float* __restrict__ x, PartView pv,
+                                                          const uint16_t* __restrict__ gain, float eps,
+                                                          bf16x8* __restrict__ xn, float* __restrict__ hf, int d,
+                                                          int MB, const int32_t* __restrict__ gather) {
     const int m = blockIdx.x;
     const int src = gather ? gather[m] : m;
     float* xr = x + (size_t)src * d;
@@ -108,12 +109,14 @@ __global__ __launch_bounds__(256) void k_norm_pack(float* __restrict__ x, const 
     float ss = 0.f;
 #pragma unroll
     for (int gi = 0; gi < NP_MAXG; ++gi) {
-        int grp = gi * 256 + threadIdx.x;
+        int grp = gi * NP_THREADS + threadIdx.x;
         if (grp < ngroups) {
             float4 a = *(const float4*)(xr + grp * 8), c = *(const float4*)(xr + grp * 8 + 4);
             float t[8] = {a.x, a.y, a.z, a.w, c.x, c.y, c.z, c.w};
+            const int nsplit = pv.nmax > 0 ? part_count(pv, grp * 8) : 0;
+#pragma unroll 4
             for (int sp = 0; sp < nsplit; ++sp) {
-                const float* p = part + (size_t)sp * split_stride + (size_t)src * ldp + grp * 8;
+                const float* p = pv.base + (size_t)sp * pv.slot_stride + (size_t)src * pv.ld + grp * 8;
                 float4 pa = *(const float4*)p, pc = *(const float4*)(p + 4);
                 t[0] += pa.x; t[1] += pa.y; t[2] += pa.z; t[3] += pa.w;
                 t[4] += pc.x; t[5] += pc.y; t[6] += pc.z; t[7] += pc.w;
@@ -126,15 +129,17 @@ __global__ __launch_bounds__(256) void k_norm_pack(float* __restrict__ x, const 
             for (int i = 0; i < 8; ++i) { v[gi][i] = t[i]; ss += t[i] * t[i]; }
         }
     }
-    __shared__ float red[4];
+    __shared__ float red[NP_THREADS / 64];
     for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
     __syncthreads();
-    ss = red[0] + red[1] + red[2] + red[3];
+    ss = 0.f;
+#pragma unroll
+    for (int w = 0; w < NP_THREADS / 64; ++w) ss += red[w];
     const float r = rsqrtf(ss / (float)d + eps);
 #pragma unroll
     for (int gi = 0; gi < NP_MAXG; ++gi) {
-        int grp = gi * 256 + threadIdx.x;
+        int grp = gi * NP_THREADS + threadIdx.x;
         if (grp < ngroups) {
             bf16x8 hi, lo;
             float f[8];
@@ -152,90 +157,99 @@ __global__ __launch_bounds__(256) void k_norm_pack(float* __restrict__ x, const 
     }
 }
 
-void launch_norm_pack(float* x, const float* part, int nsplit, size_t split_stride, int ldp, const void* gain,
-                      float eps, void* xn_packed, float* hf_out, int M, int d, int MB, const int32_t* gather,
-                      hipStream_t s) {
-    hipLaunchKernelGGL(k_norm_pack, dim3(M), dim3(256), 0, s, x, part, nsplit, split_stride, ldp,
+void launch_norm_pack(float* x, PartView pv, const void* gain, float eps, void* xn_packed, float* hf_out, int M, int d,
+                      int MB, const int32_t* gather, hipStream_t s) {
+    hipLaunchKernelGGL(k_norm_pack, dim3(M), dim3(NP_THREADS), 0, s, x, pv,
                        (const uint16_t*)gain, eps, (bf16x8*)xn_packed, hf_out, d, MB, gather);
 }
 
 // ------------------------------------------------------------------------------------------
-// Sum the QKV partials, rotate q and k to the row's position, and write q (fragment order),
-// k and v (tree scratch, block layouts). Thread (m, h, a) owns dims [8a, 8a+8) and their
-// rotary partners [hd/2 + 8a, +8).
-__global__ void k_rope_kv(const float* __restrict__ part, int nsplit, size_t split_stride, int ldp, RowTable rt,
-                          bf16x8* __restrict__ qp, uint16_t* __restrict__ kt, uint16_t* __restrict__ vt, int B, int Tp,
+// Sum the QKV partials, rotate q and k to the row's position, and write q (fragment order,
+// two-term expansion), k and v (tree scratch, block layouts, bf16). Thread (m, h, a, which)
+// owns dims [8a, 8a+8) and their rotary partners [hd/2 + 8a, +8) of q (which=0), k (1) or v (2).
+__global__ void k_rope_kv(PartView pv, RowTable rt, bf16x8* __restrict__ qp, uint16_t* __restrict__ kt, uint16_t* __restrict__ vt, int B, int Tp,
                           int nh, int hd) {
     const int na = hd / 16;
     int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= B * Tp * nh * na) return;
-    const int a = idx % na, h = (idx / na) % nh, m = idx / (na * nh);
+    if (idx >= B * Tp * nh * na * 3) return;
+    const int a = idx % na, h = (idx / na) % nh, which = (idx / (na * nh)) % 3, m = idx / (na * nh * 3);
     const int b = m / Tp, t = m % Tp, d = nh * hd, half = hd / 2;
-    float q1[8], q2[8], k1[8], k2[8], v1[8], v2[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) q1[i] = q2[i] = k1[i] = k2[i] = v1[i] = v2[i] = 0.f;
+    float4 s0 = make_float4(0, 0, 0, 0), s1 = s0, s2 = s0, s3 = s0;       // dims 8a..8a+7, half+8a..+7
+    const int col0 = which * d + h * hd + a * 8;
+    const float* p0 = pv.base + (size_t)m * pv.ld + col0;
+    const int nsplit = part_count(pv, col0);           // a head's columns share one 256-column group
     for (int sp = 0; sp < nsplit; ++sp) {
-        const float* p = part + (size_t)sp * split_stride + (size_t)m * ldp + h * hd + a * 8;
+        const float* p = p0 + (size_t)sp * pv.slot_stride;
+        float4 x0 = *(const float4*)p, x1 = *(const float4*)(p + 4);
+        float4 x2 = *(const float4*)(p + half), x3 = *(const float4*)(p + half + 4);
+        s0.x += x0.x; s0.y += x0.y; s0.z += x0.z; s0.w += x0.w;
+        s1.x += x1.x; s1.y += x1.y; s1.z += x1.z; s1.w += x1.w;
+        s2.x += x2.x; s2.y += x2.y; s2.z += x2.z; s2.w += x2.w;
+        s3.x += x3.x; s3.y += x3.y; s3.z += x3.z; s3.w += x3.w;
+    }
+    float lo[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+    float hi[8] = {s2.x, s2.y, s2.z, s2.w, s3.x, s3.y, s3.z, s3.w};
+    const int TB = Tp / 32;
+    const size_t head_off = ((size_t)b * nh + h) * TB * (32 * hd);
+    if (which == 2) {                                   // values: not rotated, scattered bf16
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            q1[i] += p[i];            q2[i] += p[half + i];
-            k1[i] += p[d + i];        k2[i] += p[d + half + i];
-            v1[i] += p[2 * d + i];    v2[i] += p[2 * d + half + i];
+            __bf16 w1 = (__bf16)lo[i], w2 = (__bf16)hi[i];
+            vt[head_off + vblk_index(t, a * 8 + i, hd)] = __builtin_bit_cast(uint16_t, w1);
+            vt[head_off + vblk_index(t, half + a * 8 + i, hd)] = __builtin_bit_cast(uint16_t, w2);
         }
+        return;
     }
-    bf16x8 ko1, ko2, qh1, ql1, qh2, ql2;
     float r1[8], r2[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         float2 cs = rt.cs[(size_t)m * half + a * 8 + i];
-        r1[i] = q1[i] * cs.x - q2[i] * cs.y;
-        r2[i] = q2[i] * cs.x + q1[i] * cs.y;
-        ko1[i] = (__bf16)(k1[i] * cs.x - k2[i] * cs.y);
-        ko2[i] = (__bf16)(k2[i] * cs.x + k1[i] * cs.y);
+        r1[i] = lo[i] * cs.x - hi[i] * cs.y;
+        r2[i] = hi[i] * cs.x + lo[i] * cs.y;
     }
-    split_hilo(r1, qh1, ql1);
-    split_hilo(r2, qh2, ql2);
-    // q: two-term expansion in fragment order; k, v: bf16, the cache's storage type
-    const int TB = Tp / 32;
-    size_t head_off = ((size_t)b * nh + h) * TB * (32 * hd);
-    size_t i1 = head_off + kblk_index(t, a * 8, hd), i2 = head_off + kblk_index(t, half + a * 8, hd);
-    size_t q1i = 2 * head_off + qblk_index(t, a * 8, hd), q2i = 2 * head_off + qblk_index(t, half + a * 8, hd);
-    qp[q1i >> 3] = qh1;
-    qp[(q1i >> 3) + 64] = ql1;
-    qp[q2i >> 3] = qh2;
-    qp[(q2i >> 3) + 64] = ql2;
-    ((bf16x8*)kt)[i1 >> 3] = ko1;
-    ((bf16x8*)kt)[i2 >> 3] = ko2;
+    if (which == 0) {                                   // queries: two-term expansion
+        bf16x8 h1, l1, h2, l2;
+        split_hilo(r1, h1, l1);
+        split_hilo(r2, h2, l2);
+        size_t q1i = 2 * head_off + qblk_index(t, a * 8, hd), q2i = 2 * head_off + qblk_index(t, half + a * 8, hd);
+        qp[q1i >> 3] = h1;
+        qp[(q1i >> 3) + 64] = l1;
+        qp[q2i >> 3] = h2;
+        qp[(q2i >> 3) + 64] = l2;
+    } else {                                            // keys: bf16, the cache's storage type
+        bf16x8 k1, k2;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        __bf16 w1 = (__bf16)v1[i], w2 = (__bf16)v2[i];
-        vt[head_off + vblk_index(t, a * 8 + i, hd)] = __builtin_bit_cast(uint16_t, w1);
-        vt[head_off + vblk_index(t, half + a * 8 + i, hd)] = __builtin_bit_cast(uint16_t, w2);
+        for (int i = 0; i < 8; ++i) { k1[i] = (__bf16)r1[i]; k2[i] = (__bf16)r2[i]; }
+        ((bf16x8*)kt)[(head_off + kblk_index(t, a * 8, hd)) >> 3] = k1;
+        ((bf16x8*)kt)[(head_off + kblk_index(t, half + a * 8, hd)) >> 3] = k2;
     }
 }
 
-void launch_rope_kv(const float* part, int nsplit, size_t split_stride, int ldp, RowTable rt, void* q_packed, void* kt,
-                    void* vt, int B, int Tp, int nh, int hd, hipStream_t s) {
-    int total = B * Tp * nh * (hd / 16);
-    hipLaunchKernelGGL(k_rope_kv, dim3((total + 255) / 256), dim3(256), 0, s, part, nsplit, split_stride, ldp, rt,
+void launch_rope_kv(PartView pv, RowTable rt, void* q_packed, void* kt, void* vt, int B, int Tp, int nh, int hd,
+                    hipStream_t s) {
+    int total = B * Tp * nh * (hd / 16) * 3;
+    hipLaunchKernelGGL(k_rope_kv, dim3((total + 255) / 256), dim3(256), 0, s, pv, rt,
                        (bf16x8*)q_packed, (uint16_t*)kt, (uint16_t*)vt, B, Tp, nh, hd);
 }
 
 // ------------------------------------------------------------------------------------------
 // act = silu(gate) * up from the gate/up partials (gate in columns [0,F), up in [Fpad, Fpad+F)).
-__global__ void k_swiglu_pack(const float* __restrict__ part, int nsplit, size_t split_stride, int ldp, int F, int Fpad,
-                              bf16x8* __restrict__ act, int M, int MB) {
+__global__ void k_swiglu_pack(PartView pv, int F, int Fpad, bf16x8* __restrict__ act, int M, int MB) {
     int idx = blockIdx.x * blockDim.x + threadIdx.x;
     int ng = F / 8;
     if (idx >= M * ng) return;
     int grp = idx % ng, m = idx / ng;
     float gsum[8] = {0, 0, 0, 0, 0, 0, 0, 0}, usum[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    for (int sp = 0; sp < nsplit; ++sp) {
-        const float* p = part + (size_t)sp * split_stride + (size_t)m * ldp + grp * 8;
+    const int ng_ = part_count(pv, grp * 8), nu_ = part_count(pv, Fpad + grp * 8);
+    for (int sp = 0; sp < ng_; ++sp) {
+        const float* p = pv.base + (size_t)sp * pv.slot_stride + (size_t)m * pv.ld + grp * 8;
         float4 a = *(const float4*)p, c = *(const float4*)(p + 4);
-        float4 ua = *(const float4*)(p + Fpad), uc = *(const float4*)(p + Fpad + 4);
         gsum[0] += a.x; gsum[1] += a.y; gsum[2] += a.z; gsum[3] += a.w;
         gsum[4] += c.x; gsum[5] += c.y; gsum[6] += c.z; gsum[7] += c.w;
+    }
+    for (int sp = 0; sp < nu_; ++sp) {
+        const float* p = pv.base + (size_t)sp * pv.slot_stride + (size_t)m * pv.ld + Fpad + grp * 8;
+        float4 ua = *(const float4*)p, uc = *(const float4*)(p + 4);
         usum[0] += ua.x; usum[1] += ua.y; usum[2] += ua.z; usum[3] += ua.w;
         usum[4] += uc.x; usum[5] += uc.y; usum[6] += uc.z; usum[7] += uc.w;
     }
@@ -249,26 +263,25 @@ __global__ void k_swiglu_pack(const float* __restrict__ part, int nsplit, size_t
     act[u + XPART / 8] = lo;
 }
 
-void launch_swiglu_pack(const float* part, int nsplit, size_t split_stride, int ldp, int F, int Fpad, void* act_packed,
-                        int M, int MB, hipStream_t s) {
+void launch_swiglu_pack(PartView pv, int F, int Fpad, void* act_packed, int M, int MB, hipStream_t s) {
     int total = M * (F / 8);
-    hipLaunchKernelGGL(k_swiglu_pack, dim3((total + 255) / 256), dim3(256), 0, s, part, nsplit, split_stride, ldp, F,
-                       Fpad, (bf16x8*)act_packed, M, MB);
+    hipLaunchKernelGGL(k_swiglu_pack, dim3((total + 255) / 256), dim3(256), 0, s, pv, F, Fpad, (bf16x8*)act_packed, M,
+                       MB);
 }
 
 // ------------------------------------------------------------------------------------------
 // Draft heads, activation stage: row (i, b) = h_b + silu(W_i h_b + bias_i), packed as the
 // operand of the shared LM-head GEMM. part columns [i*d, (i+1)*d) hold W_i h_b for row b.
-__global__ void k_medusa_act(const float* __restrict__ part, int nsplit, size_t split_stride, int ldp,
-                             const float* __restrict__ h_rows, MedusaBias bias, int B, int H, int d,
+__global__ void k_medusa_act(PartView pv, const float* __restrict__ h_rows, MedusaBias bias, int B, int H, int d,
                              bf16x8* __restrict__ xp, int MB) {
     int idx = blockIdx.x * blockDim.x + threadIdx.x;
     int ng = d / 8;
     if (idx >= H * B * ng) return;
     int grp = idx % ng, b = (idx / ng) % B, i = idx / (ng * B);
     float z[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    const int nsplit = part_count(pv, i * d + grp * 8);
     for (int sp = 0; sp < nsplit; ++sp) {
-        const float* p = part + (size_t)sp * split_stride + (size_t)b * ldp + (size_t)i * d + grp * 8;
+        const float* p = pv.base + (size_t)sp * pv.slot_stride + (size_t)b * pv.ld + (size_t)i * d + grp * 8;
 #pragma unroll
         for (int e = 0; e < 8; ++e) z[e] += p[e];
     }
@@ -286,9 +299,8 @@ __global__ void k_medusa_act(const float* __restrict__ part, int nsplit, size_t 
     xp[u + XPART / 8] = lo;
 }
 
-void launch_medusa_act(const float* part, int nsplit, size_t split_stride, int ldp, const float* h_rows,
-                       const MedusaBias& bias, int B, int H, int d, void* x_packed, int MB, hipStream_t s) {
+void launch_medusa_act(PartView pv, const float* h_rows, const MedusaBias& bias, int B, int H, int d, void* x_packed,
+                       int MB, hipStream_t s) {
     int total = H * B * (d / 8);
-    hipLaunchKernelGGL(k_medusa_act, dim3((total + 255) / 256), dim3(256), 0, s, part, nsplit, split_stride, ldp,
-                       h_rows, bias, B, H, d, (bf16x8*)x_packed, MB);
+    hipLaunchKernelGGL(k_medusa_act, dim3((total + 255) / 256), dim3(256), 0, s, pv, h_rows, bias, B, H, d, (bf16x8*)x_packed, MB);
 }

@@ -10,7 +10,7 @@
 //                                            part 0 = bf16(x), part 1 = bf16(x - part 0): the
 //                                            activations enter the MFMAs as a two-term bf16
 //                                            expansion (about 16 mantissa bits), see gemm.hip
-//   packed weight      W[nb][kb][lane][8]    element (out n, in k):  nb = n/32, kb = k/16,
+//   packed weight      W[kb][nb][lane][8]    element (out n, in k):  nb = n/32, kb = k/16,
 //                                            lane = n%32 + 32*((k/8)&1), slot = k%8
 //   key block (32 rows of one head)          K[kk][lane][8]: row c, dim e: kk = e/16,
 //                                            lane = c%32 + 32*((e/8)&1), slot = e%8
@@ -75,6 +75,30 @@ struct RowTable {
     float2* cs;        // [M][head_dim/2] (cos, sin) of the rotary angle
 };
 
+// Partial results of a GEMM whose contraction was divided over several workgroups: the
+// consumer sums `count(col)` slots. cnt == NULL means every column has nmax slots.
+struct PartView {
+    const float* base;
+    size_t slot_stride;      // floats between slots
+    int ld;                  // floats between rows
+    const int32_t* cnt;      // [ceil(ld / group_cols)] slots per column group, or NULL
+    int group_cols;
+    int nmax;
+};
+#ifdef __HIPCC__
+static __device__ inline int part_count(const PartView& p, int col) { return p.cnt ? p.cnt[col / p.group_cols] : p.nmax; }
+#endif
+
+// How one GEMM shape is launched (made once per shape at model creation).
+struct GemmPlan {
+    int MB, KB, NB;
+    int kind;                // 0: uniform split-K grid, 1: balanced contraction streaming (stream-K)
+    int nsplit;              // kind 0
+    int G, NG;               // kind 1: workgroups, 256-column groups
+    int slots;               // slots the output buffer must hold
+    int32_t* cnt_dev;        // kind 1: [NG] contributors per column group (device), else NULL
+};
+
 #define SD_MAX_BATCH 32
 #define SD_MAX_MEDUSA 15
 struct ChainArgs { int32_t off[SD_MAX_BATCH]; int32_t len[SD_MAX_BATCH]; };
@@ -90,10 +114,13 @@ struct VerifyArgs {
 
 // ---- launchers (defined in the kernel translation units) ----------------------------------
 // All take a stream; all sizes have been validated by the caller.
-void launch_pack_weight(const void* src, void* dst, int N, int K, int nb_offset, int KB, hipStream_t s);
-void launch_gemm(const void* Xp, const void* Wp, float* out, int MB, int KB, int NB, int ldo,
-                 int nsplit, size_t split_stride, hipStream_t s);
-int gemm_choose_split(int MB, int KB, int NB);
+void launch_pack_weight(const void* src, void* dst, int N, int K, int nb_offset, int NBdst, int KB, hipStream_t s);
+// fills every field of the plan except cnt_dev; cnt_host receives the per-group counts (kind 1)
+void gemm_plan_make(GemmPlan* p, int MB, int KB, int NB, int32_t* cnt_host /*[>= ceil(NB/8)]*/);
+// out must hold plan.slots * (MB*32) * (NB*32) floats; zfrag: 1 KiB of zeros (device);
+// returns the view consumers read
+PartView launch_gemm(const GemmPlan& p, const void* Xp, const void* Wp, const void* zfrag, float* out, hipStream_t s);
+void launch_reduce_slots(PartView pv, float* dst, int rows, hipStream_t s);
 
 void launch_build_rows_tree(RowTable rt, const int32_t* parent, const int32_t* depth, const int32_t* rank,
                             const int32_t* root_tok, const int32_t* cand, const int32_t* kv_len,
@@ -102,21 +129,19 @@ void launch_build_rows_tree(RowTable rt, const int32_t* parent, const int32_t* d
 void launch_build_rows_chain(RowTable rt, const int32_t* tokens, const ChainArgs& ca, const int32_t* kv_len,
                              int B, int Tp, int hd, float theta, const void* embed, int d, int V, float* x,
                              hipStream_t s);
-void launch_norm_pack(float* x, const float* part, int nsplit, size_t split_stride, int ldp,
-                      const void* gain, float eps, void* xn_packed, float* hf_out,
+void launch_norm_pack(float* x, PartView pv, const void* gain, float eps, void* xn_packed, float* hf_out,
                       int M, int d, int MB, const int32_t* gather, hipStream_t s);
-void launch_rope_kv(const float* part, int nsplit, size_t split_stride, int ldp, RowTable rt,
-                    void* q_packed, void* kt, void* vt, int B, int Tp, int nh, int hd, hipStream_t s);
+void launch_rope_kv(PartView pv, RowTable rt, void* q_packed, void* kt, void* vt, int B, int Tp, int nh, int hd,
+                    hipStream_t s);
 void launch_tree_attn(const void* q_packed, const void* kc, const void* vc, const void* kt, const void* vt,
                       const int32_t* kv_len, const uint32_t* anc, float* opart, float2* mlpart,
                       int B, int nh, int hd, int Tp, int cap_blocks, int nchunks, int blocks_per_chunk,
                       hipStream_t s);
 void launch_attn_merge(const float* opart, const float2* mlpart, void* x_packed, int B, int nh, int hd,
                        int Tp, int nparts, int MB, hipStream_t s);
-void launch_swiglu_pack(const float* part, int nsplit, size_t split_stride, int ldp, int F, int Fpad,
-                        void* act_packed, int M, int MB, hipStream_t s);
-void launch_medusa_act(const float* part, int nsplit, size_t split_stride, int ldp, const float* h_rows,
-                       const MedusaBias& bias, int B, int H, int d, void* x_packed, int MB, hipStream_t s);
+void launch_swiglu_pack(PartView pv, int F, int Fpad, void* act_packed, int M, int MB, hipStream_t s);
+void launch_medusa_act(PartView pv, const float* h_rows, const MedusaBias& bias, int B, int H, int d,
+                       void* x_packed, int MB, hipStream_t s);
 void launch_argmax(const float* logits, int ld, int V, int32_t* am, int B, int T, int Tp, hipStream_t s);
 void launch_topk(const float* logits, int ld, int V, int k, int32_t* out, int B, int H, uint32_t seq_mask,
                  hipStream_t s);
