@@ -27,9 +27,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
-# HBM bytes per GEMM launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, calibrated
-# against a copy kernel of known size (see profiles/); None until measured for this build.
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = None
+# HBM-side bytes per k_gemm_sk<2> launch (read + written) from two rocprofv3 --pmc runs
+# (FETCH_SIZE, WRITE_SIZE), scaled by what the same counters read for sd_calib's 1 GiB copy
+# kernel (1 FETCH unit = 2 KiB, 1 WRITE unit = 1 KiB): profiles/k_gemm_sk_7b_pmc_traffic.txt.
+# Only valid for the default workload; other workloads report null.
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = 124.6e6
 
 
 def parse():
@@ -73,7 +75,7 @@ def main():
     cpu_keep = None
     if not args.no_cpu_baseline:
         names = ["embed", "lm_head", "final_norm"] + [f"medusa{i}.{x}" for i in range(H) for x in "wb"]
-        names += [n for n in weights if n.startswith("l0.") or n.startswith("l1.")]
+        names += [n for n in weights if n.split(".")[0] in ("l0", "l1", "l2", "l3", "l4", "l5")]
         cpu_keep = {n: weights[n].cpu() for n in names}
     model = sd.Model(shape, weights, max_rows=max(64, ((T + 31) // 32) * 32))
     del weights
@@ -190,9 +192,9 @@ def main():
         "prefill_tokens_per_s": prompt_len / prefill_s,
         "step_hbm_frac": step_bytes / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9),
         "diverged_resets": state["diverged"],
-        "roofline": {"kernel": "k_gemm_stream (weight-streaming MFMA GEMM, all projections)", "bound": "hbm",
+        "roofline": {"kernel": "k_gemm_sk (weight-streaming MFMA GEMM, all projections)", "bound": "hbm",
                      "achieved": gemm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gemm_gbs / HBM_PEAK_GBS,
-                     "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH, "avg_launch_us": gemm_avg_us,
+                     "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH if (args.workload == "7b" and args.layers is None) else None, "avg_launch_us": gemm_avg_us,
                      "launches_per_step": g["launches"] / args.profile_steps,
                      "algorithmic_bytes_per_launch": g["bytes"] / max(g["launches"], 1)},
         "attention": {"kernel": "k_tree_attn", "achieved_GBs": attn_gbs, "frac_hbm": attn_gbs / HBM_PEAK_GBS,
@@ -208,8 +210,10 @@ def cpu_baseline(wl, shape, cpu_keep, T, tree_np, stop, n_cache):
     from oracle import specdec_oracle as orc
 
     w64 = {n: t.double().numpy() for n, t in cpu_keep.items()}
-    times = {}
-    for L in (1, 2):
+    depth_hi = min(6, shape.n_layers)
+    depth_lo = max(1, depth_hi // 2)
+
+    def one_step(L):
         sh = shape.with_layers(L)
         kv = orc.KVCache.empty(sh, n_cache + shape.n_medusa + 2)
         for l in range(L):
@@ -221,16 +225,25 @@ def cpu_baseline(wl, shape, cpu_keep, T, tree_np, stop, n_cache):
         st = orc.DecodeState(kv, root_tok=11, cand=cand)
         t0 = time.perf_counter()
         orc.spec_step(w64, sh, st, tree_np, stop)
-        times[L] = time.perf_counter() - t0
-    per_layer = max(times[2] - times[1], 1e-9)
-    rest = max(times[1] - per_layer, 0.0)
+        return time.perf_counter() - t0
+
+    one_step(1)                                      # warm-up: BLAS threads, page faults
+    reps = 3
+    t_lo = sorted(one_step(depth_lo) for _ in range(reps))[reps // 2]
+    t_hi = sorted(one_step(depth_hi) for _ in range(reps))[reps // 2]
+    if depth_hi > depth_lo:
+        per_layer = max((t_hi - t_lo) / (depth_hi - depth_lo), 1e-9)
+        rest = max(t_lo - depth_lo * per_layer, 0.0)
+    else:
+        per_layer, rest = t_hi / depth_hi, 0.0
     full = rest + shape.n_layers * per_layer
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     return {"value": T / full, "unit": "tokens/s", "cores": threads, "kind": "oracle",
-            "sample": f"one speculative step ({T}-node tree over a {n_cache}-row synthetic cache) timed at 1 and 2 "
-                      f"of the {shape.n_layers} layers (full width, LM head and draft heads included); "
-                      f"per-layer time {per_layer:.3f} s extrapolated to {shape.n_layers} layers: {full:.2f} s/step",
-            "seconds_measured": times[1] + times[2]}
+            "sample": f"one speculative step ({T}-node tree over a {n_cache}-row synthetic cache) timed at {depth_lo} "
+                      f"and {depth_hi} of the {shape.n_layers} layers (full width, LM head and draft heads included, "
+                      f"median of {reps}); per-layer time {per_layer:.3f} s, rest {rest:.3f} s, extrapolated to "
+                      f"{shape.n_layers} layers: {full:.2f} s/step",
+            "seconds_measured": reps * (t_lo + t_hi)}
 
 
 if __name__ == "__main__":

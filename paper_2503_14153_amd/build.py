@@ -30,8 +30,13 @@ def build(verbose: bool = True, jobs: int = 5) -> str:
     out = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if out.returncode != 0:
         raise RuntimeError("link failed:\n" + out.stdout)
+    calib = os.path.join(HERE, "sd_calib")
+    cmd = [hipcc, *[f for f in FLAGS if f != "-fPIC"], os.path.join(CSRC, "calib.hip"), "-o", calib]
+    out = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if out.returncode != 0:
+        raise RuntimeError("hipcc failed on calib.hip:\n" + out.stdout)
     if verbose:
-        print(f"built {LIB}")
+        print(f"built {LIB} and {calib}")
     return LIB
 
 
