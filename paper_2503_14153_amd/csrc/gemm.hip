@@ -383,6 +383,10 @@ void gemm_plan_make(GemmPlan* p, int MB, int KB, int NB, int32_t* cnt_host) {
     const int U = p->NG * KB;
     int G = U / 16;                                   // at least one ring length of steps each
     if (G > SK_MAX_WG) G = SK_MAX_WG;
+    // A small matrix (the O projection: 33 MB at the 7B shape) gains nothing from the last
+    // doubling of workgroups but pays for it in partial tiles (measured 13.5 us with 128
+    // workgroups / 8 slots against 14.9 us with 256 / 16, and the consumer reads half as much).
+    if (G == SK_MAX_WG && U <= 16 * SK_MAX_WG * 2) G = SK_MAX_WG / 2;
     if (G < 1) G = 1;
     p->G = G;
     auto ustart = [&](int gg) { return (int)(((long long)gg * U) / G); };

@@ -34,6 +34,7 @@ class Report:
     near_tie_flips: int = 0
     cand_near_ties: int = 0
     accepted: list = field(default_factory=list)
+    raw: list = field(default_factory=list)
     kv_max_abs: float = 0.0
     head_max_abs: float = 0.0
 
@@ -76,6 +77,33 @@ def resync_kv(kv: sd.KVCache, st: orc.DecodeState, shape, row0: int):
     kv.set_len([n])
 
 
+def check_step_outputs(out, b: int, rec, tree_np, stop_np, fallback: str, shape, rep: Report):
+    """Compare sequence b of one GPU step with the oracle's record of the same step.
+
+    Logits within tolerance; arg-max equal except at oracle near-ties; accepted length, tokens
+    and source slots bit-exact against the oracle's rule applied to the arg-max the GPU saw.
+    Returns (accepted length, accepted chain) as the GPU must have computed them."""
+    parent, depth, rank = tree_np
+    check_logits(out.logits[b].cpu().numpy().astype(np.float64), rec.logits, rep)
+    am = out.argmax[b].cpu().numpy()
+    flips = np.nonzero(am != rec.am)[0]
+    for j in flips:
+        assert rec.margin[j] < NEAR_TIE, f"arg-max differs at node {j} with oracle margin {rec.margin[j]:.4g}"
+    rep.near_tie_flips += len(flips)
+    ok, chain = orc.greedy_accept(rec.tok, am, parent, depth)
+    n_acc = orc.fragment_cut([rec.tok[c] for c in chain], stop_np, fallback)
+    W = shape.n_medusa + 1
+    want_tok = np.full(W, -1, np.int32)
+    want_slot = np.full(W, -1, np.int32)
+    want_tok[:n_acc] = [rec.tok[c] for c in chain[:n_acc]]
+    want_slot[:n_acc] = chain[:n_acc]
+    assert int(out.n_accept[b]) == n_acc and int(out.n_accept_raw[b]) == len(chain)
+    rep.raw.append(len(chain))
+    assert np.array_equal(out.tokens[b].cpu().numpy(), want_tok)
+    assert np.array_equal(out.src_slots[b].cpu().numpy(), want_slot)
+    return n_acc, chain
+
+
 def lockstep_spec(model: sd.Model, kv: sd.KVCache, tree: sd.Tree, tree_np, stop_np: np.ndarray,
                   stop_words: torch.Tensor, w64: dict, shape, st: orc.DecodeState, n_steps: int, fallback: str,
                   cand_fn=None, kv_tol: float = 0.05, rep: Report | None = None) -> Report:
@@ -89,25 +117,10 @@ def lockstep_spec(model: sd.Model, kv: sd.KVCache, tree: sd.Tree, tree_np, stop_
         out = sd.spec_step(model, kv, tree, stop_words, want_logits=True, want_argmax=True, want_head_logits=True)
         rec = orc.spec_step(w64, shape, st, tree_np, stop_np, fallback, cand_override=cand)
         torch.cuda.synchronize()
-        check_logits(out.logits[0].cpu().numpy().astype(np.float64), rec.logits, rep)
-        am = out.argmax[0].cpu().numpy()
-        flips = np.nonzero(am != rec.am)[0]
-        for j in flips:
-            assert rec.margin[j] < NEAR_TIE, f"arg-max differs at node {j} with oracle margin {rec.margin[j]:.4g}"
-        rep.near_tie_flips += len(flips)
-        # integer outputs: bit-exact against the oracle's rule applied to the arg-max the GPU saw
-        ok, chain = orc.greedy_accept(rec.tok, am, parent, depth)
-        n_acc = orc.fragment_cut([rec.tok[c] for c in chain], stop_np, fallback)
-        W = shape.n_medusa + 1
-        want_tok = np.full(W, -1, np.int32)
-        want_slot = np.full(W, -1, np.int32)
-        want_tok[:n_acc] = [rec.tok[c] for c in chain[:n_acc]]
-        want_slot[:n_acc] = chain[:n_acc]
-        assert int(out.n_accept[0]) == n_acc and int(out.n_accept_raw[0]) == len(chain)
-        assert np.array_equal(out.tokens[0].cpu().numpy(), want_tok)
-        assert np.array_equal(out.src_slots[0].cpu().numpy(), want_slot)
+        n_acc, chain = check_step_outputs(out, 0, rec, tree_np, stop_np, fallback, shape, rep)
         assert kv.len() == [n_old + n_acc]
         rep.accepted.append(n_acc)
+        am = out.argmax[0].cpu().numpy()
         same_path = n_acc == rec.n_accept and chain[:n_acc] == list(rec.src_slots)
         if same_path:
             compare_kv_rows(kv, st, shape, n_old, n_old + n_acc, rep, kv_tol)
