@@ -44,6 +44,7 @@ def parse():
     ap.add_argument("--draft", default="planted", choices=["planted", "random"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=32)
+    ap.add_argument("--graph", action="store_true", help="replay captured HIP graphs instead of launching every kernel (measured: no gain, the step is not host-bound)")
     return ap.parse_args()
 
 
@@ -129,6 +130,8 @@ def main():
         torch.empty(1, dtype=torch.int32, device="cuda"), torch.empty((1, H + 1), dtype=torch.int32, device="cuda"),
         torch.empty((1, H + 1), dtype=torch.int32, device="cuda"), torch.empty(1, dtype=torch.int32, device="cuda"))
     tok_host = torch.empty((1, H + 1), dtype=torch.int32).pin_memory()
+    forced = torch.zeros((1, H, k), dtype=torch.int32, device="cuda")     # fixed buffer: graphs replay on it
+    model.set_graph_mode(args.graph)
     state = {"e": 0, "emitted": 0, "diverged": 0, "resets": 0}
 
     def run_steps(n):
@@ -138,7 +141,8 @@ def main():
                 reset()
                 state["resets"] += 1
                 e = state["e"] = 0
-            sd.spec_step(model, kv, tree, stop_words, forced_cand=table_dev[e], out=out)
+            forced.copy_(table_dev[e: e + 1])
+            sd.spec_step(model, kv, tree, stop_words, forced_cand=forced, out=out)
             tok_host.copy_(out.tokens, non_blocking=True)
             n_now = kv.len()[0]                     # synchronises the stream
             n_acc = n_now - prompt_len - e
@@ -191,7 +195,7 @@ def main():
         "greedy_tokens_per_s": n_timed / greedy_s, "speedup_vs_greedy": (emitted / elapsed) / (n_timed / greedy_s),
         "prefill_tokens_per_s": prompt_len / prefill_s,
         "step_hbm_frac": step_bytes / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9),
-        "diverged_resets": state["diverged"],
+        "diverged_resets": state["diverged"], "hip_graphs": args.graph,
         "roofline": {"kernel": "k_gemm_sk (weight-streaming MFMA GEMM, all projections)", "bound": "hbm",
                      "achieved": gemm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gemm_gbs / HBM_PEAK_GBS,
                      "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH if (args.workload == "7b" and args.layers is None) else None, "avg_launch_us": gemm_avg_us,

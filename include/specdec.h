@@ -168,6 +168,15 @@ int sd_verify_tree(const sd_tree* tree, int32_t batch, int32_t n_medusa, int32_t
                    int32_t* n_accept, int32_t* n_accept_raw, int32_t* tokens, int32_t* src_slots,
                    void* stream);
 
+/* Graph mode (off by default). When on, sd_spec_step / sd_greedy_step capture their kernel
+ * sequence into a HIP graph the first time a given combination of (cache, tree, split-KV
+ * geometry, stop mask, output and candidate pointers) is seen and replay it afterwards: one
+ * launch per step instead of several hundred. The caller must then keep those pointers'
+ * memory alive and, to benefit, reuse the same buffers from step to step (e.g. copy planted
+ * candidates into one fixed buffer). Results are identical to the eager path. Graphs are
+ * not used while sd_profile_begin is active.                                               */
+int sd_set_graph_mode(sd_model* m, int32_t on);
+
 /* ---- measurement ---------------------------------------------------------------------------
  * Between sd_profile_begin and sd_profile_end every launch of the two bandwidth-bound kernel
  * classes is bracketed by HIP events on the stream it is launched on (up to max_launches

@@ -14,7 +14,7 @@ EXPORTED_SYMBOLS = [
     "sd_model_create", "sd_model_destroy", "sd_kv_bytes", "sd_kv_create", "sd_kv_destroy", "sd_kv_len",
     "sd_kv_set_len", "sd_kv_write_rows", "sd_kv_read_rows", "sd_kv_set_draft", "sd_kv_get_draft",
     "sd_tree_create", "sd_tree_destroy", "sd_prefill", "sd_spec_step", "sd_greedy_step", "sd_verify_tree",
-    "sd_profile_begin", "sd_profile_end", "sd_last_error", "sd_version",
+    "sd_set_graph_mode", "sd_profile_begin", "sd_profile_end", "sd_last_error", "sd_version",
 ]
 
 SD_ERR = {-1: "SD_ERR_NULL", -2: "SD_ERR_SHAPE", -3: "SD_ERR_BAD_TREE", -4: "SD_ERR_KV_FULL", -5: "SD_ERR_HIP",
@@ -81,6 +81,7 @@ def lib() -> C.CDLL:
         L.sd_greedy_step.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(_StepIO), C.c_void_p]
         L.sd_verify_tree.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32] + [C.c_void_p] * 8
         L.sd_profile_begin.argtypes = [C.c_void_p, C.c_int32]
+        L.sd_set_graph_mode.argtypes = [C.c_void_p, C.c_int32]
         L.sd_profile_end.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64),
                                      C.POINTER(C.c_double)]
         _LIB = L
@@ -134,6 +135,9 @@ class Model:
                      C.cast(mw, C.POINTER(C.c_void_p)), C.cast(mb, C.POINTER(C.c_void_p)))
         self.handle = C.c_void_p()
         _check(lib().sd_model_create(C.byref(self.cfg), C.byref(w), max_rows, _stream(), C.byref(self.handle)))
+
+    def set_graph_mode(self, on: bool):
+        _check(lib().sd_set_graph_mode(self.handle, 1 if on else 0))
 
     def profile_begin(self, max_launches: int = 65536):
         _check(lib().sd_profile_begin(self.handle, max_launches))

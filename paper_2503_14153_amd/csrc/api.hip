@@ -72,6 +72,11 @@ struct sd_model {
     const void* zfrag;                       // 1 KiB of zeros
     size_t part_floats;
     int max_parts;
+    // HIP-graph mode: one captured graph per distinct launch sequence of a step
+    struct StepGraph { std::vector<uint64_t> key; hipGraphExec_t exec; };
+    bool use_graphs = false;
+    std::vector<StepGraph> graphs;
+    hipStream_t cap_stream = nullptr;      // capture happens here: the caller's stream may be the null stream
     std::vector<GemmPlan> plans;             // one per (row blocks, K blocks, N blocks) in use
     int32_t* plan_cnt = nullptr;             // device: the plans' per-group slot counts
     const GemmPlan& plan(int MB, int KB, int NB) const {
@@ -330,8 +335,17 @@ extern "C" int sd_profile_end(sd_model* m, void* stream, double* ms_total, int64
     return SD_OK;
 }
 
+extern "C" int sd_set_graph_mode(sd_model* m, int32_t on) {
+    if (!m) return fail(SD_ERR_NULL, "sd_set_graph_mode: NULL model");
+    m->use_graphs = on != 0;
+    return SD_OK;
+}
+
 extern "C" int sd_model_destroy(sd_model* m) {
     if (!m) return SD_OK;
+    for (sd_model::StepGraph& g : m->graphs) hipGraphExecDestroy(g.exec);
+    m->graphs.clear();
+    if (m->cap_stream) { hipStreamDestroy(m->cap_stream); m->cap_stream = nullptr; }
     prof_free(m);
     hipFree(m->arena);
     hipFree(m->work);
@@ -662,8 +676,10 @@ static int step_common(sd_model* m, sd_kv* kv, const int32_t* parent, const int3
     int32_t* n_accept = io->n_accept ? io->n_accept : kv->i_nacc;
     int32_t* tokens = io->tokens ? io->tokens : kv->i_tokens;
     int32_t* slots = io->src_slots ? io->src_slots : kv->i_slots;
-
     const int32_t* cand = io->forced_cand ? io->forced_cand : kv->cand;
+
+    // everything the launch sequence depends on besides device-resident state
+    auto enqueue = [&](hipStream_t s) {
     launch_build_rows_tree(m->rt, parent, depth, rank, kv->root_tok, cand, kv->kv_len, B, T, Tp, H, c.topk, c.head_dim,
                            c.rope_theta, m->embed, c.d_model, c.vocab, m->x, s);
     PartView prev = run_layers(m, kv, B, Tp, n_hi, s);
@@ -680,6 +696,40 @@ static int step_common(sd_model* m, sd_kv* kv, const int32_t* parent, const int3
     launch_kv_commit(m->kt, m->vt, kv->kc, kv->vc, slots, n_accept, kv->n_old, c.n_layers, B, c.n_heads, c.head_dim,
                      Tp / 32, kv->cap_blocks, H + 1, H + 1, s);
     run_draft_heads(m, kv, B, 0xffffffffu, io->head_logits, s);
+    };
+
+    if (m->use_graphs && !m->prof.on) {
+        int nchunks, bpc;
+        attn_geometry(m, B, Tp, n_hi, &nchunks, &bpc);
+        std::vector<uint64_t> key = {(uint64_t)(uintptr_t)kv, (uint64_t)(uintptr_t)parent, (uint64_t)T, (uint64_t)Tp,
+                                     (uint64_t)nchunks, (uint64_t)bpc, (uint64_t)(uintptr_t)stop_mask,
+                                     (uint64_t)(uintptr_t)n_accept, (uint64_t)(uintptr_t)tokens,
+                                     (uint64_t)(uintptr_t)slots, (uint64_t)(uintptr_t)io->n_accept_raw,
+                                     (uint64_t)(uintptr_t)io->logits, (uint64_t)(uintptr_t)io->argmax,
+                                     (uint64_t)(uintptr_t)io->head_logits, (uint64_t)(uintptr_t)cand};
+        hipGraphExec_t exec = nullptr;
+        for (const sd_model::StepGraph& g : m->graphs)
+            if (g.key == key) { exec = g.exec; break; }
+        if (!exec) {
+            if (m->graphs.size() >= 64) {              // bounded cache: start over
+                for (sd_model::StepGraph& g : m->graphs) hipGraphExecDestroy(g.exec);
+                m->graphs.clear();
+            }
+            hipGraph_t graph = nullptr;
+            if (!m->cap_stream) HIP_TRY(hipStreamCreateWithFlags(&m->cap_stream, hipStreamNonBlocking));
+            HIP_TRY(hipStreamBeginCapture(m->cap_stream, hipStreamCaptureModeThreadLocal));
+            enqueue(m->cap_stream);
+            hipError_t e = hipStreamEndCapture(m->cap_stream, &graph);
+            if (e != hipSuccess) return fail(SD_ERR_HIP, "%s: graph capture failed: %s", who, hipGetErrorString(e));
+            e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+            hipGraphDestroy(graph);
+            if (e != hipSuccess) return fail(SD_ERR_HIP, "%s: hipGraphInstantiate: %s", who, hipGetErrorString(e));
+            m->graphs.push_back({key, exec});
+        }
+        HIP_TRY(hipGraphLaunch(exec, s));
+    } else {
+        enqueue(s);
+    }
     HIP_TRY(hipGetLastError());
     for (int b = 0; b < B; ++b) kv->len_hi[b] += (T == 1) ? 1 : H + 1;
     return SD_OK;

@@ -233,7 +233,6 @@ __global__ __launch_bounds__(512, 2) void k_gemm_sk(const bf16x8* __restrict__ X
         return Wp + ((size_t)I.kb * NB + nb) * 64 + lane;
     };
     const size_t wstep = (size_t)NB * 64;
-    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
     // Every load below is unconditional and its result is used as loaded: a fragment past the
     // end of a segment is fetched from a 1 KiB page of zeros (zfrag) by selecting the ADDRESS.
     // A branch around a load, or a select on its result, makes the compiler wait for the whole

@@ -189,3 +189,38 @@ def test_errors_leave_state_untouched(sd):
     with pytest.raises(sd.SpecDecError) as e:
         sd.prefill(model, kv, torch.from_numpy(prompt).cuda(), [20])
     assert e.value.name == "SD_ERR_KV_FULL" and kv.len() == [20]
+
+
+def test_graph_mode_replays_equal_eager(sd):
+    """Graph mode: the captured step, replayed many times with eager work and synchronisations
+    in between, gives bit-identical outputs to the eager path (same deterministic kernels)."""
+    shape = _bf16_shape("tiny")
+    lockstep, weights, w64, model, kv, prompt, stop, words, tree_np, tree = _setup(sd, shape, 40, 256, 16)
+    sd.prefill(model, kv, torch.from_numpy(prompt).cuda(), [40])
+    root0, cand0 = kv.get_draft()
+    root0, cand0 = root0.clone(), cand0.clone()
+    rng = np.random.default_rng(3)
+    cands = [np.stack([rng.permutation(shape.vocab)[: shape.topk] for _ in range(shape.n_medusa)]).astype(np.int32)
+             for _ in range(12)]
+    forced = torch.zeros((1, shape.n_medusa, shape.topk), dtype=torch.int32, device="cuda")
+
+    def run(n_steps):
+        kv.set_len([40])
+        kv.set_draft(root0, cand0)
+        res = []
+        out = sd.spec_step(model, kv, tree, words, want_logits=True, want_argmax=True, forced_cand=forced)
+        for i in range(n_steps):
+            forced.copy_(torch.from_numpy(cands[i])[None])
+            sd.spec_step(model, kv, tree, words, forced_cand=forced, out=out)
+            torch.cuda.synchronize()
+            res.append((out.logits.clone(), out.tokens.clone(), out.n_accept.clone(), out.src_slots.clone(), kv.len()))
+            _ = (out.logits * 2).sum().item()              # unrelated eager work between replays
+        return res
+
+    eager = run(12)
+    model.set_graph_mode(True)
+    graph = run(12)
+    model.set_graph_mode(False)
+    for a, b in zip(eager, graph):
+        assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1]) and torch.equal(a[2], b[2]) and torch.equal(a[3], b[3])
+        assert a[4] == b[4]
