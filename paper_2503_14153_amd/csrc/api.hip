@@ -542,23 +542,39 @@ static PartView run_gemm(sd_model* m, const void* Xp, const void* Wp, float* out
     return pv;
 }
 
-static void attn_geometry(const sd_model* m, int B, int Tp, int n_hi, int* nchunks, int* bpc) {
+// How the attention of one step is cut into workgroups (one resident per compute unit: the kernel
+// takes the whole LDS). A group is one (sequence, head, query-block group); it gets `ncparts` cache
+// parts of `per` 32-row blocks each, sized from the host's bound on the sequence lengths, and the
+// tree blocks go to a part of their own while the chip has room for it (short contexts) or to the
+// last cache part (long contexts).
+struct AttnGeom { int ncparts, per, tree_sep, nparts; };
+static AttnGeom attn_geometry(const sd_model* m, int B, int Tp, int n_hi) {
     const int nblk = ceil_div(n_hi, 32);
     const int TB = Tp / 32, TG = (TB % 2 == 0) ? TB / 2 : TB;
-    const int waves_per_chunk = B * m->cfg.n_heads * TG;
-    int want = ceil_div(2048, waves_per_chunk);
-    if (want > m->max_parts - 1) want = m->max_parts - 1;
-    if (want > ceil_div(nblk, 4)) want = ceil_div(nblk, 4);   // at least 128 cache rows per part
-    if (want < 1) { *nchunks = 0; *bpc = 1; return; }
-    *bpc = ceil_div(nblk, want);
-    *nchunks = ceil_div(nblk, *bpc);
+    const int groups = B * m->cfg.n_heads * TG;
+    int P = 256 / groups;                                  // parts per group that fit the chip at once
+    if (P < 1) P = 1;
+    if (P > m->max_parts) P = m->max_parts;
+    AttnGeom g;
+    if (nblk == 0) { g.ncparts = 0; g.per = 1; g.tree_sep = 1; g.nparts = 1; return g; }
+    const int by_work = ceil_div(nblk, 4);                 // at least one block per wave
+    if (P >= 2 && nblk <= 8 * (P - 1)) {                   // short: at most two blocks per wave, tree beside
+        g.tree_sep = 1;
+        g.ncparts = P - 1 < by_work ? P - 1 : by_work;
+    } else {
+        g.tree_sep = 0;
+        g.ncparts = P < by_work ? P : by_work;
+    }
+    g.per = ceil_div(nblk, g.ncparts);
+    g.ncparts = ceil_div(nblk, g.per);
+    g.nparts = g.ncparts + g.tree_sep;
+    return g;
 }
 
 static PartView run_layers(sd_model* m, sd_kv* kv, int B, int Tp, int n_hi, hipStream_t s) {
     const sd_config& c = m->cfg;
     const int M = B * Tp, MB = pow2_blocks(M), d = c.d_model, nh = c.n_heads, hd = c.head_dim, TB = Tp / 32;
-    int nchunks, bpc;
-    attn_geometry(m, B, Tp, n_hi, &nchunks, &bpc);
+    const AttnGeom ag = attn_geometry(m, B, Tp, n_hi);
     PartView prev = {nullptr, 0, d, nullptr, 256, 0};
     const size_t t_stride = (size_t)B * nh * TB * 32 * hd;     // elements per layer of tree scratch
     for (int l = 0; l < c.n_layers; ++l) {
@@ -571,9 +587,9 @@ static PartView run_layers(sd_model* m, sd_kv* kv, int B, int Tp, int n_hi, hipS
         // algorithmic bytes: one read of K and V of the committed rows (upper bound n_hi) + tree rows
         int pa = prof_start(m, PROF_ATTN, (double)B * (n_hi + Tp) * 2.0 * d * 2.0, s);
         launch_tree_attn(m->q, kv->kc + l * kv->layer_stride, kv->vc + l * kv->layer_stride, kt, vt, kv->kv_len,
-                         m->rt.anc, m->opart, m->mlpart, B, nh, hd, Tp, kv->cap_blocks, nchunks, bpc, s);
+                         m->rt.anc, m->opart, m->mlpart, B, nh, hd, Tp, kv->cap_blocks, ag.ncparts, ag.per, ag.tree_sep, s);
         prof_stop(m, pa, s);
-        launch_attn_merge(m->opart, m->mlpart, m->attn_x, B, nh, hd, Tp, nchunks + 1, MB, s);
+        launch_attn_merge(m->opart, m->mlpart, m->attn_x, B, nh, hd, Tp, ag.nparts, MB, s);
         PartView po = run_gemm(m, m->attn_x, lw.wo, m->part, MB, m->KBd, m->NBo, d, s);
         launch_norm_pack(m->x, po, lw.ffn_norm, c.rms_eps, m->xn, nullptr, M, d, MB, nullptr, s);
         PartView pg = run_gemm(m, m->xn, lw.wgu, m->part, MB, m->KBd, m->NBgu, 2 * c.d_ffn, s);
@@ -699,10 +715,9 @@ static int step_common(sd_model* m, sd_kv* kv, const int32_t* parent, const int3
     };
 
     if (m->use_graphs && !m->prof.on) {
-        int nchunks, bpc;
-        attn_geometry(m, B, Tp, n_hi, &nchunks, &bpc);
+        const AttnGeom ag = attn_geometry(m, B, Tp, n_hi);
         std::vector<uint64_t> key = {(uint64_t)(uintptr_t)kv, (uint64_t)(uintptr_t)parent, (uint64_t)T, (uint64_t)Tp,
-                                     (uint64_t)nchunks, (uint64_t)bpc, (uint64_t)(uintptr_t)stop_mask,
+                                     (uint64_t)ag.ncparts, (uint64_t)(ag.per * 2 + ag.tree_sep), (uint64_t)(uintptr_t)stop_mask,
                                      (uint64_t)(uintptr_t)n_accept, (uint64_t)(uintptr_t)tokens,
                                      (uint64_t)(uintptr_t)slots, (uint64_t)(uintptr_t)io->n_accept_raw,
                                      (uint64_t)(uintptr_t)io->logits, (uint64_t)(uintptr_t)io->argmax,

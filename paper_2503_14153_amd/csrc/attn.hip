@@ -3,49 +3,148 @@
 // Every tree node attends all committed cache rows plus its own ancestors in the tree. The
 // cache part is a pure stream: K and V of each head are read once from HBM and reused by all
 // T queries of that head, so the kernel is HBM-bound and is organised around that stream:
-//   * keys and values are stored as ready-made MFMA fragments (see sd_internal.h), so a wave
-//     fetches a 32-row block with sixteen fully coalesced 1 KiB loads and no LDS transpose;
+//   * keys and values are stored as ready-made MFMA fragments (see sd_internal.h), so a
+//     32-row block is sixteen contiguous 1 KiB pieces that go from memory to LDS to the
+//     matrix core without a transpose or a register detour;
 //   * S^T = K Q^T puts query t in lane t%32, and the value rows inside a block are permuted
 //     so that exp(S) -- still in the accumulator registers -- already is the B operand of
 //     O^T = V^T P^T: no cross-lane traffic between the two products;
 //   * K and V are bf16 (the cache's storage type) but queries and probabilities are not: both
 //     enter their MFMAs as two-term bf16 expansions (hi + lo), paid for with matrix-core time
 //     that an HBM-bound kernel has to spare;
-//   * the cache range is split over workgroups (split-KV); partial (max, sum, O) triples are
-//     merged by a second small kernel, which also emits the packed bf16 operand of the
-//     O-projection.
+//   * the cache range is split over workgroups (split-KV) and over the four waves of each;
+//     the waves merge through LDS, the workgroups' partial (max, sum, O) triples are merged
+//     by a second small kernel, which also emits the packed bf16 operand of the O-projection.
 #include "sd_internal.h"
 
 #define NEG_INF (-__builtin_inff())
 
-// grid: x = part (0..nchunks-1 cache chunks, nchunks = the tree rows), y = head * TG + tg, z = seq
-// one wave per workgroup; TBW = query blocks (32 rows) per wave
+// grid: x = part, y = head * TG + tg (query-block group), z = sequence. Cache part p owns the
+// cache blocks [p*per, (p+1)*per) of the head. The tree blocks go to a part of their own (short
+// contexts: one more workgroup per head, running beside the others) or to the last cache part
+// (long contexts, where every workgroup slot of the chip is wanted for the stream).
+// One workgroup = 4 waves, one per SIMD; each wave takes a contiguous quarter of the part's
+// blocks, so it reads two plain sequential streams (its K blocks and its V blocks).
+//
+// K and V never pass through registers on their way in: every wave owns two 32-row slots in
+// LDS and fills them with direct global-to-LDS loads (one 1 KiB fragment per instruction, the
+// fragment layout in memory is the layout the MFMA reads). Block j+2 is requested as soon as
+// block j's slot has been multiplied, so between one and two blocks are always in flight per
+// wave while it works, at no cost in registers. These loads are issued from inline assembly
+// and waited for with explicit vmcnt values (they complete in issue order): 8 K loads then
+// 8 V loads per block, hence "at most 24 outstanding" = the block about to be used is there.
+// The first two blocks of every wave are requested before the sequence length is known (the
+// host's bound fixes the geometry; a block past the end is fetched, in bounds, and ignored).
+// The queries of the head sit in LDS as well (fetched the same way), shared by the four waves.
+//
+// The running maximum is only raised when a block's maximum exceeds it by more than 2^8: the
+// softmax is invariant to the reference point, exp2 of at most 8 cannot overflow anything, and
+// the accumulators are then rescaled a few times per stream instead of once per block.
+#define SD_LAZY_MAX 8.0f
+
+static __device__ __forceinline__ void lds_dma16(const void* src_lane, uint32_t lds_byte_addr) {
+    // lane i's 16 bytes land at lds_byte_addr + 16 * i
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :: "s"(lds_byte_addr), "v"(src_lane) : "memory");
+}
+// x *= alpha for an accumulator that lives in an AGPR (keeps the compiler from moving the whole
+// accumulator set to VGPRs and back around the rarely taken rescaling branch)
+static __device__ __forceinline__ void acc_scale(float& x, float alpha) {
+    float t;
+    asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\tv_accvgpr_write_b32 %0, %1"
+                 : "+a"(x), "=&v"(t) : "v"(alpha));
+}
+template <int N> static __device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
+
 template <int HD, int TBW>
-__global__ __launch_bounds__(64) void k_tree_attn(const bf16x8* __restrict__ Qp, const bf16x8* __restrict__ Kc,
-                                                  const bf16x8* __restrict__ Vc, const bf16x8* __restrict__ Kt,
-                                                  const bf16x8* __restrict__ Vt, const int32_t* __restrict__ kv_len,
-                                                  const uint32_t* __restrict__ anc, float* __restrict__ opart,
-                                                  float2* __restrict__ mlpart, int nh, int Tp, int cap_blocks,
-                                                  int nchunks, int blocks_per_chunk, float scale_log2) {
-    constexpr int KK = HD / 16;        // contraction steps of QK^T
+__global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp, const bf16x8* __restrict__ Kc,
+                                                   const bf16x8* __restrict__ Vc, const bf16x8* __restrict__ Kt,
+                                                   const bf16x8* __restrict__ Vt, const int32_t* __restrict__ kv_len,
+                                                   const uint32_t* __restrict__ anc, float* __restrict__ opart,
+                                                   float2* __restrict__ mlpart, int nh, int Tp, int cap_blocks,
+                                                   int ncparts, int per, int tree_sep, float scale_log2) {
+    constexpr int KK = HD / 16;        // contraction steps of QK^T = K fragments per block
     constexpr int EB = HD / 32;        // 32-wide output blocks of PV
+    constexpr int NV = 2 * EB;         // V fragments per block
+    constexpr int NL = KK + NV;        // loads per block
     constexpr int BLK = HD * 4;        // bf16x8 units per 32-row block
-    const int lane = threadIdx.x, g = lane >> 5, tl = lane & 31;
+    constexpr int QF = TBW * KK * 2;   // query fragments held in LDS
+    constexpr int QW = QF / 4;         // of which every wave fetches this many
+    constexpr int SLOT = NL * 64;      // bf16x8 units per slot (K then V)
+    constexpr int WAVE_UNITS = 2 * SLOT;
+    constexpr int NT = TBW * EB;       // 32x32 output tiles of one wave
+    static_assert(NT * 16 * 64 * 4 <= WAVE_UNITS * 16, "a wave's O must fit its own slots for the merge");
+    static_assert(4 * TBW * 2 * 64 * 4 <= QF * 1024, "merge scalars must fit the query area");
+    __shared__ __attribute__((aligned(1024))) bf16x8 lds[QF * 64 + 4 * WAVE_UNITS];
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, tl = lane & 31;
     const int part = blockIdx.x;
     const int TB = Tp / 32, TG = TB / TBW;
     const int h = blockIdx.y / TG, tg = blockIdx.y % TG;
     const int b = blockIdx.z;
-    const int n = kv_len[b];
-    const bool tree_part = part == nchunks;
+    bf16x8* qs = lds;
+    bf16x8* mine = lds + QF * 64 + wave * WAVE_UNITS;
+    const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) bf16x8*)lds);
+    const uint32_t mine_addr = __builtin_amdgcn_readfirstlane(lds_addr + (QF * 64 + wave * WAVE_UNITS) * 16);
+    const uint32_t myq_addr = __builtin_amdgcn_readfirstlane(lds_addr + wave * QW * 1024);
+    const int nparts = ncparts + (tree_sep ? 1 : 0);
+    const bool has_cache = part < ncparts;
+    const int ntree = (part == nparts - 1) ? tg * TBW + TBW : 0;   // later tree blocks hold no ancestors
 
-    bf16x8 q[TBW][KK][2];              // two-term bf16 expansion of every query
+    // ancestor words of this lane's query rows: only the part with the tree blocks masks by them. Fetched before any
+    // direct-to-LDS load is in flight and waited for at once, so the explicit counts below stay exact.
+    static_assert(SD_ANC_WORDS == 4, "one 16-byte load per row");
+    uint4 ancq[TBW];
 #pragma unroll
-    for (int tb = 0; tb < TBW; ++tb)
+    for (int tb = 0; tb < TBW; ++tb) ancq[tb] = make_uint4(0u, 0u, 0u, 0u);
+    if (ntree) {
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk)
+        for (int tb = 0; tb < TBW; ++tb)
+            ancq[tb] = *(const uint4*)(anc + ((size_t)b * Tp + (tg * TBW + tb) * 32 + tl) * SD_ANC_WORDS);
+        wait_vm<0>();
+    }
+
+    {   // queries of this (sequence, head, query group) -> LDS, a quarter per wave
+        const bf16x8* qsrc = Qp + (((size_t)b * nh + h) * TB + tg * TBW) * (KK * 2 * 64) + lane;
 #pragma unroll
-            for (int pt = 0; pt < 2; ++pt)
-                q[tb][kk][pt] = Qp[(((((size_t)b * nh + h) * TB + tg * TBW + tb) * KK + kk) * 2 + pt) * 64 + lane];
+        for (int i = 0; i < QW; ++i) lds_dma16(qsrc + (wave * QW + i) * 64, myq_addr + i * 1024);
+    }
+
+    // The part's items: its tree blocks first, then its cache blocks; wave w owns items
+    // [w*share, (w+1)*share). Which of them exist depends on the sequence length, known later.
+    const int c0 = part * per;
+    const int total = ntree + (has_cache ? per : 0);
+    const int share = (total + 3) >> 2;
+    const int jw = __builtin_amdgcn_readfirstlane(wave * share);
+    const bf16x8* kcb = Kc + ((size_t)b * nh + h) * cap_blocks * BLK + lane;
+    const bf16x8* vcb = Vc + ((size_t)b * nh + h) * cap_blocks * BLK + lane;
+    const bf16x8* ktb = Kt + ((size_t)b * nh + h) * TB * BLK + lane;
+    const bf16x8* vtb = Vt + ((size_t)b * nh + h) * TB * BLK + lane;
+    // item -> block address, always inside the tree scratch or the cache allocation
+    auto kaddr = [&](int j) -> const bf16x8* {
+        j = min(j, total - 1);
+        return (j < ntree) ? ktb + (size_t)j * BLK : kcb + (size_t)min(c0 + j - ntree, cap_blocks - 1) * BLK;
+    };
+    auto vaddr = [&](int j) -> const bf16x8* {
+        j = min(j, total - 1);
+        return (j < ntree) ? vtb + (size_t)j * BLK : vcb + (size_t)min(c0 + j - ntree, cap_blocks - 1) * BLK;
+    };
+    auto request_k = [&](int r, int j) {
+        const bf16x8* kp = kaddr(j);
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) lds_dma16(kp + kk * 64, mine_addr + (r * SLOT + kk * 64) * 16);
+    };
+    auto request_v = [&](int r, int j) {
+        const bf16x8* vp = vaddr(j);
+#pragma unroll
+        for (int i = 0; i < NV; ++i) lds_dma16(vp + i * 64, mine_addr + (r * SLOT + (KK + i) * 64) * 16);
+    };
+    request_k(0, jw); request_v(0, jw); request_k(1, jw + 1); request_v(1, jw + 1);
+
+    const int n = kv_len[b];
+    const int nblk = (n + 31) >> 5;
+    const int ncache = has_cache ? max(0, min(per, nblk - c0)) : 0;
+    const int nit = __builtin_amdgcn_readfirstlane(max(0, min(share, ntree + ncache - jw)));       // this wave's items [jw, jw + nit)
 
     f32x16 O[TBW][EB];
     float mrun[TBW], lrun[TBW];
@@ -59,132 +158,193 @@ __global__ __launch_bounds__(64) void k_tree_attn(const bf16x8* __restrict__ Qp,
             for (int v = 0; v < 16; ++v) O[tb][eb][v] = 0.f;
     }
 
-    int blk0, blk1;
-    const bf16x8 *kbase, *vbase;
-    uint32_t ancw[TBW][SD_ANC_WORDS];
-    if (tree_part) {
-        blk0 = 0;
-        blk1 = tg * TBW + TBW;                       // later tree blocks hold no ancestors
-        kbase = Kt + ((size_t)b * nh + h) * TB * BLK;
-        vbase = Vt + ((size_t)b * nh + h) * TB * BLK;
+    // QK^T of one block. The operands come from LDS in stages of one contraction step (one K
+    // fragment and the 2*TBW query fragments that meet it); two stages are requested ahead of the
+    // one being multiplied, and the scheduler is fenced so that it keeps them that far ahead.
+    auto qk = [&](const bf16x8* ks, f32x16(&S)[TBW]) {
+        int ql = lane;
+        asm volatile("" : "+v"(ql));       // keep the query reads in the loop: hoisted, they cost 128 registers
+        bf16x8 st[3][1 + 2 * TBW];
+        auto stage = [&](int si, int kk) {
+            st[si][0] = ks[kk * 64 + ql];
+#pragma unroll
+            for (int pt = 0; pt < 2; ++pt)
+#pragma unroll
+                for (int tb = 0; tb < TBW; ++tb) st[si][1 + pt * TBW + tb] = qs[((tb * KK + kk) * 2 + pt) * 64 + ql];
+        };
+        stage(0, 0);
+        stage(1, 1);
 #pragma unroll
         for (int tb = 0; tb < TBW; ++tb)
 #pragma unroll
-            for (int w = 0; w < SD_ANC_WORDS; ++w)
-                ancw[tb][w] = anc[((size_t)b * Tp + (tg * TBW + tb) * 32 + tl) * SD_ANC_WORDS + w];
-    } else {
-        const int nblk = (n + 31) >> 5;
-        blk0 = part * blocks_per_chunk;
-        blk1 = blk0 + blocks_per_chunk;
-        if (blk1 > nblk) blk1 = nblk;
-        kbase = Kc + ((size_t)b * nh + h) * cap_blocks * BLK;
-        vbase = Vc + ((size_t)b * nh + h) * cap_blocks * BLK;
-    }
-
-    for (int blk = blk0; blk < blk1; ++blk) {
-        bf16x8 kf[KK], vf[2][EB];
-        const bf16x8* kp = kbase + (size_t)blk * BLK + lane;
-        const bf16x8* vp = vbase + (size_t)blk * BLK + lane;
+            for (int v = 0; v < 16; ++v) S[tb][v] = 0.f;
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) kf[kk] = kp[kk * 64];
+        for (int kk = 0; kk < KK; ++kk) {
+            if (kk + 2 < KK) stage((kk + 2) % 3, kk + 2);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int p = 0; p < 2; ++p)
+            for (int pt = 0; pt < 2; ++pt)
 #pragma unroll
-            for (int eb = 0; eb < EB; ++eb) vf[p][eb] = vp[(p * EB + eb) * 64];
-
+                for (int tb = 0; tb < TBW; ++tb)
+                    S[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(st[kk % 3][0], st[kk % 3][1 + pt * TBW + tb], S[tb], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    // softmax of the block's scores for both query blocks, then PV; the V fragments are requested
+    // from LDS before the softmax arithmetic starts
+    auto softmax_pv = [&](const bf16x8* vs, f32x16(&S)[TBW], int it) {
+        bf16x8 vf[NV];
+#pragma unroll
+        for (int i = 0; i < NV; ++i) vf[i] = vs[i * 64 + lane];
+        __builtin_amdgcn_sched_barrier(0);
+        const int j = jw + it;
+        const bool tr = j < ntree;
+        const int blk = tr ? j : c0 + j - ntree;
+        const int left = n - blk * 32;
+        const bool need_mask = tr || left < 32;                 // wave-uniform
+        bf16x8 pf[TBW][2], pl[TBW][2];     // probabilities, two-term expansion
 #pragma unroll
         for (int tb = 0; tb < TBW; ++tb) {
-            f32x16 S;
+            if (need_mask) {
+                uint32_t vis;
+                if (tr) {
+                    const uint64_t lo64 = ancq[tb].x | ((uint64_t)ancq[tb].y << 32), hi64 = ancq[tb].z | ((uint64_t)ancq[tb].w << 32);
+                    vis = (uint32_t)(((blk & 2) ? hi64 : lo64) >> ((blk & 1) * 32));     // word blk of the row's ancestor set
+                }
+                else vis = (1u << left) - 1u;
+                vis >>= 4 * g;          // lane (t = tl, g) holds rows 8*(v/4) + 4*g + v%4 of the block
 #pragma unroll
-            for (int v = 0; v < 16; ++v) S[v] = 0.f;
-#pragma unroll
-            for (int kk = 0; kk < KK; ++kk) {
-                S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], q[tb][kk][0], S, 0, 0, 0);
-                S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], q[tb][kk][1], S, 0, 0, 0);
+                for (int v = 0; v < 16; ++v)
+                    S[tb][v] = (vis & (1u << (8 * (v >> 2) + (v & 3)))) ? S[tb][v] : NEG_INF;
             }
-            // lane (t = tl, g) holds rows c = 8*(v/4) + 4*g + v%4 of this block
-            uint32_t vis;
-            if (tree_part) {
-                vis = ancw[tb][0];
+            float mx = S[tb][0];
 #pragma unroll
-                for (int w = 1; w < SD_ANC_WORDS; ++w) vis = (blk == w) ? ancw[tb][w] : vis;
-            } else {
-                int left = n - blk * 32;
-                vis = left >= 32 ? 0xffffffffu : ((1u << left) - 1u);
-            }
-            float mx = NEG_INF;
+            for (int v = 1; v < 16; ++v) mx = fmaxf(mx, S[tb][v]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2;
+            const bool upd = mx > mrun[tb] + SD_LAZY_MAX;
+            if (__any(upd)) {
+                const float alpha = upd ? __builtin_amdgcn_exp2f(mrun[tb] - mx) : 1.f;
+                mrun[tb] = upd ? mx : mrun[tb];
+                lrun[tb] *= alpha;
+                asm volatile("s_nop 7\n\ts_nop 7");          // the last PV product has long left the pipe; be explicit
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                int c = 8 * (v >> 2) + 4 * g + (v & 3);
-                float sv = ((vis >> c) & 1u) ? S[v] * scale_log2 : NEG_INF;
-                S[v] = sv;
-                mx = fmaxf(mx, sv);
+                for (int eb = 0; eb < EB; ++eb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) { float x = O[tb][eb][v]; acc_scale(x, alpha); O[tb][eb][v] = x; }
+                asm volatile("s_nop 7");
             }
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            float mnew = fmaxf(mrun[tb], mx);
-            float muse = (mnew == NEG_INF) ? 0.f : mnew;
-            float alpha = exp2f(mrun[tb] - muse);
+            const float muse = (mrun[tb] == NEG_INF) ? 0.f : mrun[tb];
             float psum = 0.f;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                float p = exp2f(S[v] - muse);
-                S[v] = p;
-                psum += p;
-            }
-            lrun[tb] = lrun[tb] * alpha + psum;
-            mrun[tb] = mnew;
-            bf16x8 pf[2], pl[2];               // probabilities, two-term expansion
 #pragma unroll
             for (int p = 0; p < 2; ++p)
 #pragma unroll
                 for (int s = 0; s < 8; ++s) {
-                    __bf16 hi = (__bf16)S[8 * p + s];
-                    pf[p][s] = hi;
-                    pl[p][s] = (__bf16)(S[8 * p + s] - (float)hi);
+                    const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(S[tb][8 * p + s], scale_log2, -muse));
+                    psum += pv;
+                    const __bf16 hi = (__bf16)pv;
+                    pf[tb][p][s] = hi;
+                    pl[tb][p][s] = (__bf16)(pv - (float)hi);
                 }
+            lrun[tb] += psum;
+        }
+#pragma unroll
+        for (int p = 0; p < 2; ++p)
 #pragma unroll
             for (int eb = 0; eb < EB; ++eb) {
 #pragma unroll
-                for (int v = 0; v < 16; ++v) O[tb][eb][v] *= alpha;
+                for (int tb = 0; tb < TBW; ++tb)
+                    O[tb][eb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[p * EB + eb], pf[tb][p], O[tb][eb], 0, 0, 0);
 #pragma unroll
-                for (int p = 0; p < 2; ++p) {
-                    O[tb][eb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[p][eb], pf[p], O[tb][eb], 0, 0, 0);
-                    O[tb][eb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[p][eb], pl[p], O[tb][eb], 0, 0, 0);
-                }
+                for (int tb = 0; tb < TBW; ++tb)
+                    O[tb][eb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[p * EB + eb], pl[tb][p], O[tb][eb], 0, 0, 0);
+            }
+    };
+
+    wait_vm<2 * NL>();                                 // this wave's share of the queries has landed
+    __syncthreads();                                   // queries are in LDS
+    if (nit > 0) {
+        for (int it = 0; it < nit; it += 2) {
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                const bool live = it + r < nit;
+                f32x16 S[TBW];
+                wait_vm<NV + NL>();                    // K of this block has landed
+                if (live) qk(mine + r * SLOT, S);
+                request_k(r, jw + min(it + r + 2, nit - 1));   // past the wave's last item: that item again
+                wait_vm<KK + NL>();                    // V of this block has landed
+                if (live) softmax_pv(mine + r * SLOT + KK * 64, S, it + r);
+                request_v(r, jw + min(it + r + 2, nit - 1));
             }
         }
     }
+    wait_vm<0>();                                      // no load may land in LDS after this point
 
-    const int nparts = nchunks + 1;
+    // ---- merge the four waves. Every wave parks its O tiles in its own slots and its (max, sum)
+    //      pairs in the query area; then the NT output tiles are shared out over the waves, each
+    //      combining the four contributions to its tiles and writing them straight to the partials.
+    float4* mo_all = (float4*)(lds + QF * 64);         // [wave][tile][i = 0..3][lane] as float4
+    float* mml = (float*)lds;                          // [wave][tb][2][64]
+    constexpr int WAVE_F4 = WAVE_UNITS;                // one float4 per 16-byte unit
+    __syncthreads();                                   // all waves are done with the queries
 #pragma unroll
     for (int tb = 0; tb < TBW; ++tb) {
-        int t = (tg * TBW + tb) * 32 + tl;
-        size_t row = (((size_t)b * nh + h) * nparts + part) * Tp + t;
-        float ltot = lrun[tb] + __shfl_xor(lrun[tb], 32);
-        if (g == 0) mlpart[row] = make_float2(mrun[tb], ltot);
-        float* o = opart + row * HD;
 #pragma unroll
         for (int eb = 0; eb < EB; ++eb)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                int e = eb * 32 + 8 * i + 4 * g;
-                *(float4*)(o + e) = make_float4(O[tb][eb][4 * i], O[tb][eb][4 * i + 1], O[tb][eb][4 * i + 2],
-                                                O[tb][eb][4 * i + 3]);
+            for (int i = 0; i < 4; ++i)
+                mo_all[wave * WAVE_F4 + ((tb * EB + eb) * 4 + i) * 64 + lane] =
+                    make_float4(O[tb][eb][4 * i], O[tb][eb][4 * i + 1], O[tb][eb][4 * i + 2], O[tb][eb][4 * i + 3]);
+        mml[((wave * TBW + tb) * 2 + 0) * 64 + lane] = mrun[tb];
+        mml[((wave * TBW + tb) * 2 + 1) * 64 + lane] = lrun[tb];
+    }
+    __syncthreads();
+    for (int ti = wave; ti < NT; ti += 4) {
+        const int tb = ti / EB, eb = ti % EB;
+        float mw[4], lw[4], M = NEG_INF;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            mw[w] = mml[((w * TBW + tb) * 2 + 0) * 64 + lane];
+            lw[w] = mml[((w * TBW + tb) * 2 + 1) * 64 + lane];
+            M = fmaxf(M, mw[w]);
+        }
+        const float Muse = (M == NEG_INF) ? 0.f : M;
+        float L = 0.f, sc[4];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            sc[w] = exp2f(mw[w] - Muse);               // exp2(-inf) = 0 for a wave that saw nothing
+            L += sc[w] * lw[w];
+        }
+        const int t = (tg * TBW + tb) * 32 + tl;
+        const size_t row = (((size_t)b * nh + h) * nparts + part) * Tp + t;
+        if (eb == 0) {
+            const float ltot = L + __shfl_xor(L, 32);
+            if (g == 0) mlpart[row] = make_float2(M, ltot);
+        }
+        float* o = opart + row * HD;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float4 x = mo_all[w * WAVE_F4 + (ti * 4 + i) * 64 + lane];
+                acc.x += sc[w] * x.x; acc.y += sc[w] * x.y; acc.z += sc[w] * x.z; acc.w += sc[w] * x.w;
             }
+            *(float4*)(o + eb * 32 + 8 * i + 4 * g) = acc;
+        }
     }
 }
 
 void launch_tree_attn(const void* q_packed, const void* kc, const void* vc, const void* kt, const void* vt,
                       const int32_t* kv_len, const uint32_t* anc, float* opart, float2* mlpart, int B, int nh,
-                      int hd, int Tp, int cap_blocks, int nchunks, int blocks_per_chunk, hipStream_t s) {
+                      int hd, int Tp, int cap_blocks, int ncparts, int per, int tree_sep, hipStream_t s) {
     const float scale_log2 = 1.4426950408889634f / sqrtf((float)hd);
     const int TB = Tp / 32;
     const int TBW = (TB % 2 == 0) ? 2 : 1;
-    dim3 grid(nchunks + 1, nh * (TB / TBW), B);
+    dim3 grid(ncparts + (tree_sep ? 1 : 0), nh * (TB / TBW), B);
 #define ATT(HD_, TBW_)                                                                                          \
-    hipLaunchKernelGGL((k_tree_attn<HD_, TBW_>), grid, dim3(64), 0, s, (const bf16x8*)q_packed,                \
+    hipLaunchKernelGGL((k_tree_attn<HD_, TBW_>), grid, dim3(256), 0, s, (const bf16x8*)q_packed,               \
                        (const bf16x8*)kc, (const bf16x8*)vc, (const bf16x8*)kt, (const bf16x8*)vt, kv_len, anc, \
-                       opart, mlpart, nh, Tp, cap_blocks, nchunks, blocks_per_chunk, scale_log2)
+                       opart, mlpart, nh, Tp, cap_blocks, ncparts, per, tree_sep, scale_log2)
     if (hd == 128) { if (TBW == 2) ATT(128, 2); else ATT(128, 1); }
     else           { if (TBW == 2) ATT(64, 2);  else ATT(64, 1); }
 #undef ATT
@@ -192,9 +352,12 @@ void launch_tree_attn(const void* q_packed, const void* kc, const void* vc, cons
 
 // ------------------------------------------------------------------------------------------
 // Merge the split-KV partials and emit the packed bf16 operand of the O-projection.
-// one thread per (seq, head, query t, 8 consecutive output dims)
+// one thread per (seq, head, query t, 8 consecutive output dims); the parts are read in batches
+// of eight whose loads are all issued before any is used (a part index past the end re-reads
+// the last part with weight zero, so no load sits behind a branch)
 __global__ void k_attn_merge(const float* __restrict__ opart, const float2* __restrict__ mlpart,
                              bf16x8* __restrict__ xp, int B, int nh, int hd, int Tp, int nparts, int MB) {
+    constexpr int PB = 8;
     int idx = blockIdx.x * blockDim.x + threadIdx.x;
     int e8n = hd / 8;
     int total = B * nh * Tp * e8n;
@@ -204,18 +367,35 @@ __global__ void k_attn_merge(const float* __restrict__ opart, const float2* __re
     int h = (idx / (e8n * Tp)) % nh;
     int b = idx / (e8n * Tp * nh);
     size_t base = ((size_t)b * nh + h) * nparts;
-    float M = NEG_INF;
-    for (int p = 0; p < nparts; ++p) M = fmaxf(M, mlpart[(base + p) * Tp + t].x);
-    float den = 0.f, o[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    for (int p = 0; p < nparts; ++p) {
-        float2 ml = mlpart[(base + p) * Tp + t];
-        if (ml.y == 0.f) continue;                      // empty part
-        float w = exp2f(ml.x - M);
-        den += w * ml.y;
-        const float4* src = (const float4*)(opart + ((base + p) * Tp + t) * hd + e8 * 8);
-        float4 a = src[0], c = src[1];
-        o[0] += w * a.x; o[1] += w * a.y; o[2] += w * a.z; o[3] += w * a.w;
-        o[4] += w * c.x; o[5] += w * c.y; o[6] += w * c.z; o[7] += w * c.w;
+    float M = NEG_INF, den = 0.f, o[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int p0 = 0; p0 < nparts; p0 += PB) {
+        float2 ml[PB];
+        float4 a[PB], c[PB];
+#pragma unroll
+        for (int i = 0; i < PB; ++i) {
+            const int p = min(p0 + i, nparts - 1);
+            ml[i] = mlpart[(base + p) * Tp + t];
+            const float4* src = (const float4*)(opart + ((base + p) * Tp + t) * hd + e8 * 8);
+            a[i] = src[0];
+            c[i] = src[1];
+        }
+        float Mb = M;
+#pragma unroll
+        for (int i = 0; i < PB; ++i)
+            if (p0 + i < nparts && ml[i].y != 0.f) Mb = fmaxf(Mb, ml[i].x);       // an empty part has sum 0
+        if (Mb == NEG_INF) continue;
+        const float sold = exp2f(M - Mb);              // 0 when nothing was merged yet
+        den *= sold;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o[j] *= sold;
+#pragma unroll
+        for (int i = 0; i < PB; ++i) {
+            const float w = (p0 + i < nparts && ml[i].y != 0.f) ? exp2f(ml[i].x - Mb) : 0.f;
+            den += w * ml[i].y;
+            o[0] += w * a[i].x; o[1] += w * a[i].y; o[2] += w * a[i].z; o[3] += w * a[i].w;
+            o[4] += w * c[i].x; o[5] += w * c[i].y; o[6] += w * c[i].z; o[7] += w * c[i].w;
+        }
+        M = Mb;
     }
     float inv = den > 0.f ? 1.f / den : 0.f;
     bf16x8 hi, lo;
