@@ -78,7 +78,7 @@ struct sd_model {
     std::vector<StepGraph> graphs;
     hipStream_t cap_stream = nullptr;      // capture happens here: the caller's stream may be the null stream
     std::vector<GemmPlan> plans;             // one per (row blocks, K blocks, N blocks) in use
-    int32_t* plan_cnt = nullptr;             // device: the plans' per-group slot counts
+    int32_t* plan_cnt = nullptr;             // device: the plans' launch tables (slot counts, iteration lists)
     const GemmPlan& plan(int MB, int KB, int NB) const {
         for (const GemmPlan& p : plans)
             if (p.MB == MB && p.KB == KB && p.NB == NB) return p;
@@ -232,8 +232,9 @@ extern "C" int sd_model_create(const sd_config* cfg, const sd_weights* w, int32_
                 for (const GemmPlan& q : m->plans) dup |= q.MB == mb && q.KB == sh[0] && q.NB == sh[1];
                 if (dup) continue;
                 GemmPlan pl;
-                std::vector<int32_t> cnt((sh[1] + 7) / 8 + 1, 0);
-                gemm_plan_make(&pl, mb, sh[0], sh[1], cnt.data());
+                std::vector<int32_t> cnt;
+                gemm_plan_make(&pl, mb, sh[0], sh[1], &cnt);
+                while (cnt_all.size() % 4) cnt_all.push_back(0);       // the iteration records are read 16 bytes at a time
                 cnt_off.push_back(cnt_all.size());
                 cnt_all.insert(cnt_all.end(), cnt.begin(), cnt.end());
                 m->plans.push_back(pl);
@@ -267,7 +268,7 @@ extern "C" int sd_model_create(const sd_config* cfg, const sd_weights* w, int32_
         return fail(SD_ERR_HIP, "hipMalloc(%zu) for workspace: %s", wz, hipGetErrorString(e));
     }
     for (size_t i = 0; i < m->plans.size(); ++i)
-        if (m->plans[i].kind == 1) m->plans[i].cnt_dev = m->plan_cnt + cnt_off[i];
+        if (m->plans[i].kind == 1) m->plans[i].tab_dev = m->plan_cnt + cnt_off[i];
     hipMemsetAsync(m->work, 0, wz, s);
     char* Wk = m->work;
     m->x = (float*)(Wk + w_x); m->part = (float*)(Wk + w_part); m->logits = (float*)(Wk + w_logits);

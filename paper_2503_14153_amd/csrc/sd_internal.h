@@ -23,6 +23,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
+#include <vector>
 
 #include "../../include/specdec.h"
 
@@ -96,7 +97,10 @@ struct GemmPlan {
     int nsplit;              // kind 0
     int G, NG;               // kind 1: workgroups, 256-column groups
     int slots;               // slots the output buffer must hold
-    int32_t* cnt_dev;        // kind 1: [NG] contributors per column group (device), else NULL
+    int32_t* tab_dev;        // kind 1: launch table (device), else NULL: [NG] contributors per column
+                             // group, then at off_it the first iteration of every workgroup [G+1],
+                             // then at off_iters the iterations {kb, ng, valid steps, slot or -1}
+    int off_it, off_iters;
 };
 
 #define SD_MAX_BATCH 32
@@ -115,8 +119,8 @@ struct VerifyArgs {
 // ---- launchers (defined in the kernel translation units) ----------------------------------
 // All take a stream; all sizes have been validated by the caller.
 void launch_pack_weight(const void* src, void* dst, int N, int K, int nb_offset, int NBdst, int KB, hipStream_t s);
-// fills every field of the plan except cnt_dev; cnt_host receives the per-group counts (kind 1)
-void gemm_plan_make(GemmPlan* p, int MB, int KB, int NB, int32_t* cnt_host /*[>= ceil(NB/8)]*/);
+// fills every field of the plan except tab_dev; tab receives the launch table to upload (kind 1; empty otherwise)
+void gemm_plan_make(GemmPlan* p, int MB, int KB, int NB, std::vector<int32_t>* tab);
 // out must hold plan.slots * (MB*32) * (NB*32) floats; zfrag: 1 KiB of zeros (device);
 // returns the view consumers read
 PartView launch_gemm(const GemmPlan& p, const void* Xp, const void* Wp, const void* zfrag, float* out, hipStream_t s);
