@@ -333,7 +333,7 @@ __global__ __launch_bounds__(512, 2) void k_gemm_sk(const bf16x8* __restrict__ X
 
 // ------------------------------------------------------------------------------------------
 // dst[m][c] = sum of the slots of column c (used where the consumer wants dense rows: logits)
-__global__ void k_reduce_slots(PartView pv, float* __restrict__ dst, int rows) {
+__global__ void k_reduce_slots(PartView pv, RowScale rs, float* __restrict__ dst, int rows) {
     const int c4 = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
     const int m = blockIdx.y;
     if (c4 >= pv.ld || m >= rows) return;
@@ -343,10 +343,12 @@ __global__ void k_reduce_slots(PartView pv, float* __restrict__ dst, int rows) {
         float4 v = *(const float4*)(pv.base + (size_t)sp * pv.slot_stride + (size_t)m * pv.ld + c4);
         a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
     }
+    const float r = row_scale(rs, m);
+    a.x *= r; a.y *= r; a.z *= r; a.w *= r;
     *(float4*)(dst + (size_t)m * pv.ld + c4) = a;
 }
-void launch_reduce_slots(PartView pv, float* dst, int rows, hipStream_t s) {
-    hipLaunchKernelGGL(k_reduce_slots, dim3((pv.ld / 4 + 255) / 256, rows), dim3(256), 0, s, pv, dst, rows);
+void launch_reduce_slots(PartView pv, RowScale rs, float* dst, int rows, hipStream_t s) {
+    hipLaunchKernelGGL(k_reduce_slots, dim3((pv.ld / 4 + 255) / 256, rows), dim3(256), 0, s, pv, rs, dst, rows);
 }
 
 // ------------------------------------------------------------------------------------------

@@ -103,6 +103,22 @@ struct GemmPlan {
     int off_it, off_iters;
 };
 
+// RMS normalisation whose scale is applied by the consumer of the following GEMM: the GEMM is linear in
+// its activation rows, so row m of its result is multiplied by rsqrt(sum_q ssq[m*Q+q] / d + eps)
+// afterwards instead of every activation before. ssq == NULL means "no scale".
+#define SD_NORM_Q 4
+struct RowScale {
+    const float* ssq;        // [rows][SD_NORM_Q] partial sums of squares of the residual rows, or NULL
+    float inv_d, eps;
+};
+#ifdef __HIPCC__
+static __device__ inline float row_scale(const RowScale& r, int m) {
+    if (!r.ssq) return 1.f;
+    const float4 q = *(const float4*)(r.ssq + (size_t)m * SD_NORM_Q);
+    return rsqrtf((q.x + q.y + q.z + q.w) * r.inv_d + r.eps);
+}
+#endif
+
 #define SD_MAX_BATCH 32
 #define SD_MAX_MEDUSA 15
 struct ChainArgs { int32_t off[SD_MAX_BATCH]; int32_t len[SD_MAX_BATCH]; };
@@ -124,7 +140,7 @@ void gemm_plan_make(GemmPlan* p, int MB, int KB, int NB, std::vector<int32_t>* t
 // out must hold plan.slots * (MB*32) * (NB*32) floats; zfrag: 1 KiB of zeros (device);
 // returns the view consumers read
 PartView launch_gemm(const GemmPlan& p, const void* Xp, const void* Wp, const void* zfrag, float* out, hipStream_t s);
-void launch_reduce_slots(PartView pv, float* dst, int rows, hipStream_t s);
+void launch_reduce_slots(PartView pv, RowScale rs, float* dst, int rows, hipStream_t s);
 
 void launch_build_rows_tree(RowTable rt, const int32_t* parent, const int32_t* depth, const int32_t* rank,
                             const int32_t* root_tok, const int32_t* cand, const int32_t* kv_len,
@@ -135,7 +151,10 @@ void launch_build_rows_chain(RowTable rt, const int32_t* tokens, const ChainArgs
                              hipStream_t s);
 void launch_norm_pack(float* x, PartView pv, const void* gain, float eps, void* xn_packed, float* hf_out,
                       int M, int d, int MB, const int32_t* gather, hipStream_t s);
-void launch_rope_kv(PartView pv, RowTable rt, void* q_packed, void* kt, void* vt, int B, int Tp, int nh, int hd,
+// residual += sum of slots; packed = hi/lo of residual * gain (NOT normalised); ssq[m][q] = partial sums of squares
+void launch_norm_pack_rows(float* x, PartView pv, const void* gain, void* xn_packed, float* ssq, int M, int d, int MB,
+                           hipStream_t s);
+void launch_rope_kv(PartView pv, RowScale rs, RowTable rt, void* q_packed, void* kt, void* vt, int B, int Tp, int nh, int hd,
                     hipStream_t s);
 void launch_tree_attn(const void* q_packed, const void* kc, const void* vc, const void* kt, const void* vt,
                       const int32_t* kv_len, const uint32_t* anc, float* opart, float2* mlpart,
@@ -143,7 +162,7 @@ void launch_tree_attn(const void* q_packed, const void* kc, const void* vc, cons
                       hipStream_t s);
 void launch_attn_merge(const float* opart, const float2* mlpart, void* x_packed, int B, int nh, int hd,
                        int Tp, int nparts, int MB, hipStream_t s);
-void launch_swiglu_pack(PartView pv, int F, int Fpad, void* act_packed, int M, int MB, hipStream_t s);
+void launch_swiglu_pack(PartView pv, RowScale rs, int F, int Fpad, void* act_packed, int M, int MB, hipStream_t s);
 void launch_medusa_act(PartView pv, const float* h_rows, const MedusaBias& bias, int B, int H, int d,
                        void* x_packed, int MB, hipStream_t s);
 void launch_argmax(const float* logits, int ld, int V, int32_t* am, int B, int T, int Tp, hipStream_t s);
