@@ -63,7 +63,7 @@ struct sd_model {
     MedusaBias medusa_b;
     std::vector<LayerW> layers;
     // workspace
-    float *x, *part, *logits, *hlogits, *hf, *h_rows, *opart, *ssq;
+    float *x, *part, *logits, *hlogits, *hf, *h_rows, *opart;
     float2* mlpart;
     void *xn, *attn_x, *act, *q, *kt, *vt;
     RowTable rt;
@@ -78,7 +78,7 @@ struct sd_model {
     std::vector<StepGraph> graphs;
     hipStream_t cap_stream = nullptr;      // capture happens here: the caller's stream may be the null stream
     std::vector<GemmPlan> plans;             // one per (row blocks, K blocks, N blocks) in use
-    int32_t* plan_cnt = nullptr;             // device: the plans' launch tables (slot counts, iteration lists)
+    int32_t* plan_cnt = nullptr;             // device: the plans' per-group slot counts
     const GemmPlan& plan(int MB, int KB, int NB) const {
         for (const GemmPlan& p : plans)
             if (p.MB == MB && p.KB == KB && p.NB == NB) return p;
@@ -232,9 +232,8 @@ extern "C" int sd_model_create(const sd_config* cfg, const sd_weights* w, int32_
                 for (const GemmPlan& q : m->plans) dup |= q.MB == mb && q.KB == sh[0] && q.NB == sh[1];
                 if (dup) continue;
                 GemmPlan pl;
-                std::vector<int32_t> cnt;
-                gemm_plan_make(&pl, mb, sh[0], sh[1], &cnt);
-                while (cnt_all.size() % 4) cnt_all.push_back(0);       // the iteration records are read 16 bytes at a time
+                std::vector<int32_t> cnt((sh[1] + 7) / 8 + 1, 0);
+                gemm_plan_make(&pl, mb, sh[0], sh[1], cnt.data());
                 cnt_off.push_back(cnt_all.size());
                 cnt_all.insert(cnt_all.end(), cnt.begin(), cnt.end());
                 m->plans.push_back(pl);
@@ -257,7 +256,6 @@ extern "C" int sd_model_create(const sd_config* cfg, const sd_weights* w, int32_
     size_t w_tok = wtake((size_t)Mp * 4), w_pos = wtake((size_t)Mp * 4), w_anc = wtake((size_t)Mp * SD_ANC_WORDS * 4);
     size_t w_cs = wtake((size_t)Mp * (hd / 2) * 8), w_am = wtake((size_t)Mp * 4), w_g = wtake(3 * 4);
     size_t w_zs = wtake((size_t)ceil_div(V, 32) * 4), w_zf = wtake(1024);
-    size_t w_ssq = wtake((size_t)Mp * SD_NORM_Q * 4);
     e = hipMalloc((void**)&m->work, wz);
     if (e == hipSuccess) e = hipMalloc((void**)&m->plan_cnt, cnt_all.size() * 4);
     if (e == hipSuccess) e = hipMemcpy(m->plan_cnt, cnt_all.data(), cnt_all.size() * 4, hipMemcpyHostToDevice);
@@ -269,13 +267,12 @@ extern "C" int sd_model_create(const sd_config* cfg, const sd_weights* w, int32_
         return fail(SD_ERR_HIP, "hipMalloc(%zu) for workspace: %s", wz, hipGetErrorString(e));
     }
     for (size_t i = 0; i < m->plans.size(); ++i)
-        if (m->plans[i].kind == 1) m->plans[i].tab_dev = m->plan_cnt + cnt_off[i];
+        if (m->plans[i].kind == 1) m->plans[i].cnt_dev = m->plan_cnt + cnt_off[i];
     hipMemsetAsync(m->work, 0, wz, s);
     char* Wk = m->work;
     m->x = (float*)(Wk + w_x); m->part = (float*)(Wk + w_part); m->logits = (float*)(Wk + w_logits);
     m->hlogits = (float*)(Wk + w_hlog); m->hf = (float*)(Wk + w_hf); m->h_rows = (float*)(Wk + w_hrows);
     m->opart = (float*)(Wk + w_opart); m->mlpart = (float2*)(Wk + w_ml);
-    m->ssq = (float*)(Wk + w_ssq);
     m->xn = Wk + w_xn; m->attn_x = Wk + w_attn; m->act = Wk + w_act; m->q = Wk + w_q;
     m->kt = Wk + w_kt; m->vt = Wk + w_vt;
     m->rt.tok = (int32_t*)(Wk + w_tok); m->rt.pos = (int32_t*)(Wk + w_pos); m->rt.anc = (uint32_t*)(Wk + w_anc);
@@ -578,16 +575,15 @@ static PartView run_layers(sd_model* m, sd_kv* kv, int B, int Tp, int n_hi, hipS
     const sd_config& c = m->cfg;
     const int M = B * Tp, MB = pow2_blocks(M), d = c.d_model, nh = c.n_heads, hd = c.head_dim, TB = Tp / 32;
     const AttnGeom ag = attn_geometry(m, B, Tp, n_hi);
-    const RowScale rs = {m->ssq, 1.f / (float)d, c.rms_eps};
     PartView prev = {nullptr, 0, d, nullptr, 256, 0};
     const size_t t_stride = (size_t)B * nh * TB * 32 * hd;     // elements per layer of tree scratch
     for (int l = 0; l < c.n_layers; ++l) {
         const LayerW& lw = m->layers[l];
-        launch_norm_pack_rows(m->x, prev, lw.attn_norm, m->xn, m->ssq, M, d, MB, s);
+        launch_norm_pack(m->x, prev, lw.attn_norm, c.rms_eps, m->xn, nullptr, M, d, MB, nullptr, s);
         PartView pq = run_gemm(m, m->xn, lw.wqkv, m->part, MB, m->KBd, m->NBqkv, 3 * d, s);
         uint16_t* kt = (uint16_t*)m->kt + l * t_stride;
         uint16_t* vt = (uint16_t*)m->vt + l * t_stride;
-        launch_rope_kv(pq, rs, m->rt, m->q, kt, vt, B, Tp, nh, hd, s);
+        launch_rope_kv(pq, m->rt, m->q, kt, vt, B, Tp, nh, hd, s);
         // algorithmic bytes: one read of K and V of the committed rows (upper bound n_hi) + tree rows
         int pa = prof_start(m, PROF_ATTN, (double)B * (n_hi + Tp) * 2.0 * d * 2.0, s);
         launch_tree_attn(m->q, kv->kc + l * kv->layer_stride, kv->vc + l * kv->layer_stride, kt, vt, kv->kv_len,
@@ -595,9 +591,9 @@ static PartView run_layers(sd_model* m, sd_kv* kv, int B, int Tp, int n_hi, hipS
         prof_stop(m, pa, s);
         launch_attn_merge(m->opart, m->mlpart, m->attn_x, B, nh, hd, Tp, ag.nparts, MB, s);
         PartView po = run_gemm(m, m->attn_x, lw.wo, m->part, MB, m->KBd, m->NBo, d, s);
-        launch_norm_pack_rows(m->x, po, lw.ffn_norm, m->xn, m->ssq, M, d, MB, s);
+        launch_norm_pack(m->x, po, lw.ffn_norm, c.rms_eps, m->xn, nullptr, M, d, MB, nullptr, s);
         PartView pg = run_gemm(m, m->xn, lw.wgu, m->part, MB, m->KBd, m->NBgu, 2 * c.d_ffn, s);
-        launch_swiglu_pack(pg, rs, c.d_ffn, m->Fpad, m->act, M, MB, s);
+        launch_swiglu_pack(pg, c.d_ffn, m->Fpad, m->act, M, MB, s);
         prev = run_gemm(m, m->act, lw.wdown, m->part, MB, m->KBf, m->NBo, d, s);
     }
     return prev;
@@ -607,10 +603,9 @@ static PartView run_layers(sd_model* m, sd_kv* kv, int B, int Tp, int n_hi, hipS
 static void run_lm_head(sd_model* m, PartView prev, int B, int T, int Tp, hipStream_t s) {
     const sd_config& c = m->cfg;
     const int M = B * Tp, MB = pow2_blocks(M);
-    launch_norm_pack_rows(m->x, prev, m->final_norm, m->xn, m->ssq, M, c.d_model, MB, s);
-    const RowScale rs = {m->ssq, 1.f / (float)c.d_model, c.rms_eps};
+    launch_norm_pack(m->x, prev, m->final_norm, c.rms_eps, m->xn, nullptr, M, c.d_model, MB, nullptr, s);
     PartView pl = run_gemm(m, m->xn, m->lm_head, m->part, MB, m->KBd, m->NBv, c.vocab, s);
-    launch_reduce_slots(pl, rs, m->logits, M, s);
+    launch_reduce_slots(pl, m->logits, M, s);
     launch_argmax(m->logits, m->Vpad, c.vocab, m->am, B, T, Tp, s);
 }
 
@@ -624,8 +619,7 @@ static void run_draft_heads(sd_model* m, sd_kv* kv, int B, uint32_t seq_mask, fl
     const int MBh = pow2_blocks(H * B);
     launch_medusa_act(pm, m->h_rows, m->medusa_b, B, H, d, m->xn, MBh, s);
     PartView pl = run_gemm(m, m->xn, m->lm_head, m->part, MBh, m->KBd, m->NBv, c.vocab, s);
-    const RowScale no_scale = {nullptr, 0.f, 0.f};
-    launch_reduce_slots(pl, no_scale, m->hlogits, H * B, s);
+    launch_reduce_slots(pl, m->hlogits, H * B, s);
     launch_topk(m->hlogits, m->Vpad, c.vocab, c.topk, kv->cand, B, H, seq_mask, s);
     if (head_logits_out) launch_copy_head_logits(m->hlogits, m->Vpad, head_logits_out, c.vocab, B, H, s);
 }

@@ -1,6 +1,9 @@
 // sd_calib: plain copy / read kernels of known size, used to calibrate the HBM byte counters
 // (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) and to measure what a long streaming kernel
-// reaches on this machine.   usage: sd_calib copy|read <MiB> [reps]
+// reaches on this machine.   usage: sd_calib copy|read|stream <MiB> [reps]
+//   read:   every load instruction of the grid covers one contiguous span (waves interleaved)
+//   stream: every wave walks its own contiguous region, 16 loads of 1 KiB in flight (the access
+//           pattern of the weight and KV streams of the library)
 #include <hip/hip_runtime.h>
 #include <cstdio>
 #include <cstdlib>
@@ -27,11 +30,26 @@ __global__ void k_calib_read(const u4* __restrict__ src, size_t n, unsigned* __r
     if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) sink[0] = 1;
 }
 
+// every wave streams its own contiguous region with sixteen 1 KiB loads in flight
+__global__ void k_calib_stream(const u4* __restrict__ src, size_t units_per_wave, unsigned* __restrict__ sink) {
+    const size_t wave = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const u4* q = src + wave * units_per_wave + (threadIdx.x & 63);
+    u4 acc = {0, 0, 0, 0};
+    for (size_t i = 0; i + 15 * 64 < units_per_wave; i += 16 * 64) {
+        u4 v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) v[u] = __builtin_nontemporal_load(q + i + u * 64);
+#pragma unroll
+        for (int u = 0; u < 16; ++u) acc ^= v[u];
+    }
+    if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) sink[0] = 1;
+}
+
 #define CK(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) { fprintf(stderr, "%s: %s\n", #x, hipGetErrorString(e_)); return 1; } } while (0)
 
 int main(int argc, char** argv) {
-    if (argc < 3) { fprintf(stderr, "usage: sd_calib copy|read <MiB> [reps]\n"); return 2; }
-    const bool copy = !strcmp(argv[1], "copy");
+    if (argc < 3) { fprintf(stderr, "usage: sd_calib copy|read|stream <MiB> [reps]\n"); return 2; }
+    const bool copy = !strcmp(argv[1], "copy"), stream = !strcmp(argv[1], "stream");
     const size_t bytes = (size_t)atol(argv[2]) << 20, n = bytes / 16;
     const int reps = argc > 3 ? atoi(argv[3]) : 5;
     u4 *a, *b;
@@ -45,6 +63,7 @@ int main(int argc, char** argv) {
         CK(hipEventRecord(e0));
         for (int r = 0; r < reps; ++r) {
             if (copy) hipLaunchKernelGGL(k_calib_copy, dim3(blocks), dim3(256), 0, 0, a, b, n);
+            else if (stream) hipLaunchKernelGGL(k_calib_stream, dim3(256), dim3(256), 0, 0, a, (n / 1024) & ~(size_t)1023, sink);
             else hipLaunchKernelGGL(k_calib_read, dim3(blocks), dim3(256), 0, 0, a, n, sink);
         }
         CK(hipEventRecord(e1)); CK(hipEventSynchronize(e1));

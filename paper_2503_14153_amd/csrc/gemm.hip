@@ -17,9 +17,6 @@
 // bf16 expansion x = hi + lo (two MFMAs per weight fragment), which keeps ~16 mantissa bits
 // of x and makes the product exact up to fp32 accumulation.
 #include "sd_internal.h"
-#include <algorithm>
-
-#define SK_RING 16          // weight fragments every wave of the stream-K kernel keeps in flight
 
 // ------------------------------------------------------------------------------------------
 // Re-tile a row-major bf16 matrix W[N][K] into fragment order (see sd_internal.h).
@@ -190,34 +187,43 @@ __global__ __launch_bounds__((NW + 1) * 64, (MT <= 2 ? 3 : 1)) void k_gemm_strea
 // Loads of one wave return in order, so an activation load queues behind the HBM loads issued
 // before it: chunks are therefore fetched one ring-length (R steps) ahead, by all threads, and
 // parked in registers until the chunk before them has been consumed.
-struct SkIter { int kb, ng, valid, slot; };
+struct SkIter { int kb, ng, valid, last; };
 
 template <int MT>
 __global__ __launch_bounds__(512, 2) void k_gemm_sk(const bf16x8* __restrict__ Xp, const bf16x8* __restrict__ Wp,
                                                     const bf16x8* __restrict__ zfrag, float* __restrict__ out,
-                                                    const int32_t* __restrict__ it_off, const int4* __restrict__ iters,
-                                                    int KB, int G_, int uq, int ur, int NB, int ldo, size_t slot_stride) {
-    constexpr int R = SK_RING;
+                                                    int KB, int NB, int NG, int ldo, size_t slot_stride) {
+    constexpr int R = 16;
     constexpr int XK = 8 / MT;                       // contraction blocks per chunk
     constexpr int CPI = R / XK;                      // chunks per outer iteration (2 or 4)
     constexpr int XF = 16;                           // fragments per chunk = XK * MT * 2
     constexpr int XP = XF * 64 / 512;                // 16-byte pieces per thread per chunk = 2
     __shared__ bf16x8 xs[2][XF * 64];
 
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // scalar: addresses become base + lane
-    const int g = blockIdx.x;
-    // all pointer arguments are fetched in the first batch of scalar loads, not after the index arithmetic
-    asm volatile("" :: "s"(Xp), "s"(Wp), "s"(zfrag), "s"(it_off), "s"(iters));
-    // This workgroup's outer iterations (R contraction steps of one column group each) were laid
-    // out on the host: iters[it_off[g] .. it_off[g+1]) = {kb, ng, valid steps, slot or -1}, where
-    // slot >= 0 marks the last iteration of a segment and names the partial-sum slot it writes.
-    const int it0 = it_off[g], nit_wg = it_off[g + 1] - it0;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int G = gridDim.x, g = blockIdx.x;
+    const int U = NG * KB;
+    auto ustart = [&](int gg) { return (int)(((long long)gg * U) / G); };
+    const int u0 = ustart(g), u1 = ustart(g + 1);
+
+    // k-th outer iteration (R steps) of this workgroup's padded segment list
     auto iter_info = [&](int k) {
-        SkIter r = {0, 0, 0, -1};
-        if (k < nit_wg) {
-            const int4 e = iters[it0 + k];
-            r.kb = e.x; r.ng = e.y; r.valid = e.z; r.slot = e.w;
+        SkIter r = {0, 0, 0, 0};
+        int u = u0;
+        while (u < u1) {
+            const int ng = u / KB, kb = u - ng * KB;
+            int send = (ng + 1) * KB;
+            if (send > u1) send = u1;
+            const int len = send - u, nit = (len + R - 1) / R;
+            if (k < nit) {
+                r.kb = kb + k * R;
+                r.ng = ng;
+                r.valid = len - k * R < R ? len - k * R : R;
+                r.last = (k == nit - 1);
+                return r;
+            }
+            k -= nit;
+            u = send;
         }
         return r;
     };
@@ -248,19 +254,8 @@ __global__ __launch_bounds__(512, 2) void k_gemm_sk(const bf16x8* __restrict__ X
         for (int p = 0; p < XP; ++p) xs[buf][p * 512 + tid] = src[p];
     };
 
-    // The first iteration is also worked out in registers (units [g*U/G, (g+1)*U/G) with U/G given as
-    // quotient uq and remainder ur, all in 32 bits), so that the first loads do not wait for the three
-    // dependent scalar reads that lead to the table's records. No workgroup is empty (the host gives
-    // every one at least SK_RING units), so there is no early exit to split the argument loads around.
-    SkIter cur = {0, 0, 0, -1};
-    {
-        const unsigned G = (unsigned)G_, ug = (unsigned)g;       // = gridDim.x, passed with the other arguments
-        const int u0 = (int)(ug * uq + (ug * ur) / G), u1 = (int)((ug + 1) * uq + ((ug + 1) * ur) / G);
-        cur.ng = u0 / KB;
-        cur.kb = u0 - cur.ng * KB;
-        const int len = min((cur.ng + 1) * KB, u1) - u0;
-        cur.valid = len < R ? len : R;
-    }
+    SkIter cur = iter_info(0), nxt = iter_info(1), nx2 = iter_info(2);
+    if (cur.valid == 0) return;
 
     f32x16 acc[MT];
 #pragma unroll
@@ -276,8 +271,6 @@ __global__ __launch_bounds__(512, 2) void k_gemm_sk(const bf16x8* __restrict__ X
 #pragma unroll
         for (int i = 0; i < R; ++i) w[i] = __builtin_nontemporal_load((i < cur.valid) ? wc + (size_t)i * wstep : zl);
     }
-    cur.slot = iter_info(0).slot;
-    SkIter nxt = iter_info(1), nx2 = iter_info(2);
     xstore(xr[0], 0);
     xload(xr[0], nxt, 0);
     __syncthreads();
@@ -306,10 +299,15 @@ __global__ __launch_bounds__(512, 2) void k_gemm_sk(const bf16x8* __restrict__ X
             else xload(xr[nc], nx2, 0);
             __syncthreads();
         }
-        if (cur.slot >= 0) {
+        if (cur.last) {
+            // slot = ordinal of this workgroup among those whose ranges meet column group cur.ng
+            const int first_unit = cur.ng * KB;
+            int gf = (int)(((long long)first_unit * G) / U);
+            while (gf + 1 < G && ustart(gf + 1) <= first_unit) ++gf;
+            while (gf > 0 && ustart(gf) > first_unit) --gf;
             const int nb = cur.ng * 8 + wave;
             if (nb < NB) {
-                float* o = out + (size_t)cur.slot * slot_stride + (size_t)nb * 32 + (lane & 31);
+                float* o = out + (size_t)(g - gf) * slot_stride + (size_t)nb * 32 + (lane & 31);
                 const int gq = lane >> 5;
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
@@ -333,7 +331,7 @@ __global__ __launch_bounds__(512, 2) void k_gemm_sk(const bf16x8* __restrict__ X
 
 // ------------------------------------------------------------------------------------------
 // dst[m][c] = sum of the slots of column c (used where the consumer wants dense rows: logits)
-__global__ void k_reduce_slots(PartView pv, RowScale rs, float* __restrict__ dst, int rows) {
+__global__ void k_reduce_slots(PartView pv, float* __restrict__ dst, int rows) {
     const int c4 = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
     const int m = blockIdx.y;
     if (c4 >= pv.ld || m >= rows) return;
@@ -343,12 +341,10 @@ __global__ void k_reduce_slots(PartView pv, RowScale rs, float* __restrict__ dst
         float4 v = *(const float4*)(pv.base + (size_t)sp * pv.slot_stride + (size_t)m * pv.ld + c4);
         a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
     }
-    const float r = row_scale(rs, m);
-    a.x *= r; a.y *= r; a.z *= r; a.w *= r;
     *(float4*)(dst + (size_t)m * pv.ld + c4) = a;
 }
-void launch_reduce_slots(PartView pv, RowScale rs, float* dst, int rows, hipStream_t s) {
-    hipLaunchKernelGGL(k_reduce_slots, dim3((pv.ld / 4 + 255) / 256, rows), dim3(256), 0, s, pv, rs, dst, rows);
+void launch_reduce_slots(PartView pv, float* dst, int rows, hipStream_t s) {
+    hipLaunchKernelGGL(k_reduce_slots, dim3((pv.ld / 4 + 255) / 256, rows), dim3(256), 0, s, pv, dst, rows);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -370,11 +366,9 @@ static int gemm_choose_split(int MB, int KB, int NB) {
 
 #define SK_MAX_WG 256       // one workgroup of 8 waves per CU
 
-void gemm_plan_make(GemmPlan* p, int MB, int KB, int NB, std::vector<int32_t>* tab) {
+void gemm_plan_make(GemmPlan* p, int MB, int KB, int NB, int32_t* cnt_host) {
     p->MB = MB; p->KB = KB; p->NB = NB;
-    p->tab_dev = nullptr;
-    p->off_it = p->off_iters = 0;
-    tab->clear();
+    p->cnt_dev = nullptr;
     if (MB > 2) {
         p->kind = 0;
         p->nsplit = gemm_choose_split(MB, KB, NB);
@@ -395,44 +389,21 @@ void gemm_plan_make(GemmPlan* p, int MB, int KB, int NB, std::vector<int32_t>* t
     if (G < 1) G = 1;
     p->G = G;
     auto ustart = [&](int gg) { return (int)(((long long)gg * U) / G); };
-    auto pad4 = [&]() { while (tab->size() % 4) tab->push_back(0); };
-    // table = [slots per column group (NG)] [first iteration of every workgroup (G+1)] [iterations]
-    tab->assign(p->NG, 0);
-    pad4();
-    p->off_it = (int)tab->size();
-    tab->resize(tab->size() + G + 1, 0);
-    pad4();
-    p->off_iters = (int)tab->size();
-    std::vector<int32_t> next_slot(p->NG, 0);
-    int n_iters = 0;
-    for (int g = 0; g < G; ++g) {
-        (*tab)[p->off_it + g] = n_iters;
-        int u = ustart(g);
-        const int u1 = ustart(g + 1);
-        while (u < u1) {                              // one segment = this workgroup's share of one column group
-            const int ng = u / KB, kb = u - ng * KB;
-            const int send = std::min((ng + 1) * KB, u1);
-            const int len = send - u, nit = (len + SK_RING - 1) / SK_RING;
-            const int slot = next_slot[ng]++;         // workgroups meet a group in rising order
-            for (int k = 0; k < nit; ++k) {
-                const int valid = std::min(SK_RING, len - k * SK_RING);
-                tab->push_back(kb + k * SK_RING);
-                tab->push_back(ng);
-                tab->push_back(valid);
-                tab->push_back(k == nit - 1 ? slot : -1);
-                ++n_iters;
-            }
-            u = send;
-        }
-    }
-    (*tab)[p->off_it + G] = n_iters;
     int slots = 1;
     for (int ng = 0; ng < p->NG; ++ng) {
-        (*tab)[ng] = next_slot[ng];
-        slots = std::max(slots, next_slot[ng]);
+        int first = ng * KB, last = (ng + 1) * KB - 1;
+        int gf = (int)(((long long)first * G) / U);
+        while (gf + 1 < G && ustart(gf + 1) <= first) ++gf;
+        while (gf > 0 && ustart(gf) > first) --gf;
+        int gl = (int)(((long long)last * G) / U);
+        while (gl + 1 < G && ustart(gl + 1) <= last) ++gl;
+        while (gl > 0 && ustart(gl) > last) --gl;
+        cnt_host[ng] = gl - gf + 1;
+        if (cnt_host[ng] > slots) slots = cnt_host[ng];
     }
     p->slots = slots;
 }
+
 template <int MT>
 static void launch_gemm_t(const void* Xp, const void* Wp, float* out, int KB, int NB, int ldo, int nsplit,
                           size_t split_stride, hipStream_t s) {
@@ -450,16 +421,14 @@ PartView launch_gemm(const GemmPlan& p, const void* Xp, const void* Wp, const vo
     pv.slot_stride = (size_t)p.MB * 32 * pv.ld;
     pv.group_cols = 256;
     if (p.kind == 1) {
-        pv.cnt = p.tab_dev;
+        pv.cnt = p.cnt_dev;
         pv.nmax = p.slots;
         if (p.MB == 1)
             hipLaunchKernelGGL((k_gemm_sk<1>), dim3(p.G), dim3(512), 0, s, (const bf16x8*)Xp, (const bf16x8*)Wp,
-                               (const bf16x8*)zfrag, out, p.tab_dev + p.off_it, (const int4*)(p.tab_dev + p.off_iters), p.KB,
-                               p.G, (p.NG * p.KB) / p.G, (p.NG * p.KB) % p.G, p.NB, pv.ld, pv.slot_stride);
+                               (const bf16x8*)zfrag, out, p.KB, p.NB, p.NG, pv.ld, pv.slot_stride);
         else
             hipLaunchKernelGGL((k_gemm_sk<2>), dim3(p.G), dim3(512), 0, s, (const bf16x8*)Xp, (const bf16x8*)Wp,
-                               (const bf16x8*)zfrag, out, p.tab_dev + p.off_it, (const int4*)(p.tab_dev + p.off_iters), p.KB,
-                               p.G, (p.NG * p.KB) / p.G, (p.NG * p.KB) % p.G, p.NB, pv.ld, pv.slot_stride);
+                               (const bf16x8*)zfrag, out, p.KB, p.NB, p.NG, pv.ld, pv.slot_stride);
         return pv;
     }
     pv.cnt = nullptr;

@@ -6,27 +6,6 @@
 
 static __device__ inline float bf16_bits_to_float(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 
-// Sum of the partial-sum slots for 8 consecutive columns starting at p0 (slot 0). The slots are read
-// in batches of four whose loads are all issued before any is used: a slot index past the count
-// re-reads the last slot and is weighted by zero, so no load sits behind a branch.
-static __device__ inline void sum_slots8(const float* __restrict__ p0, size_t slot_stride, int n, float (&t)[8]) {
-    for (int s0 = 0; s0 < n; s0 += 4) {
-        float4 a[4], c[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const float* p = p0 + (size_t)min(s0 + i, n - 1) * slot_stride;
-            a[i] = *(const float4*)p;
-            c[i] = *(const float4*)(p + 4);
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const float w = (s0 + i < n) ? 1.f : 0.f;
-            t[0] += w * a[i].x; t[1] += w * a[i].y; t[2] += w * a[i].z; t[3] += w * a[i].w;
-            t[4] += w * c[i].x; t[5] += w * c[i].y; t[6] += w * c[i].z; t[7] += w * c[i].w;
-        }
-    }
-}
-
 // ------------------------------------------------------------------------------------------
 // Rotary angle table entry, in float64 so that positions up to ~17k lose nothing.
 static __device__ inline float2 rope_cs(int pos, int i, int hd, float theta) {
@@ -135,7 +114,13 @@ __global__ __launch_bounds__(NP_THREADS) void k_norm_pack(float* __restrict__ x,
             float4 a = *(const float4*)(xr + grp * 8), c = *(const float4*)(xr + grp * 8 + 4);
             float t[8] = {a.x, a.y, a.z, a.w, c.x, c.y, c.z, c.w};
             const int nsplit = pv.nmax > 0 ? part_count(pv, grp * 8) : 0;
-            sum_slots8(pv.base + (size_t)src * pv.ld + grp * 8, pv.slot_stride, nsplit, t);
+#pragma unroll 4
+            for (int sp = 0; sp < nsplit; ++sp) {
+                const float* p = pv.base + (size_t)sp * pv.slot_stride + (size_t)src * pv.ld + grp * 8;
+                float4 pa = *(const float4*)p, pc = *(const float4*)(p + 4);
+                t[0] += pa.x; t[1] += pa.y; t[2] += pa.z; t[3] += pa.w;
+                t[4] += pc.x; t[5] += pc.y; t[6] += pc.z; t[7] += pc.w;
+            }
             if (nsplit > 0) {
                 *(float4*)(xr + grp * 8) = make_float4(t[0], t[1], t[2], t[3]);
                 *(float4*)(xr + grp * 8 + 4) = make_float4(t[4], t[5], t[6], t[7]);
@@ -179,75 +164,31 @@ void launch_norm_pack(float* x, PartView pv, const void* gain, float eps, void* 
 }
 
 // ------------------------------------------------------------------------------------------
-// The same residual update for the decoder layers, spread over SD_NORM_Q workgroups per row (64 rows
-// alone would leave three quarters of the chip idle): residual += sum of the slots; the packed
-// operand is residual * gain, not yet normalised; the row's sum of squares is left in SD_NORM_Q
-// pieces for the consumer of the next GEMM, which applies rsqrt(mean + eps) to that GEMM's result.
-__global__ __launch_bounds__(256) void k_norm_pack_rows(float* __restrict__ x, PartView pv,
-                                                        const uint16_t* __restrict__ gain, bf16x8* __restrict__ xn,
-                                                        float* __restrict__ ssq, int d, int MB) {
-    const int m = blockIdx.y, q = blockIdx.x;
-    float* xr = x + (size_t)m * d;
-    const int ngroups = d >> 3, gq = (ngroups + SD_NORM_Q - 1) / SD_NORM_Q;
-    float ss = 0.f;
-    for (int gl = threadIdx.x; gl < gq; gl += 256) {
-        const int grp = q * gq + gl;
-        if (grp >= ngroups) break;
-        float4 a = *(const float4*)(xr + grp * 8), c = *(const float4*)(xr + grp * 8 + 4);
-        float t[8] = {a.x, a.y, a.z, a.w, c.x, c.y, c.z, c.w};
-        const int nsplit = pv.nmax > 0 ? part_count(pv, grp * 8) : 0;
-        sum_slots8(pv.base + (size_t)m * pv.ld + grp * 8, pv.slot_stride, nsplit, t);
-        if (nsplit > 0) {
-            *(float4*)(xr + grp * 8) = make_float4(t[0], t[1], t[2], t[3]);
-            *(float4*)(xr + grp * 8 + 4) = make_float4(t[4], t[5], t[6], t[7]);
-        }
-        float f[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            ss += t[i] * t[i];
-            f[i] = t[i] * bf16_bits_to_float(gain[grp * 8 + i]);
-        }
-        bf16x8 hi, lo;
-        split_hilo(f, hi, lo);
-        const size_t u = xpack_index(m, grp * 8, MB) >> 3;
-        xn[u] = hi;
-        xn[u + XPART / 8] = lo;
-    }
-    __shared__ float red[4];
-    for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
-    __syncthreads();
-    if (threadIdx.x == 0) ssq[(size_t)m * SD_NORM_Q + q] = red[0] + red[1] + red[2] + red[3];
-}
-
-void launch_norm_pack_rows(float* x, PartView pv, const void* gain, void* xn_packed, float* ssq, int M, int d, int MB,
-                           hipStream_t s) {
-    hipLaunchKernelGGL(k_norm_pack_rows, dim3(SD_NORM_Q, M), dim3(256), 0, s, x, pv, (const uint16_t*)gain,
-                       (bf16x8*)xn_packed, ssq, d, MB);
-}
-
-// ------------------------------------------------------------------------------------------
 // Sum the QKV partials, rotate q and k to the row's position, and write q (fragment order,
 // two-term expansion), k and v (tree scratch, block layouts, bf16). Thread (m, h, a, which)
 // owns dims [8a, 8a+8) and their rotary partners [hd/2 + 8a, +8) of q (which=0), k (1) or v (2).
-__global__ void k_rope_kv(PartView pv, RowScale rs, RowTable rt, bf16x8* __restrict__ qp, uint16_t* __restrict__ kt, uint16_t* __restrict__ vt, int B, int Tp,
+__global__ void k_rope_kv(PartView pv, RowTable rt, bf16x8* __restrict__ qp, uint16_t* __restrict__ kt, uint16_t* __restrict__ vt, int B, int Tp,
                           int nh, int hd) {
     const int na = hd / 16;
     int idx = blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= B * Tp * nh * na * 3) return;
     const int a = idx % na, h = (idx / na) % nh, which = (idx / (na * nh)) % 3, m = idx / (na * nh * 3);
     const int b = m / Tp, t = m % Tp, d = nh * hd, half = hd / 2;
-    float lo[8] = {0, 0, 0, 0, 0, 0, 0, 0}, hi[8] = {0, 0, 0, 0, 0, 0, 0, 0};   // dims 8a..8a+7, half+8a..+7
+    float4 s0 = make_float4(0, 0, 0, 0), s1 = s0, s2 = s0, s3 = s0;       // dims 8a..8a+7, half+8a..+7
     const int col0 = which * d + h * hd + a * 8;
     const float* p0 = pv.base + (size_t)m * pv.ld + col0;
     const int nsplit = part_count(pv, col0);           // a head's columns share one 256-column group
-    sum_slots8(p0, pv.slot_stride, nsplit, lo);
-    sum_slots8(p0 + half, pv.slot_stride, nsplit, hi);
-    {
-        const float r = row_scale(rs, m);              // the input norm's scale, applied to the GEMM's result
-#pragma unroll
-        for (int i = 0; i < 8; ++i) { lo[i] *= r; hi[i] *= r; }
+    for (int sp = 0; sp < nsplit; ++sp) {
+        const float* p = p0 + (size_t)sp * pv.slot_stride;
+        float4 x0 = *(const float4*)p, x1 = *(const float4*)(p + 4);
+        float4 x2 = *(const float4*)(p + half), x3 = *(const float4*)(p + half + 4);
+        s0.x += x0.x; s0.y += x0.y; s0.z += x0.z; s0.w += x0.w;
+        s1.x += x1.x; s1.y += x1.y; s1.z += x1.z; s1.w += x1.w;
+        s2.x += x2.x; s2.y += x2.y; s2.z += x2.z; s2.w += x2.w;
+        s3.x += x3.x; s3.y += x3.y; s3.z += x3.z; s3.w += x3.w;
     }
+    float lo[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+    float hi[8] = {s2.x, s2.y, s2.z, s2.w, s3.x, s3.y, s3.z, s3.w};
     const int TB = Tp / 32;
     const size_t head_off = ((size_t)b * nh + h) * TB * (32 * hd);
     if (which == 2) {                                   // values: not rotated, scattered bf16
@@ -284,42 +225,48 @@ __global__ void k_rope_kv(PartView pv, RowScale rs, RowTable rt, bf16x8* __restr
     }
 }
 
-void launch_rope_kv(PartView pv, RowScale rs, RowTable rt, void* q_packed, void* kt, void* vt, int B, int Tp, int nh,
-                    int hd, hipStream_t s) {
+void launch_rope_kv(PartView pv, RowTable rt, void* q_packed, void* kt, void* vt, int B, int Tp, int nh, int hd,
+                    hipStream_t s) {
     int total = B * Tp * nh * (hd / 16) * 3;
-    hipLaunchKernelGGL(k_rope_kv, dim3((total + 255) / 256), dim3(256), 0, s, pv, rs, rt,
+    hipLaunchKernelGGL(k_rope_kv, dim3((total + 255) / 256), dim3(256), 0, s, pv, rt,
                        (bf16x8*)q_packed, (uint16_t*)kt, (uint16_t*)vt, B, Tp, nh, hd);
 }
 
 // ------------------------------------------------------------------------------------------
 // act = silu(gate) * up from the gate/up partials (gate in columns [0,F), up in [Fpad, Fpad+F)).
-__global__ void k_swiglu_pack(PartView pv, RowScale rs, int F, int Fpad, bf16x8* __restrict__ act, int M, int MB) {
+__global__ void k_swiglu_pack(PartView pv, int F, int Fpad, bf16x8* __restrict__ act, int M, int MB) {
     int idx = blockIdx.x * blockDim.x + threadIdx.x;
     int ng = F / 8;
     if (idx >= M * ng) return;
     int grp = idx % ng, m = idx / ng;
     float gsum[8] = {0, 0, 0, 0, 0, 0, 0, 0}, usum[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     const int ng_ = part_count(pv, grp * 8), nu_ = part_count(pv, Fpad + grp * 8);
-    sum_slots8(pv.base + (size_t)m * pv.ld + grp * 8, pv.slot_stride, ng_, gsum);
-    sum_slots8(pv.base + (size_t)m * pv.ld + Fpad + grp * 8, pv.slot_stride, nu_, usum);
+    for (int sp = 0; sp < ng_; ++sp) {
+        const float* p = pv.base + (size_t)sp * pv.slot_stride + (size_t)m * pv.ld + grp * 8;
+        float4 a = *(const float4*)p, c = *(const float4*)(p + 4);
+        gsum[0] += a.x; gsum[1] += a.y; gsum[2] += a.z; gsum[3] += a.w;
+        gsum[4] += c.x; gsum[5] += c.y; gsum[6] += c.z; gsum[7] += c.w;
+    }
+    for (int sp = 0; sp < nu_; ++sp) {
+        const float* p = pv.base + (size_t)sp * pv.slot_stride + (size_t)m * pv.ld + Fpad + grp * 8;
+        float4 ua = *(const float4*)p, uc = *(const float4*)(p + 4);
+        usum[0] += ua.x; usum[1] += ua.y; usum[2] += ua.z; usum[3] += ua.w;
+        usum[4] += uc.x; usum[5] += uc.y; usum[6] += uc.z; usum[7] += uc.w;
+    }
     bf16x8 hi, lo;
     float f[8];
-    const float r = row_scale(rs, m);                  // the input norm's scale, applied to the GEMM's result
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const float gv = gsum[i] * r;
-        f[i] = gv / (1.f + __expf(-gv)) * (usum[i] * r);
-    }
+    for (int i = 0; i < 8; ++i) f[i] = gsum[i] / (1.f + __expf(-gsum[i])) * usum[i];
     split_hilo(f, hi, lo);
     const size_t u = xpack_index(m, grp * 8, MB) >> 3;
     act[u] = hi;
     act[u + XPART / 8] = lo;
 }
 
-void launch_swiglu_pack(PartView pv, RowScale rs, int F, int Fpad, void* act_packed, int M, int MB, hipStream_t s) {
+void launch_swiglu_pack(PartView pv, int F, int Fpad, void* act_packed, int M, int MB, hipStream_t s) {
     int total = M * (F / 8);
-    hipLaunchKernelGGL(k_swiglu_pack, dim3((total + 255) / 256), dim3(256), 0, s, pv, rs, F, Fpad,
-                       (bf16x8*)act_packed, M, MB);
+    hipLaunchKernelGGL(k_swiglu_pack, dim3((total + 255) / 256), dim3(256), 0, s, pv, F, Fpad, (bf16x8*)act_packed, M,
+                       MB);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -333,7 +280,11 @@ __global__ void k_medusa_act(PartView pv, const float* __restrict__ h_rows, Medu
     int grp = idx % ng, b = (idx / ng) % B, i = idx / (ng * B);
     float z[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     const int nsplit = part_count(pv, i * d + grp * 8);
-    sum_slots8(pv.base + (size_t)b * pv.ld + (size_t)i * d + grp * 8, pv.slot_stride, nsplit, z);
+    for (int sp = 0; sp < nsplit; ++sp) {
+        const float* p = pv.base + (size_t)sp * pv.slot_stride + (size_t)b * pv.ld + (size_t)i * d + grp * 8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) z[e] += p[e];
+    }
     const uint16_t* bi = bias.p[i];
     bf16x8 hi, lo;
     float f[8];

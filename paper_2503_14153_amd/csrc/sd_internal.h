@@ -23,7 +23,6 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
-#include <vector>
 
 #include "../../include/specdec.h"
 
@@ -97,27 +96,8 @@ struct GemmPlan {
     int nsplit;              // kind 0
     int G, NG;               // kind 1: workgroups, 256-column groups
     int slots;               // slots the output buffer must hold
-    int32_t* tab_dev;        // kind 1: launch table (device), else NULL: [NG] contributors per column
-                             // group, then at off_it the first iteration of every workgroup [G+1],
-                             // then at off_iters the iterations {kb, ng, valid steps, slot or -1}
-    int off_it, off_iters;
+    int32_t* cnt_dev;        // kind 1: [NG] contributors per column group (device), else NULL
 };
-
-// RMS normalisation whose scale is applied by the consumer of the following GEMM: the GEMM is linear in
-// its activation rows, so row m of its result is multiplied by rsqrt(sum_q ssq[m*Q+q] / d + eps)
-// afterwards instead of every activation before. ssq == NULL means "no scale".
-#define SD_NORM_Q 4
-struct RowScale {
-    const float* ssq;        // [rows][SD_NORM_Q] partial sums of squares of the residual rows, or NULL
-    float inv_d, eps;
-};
-#ifdef __HIPCC__
-static __device__ inline float row_scale(const RowScale& r, int m) {
-    if (!r.ssq) return 1.f;
-    const float4 q = *(const float4*)(r.ssq + (size_t)m * SD_NORM_Q);
-    return rsqrtf((q.x + q.y + q.z + q.w) * r.inv_d + r.eps);
-}
-#endif
 
 #define SD_MAX_BATCH 32
 #define SD_MAX_MEDUSA 15
@@ -135,12 +115,12 @@ struct VerifyArgs {
 // ---- launchers (defined in the kernel translation units) ----------------------------------
 // All take a stream; all sizes have been validated by the caller.
 void launch_pack_weight(const void* src, void* dst, int N, int K, int nb_offset, int NBdst, int KB, hipStream_t s);
-// fills every field of the plan except tab_dev; tab receives the launch table to upload (kind 1; empty otherwise)
-void gemm_plan_make(GemmPlan* p, int MB, int KB, int NB, std::vector<int32_t>* tab);
+// fills every field of the plan except cnt_dev; cnt_host receives the per-group counts (kind 1)
+void gemm_plan_make(GemmPlan* p, int MB, int KB, int NB, int32_t* cnt_host /*[>= ceil(NB/8)]*/);
 // out must hold plan.slots * (MB*32) * (NB*32) floats; zfrag: 1 KiB of zeros (device);
 // returns the view consumers read
 PartView launch_gemm(const GemmPlan& p, const void* Xp, const void* Wp, const void* zfrag, float* out, hipStream_t s);
-void launch_reduce_slots(PartView pv, RowScale rs, float* dst, int rows, hipStream_t s);
+void launch_reduce_slots(PartView pv, float* dst, int rows, hipStream_t s);
 
 void launch_build_rows_tree(RowTable rt, const int32_t* parent, const int32_t* depth, const int32_t* rank,
                             const int32_t* root_tok, const int32_t* cand, const int32_t* kv_len,
@@ -151,10 +131,7 @@ void launch_build_rows_chain(RowTable rt, const int32_t* tokens, const ChainArgs
                              hipStream_t s);
 void launch_norm_pack(float* x, PartView pv, const void* gain, float eps, void* xn_packed, float* hf_out,
                       int M, int d, int MB, const int32_t* gather, hipStream_t s);
-// residual += sum of slots; packed = hi/lo of residual * gain (NOT normalised); ssq[m][q] = partial sums of squares
-void launch_norm_pack_rows(float* x, PartView pv, const void* gain, void* xn_packed, float* ssq, int M, int d, int MB,
-                           hipStream_t s);
-void launch_rope_kv(PartView pv, RowScale rs, RowTable rt, void* q_packed, void* kt, void* vt, int B, int Tp, int nh, int hd,
+void launch_rope_kv(PartView pv, RowTable rt, void* q_packed, void* kt, void* vt, int B, int Tp, int nh, int hd,
                     hipStream_t s);
 void launch_tree_attn(const void* q_packed, const void* kc, const void* vc, const void* kt, const void* vt,
                       const int32_t* kv_len, const uint32_t* anc, float* opart, float2* mlpart,
@@ -162,7 +139,7 @@ void launch_tree_attn(const void* q_packed, const void* kc, const void* vc, cons
                       hipStream_t s);
 void launch_attn_merge(const float* opart, const float2* mlpart, void* x_packed, int B, int nh, int hd,
                        int Tp, int nparts, int MB, hipStream_t s);
-void launch_swiglu_pack(PartView pv, RowScale rs, int F, int Fpad, void* act_packed, int M, int MB, hipStream_t s);
+void launch_swiglu_pack(PartView pv, int F, int Fpad, void* act_packed, int M, int MB, hipStream_t s);
 void launch_medusa_act(PartView pv, const float* h_rows, const MedusaBias& bias, int B, int H, int d,
                        void* x_packed, int MB, hipStream_t s);
 void launch_argmax(const float* logits, int ld, int V, int32_t* am, int B, int T, int Tp, hipStream_t s);

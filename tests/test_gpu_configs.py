@@ -48,8 +48,9 @@ def _random_draft(shape, B, seed):
     return roots, cand
 
 
-def _run_batch_steps(sd, shape, B, T, lens, cap, n_steps, tree_np=None, plant=True, fallback="keep_all"):
-    weights = wl.make_weights(shape)
+def _run_batch_steps(sd, shape, B, T, lens, cap, n_steps, tree_np=None, plant=True, fallback="keep_all",
+                     weights_device="cpu"):
+    weights = wl.make_weights(shape, device=weights_device)
     w64 = lockstep.weights_to_f64(weights)
     Tp = (T + 31) // 32 * 32
     model = sd.Model(shape, {k: v.cuda() for k, v in weights.items()}, B * Tp, fallback)
@@ -117,6 +118,17 @@ def test_long_context_synthetic_cache(sd):
     rep = _run_batch_steps(sd, shape, 1, 64, [16384], 16896, n_steps=2)
     print(f"\n[7b-long L2] {rep}")
     assert max(rep.raw) >= 2                               # the planted draft was accepted
+
+
+@pytest.mark.timeout(900)
+def test_7b_full_depth_one_step(sd):
+    """configs[1] at its full depth: all 32 layers at d=4096, a 64-node tree over 512 committed rows.
+    One step (the fp64 oracle streams 52 GB of widened weights); shows that the tolerances written for
+    the logits hold at the depth the benchmark runs, not only at the two-layer cut of the other tests."""
+    shape = dataclasses.replace(wl.preset("7b").model, dtype="bf16")
+    assert shape.n_layers == 32
+    rep = _run_batch_steps(sd, shape, 1, 64, [512], 2048, n_steps=1, weights_device="cuda")
+    print(f"\n[7b L32] {rep}")
 
 
 def test_ragged_batch_of_eight(sd):
