@@ -193,7 +193,7 @@ template <int MT>
 __global__ __launch_bounds__(512, 2) void k_gemm_sk(const bf16x8* __restrict__ Xp, const bf16x8* __restrict__ Wp,
                                                     const bf16x8* __restrict__ zfrag, float* __restrict__ out,
                                                     int KB, int NB, int NG, int ldo, size_t slot_stride) {
-    constexpr int R = 16;
+    constexpr int R = MT >= 4 ? 8 : 16;              // ring depth: with four row blocks the accumulators need the registers
     constexpr int XK = 8 / MT;                       // contraction blocks per chunk
     constexpr int CPI = R / XK;                      // chunks per outer iteration (2 or 4)
     constexpr int XF = 16;                           // fragments per chunk = XK * MT * 2
@@ -365,11 +365,17 @@ static int gemm_choose_split(int MB, int KB, int NB) {
 }
 
 #define SK_MAX_WG 256       // one workgroup of 8 waves per CU
+#ifndef SK_MAX_MB
+#define SK_MAX_MB 4          // row blocks (of 32 rows) up to which the stream-K kernel is used
+#endif
+#ifndef SK_SMALL_U
+#define SK_SMALL_U (16 * SK_MAX_WG * 2)   // (column groups x contraction blocks) up to which half the workgroups are used
+#endif
 
 void gemm_plan_make(GemmPlan* p, int MB, int KB, int NB, int32_t* cnt_host) {
     p->MB = MB; p->KB = KB; p->NB = NB;
     p->cnt_dev = nullptr;
-    if (MB > 2) {
+    if (MB > SK_MAX_MB) {
         p->kind = 0;
         p->nsplit = gemm_choose_split(MB, KB, NB);
         p->G = 0; p->NG = 0;
@@ -385,7 +391,7 @@ void gemm_plan_make(GemmPlan* p, int MB, int KB, int NB, int32_t* cnt_host) {
     // A small matrix (the O projection: 33 MB at the 7B shape) gains nothing from the last
     // doubling of workgroups but pays for it in partial tiles (measured 13.5 us with 128
     // workgroups / 8 slots against 14.9 us with 256 / 16, and the consumer reads half as much).
-    if (G == SK_MAX_WG && U <= 16 * SK_MAX_WG * 2) G = SK_MAX_WG / 2;
+    if (G == SK_MAX_WG && U <= SK_SMALL_U) G = SK_MAX_WG / 2;
     if (G < 1) G = 1;
     p->G = G;
     auto ustart = [&](int gg) { return (int)(((long long)gg * U) / G); };
@@ -426,8 +432,11 @@ PartView launch_gemm(const GemmPlan& p, const void* Xp, const void* Wp, const vo
         if (p.MB == 1)
             hipLaunchKernelGGL((k_gemm_sk<1>), dim3(p.G), dim3(512), 0, s, (const bf16x8*)Xp, (const bf16x8*)Wp,
                                (const bf16x8*)zfrag, out, p.KB, p.NB, p.NG, pv.ld, pv.slot_stride);
-        else
+        else if (p.MB == 2)
             hipLaunchKernelGGL((k_gemm_sk<2>), dim3(p.G), dim3(512), 0, s, (const bf16x8*)Xp, (const bf16x8*)Wp,
+                               (const bf16x8*)zfrag, out, p.KB, p.NB, p.NG, pv.ld, pv.slot_stride);
+        else
+            hipLaunchKernelGGL((k_gemm_sk<4>), dim3(p.G), dim3(512), 0, s, (const bf16x8*)Xp, (const bf16x8*)Wp,
                                (const bf16x8*)zfrag, out, p.KB, p.NB, p.NG, pv.ld, pv.slot_stride);
         return pv;
     }
