@@ -4,8 +4,8 @@
 // cache part is a pure stream: K and V of each head are read once from HBM and reused by all
 // T queries of that head, so the kernel is HBM-bound and is organised around that stream:
 //   * keys and values are stored as ready-made MFMA fragments (see sd_internal.h), so a
-//     32-row block is sixteen contiguous 1 KiB pieces that go from memory to LDS to the
-//     matrix core without a transpose or a register detour;
+//     32-row block is sixteen contiguous 1 KiB pieces that go from memory to registers to the
+//     matrix core without a transpose or a pass through LDS;
 //   * S^T = K Q^T puts query t in lane t%32, and the value rows inside a block are permuted
 //     so that exp(S) -- still in the accumulator registers -- already is the B operand of
 //     O^T = V^T P^T: no cross-lane traffic between the two products;
@@ -24,18 +24,18 @@
 // contexts: one more workgroup per head, running beside the others) or to the last cache part
 // (long contexts, where every workgroup slot of the chip is wanted for the stream).
 // One workgroup = 4 waves, one per SIMD; each wave takes a contiguous quarter of the part's
-// blocks, so it reads two plain sequential streams (its K blocks and its V blocks).
+// blocks, so it reads two plain sequential streams (its K blocks and its V blocks), the access
+// pattern that streams fastest from HBM.
 //
-// K and V never pass through registers on their way in: every wave owns two 32-row slots in
-// LDS and fills them with direct global-to-LDS loads (one 1 KiB fragment per instruction, the
-// fragment layout in memory is the layout the MFMA reads). Block j+2 is requested as soon as
-// block j's slot has been multiplied, so between one and two blocks are always in flight per
-// wave while it works, at no cost in registers. These loads are issued from inline assembly
-// and waited for with explicit vmcnt values (they complete in issue order): 8 K loads then
-// 8 V loads per block, hence "at most 24 outstanding" = the block about to be used is there.
+// Every wave keeps a ring of two blocks of K and V in registers (the fragments are MFMA operands
+// as loaded): block j+2 is requested as soon as block j's registers have been multiplied, so
+// between one and two blocks (16-32 KiB) are in flight per wave while it works; the loads are
+// plain and unconditional, so the compiler counts them exactly (one vmcnt step per fragment).
 // The first two blocks of every wave are requested before the sequence length is known (the
 // host's bound fixes the geometry; a block past the end is fetched, in bounds, and ignored).
-// The queries of the head sit in LDS as well (fetched the same way), shared by the four waves.
+// The queries of the head sit in LDS, shared by the four waves; they get there by direct
+// global-to-LDS loads issued from inline assembly, the first loads of each wave, waited for
+// with an explicit count ("all but the ring's loads have landed").
 //
 // The running maximum is only raised when a block's maximum exceeds it by more than 2^8: the
 // softmax is invariant to the reference point, exp2 of at most 8 cannot overflow anything, and
@@ -70,10 +70,8 @@ __global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp
     constexpr int BLK = HD * 4;        // bf16x8 units per 32-row block
     constexpr int QF = TBW * KK * 2;   // query fragments held in LDS
     constexpr int QW = QF / 4;         // of which every wave fetches this many
-    constexpr int SLOT = NL * 64;      // bf16x8 units per slot (K then V)
-    constexpr int WAVE_UNITS = 2 * SLOT;
     constexpr int NT = TBW * EB;       // 32x32 output tiles of one wave
-    static_assert(NT * 16 * 64 * 4 <= WAVE_UNITS * 16, "a wave's O must fit its own slots for the merge");
+    constexpr int WAVE_UNITS = NT * 4 * 64;          // 16-byte units of one wave's O in the merge buffer
     static_assert(4 * TBW * 2 * 64 * 4 <= QF * 1024, "merge scalars must fit the query area");
     __shared__ __attribute__((aligned(1024))) bf16x8 lds[QF * 64 + 4 * WAVE_UNITS];
 
@@ -83,9 +81,7 @@ __global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp
     const int h = blockIdx.y / TG, tg = blockIdx.y % TG;
     const int b = blockIdx.z;
     bf16x8* qs = lds;
-    bf16x8* mine = lds + QF * 64 + wave * WAVE_UNITS;
     const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) bf16x8*)lds);
-    const uint32_t mine_addr = __builtin_amdgcn_readfirstlane(lds_addr + (QF * 64 + wave * WAVE_UNITS) * 16);
     const uint32_t myq_addr = __builtin_amdgcn_readfirstlane(lds_addr + wave * QW * 1024);
     const int nparts = ncparts + (tree_sep ? 1 : 0);
     const bool has_cache = part < ncparts;
@@ -129,17 +125,18 @@ __global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp
         j = min(j, total - 1);
         return (j < ntree) ? vtb + (size_t)j * BLK : vcb + (size_t)min(c0 + j - ntree, cap_blocks - 1) * BLK;
     };
-    auto request_k = [&](int r, int j) {
+    bf16x8 kr[2][KK], vr[2][NV];
+    auto request_k = [&](bf16x8(&kd)[KK], int j) {
         const bf16x8* kp = kaddr(j);
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) lds_dma16(kp + kk * 64, mine_addr + (r * SLOT + kk * 64) * 16);
+        for (int kk = 0; kk < KK; ++kk) kd[kk] = __builtin_nontemporal_load(kp + kk * 64);
     };
-    auto request_v = [&](int r, int j) {
+    auto request_v = [&](bf16x8(&vd)[NV], int j) {
         const bf16x8* vp = vaddr(j);
 #pragma unroll
-        for (int i = 0; i < NV; ++i) lds_dma16(vp + i * 64, mine_addr + (r * SLOT + (KK + i) * 64) * 16);
+        for (int i = 0; i < NV; ++i) vd[i] = __builtin_nontemporal_load(vp + i * 64);
     };
-    request_k(0, jw); request_v(0, jw); request_k(1, jw + 1); request_v(1, jw + 1);
+    request_k(kr[0], jw); request_v(vr[0], jw); request_k(kr[1], jw + 1); request_v(vr[1], jw + 1);
 
     const int n = kv_len[b];
     const int nblk = (n + 31) >> 5;
@@ -158,15 +155,14 @@ __global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp
             for (int v = 0; v < 16; ++v) O[tb][eb][v] = 0.f;
     }
 
-    // QK^T of one block. The operands come from LDS in stages of one contraction step (one K
-    // fragment and the 2*TBW query fragments that meet it); two stages are requested ahead of the
-    // one being multiplied, and the scheduler is fenced so that it keeps them that far ahead.
-    auto qk = [&](const bf16x8* ks, f32x16(&S)[TBW]) {
+    // QK^T of one block. The query operands come from LDS in stages of one contraction step (the
+    // 2*TBW query fragments that meet one K fragment); two stages are requested ahead of the one
+    // being multiplied, and the scheduler is fenced so that it keeps them that far ahead.
+    auto qk = [&](const bf16x8(&ks)[KK], f32x16(&S)[TBW]) {
         int ql = lane;
         asm volatile("" : "+v"(ql));       // keep the query reads in the loop: hoisted, they cost 128 registers
         bf16x8 st[3][1 + 2 * TBW];
         auto stage = [&](int si, int kk) {
-            st[si][0] = ks[kk * 64 + ql];
 #pragma unroll
             for (int pt = 0; pt < 2; ++pt)
 #pragma unroll
@@ -186,17 +182,12 @@ __global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp
             for (int pt = 0; pt < 2; ++pt)
 #pragma unroll
                 for (int tb = 0; tb < TBW; ++tb)
-                    S[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(st[kk % 3][0], st[kk % 3][1 + pt * TBW + tb], S[tb], 0, 0, 0);
+                    S[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ks[kk], st[kk % 3][1 + pt * TBW + tb], S[tb], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
-    // softmax of the block's scores for both query blocks, then PV; the V fragments are requested
-    // from LDS before the softmax arithmetic starts
-    auto softmax_pv = [&](const bf16x8* vs, f32x16(&S)[TBW], int it) {
-        bf16x8 vf[NV];
-#pragma unroll
-        for (int i = 0; i < NV; ++i) vf[i] = vs[i * 64 + lane];
-        __builtin_amdgcn_sched_barrier(0);
+    // softmax of the block's scores for both query blocks, then PV
+    auto softmax_pv = [&](const bf16x8(&vf)[NV], f32x16(&S)[TBW], int it) {
         const int j = jw + it;
         const bool tr = j < ntree;
         const int blk = tr ? j : c0 + j - ntree;
@@ -268,18 +259,15 @@ __global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp
             for (int r = 0; r < 2; ++r) {
                 const bool live = it + r < nit;
                 f32x16 S[TBW];
-                wait_vm<NV + NL>();                    // K of this block has landed
-                if (live) qk(mine + r * SLOT, S);
-                request_k(r, jw + min(it + r + 2, nit - 1));   // past the wave's last item: that item again
-                wait_vm<KK + NL>();                    // V of this block has landed
-                if (live) softmax_pv(mine + r * SLOT + KK * 64, S, it + r);
-                request_v(r, jw + min(it + r + 2, nit - 1));
+                if (live) qk(kr[r], S);
+                request_k(kr[r], jw + min(it + r + 2, nit - 1));   // past the wave's last item: that item again
+                if (live) softmax_pv(vr[r], S, it + r);
+                request_v(vr[r], jw + min(it + r + 2, nit - 1));
             }
         }
     }
-    wait_vm<0>();                                      // no load may land in LDS after this point
 
-    // ---- merge the four waves. Every wave parks its O tiles in its own slots and its (max, sum)
+    // ---- merge the four waves. Every wave parks its O tiles in its own part of LDS and its (max, sum)
     //      pairs in the query area; then the NT output tiles are shared out over the waves, each
     //      combining the four contributions to its tiles and writing them straight to the partials.
     float4* mo_all = (float4*)(lds + QF * 64);         // [wave][tile][i = 0..3][lane] as float4
