@@ -34,8 +34,8 @@
 // The first two blocks of every wave are requested before the sequence length is known (the
 // host's bound fixes the geometry; a block past the end is fetched, in bounds, and ignored).
 // The queries of the head sit in LDS, shared by the four waves; they get there by direct
-// global-to-LDS loads issued from inline assembly, the first loads of each wave, waited for
-// with an explicit count ("all but the ring's loads have landed").
+// global-to-LDS loads issued from inline assembly, which the compiler does not count: each wave
+// waits for vmcnt(0) once, before the barrier that publishes the queries.
 //
 // The running maximum is only raised when a block's maximum exceeds it by more than 2^8: the
 // softmax is invariant to the reference point, exp2 of at most 8 cannot overflow anything, and
@@ -57,9 +57,8 @@ static __device__ __forceinline__ void acc_scale(float& x, float alpha) {
 template <int N> static __device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
 
 template <int HD, int TBW>
-__global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp, const bf16x8* __restrict__ Kc,
-                                                   const bf16x8* __restrict__ Vc, const bf16x8* __restrict__ Kt,
-                                                   const bf16x8* __restrict__ Vt, const int32_t* __restrict__ kv_len,
+__global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp, const bf16x8* Kc, const bf16x8* Vc,
+                                                   const bf16x8* Kt, const bf16x8* Vt, const int32_t* __restrict__ kv_len,
                                                    const uint32_t* __restrict__ anc, float* __restrict__ opart,
                                                    float2* __restrict__ mlpart, int nh, int Tp, int cap_blocks,
                                                    int ncparts, int per, int tree_sep, float scale_log2) {
@@ -87,8 +86,7 @@ __global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp
     const bool has_cache = part < ncparts;
     const int ntree = (part == nparts - 1) ? tg * TBW + TBW : 0;   // later tree blocks hold no ancestors
 
-    // ancestor words of this lane's query rows: only the part with the tree blocks masks by them. Fetched before any
-    // direct-to-LDS load is in flight and waited for at once, so the explicit counts below stay exact.
+    // ancestor words of this lane's query rows: only the part with the tree blocks masks by them
     static_assert(SD_ANC_WORDS == 4, "one 16-byte load per row");
     uint4 ancq[TBW];
 #pragma unroll
@@ -97,13 +95,6 @@ __global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp
 #pragma unroll
         for (int tb = 0; tb < TBW; ++tb)
             ancq[tb] = *(const uint4*)(anc + ((size_t)b * Tp + (tg * TBW + tb) * 32 + tl) * SD_ANC_WORDS);
-        wait_vm<0>();
-    }
-
-    {   // queries of this (sequence, head, query group) -> LDS, a quarter per wave
-        const bf16x8* qsrc = Qp + (((size_t)b * nh + h) * TB + tg * TBW) * (KK * 2 * 64) + lane;
-#pragma unroll
-        for (int i = 0; i < QW; ++i) lds_dma16(qsrc + (wave * QW + i) * 64, myq_addr + i * 1024);
     }
 
     // The part's items: its tree blocks first, then its cache blocks; wave w owns items
@@ -137,6 +128,11 @@ __global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp
         for (int i = 0; i < NV; ++i) vd[i] = __builtin_nontemporal_load(vp + i * 64);
     };
     request_k(kr[0], jw); request_v(vr[0], jw); request_k(kr[1], jw + 1); request_v(vr[1], jw + 1);
+    {   // queries of this (sequence, head, query group) -> LDS, a quarter per wave
+        const bf16x8* qsrc = Qp + (((size_t)b * nh + h) * TB + tg * TBW) * (KK * 2 * 64) + lane;
+#pragma unroll
+        for (int i = 0; i < QW; ++i) lds_dma16(qsrc + (wave * QW + i) * 64, myq_addr + i * 1024);
+    }
 
     const int n = kv_len[b];
     const int nblk = (n + 31) >> 5;
@@ -251,7 +247,10 @@ __global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp
             }
     };
 
-    wait_vm<2 * NL>();                                 // this wave's share of the queries has landed
+    // Everything this wave has requested so far has landed, its quarter of the queries included. (No
+    // smaller count is safe: the ring's loads are the compiler's to place, so how many of them follow
+    // the query loads in the instruction stream is not known here.)
+    wait_vm<0>();
     __syncthreads();                                   // queries are in LDS
     if (nit > 0) {
         for (int it = 0; it < nit; it += 2) {

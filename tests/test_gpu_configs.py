@@ -120,6 +120,43 @@ def test_long_context_synthetic_cache(sd):
     assert max(rep.raw) >= 2                               # the planted draft was accepted
 
 
+@pytest.mark.parametrize("kind", ["speculative", "greedy"])
+def test_repeated_step_is_bit_identical(sd, kind):
+    """The same step from the same state, many times over: every output must be bit-identical
+    (the kernels have no order-dependent reductions). Guards the hand-made synchronisation in the
+    attention kernel (queries published through LDS to the other waves): a wave that read them
+    early would show up here as run-to-run differences."""
+    shape = _shape("7b", 8)
+    B, T, n, cap = 1, 64, 1100, 2048
+    weights = wl.make_weights(shape, device="cuda")
+    model = sd.Model(shape, weights, 64)
+    kv = sd.KVCache(model, B, cap)
+    stop = wl.stop_set(shape.vocab, 0.2)
+    words = torch.from_numpy(wl.pack_mask_words(stop).view(np.int32)).cuda()
+    tree = sd.Tree(*wl.default_tree(T, shape.n_medusa, shape.topk), shape.n_medusa, shape.topk)
+    for layer in range(shape.n_layers):
+        dims = (n, shape.n_heads, shape.head_dim)
+        k = wl.synthetic_kv_rows(wl.SEEDS["kvfill"], f"k0.{layer}", dims, "bf16")
+        v = wl.synthetic_kv_rows(wl.SEEDS["kvfill"], f"v0.{layer}", dims, "bf16")
+        kv.write_rows(layer, 0, 0, k.cuda().contiguous(), v.cuda().contiguous())
+    roots, cand = _random_draft(shape, B, 7)
+    first = None
+    for rep in range(100):
+        kv.set_len([n])
+        kv.set_draft(roots, cand)
+        if kind == "speculative":
+            out = sd.spec_step(model, kv, tree, words, want_logits=True, want_argmax=True)
+        else:
+            out = sd.greedy_step(model, kv, want_logits=True)
+        torch.cuda.synchronize()
+        got = (out.logits.clone(), out.tokens.clone(), out.n_accept.clone())
+        if first is None:
+            first = got
+        else:
+            assert torch.equal(got[0], first[0]), f"logits differ on repetition {rep}"
+            assert torch.equal(got[1], first[1]) and torch.equal(got[2], first[2])
+
+
 @pytest.mark.timeout(900)
 def test_7b_full_depth_one_step(sd):
     """configs[1] at its full depth: all 32 layers at d=4096, a 64-node tree over 512 committed rows.
