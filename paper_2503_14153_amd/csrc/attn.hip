@@ -45,7 +45,7 @@
 static __device__ __forceinline__ void lds_dma16(const void* src_lane, uint32_t lds_byte_addr) {
     // lane i's 16 bytes land at lds_byte_addr + 16 * i
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                 :: "s"(lds_byte_addr), "v"(src_lane) : "memory");
+                 :: "s"(lds_byte_addr), "v"(src_lane) : "memory", "m0");
 }
 // x *= alpha for an accumulator that lives in an AGPR (keeps the compiler from moving the whole
 // accumulator set to VGPRs and back around the rarely taken rescaling branch)
