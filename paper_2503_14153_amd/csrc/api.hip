@@ -82,7 +82,10 @@ struct sd_model {
     const GemmPlan& plan(int MB, int KB, int NB) const {
         for (const GemmPlan& p : plans)
             if (p.MB == MB && p.KB == KB && p.NB == NB) return p;
-        return plans[0];                     // unreachable: every shape is planned at creation
+        // every shape a call can issue is planned at creation; launching with another shape's plan
+        // would read and write out of bounds, so an inconsistency here must not be survivable
+        fprintf(stderr, "libspecdec: internal error: no GEMM plan for %d row blocks, KB=%d, NB=%d\n", MB, KB, NB);
+        abort();
     }
 };
 

@@ -43,9 +43,10 @@
 #define SD_LAZY_MAX 8.0f
 
 static __device__ __forceinline__ void lds_dma16(const void* src_lane, uint32_t lds_byte_addr) {
-    // lane i's 16 bytes land at lds_byte_addr + 16 * i
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                 :: "s"(lds_byte_addr), "v"(src_lane) : "memory", "m0");
+    // lane i's 16 bytes land at lds_byte_addr + 16 * i; M0 (the LDS base of the load) is put back
+    uint32_t saved_m0;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
+                 : "=&s"(saved_m0) : "s"(lds_byte_addr), "v"(src_lane) : "memory");
 }
 // x *= alpha for an accumulator that lives in an AGPR (keeps the compiler from moving the whole
 // accumulator set to VGPRs and back around the rarely taken rescaling branch)
@@ -65,7 +66,6 @@ __global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp
     constexpr int KK = HD / 16;        // contraction steps of QK^T = K fragments per block
     constexpr int EB = HD / 32;        // 32-wide output blocks of PV
     constexpr int NV = 2 * EB;         // V fragments per block
-    constexpr int NL = KK + NV;        // loads per block
     constexpr int BLK = HD * 4;        // bf16x8 units per 32-row block
     constexpr int QF = TBW * KK * 2;   // query fragments held in LDS
     constexpr int QW = QF / 4;         // of which every wave fetches this many
