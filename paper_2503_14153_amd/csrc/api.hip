@@ -270,7 +270,7 @@ extern "C" int sd_model_create(const sd_config* cfg, const sd_weights* w, int32_
         return fail(SD_ERR_HIP, "hipMalloc(%zu) for workspace: %s", wz, hipGetErrorString(e));
     }
     for (size_t i = 0; i < m->plans.size(); ++i)
-        if (m->plans[i].kind == 1) m->plans[i].cnt_dev = m->plan_cnt + cnt_off[i];
+        m->plans[i].cnt_dev = m->plan_cnt + cnt_off[i];
     hipMemsetAsync(m->work, 0, wz, s);
     char* Wk = m->work;
     m->x = (float*)(Wk + w_x); m->part = (float*)(Wk + w_part); m->logits = (float*)(Wk + w_logits);

@@ -5,12 +5,11 @@
 // read exactly once: the kernel is bound by the HBM read of W, not by the matrix cores. The
 // design therefore (1) stores W pre-tiled as 1 KiB MFMA fragments, contraction-block-major
 // ([kb][nb]): a wave fetches a fragment with one 16-byte-per-lane load, and at any moment the
-// waves of the whole grid (all nb, similar kb) read one contiguous region of HBM, which
-// spreads over every channel instead of marching through power-of-two strides in step, (2) keeps many such loads in flight per wave
-// (a chunk of KC fragments is fetched while the previous chunk is multiplied), (3) shares the
-// small activation operand between the waves of a workgroup through LDS, and (4) splits the
-// contraction across workgroups when N alone gives too few workgroups for 256 CUs; the
-// consumer kernel sums the split partial results (deterministic, no atomics).
+// waves of the whole grid read one contiguous region of HBM, (2) keeps a ring of such loads in
+// flight per wave, refilled as it is consumed, (3) shares the small activation operand between
+// the waves of a workgroup through LDS, and (4) splits the contraction across workgroups so
+// that every one of 256 CUs streams the same number of weight bytes; the consumer kernel sums
+// the split partial results (deterministic, no atomics).
 //
 // Precision: the weights are bf16 by definition, the activations are not. Since the matrix
 // cores idle most of the time in an HBM-bound kernel, each activation enters as a two-term
@@ -46,128 +45,8 @@ void launch_pack_weight(const void* src, void* dst, int N, int K, int nb_offset,
 }
 
 // ------------------------------------------------------------------------------------------
-// MT  = number of 32-row activation blocks (all of them: W is read once for every row)
-// NW  = consumer waves per workgroup; wave w owns output columns [32*(NW*blockIdx.x + w), +32)
-// R   = depth of the per-wave ring of weight fragments: R 1-KiB loads stay in flight per wave;
-//       a ring slot is refilled with the fragment R steps ahead as soon as it is consumed
-// XK  = contraction blocks per LDS chunk of the shared activation operand (double-buffered)
-//
-// Wave NW is a producer: it alone fetches the activation chunks (L2 hits) and stores them to
-// LDS. Vector loads of one wave return in order, so an activation load issued by a consumer
-// would queue behind the R HBM loads of its ring and every chunk would cost a full HBM
-// latency; the producer's queue holds only the short L2 loads.
-template <int MT, int NW>
-__global__ __launch_bounds__((NW + 1) * 64, (MT <= 2 ? 3 : 1)) void k_gemm_stream(
-    const bf16x8* __restrict__ Xp, const bf16x8* __restrict__ Wp, float* __restrict__ out, int KB, int NB, int ldo,
-    int kb_per_split, size_t split_stride) {
-    constexpr int R = 16;
-    constexpr int XK = (MT >= 8) ? 1 : 8 / MT;
-    constexpr int XF = XK * MT * 2;                  // X fragments per chunk (hi and lo parts) = 16
-    constexpr int CPI = R / XK;                      // chunks per outer iteration (even)
-    constexpr int D = 2;                             // chunks the producer keeps in flight
-    static_assert(R % XK == 0 && CPI % 2 == 0 && XF == 16, "bad tiling");
-    __shared__ bf16x8 xs[2][XF * 64];
-
-    const int tid = threadIdx.x;
-    const int wave = tid >> 6, lane = tid & 63;
-    const int kb0 = blockIdx.y * kb_per_split;
-    int kb1 = kb0 + kb_per_split;
-    if (kb1 > KB) kb1 = KB;
-    const int nsteps = kb1 - kb0;                     // may be <= 0 for a trailing split
-    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-
-    if (wave == NW) {
-        // ---------------- producer: chunk c = contraction blocks [c*XK, (c+1)*XK) of the slice
-        if (nsteps <= 0) return;
-        const bf16x8* xbase = Xp + (size_t)kb0 * MT * 2 * 64 + lane;
-        const int nfrag = nsteps * MT * 2;            // fragments in the slice
-        bf16x8 st[D][XF];
-        auto fetch = [&](bf16x8(&dst)[XF], int c) {
-#pragma unroll
-            for (int f = 0; f < XF; ++f) {
-                int fi = c * XF + f;
-                dst[f] = (fi < nfrag) ? xbase[(size_t)fi * 64] : zero;
-            }
-        };
-        auto put = [&](const bf16x8(&src)[XF], int buf) {
-#pragma unroll
-            for (int f = 0; f < XF; ++f) xs[buf][f * 64 + lane] = src[f];
-        };
-        fetch(st[0], 0);
-        put(st[0], 0);
-        fetch(st[1], 1);                              // stage (c+1)&1 holds chunk c+1
-        fetch(st[0], 2);
-        __syncthreads();
-        for (int base = 0; base < nsteps; base += R) {
-#pragma unroll
-            for (int c = 0; c < CPI; ++c) {
-                const int step0 = base + c * XK;
-                if (step0 >= nsteps) break;
-                const int ci = step0 / XK;            // chunk being consumed; CPI even => parity of ci == c & 1
-                if (step0 + XK < nsteps) {
-                    put(st[(c + 1) & 1], (c + 1) & 1);
-                    fetch(st[(c + 1) & 1], ci + 1 + D);
-                }
-                __syncthreads();
-            }
-        }
-        return;
-    }
-
-    // -------------------- consumers
-    int nb = blockIdx.x * NW + wave;
-    const bool owns = nb < NB;
-    if (!owns) nb = NB - 1;                           // keep the wave in the barriers
-    const bf16x8* wrow = Wp + ((size_t)kb0 * NB + nb) * 64 + lane;     // fragment (kb, nb); next kb is NB further
-    const size_t wstep = (size_t)NB * 64;
-    f32x16 acc[MT];
-#pragma unroll
-    for (int i = 0; i < MT; ++i)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
-
-    if (nsteps > 0) {
-        bf16x8 w[R];
-#pragma unroll
-        for (int i = 0; i < R; ++i) w[i] = (i < nsteps) ? __builtin_nontemporal_load(wrow + (size_t)i * wstep) : zero;
-        __syncthreads();
-        for (int base = 0; base < nsteps; base += R) {
-#pragma unroll
-            for (int c = 0; c < CPI; ++c) {
-                const int step0 = base + c * XK;
-                if (step0 >= nsteps) break;           // uniform over the workgroup
-#pragma unroll
-                for (int j = 0; j < XK; ++j) {
-                    const int i = c * XK + j;         // ring slot (compile-time)
-#pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) {
-                        bf16x8 hi = xs[c & 1][((j * MT + mt) * 2) * 64 + lane];
-                        bf16x8 lo = xs[c & 1][((j * MT + mt) * 2 + 1) * 64 + lane];
-                        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hi, w[i], acc[mt], 0, 0, 0);
-                        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo, w[i], acc[mt], 0, 0, 0);
-                    }
-                    const int nxt = base + i + R;
-                    w[i] = (nxt < nsteps) ? __builtin_nontemporal_load(wrow + (size_t)nxt * wstep) : zero;
-                }
-                __syncthreads();
-            }
-        }
-    }
-
-    if (!owns) return;
-    float* o = out + (size_t)blockIdx.y * split_stride + (size_t)nb * 32 + (lane & 31);
-    const int g = lane >> 5;
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            int m = mt * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-            o[(size_t)m * ldo] = acc[mt][v];
-        }
-}
-
-// ------------------------------------------------------------------------------------------
-// Balanced streaming ("stream-K") variant for MT <= 2, the shapes of batch-1 decoding.
+// Balanced streaming ("stream-K") over MT = 1, 2 or 4 row blocks of 32 rows; more rows are done
+// in passes of four row blocks (the weights are then streamed once per pass).
 //
 // The work of one GEMM is the list of units (column group of 256 outputs, contraction block),
 // contraction block fastest; workgroup g of G takes the contiguous range [g*U/G, (g+1)*U/G),
@@ -189,10 +68,11 @@ __global__ __launch_bounds__((NW + 1) * 64, (MT <= 2 ? 3 : 1)) void k_gemm_strea
 // parked in registers until the chunk before them has been consumed.
 struct SkIter { int kb, ng, valid, last; };
 
-template <int MT>
+// PASSES: the activation holds more row blocks than this launch multiplies (x_kb_units > MT*2*64)
+template <int MT, bool PASSES>
 __global__ __launch_bounds__(512, 2) void k_gemm_sk(const bf16x8* __restrict__ Xp, const bf16x8* __restrict__ Wp,
                                                     const bf16x8* __restrict__ zfrag, float* __restrict__ out,
-                                                    int KB, int NB, int NG, int ldo, size_t slot_stride) {
+                                                    int KB, int NB, int NG, int ldo, size_t slot_stride, int x_kb_units) {
     constexpr int R = MT >= 4 ? 8 : 16;              // ring depth: with four row blocks the accumulators need the registers
     constexpr int XK = 8 / MT;                       // contraction blocks per chunk
     constexpr int CPI = R / XK;                      // chunks per outer iteration (2 or 4)
@@ -241,12 +121,16 @@ __global__ __launch_bounds__(512, 2) void k_gemm_sk(const bf16x8* __restrict__ X
     auto xload = [&](bf16x8(&dst)[XP], const SkIter& I, int c) {
         int steps = I.valid - c * XK;
         steps = steps < 0 ? 0 : (steps > XK ? XK : steps);
-        const int limit = steps * MT * 2 * 64;
-        const bf16x8* base = Xp + (size_t)(I.kb + c * XK) * MT * 2 * 64;
+        constexpr int PER_KB = MT * 2 * 64;            // 16-byte units of this pass's row blocks per contraction block
+        const int limit = steps * PER_KB;
+        // x_kb_units = units between contraction blocks of the packed activation (all its row blocks)
+        const int kb_units = PASSES ? x_kb_units : PER_KB;
+        const bf16x8* base = Xp + (size_t)(I.kb + c * XK) * kb_units;
 #pragma unroll
         for (int p = 0; p < XP; ++p) {
             const int i = p * 512 + tid;
-            dst[p] = *((i < limit) ? base + i : zl);
+            const bf16x8* src = PASSES ? base + (size_t)(i / PER_KB) * kb_units + (i % PER_KB) : base + i;
+            dst[p] = *((i < limit) ? src : zl);
         }
     };
     auto xstore = [&](const bf16x8(&src)[XP], int buf) {
@@ -348,26 +232,8 @@ void launch_reduce_slots(PartView pv, float* dst, int rows, hipStream_t s) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Uniform split-K (kind 0): enough workgroups to fill 256 CUs a few times over, slices of at
-// least 256 contraction elements, and partial sums (which the consumer re-reads) kept to a
-// fraction of the weight bytes.
-static int gemm_choose_split(int MB, int KB, int NB) {
-    const int NW = 4;
-    int groups = (NB + NW - 1) / NW;
-    int split = 1;
-    const double w_bytes = (double)NB * 32 * KB * 16 * 2;
-    while (groups * split < 512 && split < 16 && KB / (split * 2) >= 16) {
-        double part_bytes = (double)(split * 2) * (MB * 32) * (NB * 32) * 4 * 2;   // written, then read
-        if (part_bytes > 0.5 * w_bytes) break;
-        split *= 2;
-    }
-    return split;
-}
-
 #define SK_MAX_WG 256       // one workgroup of 8 waves per CU
-#ifndef SK_MAX_MB
-#define SK_MAX_MB 4          // row blocks (of 32 rows) up to which the stream-K kernel is used
-#endif
+#define SK_MAX_MT 4         // row blocks per pass
 #ifndef SK_SMALL_U
 #define SK_SMALL_U (16 * SK_MAX_WG * 2)   // (column groups x contraction blocks) up to which half the workgroups are used
 #endif
@@ -375,15 +241,6 @@ static int gemm_choose_split(int MB, int KB, int NB) {
 void gemm_plan_make(GemmPlan* p, int MB, int KB, int NB, int32_t* cnt_host) {
     p->MB = MB; p->KB = KB; p->NB = NB;
     p->cnt_dev = nullptr;
-    if (MB > SK_MAX_MB) {
-        p->kind = 0;
-        p->nsplit = gemm_choose_split(MB, KB, NB);
-        p->G = 0; p->NG = 0;
-        p->slots = p->nsplit;
-        return;
-    }
-    p->kind = 1;
-    p->nsplit = 0;
     p->NG = (NB + 7) / 8;
     const int U = p->NG * KB;
     int G = U / 16;                                   // at least one ring length of steps each
@@ -410,39 +267,27 @@ void gemm_plan_make(GemmPlan* p, int MB, int KB, int NB, int32_t* cnt_host) {
     p->slots = slots;
 }
 
-template <int MT>
-static void launch_gemm_t(const void* Xp, const void* Wp, float* out, int KB, int NB, int ldo, int nsplit,
-                          size_t split_stride, hipStream_t s) {
-    constexpr int NW = 4;
-    int groups = (NB + NW - 1) / NW;
-    int kps = (KB + nsplit - 1) / nsplit;
-    hipLaunchKernelGGL((k_gemm_stream<MT, NW>), dim3(groups, nsplit), dim3((NW + 1) * 64), 0, s,
-                       (const bf16x8*)Xp, (const bf16x8*)Wp, out, KB, NB, ldo, kps, split_stride);
-}
-
 PartView launch_gemm(const GemmPlan& p, const void* Xp, const void* Wp, const void* zfrag, float* out, hipStream_t s) {
     PartView pv;
     pv.base = out;
     pv.ld = p.NB * 32;
     pv.slot_stride = (size_t)p.MB * 32 * pv.ld;
     pv.group_cols = 256;
-    if (p.kind == 1) {
-        pv.cnt = p.cnt_dev;
-        pv.nmax = p.slots;
-        if (p.MB == 1)
-            hipLaunchKernelGGL((k_gemm_sk<1>), dim3(p.G), dim3(512), 0, s, (const bf16x8*)Xp, (const bf16x8*)Wp,
-                               (const bf16x8*)zfrag, out, p.KB, p.NB, p.NG, pv.ld, pv.slot_stride);
-        else if (p.MB == 2)
-            hipLaunchKernelGGL((k_gemm_sk<2>), dim3(p.G), dim3(512), 0, s, (const bf16x8*)Xp, (const bf16x8*)Wp,
-                               (const bf16x8*)zfrag, out, p.KB, p.NB, p.NG, pv.ld, pv.slot_stride);
-        else
-            hipLaunchKernelGGL((k_gemm_sk<4>), dim3(p.G), dim3(512), 0, s, (const bf16x8*)Xp, (const bf16x8*)Wp,
-                               (const bf16x8*)zfrag, out, p.KB, p.NB, p.NG, pv.ld, pv.slot_stride);
-        return pv;
+    pv.cnt = p.cnt_dev;
+    pv.nmax = p.slots;
+    const int MT = p.MB < SK_MAX_MT ? p.MB : SK_MAX_MT;
+    const int x_kb_units = p.MB * 2 * 64;
+    for (int r = 0; r < p.MB / MT; ++r) {              // passes of MT row blocks
+        const bf16x8* xp = (const bf16x8*)Xp + (size_t)r * MT * 2 * 64;
+        float* o = out + (size_t)r * MT * 32 * pv.ld;
+#define SK_LAUNCH(MT_, PASSES_)                                                                            \
+        hipLaunchKernelGGL((k_gemm_sk<MT_, PASSES_>), dim3(p.G), dim3(512), 0, s, xp, (const bf16x8*)Wp,   \
+                           (const bf16x8*)zfrag, o, p.KB, p.NB, p.NG, pv.ld, pv.slot_stride, x_kb_units)
+        if (MT == 1) SK_LAUNCH(1, false);
+        else if (MT == 2) SK_LAUNCH(2, false);
+        else if (p.MB == MT) SK_LAUNCH(4, false);
+        else SK_LAUNCH(4, true);
+#undef SK_LAUNCH
     }
-    pv.cnt = nullptr;
-    pv.nmax = p.nsplit;
-    if (p.MB == 4) launch_gemm_t<4>(Xp, Wp, out, p.KB, p.NB, pv.ld, p.nsplit, pv.slot_stride, s);
-    else launch_gemm_t<8>(Xp, Wp, out, p.KB, p.NB, pv.ld, p.nsplit, pv.slot_stride, s);
     return pv;
 }

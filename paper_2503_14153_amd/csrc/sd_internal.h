@@ -92,11 +92,9 @@ static __device__ inline int part_count(const PartView& p, int col) { return p.c
 // How one GEMM shape is launched (made once per shape at model creation).
 struct GemmPlan {
     int MB, KB, NB;
-    int kind;                // 0: uniform split-K grid, 1: balanced contraction streaming (stream-K)
-    int nsplit;              // kind 0
-    int G, NG;               // kind 1: workgroups, 256-column groups
+    int G, NG;               // workgroups, 256-column groups
     int slots;               // slots the output buffer must hold
-    int32_t* cnt_dev;        // kind 1: [NG] contributors per column group (device), else NULL
+    int32_t* cnt_dev;        // [NG] contributors per column group (device)
 };
 
 #define SD_MAX_BATCH 32
@@ -115,7 +113,7 @@ struct VerifyArgs {
 // ---- launchers (defined in the kernel translation units) ----------------------------------
 // All take a stream; all sizes have been validated by the caller.
 void launch_pack_weight(const void* src, void* dst, int N, int K, int nb_offset, int NBdst, int KB, hipStream_t s);
-// fills every field of the plan except cnt_dev; cnt_host receives the per-group counts (kind 1)
+// fills every field of the plan except cnt_dev; cnt_host receives the per-group counts
 void gemm_plan_make(GemmPlan* p, int MB, int KB, int NB, int32_t* cnt_host /*[>= ceil(NB/8)]*/);
 // out must hold plan.slots * (MB*32) * (NB*32) floats; zfrag: 1 KiB of zeros (device);
 // returns the view consumers read
