@@ -265,6 +265,8 @@ void gemm_plan_make(GemmPlan* p, int MB, int KB, int NB, int32_t* cnt_host) {
         if (cnt_host[ng] > slots) slots = cnt_host[ng];
     }
     p->slots = slots;
+    p->uniform = 1;                                   // every column group has the same number of contributors?
+    for (int ng = 0; ng < p->NG; ++ng) p->uniform &= (cnt_host[ng] == slots);
 }
 
 PartView launch_gemm(const GemmPlan& p, const void* Xp, const void* Wp, const void* zfrag, float* out, hipStream_t s) {
@@ -273,7 +275,7 @@ PartView launch_gemm(const GemmPlan& p, const void* Xp, const void* Wp, const vo
     pv.ld = p.NB * 32;
     pv.slot_stride = (size_t)p.MB * 32 * pv.ld;
     pv.group_cols = 256;
-    pv.cnt = p.cnt_dev;
+    pv.cnt = p.uniform ? nullptr : p.cnt_dev;         // NULL: nmax slots everywhere, the consumer need not look it up
     pv.nmax = p.slots;
     const int MT = p.MB < SK_MAX_MT ? p.MB : SK_MAX_MT;
     const int x_kb_units = p.MB * 2 * 64;

@@ -94,6 +94,7 @@ struct GemmPlan {
     int MB, KB, NB;
     int G, NG;               // workgroups, 256-column groups
     int slots;               // slots the output buffer must hold
+    int uniform;             // 1: every column group has exactly `slots` contributors
     int32_t* cnt_dev;        // [NG] contributors per column group (device)
 };
 
