@@ -120,6 +120,17 @@ def test_long_context_synthetic_cache(sd):
     assert max(rep.raw) >= 2                               # the planted draft was accepted
 
 
+@pytest.mark.parametrize("n", [1, 31, 32, 33, 1023, 1792, 1793, 2040])
+def test_context_lengths_around_the_attention_geometry_edges(sd, n):
+    """One speculative step at the 7B width over n committed rows, n chosen around the places where
+    the attention launch changes shape: a single partial block, exact block multiples, the largest
+    context that still gets a workgroup of its own for the tree blocks (56 blocks at 32 heads), the
+    first one that does not, and a cache filled to within a step of its capacity."""
+    shape = _shape("7b")
+    rep = _run_batch_steps(sd, shape, 1, 64, [n], 2048, n_steps=1, weights_device="cuda")
+    print(f"\n[7b L2 n={n}] max_abs={rep.max_abs:.3g} rel={rep.max_rel:.3g}")
+
+
 @pytest.mark.parametrize("kind", ["speculative", "greedy"])
 def test_repeated_step_is_bit_identical(sd, kind):
     """The same step from the same state, many times over: every output must be bit-identical
