@@ -11,6 +11,9 @@ What it computes follows the paper's decoding description (Section III-B):
   * a drafted token is accepted only if it, and every token before it, passes the acceptance
     test; under greedy decoding (one of the two decoding modes of Section IV-A) the test is
     "equals the base model's arg-max given the tokens before it";
+    "equals the base model's arg-max given the tokens before it"; under sampling decoding it is
+    the typical-acceptance inequality (Section III-B, Eq. 1): the base model's probability of the
+    token must exceed min(epsilon, delta * exp(-entropy of the base distribution));
   * the accepted run is then cut back to the end of its last complete syntactic fragment
     (the paper marks fragment ends with a [FRAG] token; here any id in a stop set);
   * the step emits the longest accepted, cut-back prefix over all candidates.
@@ -35,6 +38,12 @@ Conventions (readings of points the paper leaves open):
   * a tree node's token depends only on (depth, rank): tok = cand[depth-1][rank];
   * the cut keeps the stop token itself; when the accepted run holds no stop token the
     whole run is kept ("keep_all") or only its first token ("keep_one");
+  * sampling decoding (Section IV-A: temperature 0.8): probabilities are softmax(logits /
+    temperature); the root token of a step is always accepted (it was drawn from the base model
+    itself at the previous step); among several accepted paths the deepest wins, the lowest node
+    index on equal depth; the next root is drawn from the base distribution at the last kept
+    node by inverting its cumulative distribution over ascending token ids at a uniform number
+    that is an INPUT of the step (the oracle draws nothing itself);
   * precision: the paper loads its models in float16 (Section IV-A) and says nothing else.
     Here a model's `dtype` names a STORAGE format, not an arithmetic: for "bf16" the weights,
     the embeddings and every key/value row exist only as bfloat16 numbers (a K/V row is
@@ -250,6 +259,69 @@ def fragment_cut(chain_tokens, stop: np.ndarray, fallback: str = "keep_all") -> 
     return len(chain_tokens) if fallback == "keep_all" else 1
 
 
+def softmax_t(logits: np.ndarray, temperature: float) -> np.ndarray:
+    """softmax(logits / temperature) of one row, in float64."""
+    x = np.asarray(logits, F64) / F64(temperature)
+    e = np.exp(x - x.max())
+    return e / e.sum()
+
+
+def entropy(p: np.ndarray) -> float:
+    """Shannon entropy (natural log) of a probability vector; 0 log 0 = 0."""
+    q = p[p > 0]
+    return float(-(q * np.log(q)).sum())
+
+
+def typical_threshold(p: np.ndarray, epsilon: float, delta: float) -> float:
+    """Right-hand side of the typical-acceptance inequality (Section III-B, Eq. 1)."""
+    return float(min(F64(epsilon), F64(delta) * np.exp(-entropy(p))))
+
+
+def typical_accept(tok, logits, parent, depth, temperature: float, epsilon: float, delta: float):
+    """Prefix-closed typical acceptance over the tree (Section III-B, Eq. 1).
+
+    The root is always accepted. A drafted node is accepted iff its parent is accepted and the
+    base model's probability of its token, given the tokens up to its parent, exceeds
+    min(epsilon, delta * exp(-H)) with H the entropy of that same distribution. Returns
+    (ok[T], chain, log_margin[T]) where chain is the root-to-deepest accepted path (lowest node
+    index on equal depth) and log_margin[j] = log p - log threshold of node j's own test.
+    """
+    T = len(parent)
+    ok = np.zeros(T, bool)
+    ok[0] = True
+    log_margin = np.full(T, np.inf)
+    for j in range(1, T):
+        p = softmax_t(logits[parent[j]], temperature)
+        thr = typical_threshold(p, epsilon, delta)
+        pj = p[tok[j]]
+        with np.errstate(divide="ignore"):
+            log_margin[j] = np.log(pj) - np.log(thr) if thr > 0 else np.inf
+        ok[j] = ok[parent[j]] and pj > thr
+    best = 0
+    for j in range(T):
+        if ok[j] and depth[j] > depth[best]:
+            best = j
+    chain = []
+    i = best
+    while i >= 0:
+        chain.append(i)
+        i = parent[i]
+    return ok, chain[::-1], log_margin
+
+
+def sample_token(p: np.ndarray, u: float) -> int:
+    """Inverse-CDF draw: the smallest token id whose cumulative probability exceeds u in [0, 1)."""
+    acc = F64(0.0)
+    last_positive = 0
+    for v in range(len(p)):
+        if p[v] > 0:
+            last_positive = v
+        acc += p[v]
+        if acc > u:
+            return v
+    return last_positive            # u at or above the rounded total: the last token that has mass
+
+
 # ----------------------------------------------------------------------------- decoding state
 @dataclass
 class DecodeState:
@@ -276,6 +348,7 @@ class StepRecord:
     next_root: int
     next_cand: np.ndarray
     head_logits: np.ndarray
+    log_margin: np.ndarray | None = None   # typical acceptance: log p - log threshold per node
 
 
 def prefill(weights, shape, prompt, cap: int) -> DecodeState:
@@ -293,11 +366,13 @@ def prefill(weights, shape, prompt, cap: int) -> DecodeState:
 
 
 def spec_step(weights, shape, st: DecodeState, tree, stop: np.ndarray,
-              fallback: str = "keep_all", cand_override=None) -> StepRecord:
+              fallback: str = "keep_all", cand_override=None, typical=None) -> StepRecord:
     """One speculative step: draft tree -> one verifying forward -> accept -> cut -> commit.
 
     `tree` = (parent, depth, rank). `cand_override` replaces the carried draft candidates
-    (used to plant known continuations). Updates `st` in place and returns the record.
+    (used to plant known continuations). `typical` = None for greedy acceptance, or a dict
+    {temperature, epsilon, delta, u} for sampling decoding: typical acceptance (Eq. 1) and the
+    next root drawn at the uniform number u. Updates `st` in place and returns the record.
     """
     parent, depth, rank = tree
     cand = st.cand if cand_override is None else np.asarray(cand_override)
@@ -307,7 +382,12 @@ def spec_step(weights, shape, st: DecodeState, tree, stop: np.ndarray,
     tok, pos, anc = tree_inputs(st.root_tok, cand, parent, depth, rank, n)
     logits, h, k_new, v_new = forward_rows(weights, shape, tok, pos, anc, st.kv)
     am = argmax_lowest(logits)
-    ok, chain = greedy_accept(tok, am, parent, depth)
+    log_margin = None
+    if typical is None:
+        ok, chain = greedy_accept(tok, am, parent, depth)
+    else:
+        ok, chain, log_margin = typical_accept(tok, logits, parent, depth, typical["temperature"],
+                                               typical["epsilon"], typical["delta"])
     n_raw = len(chain)
     n_acc = fragment_cut([tok[c] for c in chain], stop, fallback)
     kept = chain[:n_acc]
@@ -316,6 +396,10 @@ def spec_step(weights, shape, st: DecodeState, tree, stop: np.ndarray,
         st.kv.v[:, n + j] = v_new[:, c]
     st.kv.n = n + n_acc
     last = kept[-1]
+    if typical is None:
+        next_root = int(am[last])
+    else:
+        next_root = sample_token(softmax_t(logits[last], typical["temperature"]), typical["u"])
     head_lg = medusa_logits(weights, shape, h[last])
     rec = StepRecord(
         tok=tok, pos=pos, logits=logits, am=am, ok=ok, chain=chain,
@@ -323,7 +407,8 @@ def spec_step(weights, shape, st: DecodeState, tree, stop: np.ndarray,
         tokens=np.array([tok[c] for c in kept], np.int32),
         src_slots=np.array(kept, np.int32),
         margin=top2_margin(logits),
-        next_root=int(am[last]),
+        next_root=next_root,
+        log_margin=log_margin,
         next_cand=np.stack([topk_ids(head_lg[i], shape.topk) for i in range(shape.n_medusa)]),
         head_logits=head_lg,
     )
