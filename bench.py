@@ -42,6 +42,9 @@ def parse():
     ap.add_argument("--workload", default="7b", choices=["7b", "7b-long", "13b", "tiny"])
     ap.add_argument("--layers", type=int, default=None, help="cut the depth (debugging only; result is labelled)")
     ap.add_argument("--draft", default="planted", choices=["planted", "random"])
+    ap.add_argument("--decoding", default="greedy", choices=["greedy", "sampling"],
+                    help="sampling = typical acceptance and a sampled next root at temperature 0.8 (the paper's "
+                         "second decoding setting); drafts are then the model's own heads'")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=32)
     ap.add_argument("--graph", action="store_true", help="replay captured HIP graphs instead of launching every kernel (measured: no gain, the step is not host-bound)")
@@ -132,9 +135,28 @@ def main():
     tok_host = torch.empty((1, H + 1), dtype=torch.int32).pin_memory()
     forced = torch.zeros((1, H, k), dtype=torch.int32, device="cuda")     # fixed buffer: graphs replay on it
     model.set_graph_mode(args.graph)
-    state = {"e": 0, "emitted": 0, "diverged": 0, "resets": 0}
+    state = {"e": 0, "emitted": 0, "diverged": 0, "resets": 0, "i": 0}
+    typical = dict(temperature=0.8, epsilon=0.09, delta=0.3)
+    n_u = args.steps + args.warmup + args.profile_steps
+    u_dev = torch.from_numpy(np.random.default_rng(wl.SEEDS["force"] + 1).random(n_u).astype(np.float32)).cuda()
+
+    def run_steps_sampling(n):
+        # nothing to compare the sampled stream with: e only tracks the committed length
+        for _ in range(n):
+            e, i = state["e"], state["i"]
+            if prompt_len + e + H + 1 > W.kv_cap - 1:
+                reset()
+                state["resets"] += 1
+                e = state["e"] = 0
+            sd.spec_step_typical(model, kv, tree, stop_words, u_dev[i: i + 1], out=out, **typical)
+            n_acc = kv.len()[0] - prompt_len - e      # synchronises the stream
+            state["e"] = e + n_acc
+            state["emitted"] += n_acc
+            state["i"] = i + 1
 
     def run_steps(n):
+        if args.decoding == "sampling":
+            return run_steps_sampling(n)
         for _ in range(n):
             e = state["e"]
             if e >= n_table or prompt_len + e + H + 1 > W.kv_cap - 1:
@@ -179,7 +201,8 @@ def main():
     # ---------------------------------------------------------------- CPU oracle on a bounded sample
     cpu = None
     if cpu_keep is not None:
-        cpu = cpu_baseline(wl, shape, cpu_keep, T, tree_np, stop, n_cache=prompt_len)
+        cpu = cpu_baseline(wl, shape, cpu_keep, T, tree_np, stop, n_cache=prompt_len,
+                           typical=dict(typical, u=0.5) if args.decoding == "sampling" else None)
 
     kv_bytes = (prompt_len + state["e"] / 2) * 2.0 * shape.d_model * 2 * shape.n_layers
     step_bytes = weight_bytes(shape) + kv_bytes
@@ -190,7 +213,9 @@ def main():
         "config": {"workload": f"{W.name}: {shape.n_layers}-layer d={shape.d_model} Llama-shaped decoder, "
                                f"{H} draft heads top-{k}, {T}-node tree, batch 1, Zipf prompt {prompt_len}, "
                                f"KV cap {W.kv_cap}, 20% stop ids",
-                   "draft_mode": args.draft, "planted_accuracy_by_depth": list(p_depth) if args.draft == "planted" else None},
+                   "decoding": args.decoding, "typical_acceptance": typical if args.decoding == "sampling" else None,
+                   "draft_mode": args.draft if args.decoding == "greedy" else "own heads",
+                   "planted_accuracy_by_depth": list(p_depth) if (args.draft == "planted" and args.decoding == "greedy") else None},
         "accepted_tokens_per_s": emitted / elapsed, "mean_accepted_len": emitted / args.steps,
         "greedy_tokens_per_s": n_timed / greedy_s, "speedup_vs_greedy": (emitted / elapsed) / (n_timed / greedy_s),
         "prefill_tokens_per_s": prompt_len / prefill_s,
@@ -208,7 +233,7 @@ def main():
     print(json.dumps(res))
 
 
-def cpu_baseline(wl, shape, cpu_keep, T, tree_np, stop, n_cache):
+def cpu_baseline(wl, shape, cpu_keep, T, tree_np, stop, n_cache, typical=None):
     """Time the oracle's speculative step on the host, on a bounded sample of the workload."""
     from threadpoolctl import threadpool_info
     from oracle import specdec_oracle as orc
@@ -228,7 +253,7 @@ def cpu_baseline(wl, shape, cpu_keep, T, tree_np, stop, n_cache):
         cand = (np.arange(shape.n_medusa * shape.topk, dtype=np.int32).reshape(shape.n_medusa, shape.topk) * 7 + 3) % shape.vocab
         st = orc.DecodeState(kv, root_tok=11, cand=cand)
         t0 = time.perf_counter()
-        orc.spec_step(w64, sh, st, tree_np, stop)
+        orc.spec_step(w64, sh, st, tree_np, stop, typical=typical)
         return time.perf_counter() - t0
 
     one_step(1)                                      # warm-up: BLAS threads, page faults

@@ -154,6 +154,30 @@ typedef struct sd_step_io {
  * knows; call sd_kv_len to refresh them).                                                  */
 int sd_spec_step(sd_model* m, sd_kv* kv, const sd_tree* tree, const uint32_t* stop_mask,
                  sd_step_io* io, void* stream);
+/* Sampling decoding (Section III-B, Eq. 1; Section IV-A runs it at temperature 0.8). The step
+ * is sd_spec_step with two changes. A drafted node is accepted iff its parent is and the base
+ * model's probability of its token given the tokens up to its parent, under
+ * softmax(logits / temperature), is greater than min(epsilon, delta * exp(-H)), H being the
+ * entropy (natural log) of that same distribution; the root is always accepted, the longest
+ * accepted path wins (lowest node index on equal depth) and the cut at the last stop token is
+ * unchanged. The token that starts the next step is not the arg-max but the inverse-CDF draw
+ * at u[b] from the base distribution at the last kept node: the smallest id whose cumulative
+ * probability exceeds u[b]. The caller owns the random numbers, so a run is reproducible.    */
+typedef struct sd_typical {
+    float temperature;         /* > 0                                                         */
+    float epsilon;             /* hard threshold, 0..1                                        */
+    float delta;               /* entropy-dependent threshold factor, >= 0                    */
+    const float* u;            /* dev [batch]: uniform numbers in [0, 1), read by this step   */
+    float* row_stats;          /* dev [batch][T][4] or NULL: per node {max logit, Z, H, c} of
+                                  its base distribution, Z = sum exp((logit - max) / temp) and
+                                  c = log(threshold * Z): a child token v passes iff
+                                  (logit_v - max) / temperature > c                           */
+} sd_typical;
+/* Arguments as sd_spec_step plus `ty` (host struct, read during the call). Probabilities are
+ * formed in fp32 with fp64 sums across the vocabulary. Never runs as a captured graph.
+ * SD_ERR_SHAPE for a temperature, epsilon or delta outside the ranges above.                */
+int sd_spec_step_typical(sd_model* m, sd_kv* kv, const sd_tree* tree, const uint32_t* stop_mask,
+                         sd_step_io* io, const sd_typical* ty, void* stream);
 /* Plain next-token greedy decoding: a step whose tree is the root alone (the paper's NTP
  * baseline, Section IV-B). Fills n_accept (=1), tokens, src_slots (=0); logits is
  * [batch][1][vocab].                                                                       */
@@ -167,6 +191,21 @@ int sd_verify_tree(const sd_tree* tree, int32_t batch, int32_t n_medusa, int32_t
                    int32_t vocab, const int32_t* tok, const int32_t* am, const uint32_t* stop_mask,
                    int32_t* n_accept, int32_t* n_accept_raw, int32_t* tokens, int32_t* src_slots,
                    void* stream);
+
+/* Typical acceptance + fragment cut alone (Section III-B, Eq. 1): logits dev
+ * [batch][T][vocab] = base logits of every node, tok dev [batch][T]. Writes row_stats (dev
+ * [batch][T][4], required, layout as in sd_typical) and then the four outputs as above.     */
+int sd_verify_tree_typical(const sd_tree* tree, int32_t batch, int32_t n_medusa, int32_t trunc_fallback,
+                           int32_t vocab, const int32_t* tok, const float* logits, float temperature,
+                           float epsilon, float delta, const uint32_t* stop_mask, float* row_stats,
+                           int32_t* n_accept, int32_t* n_accept_raw, int32_t* tokens, int32_t* src_slots,
+                           void* stream);
+/* Inverse-CDF draws alone (the sampling half of Section IV-A's decoding setting): out[i] =
+ * smallest id whose cumulative probability under softmax(logits[rows[i]] / temperature)
+ * exceeds u[i]. logits dev [n_rows][ld] with ld >= vocab; rows, u, out dev [n], n <= 65535;
+ * out[i] = -1 for a row index outside [0, n_rows).                                           */
+int sd_sample_tokens(const float* logits, int32_t n_rows, int32_t ld, int32_t vocab, const int32_t* rows,
+                     const float* u, int32_t n, float temperature, int32_t* out, void* stream);
 
 /* Graph mode (off by default). When on, sd_spec_step / sd_greedy_step capture their kernel
  * sequence into a HIP graph the first time a given combination of (cache, tree, split-KV

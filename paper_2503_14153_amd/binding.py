@@ -14,6 +14,7 @@ EXPORTED_SYMBOLS = [
     "sd_model_create", "sd_model_destroy", "sd_kv_bytes", "sd_kv_create", "sd_kv_destroy", "sd_kv_len",
     "sd_kv_set_len", "sd_kv_write_rows", "sd_kv_read_rows", "sd_kv_set_draft", "sd_kv_get_draft",
     "sd_tree_create", "sd_tree_destroy", "sd_prefill", "sd_spec_step", "sd_greedy_step", "sd_verify_tree",
+    "sd_spec_step_typical", "sd_verify_tree_typical", "sd_sample_tokens",
     "sd_set_graph_mode", "sd_profile_begin", "sd_profile_end", "sd_last_error", "sd_version",
 ]
 
@@ -43,6 +44,11 @@ class _Weights(C.Structure):
 class _StepIO(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("n_accept", "tokens", "src_slots", "n_accept_raw", "logits", "argmax",
                                           "head_logits", "forced_cand")]
+
+
+class _Typical(C.Structure):
+    _fields_ = [("temperature", C.c_float), ("epsilon", C.c_float), ("delta", C.c_float), ("u", C.c_void_p),
+                ("row_stats", C.c_void_p)]
 
 
 def lib_path() -> str:
@@ -80,6 +86,12 @@ def lib() -> C.CDLL:
         L.sd_spec_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(_StepIO), C.c_void_p]
         L.sd_greedy_step.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(_StepIO), C.c_void_p]
         L.sd_verify_tree.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32] + [C.c_void_p] * 8
+        L.sd_spec_step_typical.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(_StepIO),
+                                           C.POINTER(_Typical), C.c_void_p]
+        L.sd_verify_tree_typical.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                             C.c_void_p, C.c_float, C.c_float, C.c_float] + [C.c_void_p] * 7
+        L.sd_sample_tokens.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
+                                       C.c_float, C.c_void_p, C.c_void_p]
         L.sd_profile_begin.argtypes = [C.c_void_p, C.c_int32]
         L.sd_set_graph_mode.argtypes = [C.c_void_p, C.c_int32]
         L.sd_profile_end.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64),
@@ -234,6 +246,7 @@ class StepOutput:
     logits: torch.Tensor | None = None
     argmax: torch.Tensor | None = None
     head_logits: torch.Tensor | None = None
+    row_stats: torch.Tensor | None = None
 
 
 def prefill(model: Model, kv: KVCache, tokens: torch.Tensor, lens) -> None:
@@ -273,6 +286,25 @@ def spec_step(model: Model, kv: KVCache, tree: Tree, stop_mask: torch.Tensor, *,
     return out
 
 
+def spec_step_typical(model: Model, kv: KVCache, tree: Tree, stop_mask: torch.Tensor, u: torch.Tensor, *,
+                      temperature: float, epsilon: float, delta: float, want_logits=False, want_argmax=False,
+                      want_head_logits=False, want_row_stats=False, forced_cand: torch.Tensor | None = None,
+                      out: StepOutput | None = None) -> StepOutput:
+    """sd_spec_step_typical: sampling decoding. `u`: fp32 CUDA [batch], uniform numbers in [0, 1)."""
+    assert stop_mask.is_cuda and stop_mask.element_size() == 4 and stop_mask.numel() >= (model.shape.vocab + 31) // 32
+    assert u.is_cuda and u.dtype == torch.float32 and u.is_contiguous() and u.numel() == kv.batch
+    if forced_cand is not None:
+        assert forced_cand.dtype == torch.int32 and forced_cand.is_cuda and forced_cand.is_contiguous()
+        assert forced_cand.numel() == kv.batch * model.shape.n_medusa * model.shape.topk
+    out, io = _alloc_io(model, kv.batch, tree.T, want_logits, want_argmax, want_head_logits, forced_cand, out)
+    if want_row_stats and out.row_stats is None:
+        out.row_stats = torch.empty((kv.batch, tree.T, 4), dtype=torch.float32, device="cuda")
+    ty = _Typical(temperature, epsilon, delta, u.data_ptr(), _ptr(out.row_stats))
+    _check(lib().sd_spec_step_typical(model.handle, kv.handle, tree.handle, stop_mask.data_ptr(), C.byref(io),
+                                      C.byref(ty), _stream()))
+    return out
+
+
 def greedy_step(model: Model, kv: KVCache, *, want_logits=False, want_head_logits=False,
                 out: StepOutput | None = None) -> StepOutput:
     """sd_greedy_step: plain next-token decoding (tree = root only)."""
@@ -295,3 +327,34 @@ def verify_tree(tree: Tree, tok: torch.Tensor, am: torch.Tensor, stop_mask: torc
                                 vocab, tok.data_ptr(), am.data_ptr(), stop_mask.data_ptr(), n_acc.data_ptr(),
                                 n_raw.data_ptr(), tokens.data_ptr(), slots.data_ptr(), _stream()))
     return n_acc, n_raw, tokens, slots
+
+
+def verify_tree_typical(tree: Tree, tok: torch.Tensor, logits: torch.Tensor, stop_mask: torch.Tensor, *,
+                        temperature: float, epsilon: float, delta: float, trunc_fallback: str = "keep_all"):
+    """sd_verify_tree_typical: typical acceptance + fragment cut alone. tok int32 CUDA [batch, T], logits fp32
+    CUDA [batch, T, vocab]. Returns (n_accept, n_accept_raw, tokens, src_slots, row_stats)."""
+    batch, T, vocab = logits.shape
+    assert T == tree.T and tok.shape == (batch, T) and tok.dtype == torch.int32 and logits.dtype == torch.float32
+    assert tok.is_contiguous() and logits.is_contiguous() and tok.is_cuda and logits.is_cuda
+    W = tree.n_medusa + 1
+    i32 = dict(dtype=torch.int32, device="cuda")
+    n_acc, n_raw = torch.empty(batch, **i32), torch.empty(batch, **i32)
+    tokens, slots = torch.empty((batch, W), **i32), torch.empty((batch, W), **i32)
+    stats = torch.empty((batch, T, 4), dtype=torch.float32, device="cuda")
+    _check(lib().sd_verify_tree_typical(tree.handle, batch, tree.n_medusa,
+                                        {"keep_all": 0, "keep_one": 1}[trunc_fallback], vocab, tok.data_ptr(),
+                                        logits.data_ptr(), temperature, epsilon, delta, stop_mask.data_ptr(),
+                                        stats.data_ptr(), n_acc.data_ptr(), n_raw.data_ptr(), tokens.data_ptr(),
+                                        slots.data_ptr(), _stream()))
+    return n_acc, n_raw, tokens, slots, stats
+
+
+def sample_tokens(logits: torch.Tensor, rows: torch.Tensor, u: torch.Tensor, temperature: float) -> torch.Tensor:
+    """sd_sample_tokens: inverse-CDF draws. logits fp32 CUDA [n_rows, vocab]; rows int32, u fp32 CUDA [n]."""
+    assert logits.is_cuda and logits.dtype == torch.float32 and logits.dim() == 2 and logits.stride(1) == 1
+    assert rows.dtype == torch.int32 and u.dtype == torch.float32 and rows.numel() == u.numel()
+    assert rows.is_cuda and u.is_cuda and rows.is_contiguous() and u.is_contiguous()
+    out = torch.empty(rows.numel(), dtype=torch.int32, device="cuda")
+    _check(lib().sd_sample_tokens(logits.data_ptr(), logits.shape[0], logits.stride(0), logits.shape[1],
+                                  rows.data_ptr(), u.data_ptr(), rows.numel(), temperature, out.data_ptr(), _stream()))
+    return out

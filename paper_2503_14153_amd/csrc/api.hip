@@ -1,5 +1,6 @@
 // Host side of libspecdec: handle management, argument validation, and the sequencing of the
 // kernels of one speculative step (paper Section III-B) on a caller-supplied HIP stream.
+#include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -68,6 +69,7 @@ struct sd_model {
     void *xn, *attn_x, *act, *q, *kt, *vt;
     RowTable rt;
     int32_t *am, *g_parent, *g_depth, *g_rank;
+    float4* row_stats;                     // [Mp]: per tree row, statistics for typical acceptance
     uint32_t* zero_stop;
     const void* zfrag;                       // 1 KiB of zeros
     size_t part_floats;
@@ -258,6 +260,7 @@ extern "C" int sd_model_create(const sd_config* cfg, const sd_weights* w, int32_
     size_t w_kt = wtake((size_t)L * Mp * d * 2), w_vt = wtake((size_t)L * Mp * d * 2);
     size_t w_tok = wtake((size_t)Mp * 4), w_pos = wtake((size_t)Mp * 4), w_anc = wtake((size_t)Mp * SD_ANC_WORDS * 4);
     size_t w_cs = wtake((size_t)Mp * (hd / 2) * 8), w_am = wtake((size_t)Mp * 4), w_g = wtake(3 * 4);
+    size_t w_rs = wtake((size_t)Mp * 16);
     size_t w_zs = wtake((size_t)ceil_div(V, 32) * 4), w_zf = wtake(1024);
     e = hipMalloc((void**)&m->work, wz);
     if (e == hipSuccess) e = hipMalloc((void**)&m->plan_cnt, cnt_all.size() * 4);
@@ -281,6 +284,7 @@ extern "C" int sd_model_create(const sd_config* cfg, const sd_weights* w, int32_
     m->rt.tok = (int32_t*)(Wk + w_tok); m->rt.pos = (int32_t*)(Wk + w_pos); m->rt.anc = (uint32_t*)(Wk + w_anc);
     m->rt.cs = (float2*)(Wk + w_cs);
     m->am = (int32_t*)(Wk + w_am);
+    m->row_stats = (float4*)(Wk + w_rs);
     m->g_parent = (int32_t*)(Wk + w_g); m->g_depth = m->g_parent + 1; m->g_rank = m->g_parent + 2;
     m->zero_stop = (uint32_t*)(Wk + w_zs);
     m->zfrag = Wk + w_zf;
@@ -678,7 +682,8 @@ extern "C" int sd_prefill(sd_model* m, sd_kv* kv, const int32_t* tokens, const i
 
 // ------------------------------------------------------------------------------------------ steps
 static int step_common(sd_model* m, sd_kv* kv, const int32_t* parent, const int32_t* depth, const int32_t* rank, int T,
-                       int Tp, const uint32_t* stop_mask, sd_step_io* io, hipStream_t s, const char* who) {
+                       int Tp, const uint32_t* stop_mask, sd_step_io* io, hipStream_t s, const char* who,
+                       const sd_typical* ty = nullptr) {
     const sd_config& c = m->cfg;
     const int B = kv->B, H = c.n_medusa;
     if (kv->m != m) return fail(SD_ERR_STATE, "%s: cache belongs to another model", who);
@@ -711,13 +716,24 @@ static int step_common(sd_model* m, sd_kv* kv, const int32_t* parent, const int3
     va.tok = m->rt.tok; va.am = m->am; va.stop_mask = stop_mask;
     va.n_accept = n_accept; va.n_accept_raw = io->n_accept_raw; va.tokens = tokens; va.src_slots = slots;
     va.kv_len = kv->kv_len; va.n_old = kv->n_old; va.root_tok = kv->root_tok; va.last_row = kv->last_row;
+    va.logits = nullptr; va.ld = 0; va.row_stats = nullptr; va.inv_temperature = 1.f;
+    if (ty) {
+        va.inv_temperature = 1.f / ty->temperature;
+        launch_row_stats(m->logits, m->Vpad, c.vocab, m->row_stats, B, T, Tp, va.inv_temperature, ty->epsilon,
+                         ty->delta, s);
+        if (ty->row_stats) launch_copy_row_stats(m->row_stats, (float4*)ty->row_stats, B, T, Tp, s);
+        va.logits = m->logits; va.ld = m->Vpad; va.row_stats = m->row_stats;
+    }
     launch_verify(va, B, s);
+    if (ty)      // the next root is drawn from the base distribution at the last kept node
+        launch_sample_root(m->logits, m->Vpad, c.vocab, kv->last_row, ty->u, va.inv_temperature, kv->root_tok, B,
+                           B * Tp, s);
     launch_kv_commit(m->kt, m->vt, kv->kc, kv->vc, slots, n_accept, kv->n_old, c.n_layers, B, c.n_heads, c.head_dim,
                      Tp / 32, kv->cap_blocks, H + 1, H + 1, s);
     run_draft_heads(m, kv, B, 0xffffffffu, io->head_logits, s);
     };
 
-    if (m->use_graphs && !m->prof.on) {
+    if (m->use_graphs && !m->prof.on && !ty) {
         const AttnGeom ag = attn_geometry(m, B, Tp, n_hi);
         std::vector<uint64_t> key = {(uint64_t)(uintptr_t)kv, (uint64_t)(uintptr_t)parent, (uint64_t)T, (uint64_t)Tp,
                                      (uint64_t)ag.ncparts, (uint64_t)(ag.per * 2 + ag.tree_sep), (uint64_t)(uintptr_t)stop_mask,
@@ -762,6 +778,25 @@ extern "C" int sd_spec_step(sd_model* m, sd_kv* kv, const sd_tree* tree, const u
                        (hipStream_t)stream, "sd_spec_step");
 }
 
+static int check_typical(float temperature, float epsilon, float delta, const char* who) {
+    if (!(temperature > 0.f) || !std::isfinite(temperature))
+        return fail(SD_ERR_SHAPE, "%s: temperature must be positive and finite", who);
+    if (!(epsilon >= 0.f && epsilon <= 1.f) || !(delta >= 0.f) || !std::isfinite(delta))
+        return fail(SD_ERR_SHAPE, "%s: need 0 <= epsilon <= 1 and 0 <= delta < inf", who);
+    return SD_OK;
+}
+
+extern "C" int sd_spec_step_typical(sd_model* m, sd_kv* kv, const sd_tree* tree, const uint32_t* stop_mask,
+                                    sd_step_io* io, const sd_typical* ty, void* stream) {
+    if (!m || !kv || !tree || !stop_mask || !io || !ty) return fail(SD_ERR_NULL, "sd_spec_step_typical: NULL argument");
+    if (tree->H != m->cfg.n_medusa || tree->topk != m->cfg.topk)
+        return fail(SD_ERR_BAD_TREE, "sd_spec_step_typical: tree was built for %d heads / top-%d", tree->H, tree->topk);
+    if (!ty->u) return fail(SD_ERR_NULL, "sd_spec_step_typical: sd_typical.u is NULL");
+    if (int rc = check_typical(ty->temperature, ty->epsilon, ty->delta, "sd_spec_step_typical")) return rc;
+    return step_common(m, kv, tree->parent, tree->depth, tree->rank, tree->T, tree->Tp, stop_mask, io,
+                       (hipStream_t)stream, "sd_spec_step_typical", ty);
+}
+
 extern "C" int sd_greedy_step(sd_model* m, sd_kv* kv, sd_step_io* io, void* stream) {
     if (!m || !kv || !io) return fail(SD_ERR_NULL, "sd_greedy_step: NULL argument");
     return step_common(m, kv, m->g_parent, m->g_depth, m->g_rank, 1, 32, m->zero_stop, io, (hipStream_t)stream,
@@ -785,6 +820,46 @@ extern "C" int sd_verify_tree(const sd_tree* tree, int32_t batch, int32_t n_medu
     va.tok = tok; va.am = am; va.stop_mask = stop_mask;
     va.n_accept = n_accept; va.n_accept_raw = n_accept_raw; va.tokens = tokens; va.src_slots = src_slots;
     launch_verify(va, batch, (hipStream_t)stream);
+    HIP_TRY(hipGetLastError());
+    return SD_OK;
+}
+
+extern "C" int sd_verify_tree_typical(const sd_tree* tree, int32_t batch, int32_t n_medusa, int32_t trunc_fallback,
+                                      int32_t vocab, const int32_t* tok, const float* logits, float temperature,
+                                      float epsilon, float delta, const uint32_t* stop_mask, float* row_stats,
+                                      int32_t* n_accept, int32_t* n_accept_raw, int32_t* tokens, int32_t* src_slots,
+                                      void* stream) {
+    if (!tree || !tok || !logits || !stop_mask || !row_stats || !n_accept || !tokens || !src_slots)
+        return fail(SD_ERR_NULL, "sd_verify_tree_typical: NULL argument");
+    if (batch < 1 || batch > 65535) return fail(SD_ERR_SHAPE, "sd_verify_tree_typical: bad batch");
+    if (vocab < 1 || vocab > 163840) return fail(SD_ERR_SHAPE, "sd_verify_tree_typical: bad vocab");
+    if (n_medusa != tree->H) return fail(SD_ERR_BAD_TREE, "sd_verify_tree_typical: tree was built for %d heads", tree->H);
+    if (trunc_fallback != SD_TRUNC_KEEP_ALL && trunc_fallback != SD_TRUNC_KEEP_ONE)
+        return fail(SD_ERR_SHAPE, "sd_verify_tree_typical: bad trunc_fallback");
+    if (int rc = check_typical(temperature, epsilon, delta, "sd_verify_tree_typical")) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    const int T = tree->T;
+    launch_row_stats(logits, vocab, vocab, (float4*)row_stats, batch, T, T, 1.f / temperature, epsilon, delta, s);
+    VerifyArgs va;
+    memset(&va, 0, sizeof(va));
+    va.parent = tree->parent; va.depth = tree->depth; va.T = T; va.H = tree->H; va.fallback = trunc_fallback;
+    va.src_stride = T; va.Tp = tree->Tp; va.V = vocab;
+    va.tok = tok; va.am = tok; va.stop_mask = stop_mask;      // am is not read under typical acceptance
+    va.n_accept = n_accept; va.n_accept_raw = n_accept_raw; va.tokens = tokens; va.src_slots = src_slots;
+    va.logits = logits; va.ld = vocab; va.row_stats = (const float4*)row_stats; va.inv_temperature = 1.f / temperature;
+    launch_verify(va, batch, s);
+    HIP_TRY(hipGetLastError());
+    return SD_OK;
+}
+
+extern "C" int sd_sample_tokens(const float* logits, int32_t n_rows, int32_t ld, int32_t vocab, const int32_t* rows,
+                                const float* u, int32_t n, float temperature, int32_t* out, void* stream) {
+    if (!logits || !rows || !u || !out) return fail(SD_ERR_NULL, "sd_sample_tokens: NULL argument");
+    if (n < 1 || n > 65535 || n_rows < 1) return fail(SD_ERR_SHAPE, "sd_sample_tokens: bad n");
+    if (vocab < 1 || vocab > 163840 || ld < vocab) return fail(SD_ERR_SHAPE, "sd_sample_tokens: bad vocab / ld");
+    if (!(temperature > 0.f) || !std::isfinite(temperature))
+        return fail(SD_ERR_SHAPE, "sd_sample_tokens: temperature must be positive and finite");
+    launch_sample_root(logits, ld, vocab, rows, u, 1.f / temperature, out, n, n_rows, (hipStream_t)stream);
     HIP_TRY(hipGetLastError());
     return SD_OK;
 }

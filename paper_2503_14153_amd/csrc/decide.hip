@@ -16,35 +16,39 @@ static __device__ inline void wave_best(float& v, int& i) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Row-wise arg-max over V columns (lowest id on ties). One workgroup per row.
-__global__ __launch_bounds__(256) void k_argmax(const float* __restrict__ logits, int ld, int V, int32_t* __restrict__ am,
-                                                int T, int Tp) {
+// Row-wise arg-max over V columns (lowest id on ties). One workgroup of 1024 threads per row;
+// the loop is unrolled so that several 16-byte loads per thread are in flight.
+#define ARGMAX_THREADS 1024
+__global__ __launch_bounds__(ARGMAX_THREADS) void k_argmax(const float* __restrict__ logits, int ld, int V,
+                                                           int32_t* __restrict__ am, int T, int Tp) {
     const int b = blockIdx.x / T, j = blockIdx.x % T;
     const int m = b * Tp + j;
     const float* row = logits + (size_t)m * ld;
     float bv = NEG_INF;
     int bi = 0x7fffffff;
-    for (int i = threadIdx.x * 4; i < V; i += 256 * 4) {
-        float4 f = *(const float4*)(row + i);
+#pragma unroll 4
+    for (int i = threadIdx.x * 4; i < V; i += ARGMAX_THREADS * 4) {
+        float4 f = *(const float4*)(row + i);         // rows are padded to a multiple of 4 columns
         float vals[4] = {f.x, f.y, f.z, f.w};
 #pragma unroll
         for (int e = 0; e < 4; ++e)
             if (i + e < V && better(vals[e], i + e, bv, bi)) { bv = vals[e]; bi = i + e; }
     }
     wave_best(bv, bi);
-    __shared__ float sv[4];
-    __shared__ int si[4];
+    __shared__ float sv[ARGMAX_THREADS / 64];
+    __shared__ int si[ARGMAX_THREADS / 64];
     if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        for (int w = 1; w < 4; ++w)
-            if (better(sv[w], si[w], bv, bi)) { bv = sv[w]; bi = si[w]; }
-        am[m] = bi;
+    if (threadIdx.x < 64) {
+        bv = threadIdx.x < ARGMAX_THREADS / 64 ? sv[threadIdx.x] : NEG_INF;
+        bi = threadIdx.x < ARGMAX_THREADS / 64 ? si[threadIdx.x] : 0x7fffffff;
+        wave_best(bv, bi);
+        if (threadIdx.x == 0) am[m] = bi;
     }
 }
 
 void launch_argmax(const float* logits, int ld, int V, int32_t* am, int B, int T, int Tp, hipStream_t s) {
-    hipLaunchKernelGGL(k_argmax, dim3(B * T), dim3(256), 0, s, logits, ld, V, am, T, Tp);
+    hipLaunchKernelGGL(k_argmax, dim3(B * T), dim3(ARGMAX_THREADS), 0, s, logits, ld, V, am, T, Tp);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -70,14 +74,17 @@ __global__ __launch_bounds__(TOPK_THREADS) void k_topk(const float* __restrict__
     __shared__ float sv[TOPK_THREADS / 64];
     __shared__ int si[TOPK_THREADS / 64];
     __shared__ int chosen;
-    for (int round = 0; round < k; ++round) {
-        float bv = NEG_INF;
-        int bi = 0x7fffffff;
+    // thread-local best of the elements not yet retired; only the owner of a retired element rescans
+    float lbv = NEG_INF;
+    int lbi = 0x7fffffff;
 #pragma unroll
-        for (int j = 0; j < NPT; ++j) {       // ascending ids: strict > keeps the lowest id
-            int c = j * TOPK_THREADS + tid;
-            if (c < V && v[j] > bv) { bv = v[j]; bi = c; }
-        }
+    for (int j = 0; j < NPT; ++j) {           // ascending ids: strict > keeps the lowest id
+        int c = j * TOPK_THREADS + tid;
+        if (c < V && v[j] > lbv) { lbv = v[j]; lbi = c; }
+    }
+    for (int round = 0; round < k; ++round) {
+        float bv = lbv;
+        int bi = lbi;
         wave_best(bv, bi);
         if ((tid & 63) == 0) { sv[tid >> 6] = bv; si[tid >> 6] = bi; }
         __syncthreads();
@@ -93,9 +100,14 @@ __global__ __launch_bounds__(TOPK_THREADS) void k_topk(const float* __restrict__
         __syncthreads();
         const int ch = chosen;
         if ((ch % TOPK_THREADS) == tid) {
+            lbv = NEG_INF;
+            lbi = 0x7fffffff;
 #pragma unroll
-            for (int j = 0; j < NPT; ++j)
+            for (int j = 0; j < NPT; ++j) {
                 if (j == ch / TOPK_THREADS) v[j] = NEG_INF;
+                int c = j * TOPK_THREADS + tid;
+                if (c < V && v[j] > lbv) { lbv = v[j]; lbi = c; }
+            }
         }
     }
 }
@@ -114,9 +126,162 @@ void launch_topk(const float* logits, int ld, int V, int k, int32_t* out, int B,
 }
 
 // ------------------------------------------------------------------------------------------
+// Sampling decoding, statistics of the base distribution of every tree row at a temperature:
+// with x_v = (logit_v - max) / temperature, Z = sum exp(x_v), E = sum exp(x_v) x_v, the entropy
+// of softmax is H = log Z - E / Z and the typical-acceptance threshold is min(eps, delta exp(-H)).
+// A token passes iff exp(x_tok) / Z > threshold, i.e. x_tok > c with
+// c = min(log eps, log delta - H) + log Z. One workgroup of 1024 threads per row, the row kept
+// in registers between the two reductions; thread sums in fp32, cross-thread sums in fp64.
+#define RS_THREADS 1024
+static __device__ inline double block_sum_f64(double v, double* sh) {
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    __syncthreads();                                   // sh may still be read from the previous call
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    double t = 0.0;
+    for (int w = 0; w < RS_THREADS / 64; ++w) t += sh[w];
+    return t;
+}
+template <int NPT>
+__global__ __launch_bounds__(RS_THREADS) void k_row_stats(const float* __restrict__ logits, int ld, int V,
+                                                          float4* __restrict__ stats, int T, int Tp,
+                                                          float inv_temperature, float log_eps, float log_delta) {
+    const int j = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const size_t r = (size_t)b * Tp + j;
+    const float* row = logits + r * ld;
+    float v[NPT];
+    float mx = NEG_INF;
+#pragma unroll
+    for (int i = 0; i < NPT; ++i) {
+        const int c = i * RS_THREADS + tid;
+        v[i] = c < V ? row[c] : NEG_INF;
+        mx = fmaxf(mx, v[i]);
+    }
+    __shared__ float smax[RS_THREADS / 64];
+    __shared__ double ssum[RS_THREADS / 64];
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    if ((tid & 63) == 0) smax[tid >> 6] = mx;
+    __syncthreads();
+    mx = smax[0];
+    for (int w = 1; w < RS_THREADS / 64; ++w) mx = fmaxf(mx, smax[w]);
+    float z = 0.f, e = 0.f;
+#pragma unroll
+    for (int i = 0; i < NPT; ++i) {
+        const int c = i * RS_THREADS + tid;
+        if (c < V) {
+            const float x = (v[i] - mx) * inv_temperature;
+            const float ex = __expf(x);
+            z += ex;
+            e += ex * x;                               // exp(x) x -> 0 as x -> -inf
+        }
+    }
+    const double Z = block_sum_f64((double)z, ssum);
+    const double E = block_sum_f64((double)e, ssum);
+    if (tid == 0) {
+        const double H = log(Z) - E / Z;
+        const double log_thr = fmin((double)log_eps, (double)log_delta - H);
+        stats[r] = make_float4(mx, (float)Z, (float)H, (float)(log_thr + log(Z)));
+    }
+}
+
+void launch_row_stats(const float* logits, int ld, int V, float4* stats, int B, int T, int Tp, float inv_temperature,
+                      float epsilon, float delta, hipStream_t s) {
+    const float log_eps = epsilon > 0.f ? logf(epsilon) : NEG_INF, log_delta = delta > 0.f ? logf(delta) : NEG_INF;
+    const int npt = (V + RS_THREADS - 1) / RS_THREADS;
+#define RS(N) hipLaunchKernelGGL((k_row_stats<N>), dim3(T, B), dim3(RS_THREADS), 0, s, logits, ld, V, stats, T, Tp, \
+                                 inv_temperature, log_eps, log_delta)
+    if (npt <= 1) RS(1);
+    else if (npt <= 4) RS(4);
+    else if (npt <= 16) RS(16);
+    else if (npt <= 32) RS(32);
+    else if (npt <= 64) RS(64);
+    else RS(160);
+#undef RS
+}
+
+// ------------------------------------------------------------------------------------------
+// Sampling decoding, the next root: the smallest token id whose cumulative probability under
+// softmax(logits[last_row] / temperature) exceeds u. One workgroup of 16 waves per sequence.
+// Wave w owns the contiguous ids [w*S, (w+1)*S) and sums their weights exp((l - max)/temp) with
+// coalesced loads; the wave whose segment holds the target u * total then walks it 64 ids at a
+// time with a wave-wide inclusive scan. Sums are in fp64, so the draw only differs from an
+// exact one when u lies within fp32 rounding of the weights of a boundary of the CDF.
+static __device__ inline double wave_incl_scan_f64(double v, int lane) {
+    for (int o = 1; o < 64; o <<= 1) {
+        double t = __shfl_up(v, o);
+        if (lane >= o) v += t;
+    }
+    return v;
+}
+__global__ __launch_bounds__(RS_THREADS) void k_sample_root(const float* __restrict__ logits, int ld, int V,
+                                                            const int32_t* __restrict__ last_row,
+                                                            const float* __restrict__ u, float inv_temperature,
+                                                            int32_t* __restrict__ root_tok, int n_rows) {
+    constexpr int NW = RS_THREADS / 64;
+    const int b = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int r = last_row[b];
+    if (r < 0 || r >= n_rows) {                        // uniform over the workgroup
+        if (tid == 0) root_tok[b] = -1;
+        return;
+    }
+    const float* row = logits + (size_t)r * ld;
+    __shared__ float smax[NW];
+    __shared__ double wsum[NW];
+    float mx = NEG_INF;
+#pragma unroll 4
+    for (int c = tid; c < V; c += RS_THREADS) mx = fmaxf(mx, row[c]);
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    if (lane == 0) smax[wave] = mx;
+    __syncthreads();
+    mx = smax[0];
+    for (int w = 1; w < NW; ++w) mx = fmaxf(mx, smax[w]);
+    const int S = ((V + NW - 1) / NW + 63) & ~63;      // segment length, a multiple of the wave size
+    const int s0 = min(wave * S, V), s1 = min(s0 + S, V);
+    double part = 0.0;
+#pragma unroll 4
+    for (int c = s0 + lane; c < s1; c += 64) part += (double)__expf((row[c] - mx) * inv_temperature);
+    for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o);
+    if (lane == 0) wsum[wave] = part;
+    __syncthreads();
+    double total = 0.0;
+    for (int w = 0; w < NW; ++w) total += wsum[w];
+    const double target = (double)u[b] * total;
+    // the segment that holds the target; if rounding leaves none, the last one that has any mass, walked to its end
+    int seg = -1, last_mass = 0;
+    double base = 0.0, acc = 0.0;
+    for (int w = 0; w < NW; ++w) {
+        if (wsum[w] > 0.0) last_mass = w;
+        if (seg < 0 && acc + wsum[w] > target) { seg = w; base = acc; }
+        acc += wsum[w];
+    }
+    const bool to_end = seg < 0;
+    if (to_end) seg = last_mass;
+    if (wave != seg) return;
+    int pick = -1, last_pos = s0;
+    for (int c0 = s0; c0 < s1 && pick < 0; c0 += 64) {
+        const int c = c0 + lane;
+        const double e = c < s1 ? (double)__expf((row[c] - mx) * inv_temperature) : 0.0;
+        const double cum = base + wave_incl_scan_f64(e, lane);
+        const unsigned long long pos = __ballot(e > 0.0);
+        if (pos) last_pos = c0 + 63 - __builtin_clzll(pos);
+        const unsigned long long hit = __ballot(!to_end && cum > target);
+        if (hit) pick = c0 + __builtin_ctzll(hit);
+        base = __shfl(cum, 63);
+    }
+    if (lane == 0) root_tok[b] = pick >= 0 ? pick : last_pos;
+}
+
+void launch_sample_root(const float* logits, int ld, int V, const int32_t* last_row, const float* u,
+                        float inv_temperature, int32_t* root_tok, int B, int n_rows, hipStream_t s) {
+    hipLaunchKernelGGL(k_sample_root, dim3(B), dim3(RS_THREADS), 0, s, logits, ld, V, last_row, u, inv_temperature,
+                       root_tok, n_rows);
+}
+
+// ------------------------------------------------------------------------------------------
 // Greedy acceptance + fragment cut. One workgroup of SD_MAX_TREE threads per sequence, thread
 // j = tree node j.
-//   match[j]  = tok[j] == am[parent[j]]                     (root: true)
+//   match[j]  = tok[j] == am[parent[j]]                     (root: true); under sampling decoding
+//               instead: p(tok[j] | parent) > min(eps, delta * exp(-entropy)), from k_row_stats
 //   ok[j]     = match holds on every node of j's root path  (prefix-closed acceptance): with
 //               the per-wave ballots of `match` gathered into a T-bit mask, ok[j] is one
 //               AND of j's ancestor bitset with the complement of that mask
@@ -138,7 +303,18 @@ __global__ __launch_bounds__(SD_MAX_TREE) void k_verify(VerifyArgs a) {
         dj = a.depth[j];
         pj = a.parent[j];
         tj = tok[j];
-        match = (j == 0) || (tj == am[pj]);
+        if (j == 0) {
+            match = true;
+        } else if (a.row_stats) {
+            // the base model's probability of this token at its parent exceeds the threshold of that
+            // row, tested on the log side: (logit - max) / temperature > log(threshold * Z)
+            const size_t r = (size_t)b * a.src_stride + pj;
+            const float4 st = a.row_stats[r];
+            match = false;
+            if (tj >= 0 && tj < a.V) match = (a.logits[r * a.ld + tj] - st.x) * a.inv_temperature > st.w;
+        } else {
+            match = tj == am[pj];
+        }
         for (int i = j, guard = 0; i >= 0 && guard <= H; i = a.parent[i], ++guard) anc[i >> 6] |= 1ull << (i & 63);
     }
     unsigned long long bal = __ballot(match);
@@ -256,6 +432,14 @@ __global__ void k_copy_logits(const float* __restrict__ src, int ld, float* __re
 }
 void launch_copy_logits(const float* src, int ld, float* dst, int V, int B, int T, int Tp, hipStream_t s) {
     hipLaunchKernelGGL(k_copy_logits, dim3(16, B * T), dim3(256), 0, s, src, ld, dst, V, T, Tp);
+}
+
+__global__ void k_copy_row_stats(const float4* __restrict__ src, float4* __restrict__ dst, int B, int T, int Tp) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < B * T) dst[i] = src[(i / T) * Tp + i % T];
+}
+void launch_copy_row_stats(const float4* src, float4* dst, int B, int T, int Tp, hipStream_t s) {
+    hipLaunchKernelGGL(k_copy_row_stats, dim3((B * T + 255) / 256), dim3(256), 0, s, src, dst, B, T, Tp);
 }
 
 __global__ void k_copy_rows_i32(const int32_t* __restrict__ src, int32_t* __restrict__ dst, int B, int T, int Tp) {

@@ -109,6 +109,11 @@ struct VerifyArgs {
     const uint32_t* stop_mask;
     int32_t *n_accept, *n_accept_raw, *tokens, *src_slots;   // outputs, [B] / [B][H+1]
     int32_t *kv_len, *n_old, *root_tok, *last_row;           // carried state, may be NULL
+    // typical acceptance (sampling decoding) instead of greedy when row_stats != NULL
+    const float* logits;                // [B*Tp][ld]
+    int ld;
+    const float4* row_stats;            // [B*Tp]: {max logit, Z, entropy, c = log(threshold * Z)} per row
+    float inv_temperature;
 };
 
 // ---- launchers (defined in the kernel translation units) ----------------------------------
@@ -147,6 +152,14 @@ void launch_topk(const float* logits, int ld, int V, int k, int32_t* out, int B,
 void launch_pick_root(const int32_t* am, const int32_t* last_row, int32_t* root_tok, int B, uint32_t seq_mask,
                       hipStream_t s);
 void launch_verify(const VerifyArgs& a, int B, hipStream_t s);
+// per tree row: softmax statistics at a temperature and the typical-acceptance threshold (see decide.hip)
+void launch_row_stats(const float* logits, int ld, int V, float4* stats, int B, int T, int Tp, float inv_temperature,
+                      float epsilon, float delta, hipStream_t s);
+// root_tok[b] = inverse-CDF draw at u[b] from softmax(logits[last_row[b]] * inv_temperature);
+// -1 for a row index outside [0, n_rows)
+void launch_sample_root(const float* logits, int ld, int V, const int32_t* last_row, const float* u,
+                        float inv_temperature, int32_t* root_tok, int B, int n_rows, hipStream_t s);
+void launch_copy_row_stats(const float4* src, float4* dst, int B, int T, int Tp, hipStream_t s);
 void launch_kv_commit(const void* kt_all, const void* vt_all, void* kc_all, void* vc_all,
                       const int32_t* src_slots, const int32_t* n_accept, const int32_t* n_old,
                       int L, int B, int nh, int hd, int TB, int cap_blocks, int rows, int W, hipStream_t s);

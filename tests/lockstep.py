@@ -37,6 +37,9 @@ class Report:
     raw: list = field(default_factory=list)
     kv_max_abs: float = 0.0
     head_max_abs: float = 0.0
+    accept_near_ties: int = 0       # typical acceptance: decisions that differ at an oracle near-tie
+    root_near_ties: int = 0         # sampled next root differs with u near a boundary of the oracle's CDF
+    stats_max_abs: float = 0.0
 
 
 def check_logits(got: np.ndarray, want: np.ndarray, rep: Report, max_abs=LOGIT_MAX_ABS, rel=LOGIT_REL):
@@ -134,6 +137,161 @@ def lockstep_spec(model: sd.Model, kv: sd.KVCache, tree: sd.Tree, tree_np, stop_
             assert herr <= 2 * LOGIT_MAX_ABS, f"draft-head logits differ by {herr:.4g}"
             check_cand(gcand[0].cpu().numpy(), rec.next_cand, rec.head_logits, rep)
         else:
+            resync_kv(kv, st, shape, n_old)
+        rep.steps += 1
+    return rep
+
+
+# ----------------------------------------------------------------------------- sampling decoding
+FP32_LOG_MARGIN = 2e-4    # |log p - log threshold| below which fp32 sums may decide the other way
+FP32_CDF = 2e-5           # distance of u from a CDF boundary below which fp32 sums may pick a neighbour
+
+
+def check_row_stats(stats: np.ndarray, logits64: np.ndarray, ty: dict, rep: Report):
+    """{max, Z, H, c} of every row against their definitions evaluated in fp64 on the same logits."""
+    for j in range(logits64.shape[0]):
+        x = (logits64[j] - logits64[j].max()) / ty["temperature"]
+        Z = np.exp(x).sum()
+        p = np.exp(x) / Z
+        H = orc.entropy(p)
+        with np.errstate(divide="ignore"):
+            c = min(np.log(ty["epsilon"]), np.log(ty["delta"]) - H) + np.log(Z)
+        want = np.array([logits64[j].max(), Z, H, c])
+        err = np.abs(stats[j].astype(np.float64) - want)
+        err[1] /= Z                                             # Z: relative
+        if not np.isfinite(c):
+            assert stats[j, 3] == want[3]
+            err[3] = 0.0
+        rep.stats_max_abs = max(rep.stats_max_abs, float(err.max()))
+        assert err[0] == 0.0 and err.max() < 1e-4, f"row {j}: stats {stats[j]} vs {want}"
+
+
+def typical_outputs_from_logits(tok, logits64, tree_np, stop_np, fallback, ty):
+    parent, depth, rank = tree_np
+    ok, chain, log_margin = orc.typical_accept(tok, logits64, parent, depth, ty["temperature"], ty["epsilon"],
+                                               ty["delta"])
+    n_acc = orc.fragment_cut([tok[c] for c in chain], stop_np, fallback)
+    return ok, chain, log_margin, n_acc
+
+
+def check_typical_decision(got_n_raw, got_n_acc, got_tokens, got_slots, tok, logits64, tree_np, stop_np, fallback, ty,
+                           H, rep: Report, tol=FP32_LOG_MARGIN):
+    """The GPU's acceptance outputs against the oracle's rule on the very logits the GPU used.
+
+    Bit-exact unless some node's own test lies within `tol` of its threshold (then the outputs
+    must equal the oracle's for one of the ways those few tests can fall). Returns the chain."""
+    parent, depth, rank = tree_np
+    ok, chain, lm, n_acc = typical_outputs_from_logits(tok, logits64, tree_np, stop_np, fallback, ty)
+    W = H + 1
+
+    def pack(chain, n_acc):
+        t, s = np.full(W, -1, np.int32), np.full(W, -1, np.int32)
+        t[:n_acc] = [tok[c] for c in chain[:n_acc]]
+        s[:n_acc] = chain[:n_acc]
+        return len(chain), n_acc, t, s
+
+    def same(w):
+        return (got_n_raw == w[0] and got_n_acc == w[1] and np.array_equal(got_tokens, w[2])
+                and np.array_equal(got_slots, w[3]))
+
+    if same(pack(chain, n_acc)):
+        return chain[:n_acc]
+    close = [j for j in range(1, len(parent)) if abs(lm[j]) < tol]
+    assert close and len(close) <= 8, f"typical acceptance differs with no test near its threshold (got n_raw " \
+                                      f"{got_n_raw}, want {len(chain)})"
+    T = len(parent)
+    p_tok = np.array([np.inf] + [lm[j] for j in range(1, T)])
+    for bits in range(1, 1 << len(close)):
+        match = p_tok > 0
+        for i, j in enumerate(close):
+            if (bits >> i) & 1:
+                match[j] = not match[j]
+        okf = np.zeros(T, bool)
+        okf[0] = True
+        for j in range(1, T):
+            okf[j] = okf[parent[j]] and match[j]
+        best = 0
+        for j in range(T):
+            if okf[j] and depth[j] > depth[best]:
+                best = j
+        ch, i = [], best
+        while i >= 0:
+            ch.append(i)
+            i = parent[i]
+        ch = ch[::-1]
+        na = orc.fragment_cut([tok[c] for c in ch], stop_np, fallback)
+        if same(pack(ch, na)):
+            rep.accept_near_ties += 1
+            return ch[:na]
+    raise AssertionError("typical acceptance differs beyond what the near-threshold tests explain")
+
+
+def check_sampled(got: int, logits_row64: np.ndarray, u: float, temperature: float, tol: float) -> bool:
+    """True if `got` is the inverse-CDF draw at u, or u is within tol of got's CDF interval."""
+    p = orc.softmax_t(logits_row64, temperature)
+    if got == orc.sample_token(p, u):
+        return True
+    F = np.cumsum(p)
+    lo = F[got - 1] if got > 0 else 0.0
+    assert lo - tol <= u < F[got] + tol, f"sampled id {got}: u={u} outside [{lo}, {F[got]}) by more than {tol}"
+    return False
+
+
+def lockstep_typical(model: sd.Model, kv: sd.KVCache, tree: sd.Tree, tree_np, stop_np: np.ndarray,
+                     stop_words: torch.Tensor, w64: dict, shape, st: orc.DecodeState, n_steps: int, fallback: str,
+                     ty: dict, rng: np.random.Generator, cand_fn=None, kv_tol: float = 0.05,
+                     rep: Report | None = None) -> Report:
+    """Sampling decoding on both sides (batch 1): typical acceptance and a sampled next root.
+
+    Two comparisons per step. (1) The GPU's decisions against the oracle's rule applied, in
+    fp64, to the GPU's own logits: exact up to fp32 summation (FP32_* margins). (2) The GPU
+    step against the oracle's step on its own fp64 logits: logits within tolerance, decisions
+    equal unless the oracle's margin is below what this step's measured logit differences can move."""
+    rep = rep or Report()
+    tau = ty["temperature"]
+    for _ in range(n_steps):
+        cand = np.asarray(st.cand if cand_fn is None else cand_fn(st), dtype=np.int32)
+        n_old = st.kv.n
+        u = float(np.float32(rng.random()))
+        kv.set_draft([st.root_tok], cand[None])
+        out = sd.spec_step_typical(model, kv, tree, stop_words, torch.tensor([u], dtype=torch.float32, device="cuda"),
+                                   temperature=tau, epsilon=ty["epsilon"], delta=ty["delta"], want_logits=True,
+                                   want_argmax=True, want_head_logits=True, want_row_stats=True)
+        rec = orc.spec_step(w64, shape, st, tree_np, stop_np, fallback, cand_override=cand, typical=dict(ty, u=u))
+        torch.cuda.synchronize()
+        g_logits = out.logits[0].cpu().numpy().astype(np.float64)
+        check_logits(g_logits, rec.logits, rep)
+        # how far this step's logit differences can move a log-probability (the token's logit and log Z each by
+        # err / tau), the log-threshold (through the entropy, by about as much again), and a cumulative probability
+        err = float(np.abs(g_logits - rec.logits).max())
+        logit_margin = 4 * err / tau + FP32_LOG_MARGIN
+        cdf_margin = float(np.expm1(2 * err / tau)) + FP32_CDF
+        check_row_stats(out.row_stats[0].cpu().numpy(), g_logits, ty, rep)
+        n_raw, n_acc = int(out.n_accept_raw[0]), int(out.n_accept[0])
+        kept = check_typical_decision(n_raw, n_acc, out.tokens[0].cpu().numpy(), out.src_slots[0].cpu().numpy(),
+                                      rec.tok, g_logits, tree_np, stop_np, fallback, ty, shape.n_medusa, rep)
+        assert kv.len() == [n_old + n_acc]
+        rep.accepted.append(n_acc)
+        rep.raw.append(n_raw)
+        root, gcand = kv.get_draft()
+        root = int(root[0])
+        if not check_sampled(root, g_logits[kept[-1]], u, tau, FP32_CDF):
+            rep.root_near_ties += 1
+        same_path = n_acc == rec.n_accept and kept == list(rec.src_slots)
+        if same_path:
+            compare_kv_rows(kv, st, shape, n_old, n_old + n_acc, rep, kv_tol)
+            if not check_sampled(root, rec.logits[kept[-1]], u, tau, cdf_margin):
+                rep.root_near_ties += 1
+            hl = out.head_logits[0].cpu().numpy().astype(np.float64)
+            herr = float(np.abs(hl - rec.head_logits).max())
+            rep.head_max_abs = max(rep.head_max_abs, herr)
+            assert herr <= 2 * LOGIT_MAX_ABS, f"draft-head logits differ by {herr:.4g}"
+            check_cand(gcand[0].cpu().numpy(), rec.next_cand, rec.head_logits, rep)
+        else:
+            # the two sides took different paths: only legitimate at an oracle near-tie
+            lm = rec.log_margin
+            assert np.any(np.abs(lm[1:]) < logit_margin), "paths differ with every oracle margin clear of its threshold"
+            rep.accept_near_ties += 1
             resync_kv(kv, st, shape, n_old)
         rep.steps += 1
     return rep
