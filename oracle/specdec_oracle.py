@@ -10,7 +10,6 @@ What it computes follows the paper's decoding description (Section III-B):
   * the candidates of a step are the top-k tokens of the base model and of every head;
   * a drafted token is accepted only if it, and every token before it, passes the acceptance
     test; under greedy decoding (one of the two decoding modes of Section IV-A) the test is
-    "equals the base model's arg-max given the tokens before it";
     "equals the base model's arg-max given the tokens before it"; under sampling decoding it is
     the typical-acceptance inequality (Section III-B, Eq. 1): the base model's probability of the
     token must exceed min(epsilon, delta * exp(-entropy of the base distribution));

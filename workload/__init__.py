@@ -9,6 +9,7 @@ from .configs import ModelShape, Workload, PRESETS, preset
 from .gen import (
     make_weights,
     zipf_prompt,
+    frag_filled_labels,
     stop_set,
     pack_mask_words,
     default_tree,
@@ -22,7 +23,7 @@ from .gen import (
 
 __all__ = [
     "ModelShape", "Workload", "PRESETS", "preset",
-    "make_weights", "zipf_prompt", "stop_set", "pack_mask_words",
+    "make_weights", "zipf_prompt", "frag_filled_labels", "stop_set", "pack_mask_words",
     "default_tree", "chain_tree", "full_tree", "synthetic_kv_rows", "plant_drafts",
     "round_to_bf16", "SEEDS",
 ]

@@ -18,7 +18,7 @@ import torch
 from .configs import ModelShape
 
 # One seed per input family, so inputs can be regenerated independently.
-SEEDS = {"weights": 1234, "prompt": 1, "stop": 2, "kvfill": 3, "force": 4, "kvlen": 5}
+SEEDS = {"weights": 1234, "prompt": 1, "stop": 2, "kvfill": 3, "force": 4, "kvlen": 5, "labels": 6}
 
 
 # --------------------------------------------------------------------------- numeric helpers
@@ -107,6 +107,28 @@ def zipf_prompt(vocab: int, length: int, seed: int = SEEDS["prompt"], s: float =
     cdf /= cdf[-1]
     u = rng.random(length)
     return np.minimum(np.searchsorted(cdf, u, side="right"), vocab - 1).astype(np.int32)
+
+
+def frag_filled_labels(batch: int, seq: int, vocab: int, frag_id: int, pad_id: int, mean_fragment: float = 4.0,
+                       min_fill: float = 0.5, seed: int = SEEDS["labels"]) -> np.ndarray:
+    """Base-model label rows [batch, seq]: Zipf token ids with `frag_id` inserted after fragments whose lengths are
+    geometric with the given mean (identifiers, keywords and operators are a few tokens each); every sequence holds
+    between min_fill*seq and seq such entries and is filled up with `pad_id`. Ids equal to frag_id / pad_id never
+    occur as ordinary tokens."""
+    rng = np.random.Generator(np.random.Philox(key=seed))
+    out = np.full((batch, seq), pad_id, dtype=np.int32)
+    for b in range(batch):
+        n = int(rng.integers(int(min_fill * seq), seq + 1))
+        toks = zipf_prompt(vocab, n, seed=seed * 1000 + b)
+        toks = np.where((toks == frag_id) | (toks == pad_id), 0, toks)
+        row, i = [], 0
+        while len(row) < n:
+            L = int(rng.geometric(1.0 / mean_fragment))
+            row.extend(toks[i: i + L].tolist())
+            row.append(frag_id)
+            i += L
+        out[b, :n] = row[:n]
+    return out
 
 
 def stop_set(vocab: int, frac: float = 0.2, seed: int = SEEDS["stop"]) -> np.ndarray:
