@@ -32,6 +32,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # kernel (1 FETCH unit = 2 KiB, 1 WRITE unit = 1 KiB): profiles/k_gemm_sk_7b_pmc_traffic.txt.
 # Only valid for the default workload; other workloads report null.
 GEMM_TRAFFIC_BYTES_PER_LAUNCH = 122.5e6
+# same counters for k_build_labels at the `labels` workload: profiles/k_build_labels_256x8192_kernel_trace_and_traffic.txt
+LABELS_TRAFFIC_BYTES_PER_LAUNCH = 100.9e6
 
 
 def parse():
@@ -39,7 +41,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=256)
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", default="7b", choices=["7b", "7b-long", "13b", "tiny"])
+    ap.add_argument("--workload", default="7b", choices=["7b", "7b-long", "13b", "tiny", "labels"],
+                    help="labels = the training-side label construction alone (not the headline step)")
     ap.add_argument("--layers", type=int, default=None, help="cut the depth (debugging only; result is labelled)")
     ap.add_argument("--draft", default="planted", choices=["planted", "random"])
     ap.add_argument("--decoding", default="greedy", choices=["greedy", "sampling"],
@@ -69,6 +72,8 @@ def main():
 
     sd.lib()
     torch.cuda.set_device(0)
+    if args.workload == "labels":
+        return bench_labels(args, torch, wl, sd)
     W = wl.preset(args.workload, args.layers)
     shape = dataclasses.replace(W.model, dtype="bf16")
     T, H, k = W.tree_nodes, shape.n_medusa, shape.topk
@@ -231,6 +236,48 @@ def main():
         "cpu_baseline": cpu,
     }
     print(json.dumps(res))
+
+
+def bench_labels(args, torch, wl, sd):
+    """Syntax-enriched label construction (Section III-C) for one training batch: 256 sequences of the paper's
+    8192-token limit, ten heads. A "step" is one launch; timed with HIP events on the launch stream."""
+    B, S, H, V = 256, 8192, 10, 32000
+    frag, pad, ign = V + 1, V + 2, -100
+    l0_np = np.tile(wl.frag_filled_labels(16, S, V, frag, pad), (B // 16, 1))
+    l0 = torch.from_numpy(l0_np).cuda()
+    out = torch.empty((B, H + 1, S), dtype=torch.int32, device="cuda")
+    for _ in range(args.warmup):
+        sd.build_labels(l0, H, frag, pad, ign, out=out)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()                                       # the binding launches on torch's current stream
+    for _ in range(args.steps):
+        sd.build_labels(l0, H, frag, pad, ign, out=out)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    nbytes = B * S * 4.0 * (H + 2)                    # one read of L_0, one write of the matrix
+    gbs = nbytes / (ms * 1e-3) / 1e9
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import labels_oracle as lab
+        t0 = time.perf_counter()
+        n = 0
+        while time.perf_counter() - t0 < 10.0:
+            lab.syntax_enriched_labels(l0_np[n % 16], H, frag, pad, ign)
+            n += 1
+        dt = time.perf_counter() - t0
+        cpu = {"value": n * S / dt, "unit": "positions/s", "cores": 1, "kind": "oracle",
+               "sample": f"{n} sequences of {S} positions with {H} heads, one at a time, {dt:.1f} s"}
+    print(json.dumps({
+        "metric": "label_positions_per_s", "value": B * S / (ms * 1e-3), "unit": "positions/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "int32", "data": "synthetic",
+        "config": {"workload": f"labels: {B} sequences x {S} positions, {H} heads, geometric fragments of mean 4 tokens"},
+        "roofline": {"kernel": "k_build_labels", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": gbs / HBM_PEAK_GBS, "traffic": LABELS_TRAFFIC_BYTES_PER_LAUNCH, "avg_launch_us": ms * 1e3,
+                     "algorithmic_bytes_per_launch": nbytes},
+        "cpu_baseline": cpu}))
 
 
 def cpu_baseline(wl, shape, cpu_keep, T, tree_np, stop, n_cache, typical=None):

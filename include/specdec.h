@@ -207,6 +207,21 @@ int sd_verify_tree_typical(const sd_tree* tree, int32_t batch, int32_t n_medusa,
 int sd_sample_tokens(const float* logits, int32_t n_rows, int32_t ld, int32_t vocab, const int32_t* rows,
                      const float* u, int32_t n, float temperature, int32_t* out, void* stream);
 
+/* ---- training-side data preparation ----------------------------------------------------------
+ * Syntax-enriched labels (Section III-C, Fig. 3). l0: dev int32 [batch][seq], the base model's
+ * label rows: token ids with frag_id at every fragment boundary, filled up with pad_id.
+ * labels: dev int32 [batch][n_heads + 1][seq], written in full: row i of a sequence is its l0
+ * row shifted left by i (entries past the end = pad_id); then, per position, every entry in a
+ * row after the last row that holds frag_id becomes ignore_id. A position whose n_heads + 1
+ * entries hold no frag_id keeps row 0 only (SD_LABELS_KEEP_BASE) or stays as it is
+ * (SD_LABELS_KEEP_ALL). seq >= 0 (0 writes nothing), 0 <= n_heads <= SD_LABELS_MAX_HEADS,
+ * 1 <= batch <= 65535; l0 and labels must not overlap. The caller owns both buffers.       */
+#define SD_LABELS_MAX_HEADS 64
+#define SD_LABELS_KEEP_BASE 0
+#define SD_LABELS_KEEP_ALL  1
+int sd_build_labels(const int32_t* l0, int32_t batch, int32_t seq, int32_t n_heads, int32_t frag_id,
+                    int32_t pad_id, int32_t ignore_id, int32_t no_frag, int32_t* labels, void* stream);
+
 /* Graph mode (off by default). When on, sd_spec_step / sd_greedy_step capture their kernel
  * sequence into a HIP graph the first time a given combination of (cache, tree, split-KV
  * geometry, stop mask, output and candidate pointers) is seen and replay it afterwards: one

@@ -6,6 +6,6 @@ for device memory and streams. Importing the package does not load the library; 
 call does, and fails loudly if it has not been built (`python -m paper_2503_14153_amd.build`).
 """
 from .binding import (  # noqa: F401
-    KVCache, Model, SpecDecError, StepOutput, Tree, greedy_step, lib, lib_path, prefill, sample_tokens, spec_step,
+    KVCache, Model, build_labels, SpecDecError, StepOutput, Tree, greedy_step, lib, lib_path, prefill, sample_tokens, spec_step,
     spec_step_typical, verify_tree, verify_tree_typical, EXPORTED_SYMBOLS,
 )

@@ -14,7 +14,7 @@ EXPORTED_SYMBOLS = [
     "sd_model_create", "sd_model_destroy", "sd_kv_bytes", "sd_kv_create", "sd_kv_destroy", "sd_kv_len",
     "sd_kv_set_len", "sd_kv_write_rows", "sd_kv_read_rows", "sd_kv_set_draft", "sd_kv_get_draft",
     "sd_tree_create", "sd_tree_destroy", "sd_prefill", "sd_spec_step", "sd_greedy_step", "sd_verify_tree",
-    "sd_spec_step_typical", "sd_verify_tree_typical", "sd_sample_tokens",
+    "sd_spec_step_typical", "sd_verify_tree_typical", "sd_sample_tokens", "sd_build_labels",
     "sd_set_graph_mode", "sd_profile_begin", "sd_profile_end", "sd_last_error", "sd_version",
 ]
 
@@ -92,6 +92,7 @@ def lib() -> C.CDLL:
                                              C.c_void_p, C.c_float, C.c_float, C.c_float] + [C.c_void_p] * 7
         L.sd_sample_tokens.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
                                        C.c_float, C.c_void_p, C.c_void_p]
+        L.sd_build_labels.argtypes = [C.c_void_p] + [C.c_int32] * 7 + [C.c_void_p, C.c_void_p]
         L.sd_profile_begin.argtypes = [C.c_void_p, C.c_int32]
         L.sd_set_graph_mode.argtypes = [C.c_void_p, C.c_int32]
         L.sd_profile_end.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64),
@@ -357,4 +358,17 @@ def sample_tokens(logits: torch.Tensor, rows: torch.Tensor, u: torch.Tensor, tem
     out = torch.empty(rows.numel(), dtype=torch.int32, device="cuda")
     _check(lib().sd_sample_tokens(logits.data_ptr(), logits.shape[0], logits.stride(0), logits.shape[1],
                                   rows.data_ptr(), u.data_ptr(), rows.numel(), temperature, out.data_ptr(), _stream()))
+    return out
+
+
+def build_labels(l0: torch.Tensor, n_heads: int, frag_id: int, pad_id: int, ignore_id: int = -100,
+                 no_frag: str = "keep_base", out: torch.Tensor | None = None) -> torch.Tensor:
+    """sd_build_labels: int32 CUDA [batch, seq] -> int32 CUDA [batch, n_heads + 1, seq]."""
+    assert l0.is_cuda and l0.dtype == torch.int32 and l0.dim() == 2 and l0.is_contiguous()
+    batch, seq = l0.shape
+    if out is None:
+        out = torch.empty((batch, n_heads + 1, seq), dtype=torch.int32, device="cuda")
+    assert out.is_cuda and out.dtype == torch.int32 and out.is_contiguous() and out.shape == (batch, n_heads + 1, seq)
+    _check(lib().sd_build_labels(l0.data_ptr(), batch, seq, n_heads, frag_id, pad_id, ignore_id,
+                                 {"keep_base": 0, "keep_all": 1}[no_frag], out.data_ptr(), _stream()))
     return out

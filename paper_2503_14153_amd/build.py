@@ -8,13 +8,13 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspecdec.so")
-SOURCES = ["api.hip", "gemm.hip", "attn.hip", "rows.hip", "decide.hip"]
+SOURCES = ["api.hip", "gemm.hip", "attn.hip", "rows.hip", "decide.hip", "labels.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-result", "-Wno-unused-value",
          # keep hipcc from forming packed-fp32 VALU ops ("compiler flags")
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
-def build(verbose: bool = True, jobs: int = 5) -> str:
+def build(verbose: bool = True, jobs: int = 6) -> str:
     """Compile every translation unit and link the shared library. Returns its path."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs, procs = [], []

@@ -342,6 +342,21 @@ extern "C" int sd_profile_end(sd_model* m, void* stream, double* ms_total, int64
     return SD_OK;
 }
 
+extern "C" int sd_build_labels(const int32_t* l0, int32_t batch, int32_t seq, int32_t n_heads, int32_t frag_id,
+                               int32_t pad_id, int32_t ignore_id, int32_t no_frag, int32_t* labels, void* stream) {
+    if (batch < 1 || batch > 65535 || seq < 0) return fail(SD_ERR_SHAPE, "sd_build_labels: bad batch or seq");
+    if (n_heads < 0 || n_heads > SD_LABELS_MAX_HEADS)
+        return fail(SD_ERR_SHAPE, "sd_build_labels: n_heads must be in 0..%d", SD_LABELS_MAX_HEADS);
+    if (no_frag != SD_LABELS_KEEP_BASE && no_frag != SD_LABELS_KEEP_ALL)
+        return fail(SD_ERR_SHAPE, "sd_build_labels: bad no_frag policy");
+    if (seq == 0) return SD_OK;                        // nothing to write; the pointers are not looked at
+    if (!l0 || !labels) return fail(SD_ERR_NULL, "sd_build_labels: NULL argument");
+    launch_build_labels(l0, batch, seq, n_heads, frag_id, pad_id, ignore_id, no_frag == SD_LABELS_KEEP_ALL, labels,
+                        (hipStream_t)stream);
+    HIP_TRY(hipGetLastError());
+    return SD_OK;
+}
+
 extern "C" int sd_set_graph_mode(sd_model* m, int32_t on) {
     if (!m) return fail(SD_ERR_NULL, "sd_set_graph_mode: NULL model");
     m->use_graphs = on != 0;

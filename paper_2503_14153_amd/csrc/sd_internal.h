@@ -159,6 +159,9 @@ void launch_row_stats(const float* logits, int ld, int V, float4* stats, int B, 
 // -1 for a row index outside [0, n_rows)
 void launch_sample_root(const float* logits, int ld, int V, const int32_t* last_row, const float* u,
                         float inv_temperature, int32_t* root_tok, int B, int n_rows, hipStream_t s);
+// syntax-enriched label matrix [B][H+1][S] from the base label rows [B][S] (labels.hip)
+void launch_build_labels(const int32_t* l0, int B, int S, int H, int32_t frag, int32_t pad, int32_t ignore,
+                         int keep_all, int32_t* labels, hipStream_t s);
 void launch_copy_row_stats(const float4* src, float4* dst, int B, int T, int Tp, hipStream_t s);
 void launch_kv_commit(const void* kt_all, const void* vt_all, void* kc_all, void* vc_all,
                       const int32_t* src_slots, const int32_t* n_accept, const int32_t* n_old,
