@@ -542,26 +542,23 @@ extern "C" int sd_tree_destroy(sd_tree* t) {
 // ------------------------------------------------------------------------------------------ forward
 // Layers 0..L-1 on the rows described by m->rt / m->x (B sequences of Tp rows each). Leaves the
 // last down-projection's partial sums in m->part (added by the caller's next norm).
-static int prof_start(sd_model* m, int cls, double bytes, hipStream_t s) {
+// Claims the next pair of profile events (or -1): the launcher hands them to the kernel launch, which
+// stamps them with the kernel's own start and end, so launch gaps are not counted.
+static int prof_claim(sd_model* m, int cls, double bytes) {
     Profile& p = m->prof;
     if (!p.on || p.used * 2 + 1 >= p.ev.size()) return -1;
     int i = (int)p.used++;
     p.cls[i] = cls;
     p.bytes[i] = bytes;
-    hipEventRecord(p.ev[2 * i], s);
     return i;
 }
-static void prof_stop(sd_model* m, int i, hipStream_t s) {
-    if (i >= 0) hipEventRecord(m->prof.ev[2 * i + 1], s);
-}
+static hipEvent_t prof_ev(sd_model* m, int i, int which) { return i >= 0 ? m->prof.ev[2 * i + which] : nullptr; }
 
 // One weight-streaming GEMM; algorithmic bytes = one read of the (unpadded) weight matrix.
 static PartView run_gemm(sd_model* m, const void* Xp, const void* Wp, float* out, int MB, int KB, int NB, int n_real,
                          hipStream_t s) {
-    int pi = prof_start(m, PROF_GEMM, (double)n_real * KB * 16 * 2, s);
-    PartView pv = launch_gemm(m->plan(MB, KB, NB), Xp, Wp, m->zfrag, out, s);
-    prof_stop(m, pi, s);
-    return pv;
+    const int pi = prof_claim(m, PROF_GEMM, (double)n_real * KB * 16 * 2);
+    return launch_gemm(m->plan(MB, KB, NB), Xp, Wp, m->zfrag, out, s, prof_ev(m, pi, 0), prof_ev(m, pi, 1));
 }
 
 // How the attention of one step is cut into workgroups (one resident per compute unit: the kernel
@@ -607,10 +604,10 @@ static PartView run_layers(sd_model* m, sd_kv* kv, int B, int Tp, int n_hi, hipS
         uint16_t* vt = (uint16_t*)m->vt + l * t_stride;
         launch_rope_kv(pq, m->rt, m->q, kt, vt, B, Tp, nh, hd, s);
         // algorithmic bytes: one read of K and V of the committed rows (upper bound n_hi) + tree rows
-        int pa = prof_start(m, PROF_ATTN, (double)B * (n_hi + Tp) * 2.0 * d * 2.0, s);
+        const int pa = prof_claim(m, PROF_ATTN, (double)B * (n_hi + Tp) * 2.0 * d * 2.0);
         launch_tree_attn(m->q, kv->kc + l * kv->layer_stride, kv->vc + l * kv->layer_stride, kt, vt, kv->kv_len,
-                         m->rt.anc, m->opart, m->mlpart, B, nh, hd, Tp, kv->cap_blocks, ag.ncparts, ag.per, ag.tree_sep, s);
-        prof_stop(m, pa, s);
+                         m->rt.anc, m->opart, m->mlpart, B, nh, hd, Tp, kv->cap_blocks, ag.ncparts, ag.per, ag.tree_sep, s,
+                         prof_ev(m, pa, 0), prof_ev(m, pa, 1));
         launch_attn_merge(m->opart, m->mlpart, m->attn_x, B, nh, hd, Tp, ag.nparts, MB, s);
         PartView po = run_gemm(m, m->attn_x, lw.wo, m->part, MB, m->KBd, m->NBo, d, s);
         launch_norm_pack(m->x, po, lw.ffn_norm, c.rms_eps, m->xn, nullptr, M, d, MB, nullptr, s);

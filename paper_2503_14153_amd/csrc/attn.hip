@@ -323,18 +323,25 @@ __global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp
 
 void launch_tree_attn(const void* q_packed, const void* kc, const void* vc, const void* kt, const void* vt,
                       const int32_t* kv_len, const uint32_t* anc, float* opart, float2* mlpart, int B, int nh,
-                      int hd, int Tp, int cap_blocks, int ncparts, int per, int tree_sep, hipStream_t s) {
+                      int hd, int Tp, int cap_blocks, int ncparts, int per, int tree_sep, hipStream_t s, hipEvent_t ev0,
+                      hipEvent_t ev1) {
     const float scale_log2 = 1.4426950408889634f / sqrtf((float)hd);
     const int TB = Tp / 32;
     const int TBW = (TB % 2 == 0) ? 2 : 1;
     dim3 grid(ncparts + (tree_sep ? 1 : 0), nh * (TB / TBW), B);
+#define ATT_ARGS (const bf16x8*)q_packed, (const bf16x8*)kc, (const bf16x8*)vc, (const bf16x8*)kt, (const bf16x8*)vt, \
+                 kv_len, anc, opart, mlpart, nh, Tp, cap_blocks, ncparts, per, tree_sep, scale_log2
 #define ATT(HD_, TBW_)                                                                                          \
-    hipLaunchKernelGGL((k_tree_attn<HD_, TBW_>), grid, dim3(256), 0, s, (const bf16x8*)q_packed,               \
-                       (const bf16x8*)kc, (const bf16x8*)vc, (const bf16x8*)kt, (const bf16x8*)vt, kv_len, anc, \
-                       opart, mlpart, nh, Tp, cap_blocks, ncparts, per, tree_sep, scale_log2)
+    do {                                                                                                        \
+        if (ev0 || ev1)                                                                                         \
+            hipExtLaunchKernelGGL((k_tree_attn<HD_, TBW_>), grid, dim3(256), 0, s, ev0, ev1, 0, ATT_ARGS);      \
+        else                                                                                                    \
+            hipLaunchKernelGGL((k_tree_attn<HD_, TBW_>), grid, dim3(256), 0, s, ATT_ARGS);                      \
+    } while (0)
     if (hd == 128) { if (TBW == 2) ATT(128, 2); else ATT(128, 1); }
     else           { if (TBW == 2) ATT(64, 2);  else ATT(64, 1); }
 #undef ATT
+#undef ATT_ARGS
 }
 
 // ------------------------------------------------------------------------------------------

@@ -269,7 +269,8 @@ void gemm_plan_make(GemmPlan* p, int MB, int KB, int NB, int32_t* cnt_host) {
     for (int ng = 0; ng < p->NG; ++ng) p->uniform &= (cnt_host[ng] == slots);
 }
 
-PartView launch_gemm(const GemmPlan& p, const void* Xp, const void* Wp, const void* zfrag, float* out, hipStream_t s) {
+PartView launch_gemm(const GemmPlan& p, const void* Xp, const void* Wp, const void* zfrag, float* out, hipStream_t s,
+                     hipEvent_t ev0, hipEvent_t ev1) {
     PartView pv;
     pv.base = out;
     pv.ld = p.NB * 32;
@@ -279,17 +280,25 @@ PartView launch_gemm(const GemmPlan& p, const void* Xp, const void* Wp, const vo
     pv.nmax = p.slots;
     const int MT = p.MB < SK_MAX_MT ? p.MB : SK_MAX_MT;
     const int x_kb_units = p.MB * 2 * 64;
-    for (int r = 0; r < p.MB / MT; ++r) {              // passes of MT row blocks
+    const int passes = p.MB / MT;
+    for (int r = 0; r < passes; ++r) {                 // passes of MT row blocks
         const bf16x8* xp = (const bf16x8*)Xp + (size_t)r * MT * 2 * 64;
         float* o = out + (size_t)r * MT * 32 * pv.ld;
+        hipEvent_t e0 = r == 0 ? ev0 : nullptr, e1 = r == passes - 1 ? ev1 : nullptr;
+#define SK_ARGS xp, (const bf16x8*)Wp, (const bf16x8*)zfrag, o, p.KB, p.NB, p.NG, pv.ld, pv.slot_stride, x_kb_units
 #define SK_LAUNCH(MT_, PASSES_)                                                                            \
-        hipLaunchKernelGGL((k_gemm_sk<MT_, PASSES_>), dim3(p.G), dim3(512), 0, s, xp, (const bf16x8*)Wp,   \
-                           (const bf16x8*)zfrag, o, p.KB, p.NB, p.NG, pv.ld, pv.slot_stride, x_kb_units)
+        do {                                                                                               \
+            if (e0 || e1)                                                                                  \
+                hipExtLaunchKernelGGL((k_gemm_sk<MT_, PASSES_>), dim3(p.G), dim3(512), 0, s, e0, e1, 0, SK_ARGS); \
+            else                                                                                           \
+                hipLaunchKernelGGL((k_gemm_sk<MT_, PASSES_>), dim3(p.G), dim3(512), 0, s, SK_ARGS);        \
+        } while (0)
         if (MT == 1) SK_LAUNCH(1, false);
         else if (MT == 2) SK_LAUNCH(2, false);
         else if (p.MB == MT) SK_LAUNCH(4, false);
         else SK_LAUNCH(4, true);
 #undef SK_LAUNCH
+#undef SK_ARGS
     }
     return pv;
 }

@@ -21,6 +21,7 @@
 //      come out of the QK^T accumulator, are already the B operand of the PV product)
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <stddef.h>
 
@@ -123,7 +124,10 @@ void launch_pack_weight(const void* src, void* dst, int N, int K, int nb_offset,
 void gemm_plan_make(GemmPlan* p, int MB, int KB, int NB, int32_t* cnt_host /*[>= ceil(NB/8)]*/);
 // out must hold plan.slots * (MB*32) * (NB*32) floats; zfrag: 1 KiB of zeros (device);
 // returns the view consumers read
-PartView launch_gemm(const GemmPlan& p, const void* Xp, const void* Wp, const void* zfrag, float* out, hipStream_t s);
+// ev0 / ev1 (both or neither): events that receive the kernel's own start and end time stamps
+// (first pass's start, last pass's end), for per-kernel timing without launch gaps
+PartView launch_gemm(const GemmPlan& p, const void* Xp, const void* Wp, const void* zfrag, float* out, hipStream_t s,
+                     hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 void launch_reduce_slots(PartView pv, float* dst, int rows, hipStream_t s);
 
 void launch_build_rows_tree(RowTable rt, const int32_t* parent, const int32_t* depth, const int32_t* rank,
@@ -140,7 +144,7 @@ void launch_rope_kv(PartView pv, RowTable rt, void* q_packed, void* kt, void* vt
 void launch_tree_attn(const void* q_packed, const void* kc, const void* vc, const void* kt, const void* vt,
                       const int32_t* kv_len, const uint32_t* anc, float* opart, float2* mlpart,
                       int B, int nh, int hd, int Tp, int cap_blocks, int ncparts, int per, int tree_sep,
-                      hipStream_t s);
+                      hipStream_t s, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 void launch_attn_merge(const float* opart, const float2* mlpart, void* x_packed, int B, int nh, int hd,
                        int Tp, int nparts, int MB, hipStream_t s);
 void launch_swiglu_pack(PartView pv, int F, int Fpad, void* act_packed, int M, int MB, hipStream_t s);
