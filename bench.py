@@ -41,7 +41,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=256)
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", default="7b", choices=["7b", "7b-long", "13b", "tiny", "labels"],
+    ap.add_argument("--workload", default="7b", choices=["7b", "7b-long", "13b", "7b-h10", "tiny", "labels"],
                     help="labels = the training-side label construction alone (not the headline step)")
     ap.add_argument("--layers", type=int, default=None, help="cut the depth (debugging only; result is labelled)")
     ap.add_argument("--draft", default="planted", choices=["planted", "random"])
@@ -122,7 +122,7 @@ def main():
 
     # ---------------------------------------------------------------- planted-draft table
     rng = np.random.default_rng(wl.SEEDS["force"])
-    p_depth = (0.9, 0.85, 0.8, 0.75, 0.7)[:H]
+    p_depth = tuple(round(max(0.5, 0.9 - 0.05 * i), 2) for i in range(H))
     n_table = len(truth) - H
     table = np.zeros((n_table, H, k), np.int32)
     for e in range(n_table):

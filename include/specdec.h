@@ -20,7 +20,7 @@
  *     be used from one thread and one stream at a time.
  *   - All weight matrices are row-major [out_features][in_features] (y = W x), bf16.
  *   - Only dtype = SD_DTYPE_BF16 is implemented; head_dim must be 64 or 128; d_model and
- *     d_ffn must be multiples of 16; n_medusa <= 15; topk <= 32; tree nodes <= 128.
+ *     d_ffn must be multiples of 16; n_medusa <= 15; topk <= 32; tree nodes <= 256.
  */
 #ifndef SPECDEC_H
 #define SPECDEC_H

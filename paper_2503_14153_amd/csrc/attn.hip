@@ -57,7 +57,8 @@ static __device__ __forceinline__ void acc_scale(float& x, float alpha) {
 }
 template <int N> static __device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
 
-template <int HD, int TBW>
+// AW = ancestor words a query row needs: 4 for trees of up to 128 nodes, 8 beyond
+template <int HD, int TBW, int AW>
 __global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp, const bf16x8* Kc, const bf16x8* Vc,
                                                    const bf16x8* Kt, const bf16x8* Vt, const int32_t* __restrict__ kv_len,
                                                    const uint32_t* __restrict__ anc, float* __restrict__ opart,
@@ -87,14 +88,18 @@ __global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp
     const int ntree = (part == nparts - 1) ? tg * TBW + TBW : 0;   // later tree blocks hold no ancestors
 
     // ancestor words of this lane's query rows: only the part with the tree blocks masks by them
-    static_assert(SD_ANC_WORDS == 4, "one 16-byte load per row");
-    uint4 ancq[TBW];
+    static_assert(SD_ANC_WORDS == 8 && (AW == 4 || AW == 8), "one or two 16-byte loads per row");
+    uint4 ancq[TBW][AW / 4];
 #pragma unroll
-    for (int tb = 0; tb < TBW; ++tb) ancq[tb] = make_uint4(0u, 0u, 0u, 0u);
+    for (int tb = 0; tb < TBW; ++tb)
+#pragma unroll
+        for (int q = 0; q < AW / 4; ++q) ancq[tb][q] = make_uint4(0u, 0u, 0u, 0u);
     if (ntree) {
 #pragma unroll
         for (int tb = 0; tb < TBW; ++tb)
-            ancq[tb] = *(const uint4*)(anc + ((size_t)b * Tp + (tg * TBW + tb) * 32 + tl) * SD_ANC_WORDS);
+#pragma unroll
+            for (int q = 0; q < AW / 4; ++q)
+                ancq[tb][q] = *(const uint4*)(anc + ((size_t)b * Tp + (tg * TBW + tb) * 32 + tl) * SD_ANC_WORDS + 4 * q);
     }
 
     // The part's items: its tree blocks first, then its cache blocks; wave w owns items
@@ -195,7 +200,13 @@ __global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp
             if (need_mask) {
                 uint32_t vis;
                 if (tr) {
-                    const uint64_t lo64 = ancq[tb].x | ((uint64_t)ancq[tb].y << 32), hi64 = ancq[tb].z | ((uint64_t)ancq[tb].w << 32);
+                    uint4 aq = ancq[tb][0];
+                    if constexpr (AW == 8) {
+                        const bool up = (blk & 4) != 0;
+                        aq.x = up ? ancq[tb][1].x : aq.x; aq.y = up ? ancq[tb][1].y : aq.y;
+                        aq.z = up ? ancq[tb][1].z : aq.z; aq.w = up ? ancq[tb][1].w : aq.w;
+                    }
+                    const uint64_t lo64 = aq.x | ((uint64_t)aq.y << 32), hi64 = aq.z | ((uint64_t)aq.w << 32);
                     vis = (uint32_t)(((blk & 2) ? hi64 : lo64) >> ((blk & 1) * 32));     // word blk of the row's ancestor set
                 }
                 else vis = (1u << left) - 1u;
@@ -331,15 +342,17 @@ void launch_tree_attn(const void* q_packed, const void* kc, const void* vc, cons
     dim3 grid(ncparts + (tree_sep ? 1 : 0), nh * (TB / TBW), B);
 #define ATT_ARGS (const bf16x8*)q_packed, (const bf16x8*)kc, (const bf16x8*)vc, (const bf16x8*)kt, (const bf16x8*)vt, \
                  kv_len, anc, opart, mlpart, nh, Tp, cap_blocks, ncparts, per, tree_sep, scale_log2
-#define ATT(HD_, TBW_)                                                                                          \
+#define ATT(HD_, TBW_, AW_)                                                                                          \
     do {                                                                                                        \
         if (ev0 || ev1)                                                                                         \
-            hipExtLaunchKernelGGL((k_tree_attn<HD_, TBW_>), grid, dim3(256), 0, s, ev0, ev1, 0, ATT_ARGS);      \
+            hipExtLaunchKernelGGL((k_tree_attn<HD_, TBW_, AW_>), grid, dim3(256), 0, s, ev0, ev1, 0, ATT_ARGS); \
         else                                                                                                    \
-            hipLaunchKernelGGL((k_tree_attn<HD_, TBW_>), grid, dim3(256), 0, s, ATT_ARGS);                      \
+            hipLaunchKernelGGL((k_tree_attn<HD_, TBW_, AW_>), grid, dim3(256), 0, s, ATT_ARGS);                 \
     } while (0)
-    if (hd == 128) { if (TBW == 2) ATT(128, 2); else ATT(128, 1); }
-    else           { if (TBW == 2) ATT(64, 2);  else ATT(64, 1); }
+#define ATT2(HD_, TBW_) do { if (Tp > 128) ATT(HD_, TBW_, 8); else ATT(HD_, TBW_, 4); } while (0)
+    if (hd == 128) { if (TBW == 2) ATT2(128, 2); else ATT2(128, 1); }
+    else           { if (TBW == 2) ATT2(64, 2);  else ATT2(64, 1); }
+#undef ATT2
 #undef ATT
 #undef ATT_ARGS
 }

@@ -278,8 +278,8 @@ void launch_sample_root(const float* logits, int ld, int V, const int32_t* last_
 }
 
 // ------------------------------------------------------------------------------------------
-// Greedy acceptance + fragment cut. One workgroup of SD_MAX_TREE threads per sequence, thread
-// j = tree node j.
+// Greedy acceptance + fragment cut. One workgroup of 64*NW >= T threads per sequence, thread
+// j = tree node j (NW = 2 for trees of up to 128 nodes, 4 beyond).
 //   match[j]  = tok[j] == am[parent[j]]                     (root: true); under sampling decoding
 //               instead: p(tok[j] | parent) > min(eps, delta * exp(-entropy)), from k_row_stats
 //   ok[j]     = match holds on every node of j's root path  (prefix-closed acceptance): with
@@ -289,15 +289,16 @@ void launch_sample_root(const float* logits, int ld, int V, const int32_t* last_
 //   chain     = best's ancestor bitset; node j of the chain sits at chain index depth[j]
 //   cut       = 1 + largest chain index whose token is in the stop set; without any stop
 //               token: whole chain (keep_all) or 1 (keep_one)
-__global__ __launch_bounds__(SD_MAX_TREE) void k_verify(VerifyArgs a) {
+template <int NW>
+__global__ __launch_bounds__(64 * NW) void k_verify(VerifyArgs a) {
     const int b = blockIdx.x, j = threadIdx.x, T = a.T, H = a.H;
     const bool valid = j < T;
     const int32_t* tok = a.tok + (size_t)b * a.src_stride;
     const int32_t* am = a.am + (size_t)b * a.src_stride;
-    __shared__ unsigned long long matchw[2], bestanc[2];
-    __shared__ int wkey[2], stopmax[2];
+    __shared__ unsigned long long matchw[NW], bestanc[NW];
+    __shared__ int wkey[NW], stopmax[NW];
     int dj = 0, tj = 0, pj = -1;
-    unsigned long long anc[2] = {0ull, 0ull};
+    unsigned long long anc[NW] = {};
     bool match = false;
     if (valid) {
         dj = a.depth[j];
@@ -320,16 +321,25 @@ __global__ __launch_bounds__(SD_MAX_TREE) void k_verify(VerifyArgs a) {
     unsigned long long bal = __ballot(match);
     if ((j & 63) == 0) matchw[j >> 6] = bal;
     __syncthreads();
-    const bool ok = valid && ((anc[0] & ~matchw[0]) | (anc[1] & ~matchw[1])) == 0ull;
+    unsigned long long miss = 0ull;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) miss |= anc[w] & ~matchw[w];
+    const bool ok = valid && miss == 0ull;
     // deepest accepted node, lowest index on ties: maximise depth * 256 + (255 - j)
+    static_assert(SD_MAX_TREE <= 256, "the key holds the node index in 8 bits");
     int key = ok ? dj * 256 + (255 - j) : -1;
     for (int o = 32; o > 0; o >>= 1) key = max(key, __shfl_xor(key, o));
     if ((j & 63) == 0) wkey[j >> 6] = key;
     __syncthreads();
-    key = max(wkey[0], wkey[1]);
+    key = wkey[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) key = max(key, wkey[w]);
     const int best = 255 - (key & 255);
     const int n_raw = (key >> 8) + 1;
-    if (j == best) { bestanc[0] = anc[0]; bestanc[1] = anc[1]; }
+    if (j == best) {
+#pragma unroll
+        for (int w = 0; w < NW; ++w) bestanc[w] = anc[w];
+    }
     __syncthreads();
     const bool on_chain = valid && ((bestanc[j >> 6] >> (j & 63)) & 1ull);
     const bool is_stop = on_chain && tj >= 0 && tj < a.V && ((a.stop_mask[tj >> 5] >> (tj & 31)) & 1u);
@@ -337,7 +347,9 @@ __global__ __launch_bounds__(SD_MAX_TREE) void k_verify(VerifyArgs a) {
     for (int o = 32; o > 0; o >>= 1) sm = max(sm, __shfl_xor(sm, o));
     if ((j & 63) == 0) stopmax[j >> 6] = sm;
     __syncthreads();
-    sm = max(stopmax[0], stopmax[1]);
+    sm = stopmax[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) sm = max(sm, stopmax[w]);
     const int n_acc = sm >= 0 ? sm + 1 : (a.fallback == SD_TRUNC_KEEP_ALL ? n_raw : 1);
     const int W = H + 1;
     if (on_chain && dj < n_acc) {
@@ -364,7 +376,8 @@ __global__ __launch_bounds__(SD_MAX_TREE) void k_verify(VerifyArgs a) {
 }
 
 void launch_verify(const VerifyArgs& a, int B, hipStream_t s) {
-    hipLaunchKernelGGL(k_verify, dim3(B), dim3(SD_MAX_TREE), 0, s, a);
+    if (a.T <= 128) hipLaunchKernelGGL(k_verify<2>, dim3(B), dim3(128), 0, s, a);
+    else hipLaunchKernelGGL(k_verify<4>, dim3(B), dim3(256), 0, s, a);
 }
 
 // ------------------------------------------------------------------------------------------

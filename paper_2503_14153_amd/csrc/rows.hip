@@ -32,7 +32,7 @@ __global__ void k_build_rows_tree(RowTable rt, const int32_t* __restrict__ paren
     const int m = blockIdx.x, b = m / Tp, j = m % Tp;
     const bool valid = j < T;
     int tok = 0, pos = kv_len[b];
-    uint32_t a[SD_ANC_WORDS] = {0, 0, 0, 0};
+    uint32_t a[SD_ANC_WORDS] = {};
     if (valid) {
         int dj = depth[j];
         tok = (j == 0) ? root_tok[b] : cand[((size_t)b * H + (dj - 1)) * topk + rank[j]];
@@ -67,7 +67,7 @@ __global__ void k_build_rows_chain(RowTable rt, const int32_t* __restrict__ toke
     const bool valid = j < ca.len[b];
     int tok = valid ? min(max(tokens[ca.off[b] + j], 0), V - 1) : 0;
     int pos = kv_len[b] + (valid ? j : 0);
-    uint32_t a[SD_ANC_WORDS] = {0, 0, 0, 0};
+    uint32_t a[SD_ANC_WORDS] = {};
     if (valid) {
         for (int w = 0; w < SD_ANC_WORDS; ++w) {
             int hi = j - 32 * w;

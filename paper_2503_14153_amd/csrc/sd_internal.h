@@ -43,8 +43,8 @@ static __device__ inline void split_hilo(const float (&f)[8], bf16x8& hi, bf16x8
 }
 #endif
 
-#define SD_MAX_TREE 128
-#define SD_ANC_WORDS 4
+#define SD_MAX_TREE 256
+#define SD_ANC_WORDS 8
 
 // element index of (row m, col k) in part 0 of a packed activation; part 1 is XPART further
 #define XPART 512

@@ -196,6 +196,25 @@ def test_13b_shape_128_node_tree(sd):
     print(f"\n[13b L2] {rep}")
 
 
+def test_ten_heads_256_node_tree(sd):
+    """The paper's ten draft heads (Section IV-A) with the largest tree the library takes: 256 nodes = eight
+    row blocks (two GEMM passes, four query groups in attention, eight ancestor words per row)."""
+    shape = _shape("7b-h10")
+    rep = _run_batch_steps(sd, shape, 1, 256, [700], 1024, n_steps=2)
+    print(f"\n[7b-h10 L2 T=256] {rep}")
+    assert max(rep.raw) >= 2
+
+
+@pytest.mark.parametrize("T", [129, 160, 200, 256])
+def test_tree_sizes_beyond_128_nodes(sd, T):
+    """Tiny width, six heads: node counts that give 5, 5, 7 and 8 row blocks (odd counts take the one-block
+    attention tile, even ones the two-block tile)."""
+    shape = dataclasses.replace(_shape("tiny"), n_medusa=6)
+    rep = _run_batch_steps(sd, shape, 1, T, [45], 128, n_steps=3)
+    print(f"\n[tiny H=6 T={T}] {rep}")
+    assert max(rep.raw) >= 2
+
+
 @pytest.mark.parametrize("kind", ["root_only", "chain", "ragged33", "full_k3"])
 def test_degenerate_trees(sd, kind):
     shape = _shape("tiny")

@@ -36,7 +36,8 @@ def _paths(parent):
 # ----------------------------------------------------------------------------- verify kernel
 @pytest.mark.parametrize("T,H,k,fallback", [(16, 3, 4, "keep_all"), (64, 4, 10, "keep_all"), (64, 4, 10, "keep_one"),
                                             (128, 5, 10, "keep_all"), (1, 3, 4, "keep_one"), (33, 4, 10, "keep_all"),
-                                            (100, 15, 2, "keep_one")])
+                                            (100, 15, 2, "keep_one"), (129, 10, 10, "keep_all"),
+                                            (256, 10, 10, "keep_all"), (200, 15, 2, "keep_one")])
 def test_verify_kernel_bit_exact(sd, T, H, k, fallback):
     """Acceptance + fragment cut alone, many random cases per launch, bit-exact."""
     rng = np.random.default_rng(T * 131 + H)

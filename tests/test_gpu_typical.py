@@ -39,7 +39,8 @@ def _peaked_logits(rng, rows, V, scales):
 # ----------------------------------------------------------------------------- single stages
 @pytest.mark.parametrize("T,H,k,V,batch,fallback", [(16, 3, 4, 50, 256, "keep_all"), (64, 4, 10, 1000, 64, "keep_one"),
                                                     (64, 4, 10, 32000, 4, "keep_all"), (33, 4, 10, 32001, 3, "keep_all"),
-                                                    (1, 3, 4, 50, 8, "keep_all"), (128, 5, 10, 5000, 8, "keep_all")])
+                                                    (1, 3, 4, 50, 8, "keep_all"), (128, 5, 10, 5000, 8, "keep_all"),
+                                                    (256, 10, 10, 2000, 16, "keep_all")])
 def test_typical_verify_kernel(sd, T, H, k, V, batch, fallback):
     """Row statistics + typical acceptance + cut alone on synthetic logits, many cases per launch."""
     rng = np.random.default_rng(T * 977 + V)

@@ -1,4 +1,4 @@
-"""Named workload presets: the five benchmark configurations plus reduced-depth test cuts.
+"""Named workload presets: the five benchmark configurations, a ten-head variant, and reduced-depth test cuts.
 
 Shapes follow a Llama-style decoder-only model (the paper's CodeLlama-7b base, Section
 III-B / IV-A) with Medusa-style draft heads on the last hidden state. The paper fixes none
@@ -42,6 +42,7 @@ class Workload:
 _TINY = ModelShape(2, 256, 4, 64, 688, 1024, 3, 4, "f32", 1e4)
 _7B = ModelShape(32, 4096, 32, 128, 11008, 32016, 4, 10, "bf16", 1e6)
 _13B = ModelShape(40, 5120, 40, 128, 13824, 32016, 5, 10, "bf16", 1e6)
+_7B_H10 = ModelShape(32, 4096, 32, 128, 11008, 32016, 10, 10, "bf16", 1e6)     # the paper's ten heads (Section IV-A)
 
 PRESETS = {
     # configs[0]: the small case the oracle finishes in seconds
@@ -54,6 +55,8 @@ PRESETS = {
     "7b-batch8": Workload("7b-batch8", _7B, 32, 8, 0, 64, 4096 + 64 * 5),
     # configs[4]
     "13b": Workload("13b", _13B, 128, 1, 4096, 128, 4096 + 128 * 6),
+    # beyond the five benchmark configurations: ten draft heads and the largest tree the library takes
+    "7b-h10": Workload("7b-h10", _7B_H10, 256, 1, 512, 128, 2048),
 }
 
 
