@@ -45,8 +45,9 @@ void launch_pack_weight(const void* src, void* dst, int N, int K, int nb_offset,
 }
 
 // ------------------------------------------------------------------------------------------
-// Balanced streaming ("stream-K") over MT = 1, 2 or 4 row blocks of 32 rows; more rows are done
-// in passes of four row blocks (the weights are then streamed once per pass).
+// Balanced streaming ("stream-K") over MT = 1 or 2 row blocks of 32 rows (this kernel) or four (the
+// kernel after it); more rows are done in passes of four row blocks (the weights are then streamed
+// once per pass).
 //
 // The work of one GEMM is the list of units (column group of 256 outputs, contraction block),
 // contraction block fastest; workgroup g of G takes the contiguous range [g*U/G, (g+1)*U/G),
@@ -68,12 +69,14 @@ void launch_pack_weight(const void* src, void* dst, int N, int K, int nb_offset,
 // parked in registers until the chunk before them has been consumed.
 struct SkIter { int kb, ng, valid, last; };
 
-// PASSES: the activation holds more row blocks than this launch multiplies (x_kb_units > MT*2*64)
+// PASSES: the activation holds more row blocks than this launch multiplies (x_kb_units > MT*2*64);
+// only the four-row-block kernel is launched that way
 template <int MT, bool PASSES>
 __global__ __launch_bounds__(512, 2) void k_gemm_sk(const bf16x8* __restrict__ Xp, const bf16x8* __restrict__ Wp,
                                                     const bf16x8* __restrict__ zfrag, float* __restrict__ out,
                                                     int KB, int NB, int NG, int ldo, size_t slot_stride, int x_kb_units) {
-    constexpr int R = MT >= 4 ? 8 : 16;              // ring depth: with four row blocks the accumulators need the registers
+    static_assert(MT == 1 || MT == 2, "four row blocks: k_gemm_sk_wide");
+    constexpr int R = 16;                            // ring depth
     constexpr int XK = 8 / MT;                       // contraction blocks per chunk
     constexpr int CPI = R / XK;                      // chunks per outer iteration (2 or 4)
     constexpr int XF = 16;                           // fragments per chunk = XK * MT * 2
@@ -214,6 +217,179 @@ __global__ __launch_bounds__(512, 2) void k_gemm_sk(const bf16x8* __restrict__ X
 }
 
 // ------------------------------------------------------------------------------------------
+// Four row blocks (128 rows per pass). The kernel above, instantiated for four row blocks, needs
+// more registers than two waves per SIMD can have (it spills) and issues eight LDS fragment reads
+// and eight MFMAs, in dependent pairs, per weight fragment: it is bound by those, not by HBM.
+// Here a workgroup is four waves, one per SIMD, so that a wave may hold up to 512 registers; wave
+// w owns column blocks 2w and 2w+1 of the same 256-column group, every activation fragment read
+// from LDS feeds two weight fragments (half the LDS traffic per weight byte), and the four MFMAs
+// of a row block alternate between its two accumulators, so that none waits for the one before
+// it. Units, ring, segments, zero page and slots exactly as above.
+#define SKW_THREADS 256
+#ifndef SKW_R
+#define SKW_R 8
+#endif
+template <bool PASSES>
+__global__ __launch_bounds__(SKW_THREADS, 1) void k_gemm_sk_wide(const bf16x8* __restrict__ Xp,
+                                                                 const bf16x8* __restrict__ Wp,
+                                                                 const bf16x8* __restrict__ zfrag,
+                                                                 float* __restrict__ out, int KB, int NB, int NG, int ldo,
+                                                                 size_t slot_stride, int x_kb_units) {
+    constexpr int MT = 4, CB = 2, R = SKW_R, XK = 2, CPI = R / XK, XF = XK * MT * 2, XP = XF * 64 / SKW_THREADS;
+    __shared__ bf16x8 xs[2][XF * 64];
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int G = gridDim.x, g = blockIdx.x;
+    const int U = NG * KB;
+    auto ustart = [&](int gg) { return (int)(((long long)gg * U) / G); };
+    const int u0 = ustart(g), u1 = ustart(g + 1);
+    auto iter_info = [&](int k) {
+        SkIter r = {0, 0, 0, 0};
+        int u = u0;
+        while (u < u1) {
+            const int ng = u / KB, kb = u - ng * KB;
+            int send = (ng + 1) * KB;
+            if (send > u1) send = u1;
+            const int len = send - u, nit = (len + R - 1) / R;
+            if (k < nit) {
+                r.kb = kb + k * R;
+                r.ng = ng;
+                r.valid = len - k * R < R ? len - k * R : R;
+                r.last = (k == nit - 1);
+                return r;
+            }
+            k -= nit;
+            u = send;
+        }
+        return r;
+    };
+    // the wave's two fragments of a contraction block lie side by side (2 KiB)
+    auto wptr = [&](const SkIter& I, int cb) {
+        int nb = I.ng * 8 + wave * CB + cb;
+        if (nb >= NB) nb = NB - 1;
+        return Wp + ((size_t)I.kb * NB + nb) * 64 + lane;
+    };
+    const size_t wstep = (size_t)NB * 64;
+    const bf16x8* zl = zfrag + lane;
+    auto xload = [&](bf16x8(&dst)[XP], const SkIter& I, int c) {
+        int steps = I.valid - c * XK;
+        steps = steps < 0 ? 0 : (steps > XK ? XK : steps);
+        constexpr int PER_KB = MT * 2 * 64;
+        const int limit = steps * PER_KB;
+        const int kb_units = PASSES ? x_kb_units : PER_KB;
+        const bf16x8* base = Xp + (size_t)(I.kb + c * XK) * kb_units;
+#pragma unroll
+        for (int p = 0; p < XP; ++p) {
+            const int i = p * SKW_THREADS + tid;
+            const bf16x8* src = PASSES ? base + (size_t)(i / PER_KB) * kb_units + (i % PER_KB) : base + i;
+            dst[p] = *((i < limit) ? src : zl);
+        }
+    };
+    auto xstore = [&](const bf16x8(&src)[XP], int buf) {
+#pragma unroll
+        for (int p = 0; p < XP; ++p) xs[buf][p * SKW_THREADS + tid] = src[p];
+    };
+
+    SkIter cur = iter_info(0), nxt = iter_info(1), nx2 = iter_info(2);
+    if (cur.valid == 0) return;
+
+    f32x16 acc[MT][CB];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][cb][v] = 0.f;
+
+    bf16x8 w[R][CB], xr[CPI][XP];
+#pragma unroll
+    for (int c = 0; c < CPI; ++c) xload(xr[c], cur, c);
+    {
+        const bf16x8* wc[CB];
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) wc[cb] = wptr(cur, cb);
+#pragma unroll
+        for (int i = 0; i < R; ++i)
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+                w[i][cb] = __builtin_nontemporal_load((i < cur.valid) ? wc[cb] + (size_t)i * wstep : zl);
+    }
+    xstore(xr[0], 0);
+    xload(xr[0], nxt, 0);
+    __syncthreads();
+
+    for (int k = 0;; ++k) {
+        const bf16x8* wn[CB];
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) wn[cb] = wptr(nxt, cb);
+#pragma unroll
+        for (int c = 0; c < CPI; ++c) {
+            // The activation fragments are read from LDS one (hi, lo) pair ahead of the MFMAs
+            // that use them: with one wave per SIMD nothing else hides the LDS latency.
+            bf16x8 ph[2], pl[2];
+            ph[0] = xs[c & 1][lane];
+            pl[0] = xs[c & 1][64 + lane];
+#pragma unroll
+            for (int q = 0; q < XK * MT; ++q) {
+                const int j = q / MT, mt = q % MT;
+                const int i = c * XK + j;                         // ring slot (compile-time)
+                if (q + 1 < XK * MT) {
+                    ph[(q + 1) & 1] = xs[c & 1][((q + 1) * 2) * 64 + lane];
+                    pl[(q + 1) & 1] = xs[c & 1][((q + 1) * 2 + 1) * 64 + lane];
+                }
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+                    acc[mt][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph[q & 1], w[i][cb], acc[mt][cb], 0, 0, 0);
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+                    acc[mt][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pl[q & 1], w[i][cb], acc[mt][cb], 0, 0, 0);
+                if (mt == MT - 1) {
+#pragma unroll
+                    for (int cb = 0; cb < CB; ++cb)
+                        w[i][cb] = __builtin_nontemporal_load((i < nxt.valid) ? wn[cb] + (size_t)i * wstep : zl);
+                }
+            }
+            const int nc = (c + 1) % CPI;
+            xstore(xr[nc], (c + 1) & 1);
+            if (c + 1 < CPI) xload(xr[nc], nxt, c + 1);
+            else xload(xr[nc], nx2, 0);
+            __syncthreads();
+        }
+        if (cur.last) {
+            const int first_unit = cur.ng * KB;
+            int gf = (int)(((long long)first_unit * G) / U);
+            while (gf + 1 < G && ustart(gf + 1) <= first_unit) ++gf;
+            while (gf > 0 && ustart(gf) > first_unit) --gf;
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) {
+                const int nb = cur.ng * 8 + wave * CB + cb;
+                if (nb < NB) {
+                    float* o = out + (size_t)(g - gf) * slot_stride + (size_t)nb * 32 + (lane & 31);
+                    const int gq = lane >> 5;
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            int m = mt * 32 + 8 * (v >> 2) + 4 * gq + (v & 3);
+                            o[(size_t)m * ldo] = acc[mt][cb][v];
+                        }
+                }
+            }
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[mt][cb][v] = 0.f;
+        }
+        if (nxt.valid == 0) break;
+        cur = nxt;
+        nxt = nx2;
+        nx2 = iter_info(k + 3);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // dst[m][c] = sum of the slots of column c (used where the consumer wants dense rows: logits)
 __global__ void k_reduce_slots(PartView pv, float* __restrict__ dst, int rows) {
     const int c4 = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
@@ -293,10 +469,18 @@ PartView launch_gemm(const GemmPlan& p, const void* Xp, const void* Wp, const vo
             else                                                                                           \
                 hipLaunchKernelGGL((k_gemm_sk<MT_, PASSES_>), dim3(p.G), dim3(512), 0, s, SK_ARGS);        \
         } while (0)
+#define SK_LAUNCH_WIDE(PASSES_)                                                                             \
+        do {                                                                                               \
+            if (e0 || e1)                                                                                  \
+                hipExtLaunchKernelGGL((k_gemm_sk_wide<PASSES_>), dim3(p.G), dim3(SKW_THREADS), 0, s, e0, e1, 0, SK_ARGS); \
+            else                                                                                           \
+                hipLaunchKernelGGL((k_gemm_sk_wide<PASSES_>), dim3(p.G), dim3(SKW_THREADS), 0, s, SK_ARGS); \
+        } while (0)
         if (MT == 1) SK_LAUNCH(1, false);
         else if (MT == 2) SK_LAUNCH(2, false);
-        else if (p.MB == MT) SK_LAUNCH(4, false);
-        else SK_LAUNCH(4, true);
+        else if (p.MB == MT) SK_LAUNCH_WIDE(false);
+        else SK_LAUNCH_WIDE(true);
+#undef SK_LAUNCH_WIDE
 #undef SK_LAUNCH
 #undef SK_ARGS
     }
