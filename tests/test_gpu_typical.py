@@ -212,3 +212,53 @@ def test_7b_width_two_layers_typical_lockstep(sd, temperature):
     print(f"\n[7b-L2 typical T={temperature}] {rep}")
     assert rep.steps == 4
     assert rep.accept_near_ties <= 1 and rep.root_near_ties <= 1
+
+
+def test_typical_step_batch_of_three(sd):
+    """Sampling decoding for three sequences at once (different committed lengths, one uniform number each):
+    every sequence against the oracle's own step, decisions exact on the GPU's logits."""
+    shape = _shape("tiny")
+    B, T, cap, fallback = 3, 16, 192, "keep_all"
+    ty = dict(TY, temperature=0.04)
+    weights = wl.make_weights(shape)
+    w64 = lockstep.weights_to_f64(weights)
+    model = sd.Model(shape, {k: v.cuda() for k, v in weights.items()}, B * 32, fallback)
+    kv = sd.KVCache(model, B, cap)
+    stop = wl.stop_set(shape.vocab, 0.2)
+    words = torch.from_numpy(wl.pack_mask_words(stop).view(np.int32)).cuda()
+    tree_np = wl.default_tree(T, shape.n_medusa, shape.topk)
+    tree = sd.Tree(*tree_np, shape.n_medusa, shape.topk)
+    lens = [40, 17, 64]
+    prompts = [wl.zipf_prompt(shape.vocab, n, seed=100 + b) for b, n in enumerate(lens)]
+    sd.prefill(model, kv, torch.from_numpy(np.concatenate(prompts)).cuda(), lens)
+    states = [orc.prefill(w64, shape, p, cap) for p in prompts]
+    rng = np.random.default_rng(5)
+    plant = _plant_greedy_continuation(w64, shape, (0.9, 0.8, 0.7), np.random.default_rng(6))
+    rep = lockstep.Report()
+    for step in range(6):
+        cand = np.stack([np.asarray(plant(st), np.int32) for st in states])
+        u = rng.random(B).astype(np.float32)
+        n_old = [st.kv.n for st in states]
+        kv.set_draft([st.root_tok for st in states], cand)
+        out = sd.spec_step_typical(model, kv, tree, words, torch.from_numpy(u).cuda(), want_logits=True,
+                                   want_row_stats=True, **ty)
+        recs = [orc.spec_step(w64, shape, st, tree_np, stop, fallback, cand_override=cand[b],
+                              typical=dict(ty, u=float(u[b]))) for b, st in enumerate(states)]
+        torch.cuda.synchronize()
+        lens_now = kv.len()
+        roots, _ = kv.get_draft()
+        for b, rec in enumerate(recs):
+            g_logits = out.logits[b].cpu().numpy().astype(np.float64)
+            lockstep.check_logits(g_logits, rec.logits, rep)
+            lockstep.check_row_stats(out.row_stats[b].cpu().numpy(), g_logits, ty, rep)
+            kept = lockstep.check_typical_decision(int(out.n_accept_raw[b]), int(out.n_accept[b]),
+                                                   out.tokens[b].cpu().numpy(), out.src_slots[b].cpu().numpy(), rec.tok,
+                                                   g_logits, tree_np, stop, fallback, ty, shape.n_medusa, rep)
+            assert lens_now[b] == n_old[b] + len(kept)
+            assert lockstep.check_sampled(int(roots[b]), g_logits[kept[-1]], float(u[b]), ty["temperature"],
+                                          lockstep.FP32_CDF)
+            # this seed has no near-threshold case: the two sides walk the same path
+            assert kept == list(rec.src_slots) and int(roots[b]) == rec.next_root
+            rep.raw.append(int(out.n_accept_raw[b]))
+    print(f"\n[tiny typical batch 3] raw lengths {rep.raw}, max logits error {rep.max_abs:.2e}")
+    assert len(set(rep.raw)) > 1
