@@ -69,12 +69,10 @@ void launch_pack_weight(const void* src, void* dst, int N, int K, int nb_offset,
 // parked in registers until the chunk before them has been consumed.
 struct SkIter { int kb, ng, valid, last; };
 
-// PASSES: the activation holds more row blocks than this launch multiplies (x_kb_units > MT*2*64);
-// only the four-row-block kernel is launched that way
-template <int MT, bool PASSES>
+template <int MT>
 __global__ __launch_bounds__(512, 2) void k_gemm_sk(const bf16x8* __restrict__ Xp, const bf16x8* __restrict__ Wp,
                                                     const bf16x8* __restrict__ zfrag, float* __restrict__ out,
-                                                    int KB, int NB, int NG, int ldo, size_t slot_stride, int x_kb_units) {
+                                                    int KB, int NB, int NG, int ldo, size_t slot_stride) {
     static_assert(MT == 1 || MT == 2, "four row blocks: k_gemm_sk_wide");
     constexpr int R = 16;                            // ring depth
     constexpr int XK = 8 / MT;                       // contraction blocks per chunk
@@ -124,16 +122,13 @@ __global__ __launch_bounds__(512, 2) void k_gemm_sk(const bf16x8* __restrict__ X
     auto xload = [&](bf16x8(&dst)[XP], const SkIter& I, int c) {
         int steps = I.valid - c * XK;
         steps = steps < 0 ? 0 : (steps > XK ? XK : steps);
-        constexpr int PER_KB = MT * 2 * 64;            // 16-byte units of this pass's row blocks per contraction block
+        constexpr int PER_KB = MT * 2 * 64;            // 16-byte units of the row blocks per contraction block
         const int limit = steps * PER_KB;
-        // x_kb_units = units between contraction blocks of the packed activation (all its row blocks)
-        const int kb_units = PASSES ? x_kb_units : PER_KB;
-        const bf16x8* base = Xp + (size_t)(I.kb + c * XK) * kb_units;
+        const bf16x8* base = Xp + (size_t)(I.kb + c * XK) * PER_KB;
 #pragma unroll
         for (int p = 0; p < XP; ++p) {
             const int i = p * 512 + tid;
-            const bf16x8* src = PASSES ? base + (size_t)(i / PER_KB) * kb_units + (i % PER_KB) : base + i;
-            dst[p] = *((i < limit) ? src : zl);
+            dst[p] = *((i < limit) ? base + i : zl);
         }
     };
     auto xstore = [&](const bf16x8(&src)[XP], int buf) {
@@ -225,6 +220,8 @@ __global__ __launch_bounds__(512, 2) void k_gemm_sk(const bf16x8* __restrict__ X
 // from LDS feeds two weight fragments (half the LDS traffic per weight byte), and the four MFMAs
 // of a row block alternate between its two accumulators, so that none waits for the one before
 // it. Units, ring, segments, zero page and slots exactly as above.
+// PASSES: the activation holds more row blocks than one launch multiplies; x_kb_units = 16-byte units
+// between contraction blocks of the packed activation (all its row blocks).
 #define SKW_THREADS 256
 #ifndef SKW_R
 #define SKW_R 8
@@ -461,23 +458,23 @@ PartView launch_gemm(const GemmPlan& p, const void* Xp, const void* Wp, const vo
         const bf16x8* xp = (const bf16x8*)Xp + (size_t)r * MT * 2 * 64;
         float* o = out + (size_t)r * MT * 32 * pv.ld;
         hipEvent_t e0 = r == 0 ? ev0 : nullptr, e1 = r == passes - 1 ? ev1 : nullptr;
-#define SK_ARGS xp, (const bf16x8*)Wp, (const bf16x8*)zfrag, o, p.KB, p.NB, p.NG, pv.ld, pv.slot_stride, x_kb_units
-#define SK_LAUNCH(MT_, PASSES_)                                                                            \
+#define SK_ARGS xp, (const bf16x8*)Wp, (const bf16x8*)zfrag, o, p.KB, p.NB, p.NG, pv.ld, pv.slot_stride
+#define SK_LAUNCH(MT_)                                                                                     \
         do {                                                                                               \
             if (e0 || e1)                                                                                  \
-                hipExtLaunchKernelGGL((k_gemm_sk<MT_, PASSES_>), dim3(p.G), dim3(512), 0, s, e0, e1, 0, SK_ARGS); \
+                hipExtLaunchKernelGGL((k_gemm_sk<MT_>), dim3(p.G), dim3(512), 0, s, e0, e1, 0, SK_ARGS);   \
             else                                                                                           \
-                hipLaunchKernelGGL((k_gemm_sk<MT_, PASSES_>), dim3(p.G), dim3(512), 0, s, SK_ARGS);        \
+                hipLaunchKernelGGL((k_gemm_sk<MT_>), dim3(p.G), dim3(512), 0, s, SK_ARGS);                 \
         } while (0)
 #define SK_LAUNCH_WIDE(PASSES_)                                                                             \
         do {                                                                                               \
             if (e0 || e1)                                                                                  \
-                hipExtLaunchKernelGGL((k_gemm_sk_wide<PASSES_>), dim3(p.G), dim3(SKW_THREADS), 0, s, e0, e1, 0, SK_ARGS); \
+                hipExtLaunchKernelGGL((k_gemm_sk_wide<PASSES_>), dim3(p.G), dim3(SKW_THREADS), 0, s, e0, e1, 0, SK_ARGS, x_kb_units); \
             else                                                                                           \
-                hipLaunchKernelGGL((k_gemm_sk_wide<PASSES_>), dim3(p.G), dim3(SKW_THREADS), 0, s, SK_ARGS); \
+                hipLaunchKernelGGL((k_gemm_sk_wide<PASSES_>), dim3(p.G), dim3(SKW_THREADS), 0, s, SK_ARGS, x_kb_units); \
         } while (0)
-        if (MT == 1) SK_LAUNCH(1, false);
-        else if (MT == 2) SK_LAUNCH(2, false);
+        if (MT == 1) SK_LAUNCH(1);
+        else if (MT == 2) SK_LAUNCH(2);
         else if (p.MB == MT) SK_LAUNCH_WIDE(false);
         else SK_LAUNCH_WIDE(true);
 #undef SK_LAUNCH_WIDE
