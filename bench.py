@@ -204,6 +204,23 @@ def main():
     attn_gbs = a["bytes"] / max(a["ms"], 1e-9) / 1e6
 
     # ---------------------------------------------------------------- CPU oracle on a bounded sample
+    # ---------------------------------------------------------------- sampling: replay check
+    # there is no reference stream under sampling; the self-check is that a replay from the same state with
+    # the same uniform numbers emits the same tokens (run outside the timed region)
+    replay_mismatches = None
+    if args.decoding == "sampling":
+        def sampled_stream(n):
+            reset()
+            toks = []
+            for i in range(n):
+                sd.spec_step_typical(model, kv, tree, stop_words, u_dev[i: i + 1], out=out, **typical)
+                n_acc = int(out.n_accept.cpu()[0])
+                toks.append(out.tokens.cpu()[0, :n_acc].tolist())
+            return toks
+        n_rep = min(32, n_u)
+        first, second = sampled_stream(n_rep), sampled_stream(n_rep)
+        replay_mismatches = sum(a != b for a, b in zip(first, second))
+
     cpu = None
     if cpu_keep is not None:
         cpu = cpu_baseline(wl, shape, cpu_keep, T, tree_np, stop, n_cache=prompt_len,
@@ -225,7 +242,7 @@ def main():
         "greedy_tokens_per_s": n_timed / greedy_s, "speedup_vs_greedy": (emitted / elapsed) / (n_timed / greedy_s),
         "prefill_tokens_per_s": prompt_len / prefill_s,
         "step_hbm_frac": step_bytes / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9),
-        "diverged_resets": state["diverged"], "hip_graphs": args.graph,
+        "diverged_resets": state["diverged"], "sampling_replay_mismatches": replay_mismatches, "hip_graphs": args.graph,
         "roofline": {"kernel": "k_gemm_sk (weight-streaming MFMA GEMM, all projections)", "bound": "hbm",
                      "achieved": gemm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gemm_gbs / HBM_PEAK_GBS,
                      "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH if (args.workload == "7b" and args.layers is None) else None, "avg_launch_us": gemm_avg_us,
