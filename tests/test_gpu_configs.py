@@ -247,3 +247,28 @@ def test_prompt_of_one_token_and_continued_prefill(sd):
     sd.prefill(model, kv, torch.from_numpy(prompt[:1].copy()).cuda(), [1])
     st = orc.prefill(w64, shape, prompt[:1], 16)
     assert kv.len() == [1] and int(kv.get_draft()[0][0]) == st.root_tok
+
+
+@pytest.mark.parametrize("name,prompt_len,max_rows", [("tiny", 300, 128), ("tiny", 129, 96), ("7b", 200, 128)])
+def test_prefill_in_chunks_of_up_to_128_rows(sd, name, prompt_len, max_rows):
+    """Prompt chunks follow the model's max_rows (128 -> 128 + 128 + 44 rows, 96 -> 96 + 33): committed K/V rows and
+    the draft state after the prompt against the oracle's causal forward."""
+    shape = _shape(name, 2)
+    weights = wl.make_weights(shape)
+    w64 = lockstep.weights_to_f64(weights)
+    model = sd.Model(shape, {k: v.cuda() for k, v in weights.items()}, max_rows)
+    cap = prompt_len + 32
+    kv = sd.KVCache(model, 1, cap)
+    prompt = wl.zipf_prompt(shape.vocab, prompt_len)
+    sd.prefill(model, kv, torch.from_numpy(prompt).cuda(), [prompt_len])
+    st = orc.prefill(w64, shape, prompt, cap)
+    assert kv.len() == [prompt_len]
+    rep = lockstep.Report()
+    lockstep.compare_kv_rows(kv, st, shape, 0, prompt_len, rep, 0.08)
+    root, cand = kv.get_draft()
+    assert int(root[0]) == st.root_tok
+    hl = orc.medusa_logits(w64, shape, orc.forward_rows(w64, shape, prompt, np.arange(prompt_len),
+                                                          np.tril(np.ones((prompt_len, prompt_len), bool)),
+                                                          orc.KVCache.empty(shape, cap))[1][-1])
+    lockstep.check_cand(cand[0].cpu().numpy(), np.asarray(st.cand), hl, rep)
+    print(f"\n[{name} prefill {prompt_len} rows, chunks of {max_rows}] K/V max-abs {rep.kv_max_abs:.3g}")
