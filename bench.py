@@ -321,7 +321,7 @@ def cpu_baseline(wl, shape, cpu_keep, T, tree_np, stop, n_cache, typical=None):
         return time.perf_counter() - t0
 
     one_step(1)                                      # warm-up: BLAS threads, page faults
-    reps = 3
+    reps = 9
     t_lo = sorted(one_step(depth_lo) for _ in range(reps))[reps // 2]
     t_hi = sorted(one_step(depth_hi) for _ in range(reps))[reps // 2]
     if depth_hi > depth_lo:
