@@ -224,7 +224,7 @@ __global__ __launch_bounds__(512, 2) void k_gemm_sk(const bf16x8* __restrict__ X
 // between contraction blocks of the packed activation (all its row blocks).
 #define SKW_THREADS 256
 #ifndef SKW_R
-#define SKW_R 8
+#define SKW_R 6
 #endif
 template <bool PASSES>
 __global__ __launch_bounds__(SKW_THREADS, 1) void k_gemm_sk_wide(const bf16x8* __restrict__ Xp,
@@ -233,7 +233,8 @@ __global__ __launch_bounds__(SKW_THREADS, 1) void k_gemm_sk_wide(const bf16x8* _
                                                                  float* __restrict__ out, int KB, int NB, int NG, int ldo,
                                                                  size_t slot_stride, int x_kb_units) {
     constexpr int MT = 4, CB = 2, R = SKW_R, XK = 2, CPI = R / XK, XF = XK * MT * 2, XP = XF * 64 / SKW_THREADS;
-    __shared__ bf16x8 xs[2][XF * 64];
+    static_assert(CPI == 3, "three chunks per ring length, three LDS buffers");
+    __shared__ bf16x8 xs[3][XF * 64];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int G = gridDim.x, g = blockIdx.x;
@@ -311,9 +312,18 @@ __global__ __launch_bounds__(SKW_THREADS, 1) void k_gemm_sk_wide(const bf16x8* _
             for (int cb = 0; cb < CB; ++cb)
                 w[i][cb] = __builtin_nontemporal_load((i < cur.valid) ? wc[cb] + (size_t)i * wstep : zl);
     }
+    // LDS holds three chunks: the one in use and the next two. Chunk t+2 is written at the start of
+    // chunk t (its buffer was last read during chunk t-1, which every wave left through a barrier),
+    // so the first fragments of chunk t+1 can be read before the barrier that ends chunk t, and
+    // neither the LDS writes nor those reads sit on the critical path behind a barrier.
     xstore(xr[0], 0);
+    xstore(xr[1], 1);
     xload(xr[0], nxt, 0);
+    xload(xr[1], nxt, 1);
     __syncthreads();
+    bf16x8 ph[2], pl[2];
+    ph[0] = xs[0][lane];
+    pl[0] = xs[0][64 + lane];
 
     for (int k = 0;; ++k) {
         const bf16x8* wn[CB];
@@ -321,18 +331,23 @@ __global__ __launch_bounds__(SKW_THREADS, 1) void k_gemm_sk_wide(const bf16x8* _
         for (int cb = 0; cb < CB; ++cb) wn[cb] = wptr(nxt, cb);
 #pragma unroll
         for (int c = 0; c < CPI; ++c) {
-            // The activation fragments are read from LDS one (hi, lo) pair ahead of the MFMAs
-            // that use them: with one wave per SIMD nothing else hides the LDS latency.
-            bf16x8 ph[2], pl[2];
-            ph[0] = xs[c & 1][lane];
-            pl[0] = xs[c & 1][64 + lane];
+            // chunk t+2 -> LDS; its staging slot is refilled with the chunk one ring length further on
+            constexpr int XQ = XK * MT;                            // (hi, lo) pairs per chunk, even
+            const int sl = (c + 2) % CPI;
+            xstore(xr[sl], sl);
+            if (c == 0) xload(xr[sl], nxt, 2);
+            else xload(xr[sl], nx2, c - 1);
+            // the pairs are read one ahead of the MFMAs that use them (pair 0 was read before the barrier)
 #pragma unroll
-            for (int q = 0; q < XK * MT; ++q) {
+            for (int q = 0; q < XQ; ++q) {
                 const int j = q / MT, mt = q % MT;
                 const int i = c * XK + j;                         // ring slot (compile-time)
-                if (q + 1 < XK * MT) {
-                    ph[(q + 1) & 1] = xs[c & 1][((q + 1) * 2) * 64 + lane];
-                    pl[(q + 1) & 1] = xs[c & 1][((q + 1) * 2 + 1) * 64 + lane];
+                if (q + 1 < XQ) {
+                    ph[(q + 1) & 1] = xs[c][((q + 1) * 2) * 64 + lane];
+                    pl[(q + 1) & 1] = xs[c][((q + 1) * 2 + 1) * 64 + lane];
+                } else {
+                    ph[0] = xs[(c + 1) % CPI][lane];
+                    pl[0] = xs[(c + 1) % CPI][64 + lane];
                 }
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb)
@@ -346,10 +361,6 @@ __global__ __launch_bounds__(SKW_THREADS, 1) void k_gemm_sk_wide(const bf16x8* _
                         w[i][cb] = __builtin_nontemporal_load((i < nxt.valid) ? wn[cb] + (size_t)i * wstep : zl);
                 }
             }
-            const int nc = (c + 1) % CPI;
-            xstore(xr[nc], (c + 1) & 1);
-            if (c + 1 < CPI) xload(xr[nc], nxt, c + 1);
-            else xload(xr[nc], nx2, 0);
             __syncthreads();
         }
         if (cur.last) {
