@@ -237,10 +237,11 @@ extern "C" int sd_model_create(const sd_config* cfg, const sd_weights* w, int32_
                 for (const GemmPlan& q : m->plans) dup |= q.MB == mb && q.KB == sh[0] && q.NB == sh[1];
                 if (dup) continue;
                 GemmPlan pl;
-                std::vector<int32_t> cnt((sh[1] + 7) / 8 + 1, 0);
-                gemm_plan_make(&pl, mb, sh[0], sh[1], cnt.data());
+                std::vector<int32_t> cnt((sh[1] + 7) / 8 + 1, 0), slot0(256, 0);
+                gemm_plan_make(&pl, mb, sh[0], sh[1], cnt.data(), slot0.data());
                 cnt_off.push_back(cnt_all.size());
                 cnt_all.insert(cnt_all.end(), cnt.begin(), cnt.end());
+                cnt_all.insert(cnt_all.end(), slot0.begin(), slot0.end());
                 m->plans.push_back(pl);
                 pf = std::max(pf, (size_t)pl.slots * (mb * 32) * (size_t)sh[1] * 32);
             }
@@ -272,8 +273,10 @@ extern "C" int sd_model_create(const sd_config* cfg, const sd_weights* w, int32_
         delete m;
         return fail(SD_ERR_HIP, "hipMalloc(%zu) for workspace: %s", wz, hipGetErrorString(e));
     }
-    for (size_t i = 0; i < m->plans.size(); ++i)
+    for (size_t i = 0; i < m->plans.size(); ++i) {
         m->plans[i].cnt_dev = m->plan_cnt + cnt_off[i];
+        m->plans[i].slot0_dev = m->plans[i].cnt_dev + (m->plans[i].NB + 7) / 8 + 1;      // right behind the counts
+    }
     hipMemsetAsync(m->work, 0, wz, s);
     char* Wk = m->work;
     m->x = (float*)(Wk + w_x); m->part = (float*)(Wk + w_part); m->logits = (float*)(Wk + w_logits);

@@ -69,10 +69,40 @@ void launch_pack_weight(const void* src, void* dst, int N, int K, int nb_offset,
 // parked in registers until the chunk before them has been consumed.
 struct SkIter { int kb, ng, valid, last; };
 
+// A workgroup's walk over its unit range [u, u1) in outer iterations of R steps, without any division
+// after the first position: the next iteration starts at (ng, kb), covers min(R, rest of the segment)
+// steps and is the segment's last if the segment ends within it.
+struct SkWalk { int u, u1, ng, kb; };
+static __device__ inline SkWalk sk_walk_init(int g, int upw, int rem, int KB) {
+    SkWalk w;
+    w.u = g * upw + (g < rem ? g : rem);               // workgroup g takes upw units, the first `rem` one more
+    w.u1 = w.u + upw + (g < rem ? 1 : 0);
+    w.ng = w.u / KB;
+    w.kb = w.u - w.ng * KB;
+    return w;
+}
+template <int R>
+static __device__ inline SkIter sk_walk_next(SkWalk& w, int KB) {
+    SkIter r = {0, 0, 0, 0};
+    if (w.u >= w.u1) return r;
+    int send = (w.ng + 1) * KB;
+    if (send > w.u1) send = w.u1;
+    const int len = send - w.u;
+    r.kb = w.kb;
+    r.ng = w.ng;
+    r.valid = len < R ? len : R;
+    r.last = len <= R;
+    w.u += r.valid;
+    w.kb += r.valid;
+    if (w.kb >= KB) { w.kb = 0; ++w.ng; }
+    return r;
+}
+
 template <int MT>
 __global__ __launch_bounds__(512, 2) void k_gemm_sk(const bf16x8* __restrict__ Xp, const bf16x8* __restrict__ Wp,
                                                     const bf16x8* __restrict__ zfrag, float* __restrict__ out,
-                                                    int KB, int NB, int NG, int ldo, size_t slot_stride) {
+                                                    int KB, int NB, int ldo, size_t slot_stride, int upw, int rem,
+                                                    const int32_t* __restrict__ slot0_tab) {
     static_assert(MT == 1 || MT == 2, "four row blocks: k_gemm_sk_wide");
     constexpr int R = 16;                            // ring depth
     constexpr int XK = 8 / MT;                       // contraction blocks per chunk
@@ -82,32 +112,11 @@ __global__ __launch_bounds__(512, 2) void k_gemm_sk(const bf16x8* __restrict__ X
     __shared__ bf16x8 xs[2][XF * 64];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int G = gridDim.x, g = blockIdx.x;
-    const int U = NG * KB;
-    auto ustart = [&](int gg) { return (int)(((long long)gg * U) / G); };
-    const int u0 = ustart(g), u1 = ustart(g + 1);
+    const int g = blockIdx.x;
+    SkWalk walk = sk_walk_init(g, upw, rem, KB);
+    const int slot0 = slot0_tab[g];                    // slot of this workgroup's first segment (later ones: 0)
+    int nseg = 0;
 
-    // k-th outer iteration (R steps) of this workgroup's padded segment list
-    auto iter_info = [&](int k) {
-        SkIter r = {0, 0, 0, 0};
-        int u = u0;
-        while (u < u1) {
-            const int ng = u / KB, kb = u - ng * KB;
-            int send = (ng + 1) * KB;
-            if (send > u1) send = u1;
-            const int len = send - u, nit = (len + R - 1) / R;
-            if (k < nit) {
-                r.kb = kb + k * R;
-                r.ng = ng;
-                r.valid = len - k * R < R ? len - k * R : R;
-                r.last = (k == nit - 1);
-                return r;
-            }
-            k -= nit;
-            u = send;
-        }
-        return r;
-    };
     auto wptr = [&](const SkIter& I) {
         int nb = I.ng * 8 + wave;
         if (nb >= NB) nb = NB - 1;
@@ -136,7 +145,7 @@ __global__ __launch_bounds__(512, 2) void k_gemm_sk(const bf16x8* __restrict__ X
         for (int p = 0; p < XP; ++p) xs[buf][p * 512 + tid] = src[p];
     };
 
-    SkIter cur = iter_info(0), nxt = iter_info(1), nx2 = iter_info(2);
+    SkIter cur = sk_walk_next<R>(walk, KB), nxt = sk_walk_next<R>(walk, KB), nx2 = sk_walk_next<R>(walk, KB);
     if (cur.valid == 0) return;
 
     f32x16 acc[MT];
@@ -157,7 +166,7 @@ __global__ __launch_bounds__(512, 2) void k_gemm_sk(const bf16x8* __restrict__ X
     xload(xr[0], nxt, 0);
     __syncthreads();
 
-    for (int k = 0;; ++k) {
+    for (;;) {
         const bf16x8* wn = wptr(nxt);
 #pragma unroll
         for (int c = 0; c < CPI; ++c) {
@@ -182,14 +191,13 @@ __global__ __launch_bounds__(512, 2) void k_gemm_sk(const bf16x8* __restrict__ X
             __syncthreads();
         }
         if (cur.last) {
-            // slot = ordinal of this workgroup among those whose ranges meet column group cur.ng
-            const int first_unit = cur.ng * KB;
-            int gf = (int)(((long long)first_unit * G) / U);
-            while (gf + 1 < G && ustart(gf + 1) <= first_unit) ++gf;
-            while (gf > 0 && ustart(gf) > first_unit) --gf;
+            // slot = ordinal of this workgroup among those whose ranges meet column group cur.ng: known
+            // from the plan for the first segment; every later segment starts its column group
+            const int slot = nseg == 0 ? slot0 : 0;
+            ++nseg;
             const int nb = cur.ng * 8 + wave;
             if (nb < NB) {
-                float* o = out + (size_t)(g - gf) * slot_stride + (size_t)nb * 32 + (lane & 31);
+                float* o = out + (size_t)slot * slot_stride + (size_t)nb * 32 + (lane & 31);
                 const int gq = lane >> 5;
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
@@ -207,7 +215,7 @@ __global__ __launch_bounds__(512, 2) void k_gemm_sk(const bf16x8* __restrict__ X
         if (nxt.valid == 0) break;
         cur = nxt;
         nxt = nx2;
-        nx2 = iter_info(k + 3);
+        nx2 = sk_walk_next<R>(walk, KB);
     }
 }
 
@@ -230,37 +238,18 @@ template <bool PASSES>
 __global__ __launch_bounds__(SKW_THREADS, 1) void k_gemm_sk_wide(const bf16x8* __restrict__ Xp,
                                                                  const bf16x8* __restrict__ Wp,
                                                                  const bf16x8* __restrict__ zfrag,
-                                                                 float* __restrict__ out, int KB, int NB, int NG, int ldo,
-                                                                 size_t slot_stride, int x_kb_units) {
+                                                                 float* __restrict__ out, int KB, int NB, int ldo,
+                                                                 size_t slot_stride, int upw, int rem,
+                                                                 const int32_t* __restrict__ slot0_tab, int x_kb_units) {
     constexpr int MT = 4, CB = 2, R = SKW_R, XK = 2, CPI = R / XK, XF = XK * MT * 2, XP = XF * 64 / SKW_THREADS;
     static_assert(CPI == 3, "three chunks per ring length, three LDS buffers");
     __shared__ bf16x8 xs[3][XF * 64];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int G = gridDim.x, g = blockIdx.x;
-    const int U = NG * KB;
-    auto ustart = [&](int gg) { return (int)(((long long)gg * U) / G); };
-    const int u0 = ustart(g), u1 = ustart(g + 1);
-    auto iter_info = [&](int k) {
-        SkIter r = {0, 0, 0, 0};
-        int u = u0;
-        while (u < u1) {
-            const int ng = u / KB, kb = u - ng * KB;
-            int send = (ng + 1) * KB;
-            if (send > u1) send = u1;
-            const int len = send - u, nit = (len + R - 1) / R;
-            if (k < nit) {
-                r.kb = kb + k * R;
-                r.ng = ng;
-                r.valid = len - k * R < R ? len - k * R : R;
-                r.last = (k == nit - 1);
-                return r;
-            }
-            k -= nit;
-            u = send;
-        }
-        return r;
-    };
+    const int g = blockIdx.x;
+    SkWalk walk = sk_walk_init(g, upw, rem, KB);
+    const int slot0 = slot0_tab[g];                    // slot of this workgroup's first segment (later ones: 0)
+    int nseg = 0;
     // the wave's two fragments of a contraction block lie side by side (2 KiB)
     auto wptr = [&](const SkIter& I, int cb) {
         int nb = I.ng * 8 + wave * CB + cb;
@@ -288,7 +277,7 @@ __global__ __launch_bounds__(SKW_THREADS, 1) void k_gemm_sk_wide(const bf16x8* _
         for (int p = 0; p < XP; ++p) xs[buf][p * SKW_THREADS + tid] = src[p];
     };
 
-    SkIter cur = iter_info(0), nxt = iter_info(1), nx2 = iter_info(2);
+    SkIter cur = sk_walk_next<R>(walk, KB), nxt = sk_walk_next<R>(walk, KB), nx2 = sk_walk_next<R>(walk, KB);
     if (cur.valid == 0) return;
 
     f32x16 acc[MT][CB];
@@ -325,7 +314,7 @@ __global__ __launch_bounds__(SKW_THREADS, 1) void k_gemm_sk_wide(const bf16x8* _
     ph[0] = xs[0][lane];
     pl[0] = xs[0][64 + lane];
 
-    for (int k = 0;; ++k) {
+    for (;;) {
         const bf16x8* wn[CB];
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) wn[cb] = wptr(nxt, cb);
@@ -364,15 +353,13 @@ __global__ __launch_bounds__(SKW_THREADS, 1) void k_gemm_sk_wide(const bf16x8* _
             __syncthreads();
         }
         if (cur.last) {
-            const int first_unit = cur.ng * KB;
-            int gf = (int)(((long long)first_unit * G) / U);
-            while (gf + 1 < G && ustart(gf + 1) <= first_unit) ++gf;
-            while (gf > 0 && ustart(gf) > first_unit) --gf;
+            const int slot = nseg == 0 ? slot0 : 0;
+            ++nseg;
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb) {
                 const int nb = cur.ng * 8 + wave * CB + cb;
                 if (nb < NB) {
-                    float* o = out + (size_t)(g - gf) * slot_stride + (size_t)nb * 32 + (lane & 31);
+                    float* o = out + (size_t)slot * slot_stride + (size_t)nb * 32 + (lane & 31);
                     const int gq = lane >> 5;
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt)
@@ -393,7 +380,7 @@ __global__ __launch_bounds__(SKW_THREADS, 1) void k_gemm_sk_wide(const bf16x8* _
         if (nxt.valid == 0) break;
         cur = nxt;
         nxt = nx2;
-        nx2 = iter_info(k + 3);
+        nx2 = sk_walk_next<R>(walk, KB);
     }
 }
 
@@ -422,9 +409,10 @@ void launch_reduce_slots(PartView pv, float* dst, int rows, hipStream_t s) {
 #define SK_SMALL_U (16 * SK_MAX_WG * 2)   // (column groups x contraction blocks) up to which half the workgroups are used
 #endif
 
-void gemm_plan_make(GemmPlan* p, int MB, int KB, int NB, int32_t* cnt_host) {
+void gemm_plan_make(GemmPlan* p, int MB, int KB, int NB, int32_t* cnt_host, int32_t* slot0_host) {
     p->MB = MB; p->KB = KB; p->NB = NB;
     p->cnt_dev = nullptr;
+    p->slot0_dev = nullptr;
     p->NG = (NB + 7) / 8;
     const int U = p->NG * KB;
     int G = U / 16;                                   // at least one ring length of steps each
@@ -435,19 +423,18 @@ void gemm_plan_make(GemmPlan* p, int MB, int KB, int NB, int32_t* cnt_host) {
     if (G == SK_MAX_WG && U <= SK_SMALL_U) G = SK_MAX_WG / 2;
     if (G < 1) G = 1;
     p->G = G;
-    auto ustart = [&](int gg) { return (int)(((long long)gg * U) / G); };
-    int slots = 1;
-    for (int ng = 0; ng < p->NG; ++ng) {
-        int first = ng * KB, last = (ng + 1) * KB - 1;
-        int gf = (int)(((long long)first * G) / U);
-        while (gf + 1 < G && ustart(gf + 1) <= first) ++gf;
-        while (gf > 0 && ustart(gf) > first) --gf;
-        int gl = (int)(((long long)last * G) / U);
-        while (gl + 1 < G && ustart(gl + 1) <= last) ++gl;
-        while (gl > 0 && ustart(gl) > last) --gl;
-        cnt_host[ng] = gl - gf + 1;
-        if (cnt_host[ng] > slots) slots = cnt_host[ng];
+    // workgroup g takes upw units, the first `rem` workgroups one more (the kernels compute the same)
+    p->upw = U / G;
+    p->rem = U % G;
+    for (int ng = 0; ng < p->NG; ++ng) cnt_host[ng] = 0;
+    for (int g = 0; g < G; ++g) {
+        const int u0 = g * p->upw + (g < p->rem ? g : p->rem), u1 = u0 + p->upw + (g < p->rem ? 1 : 0);
+        const int ng0 = u0 / KB, ng1 = (u1 - 1) / KB;
+        slot0_host[g] = cnt_host[ng0];                // contributors of its first column group before it
+        for (int ng = ng0; ng <= ng1; ++ng) ++cnt_host[ng];
     }
+    int slots = 1;
+    for (int ng = 0; ng < p->NG; ++ng) slots = cnt_host[ng] > slots ? cnt_host[ng] : slots;
     p->slots = slots;
     p->uniform = 1;                                   // every column group has the same number of contributors?
     for (int ng = 0; ng < p->NG; ++ng) p->uniform &= (cnt_host[ng] == slots);
@@ -469,7 +456,7 @@ PartView launch_gemm(const GemmPlan& p, const void* Xp, const void* Wp, const vo
         const bf16x8* xp = (const bf16x8*)Xp + (size_t)r * MT * 2 * 64;
         float* o = out + (size_t)r * MT * 32 * pv.ld;
         hipEvent_t e0 = r == 0 ? ev0 : nullptr, e1 = r == passes - 1 ? ev1 : nullptr;
-#define SK_ARGS xp, (const bf16x8*)Wp, (const bf16x8*)zfrag, o, p.KB, p.NB, p.NG, pv.ld, pv.slot_stride
+#define SK_ARGS xp, (const bf16x8*)Wp, (const bf16x8*)zfrag, o, p.KB, p.NB, pv.ld, pv.slot_stride, p.upw, p.rem, p.slot0_dev
 #define SK_LAUNCH(MT_)                                                                                     \
         do {                                                                                               \
             if (e0 || e1)                                                                                  \

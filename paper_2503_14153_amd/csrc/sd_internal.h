@@ -94,9 +94,11 @@ static __device__ inline int part_count(const PartView& p, int col) { return p.c
 struct GemmPlan {
     int MB, KB, NB;
     int G, NG;               // workgroups, 256-column groups
+    int upw, rem;            // units per workgroup; the first `rem` workgroups take one more
     int slots;               // slots the output buffer must hold
     int uniform;             // 1: every column group has exactly `slots` contributors
     int32_t* cnt_dev;        // [NG] contributors per column group (device)
+    int32_t* slot0_dev;      // [G] slot of every workgroup's first segment (device)
 };
 
 #define SD_MAX_BATCH 32
@@ -121,7 +123,8 @@ struct VerifyArgs {
 // All take a stream; all sizes have been validated by the caller.
 void launch_pack_weight(const void* src, void* dst, int N, int K, int nb_offset, int NBdst, int KB, hipStream_t s);
 // fills every field of the plan except cnt_dev; cnt_host receives the per-group counts
-void gemm_plan_make(GemmPlan* p, int MB, int KB, int NB, int32_t* cnt_host /*[>= ceil(NB/8)]*/);
+// cnt_host [>= ceil(NB/8)] and slot0_host [>= 256] receive the tables the device copies hold
+void gemm_plan_make(GemmPlan* p, int MB, int KB, int NB, int32_t* cnt_host, int32_t* slot0_host);
 // out must hold plan.slots * (MB*32) * (NB*32) floats; zfrag: 1 KiB of zeros (device);
 // returns the view consumers read
 // ev0 / ev1 (both or neither): events that receive the kernel's own start and end time stamps
