@@ -597,7 +597,7 @@ static PartView run_layers(sd_model* m, sd_kv* kv, int B, int Tp, int n_hi, hipS
     const sd_config& c = m->cfg;
     const int M = B * Tp, MB = pow2_blocks(M), d = c.d_model, nh = c.n_heads, hd = c.head_dim, TB = Tp / 32;
     const AttnGeom ag = attn_geometry(m, B, Tp, n_hi);
-    PartView prev = {nullptr, 0, d, nullptr, 256, 0};
+    PartView prev = {nullptr, 0, d, nullptr, 0};
     const size_t t_stride = (size_t)B * nh * TB * 32 * hd;     // elements per layer of tree scratch
     for (int l = 0; l < c.n_layers; ++l) {
         const LayerW& lw = m->layers[l];
@@ -635,7 +635,7 @@ static void run_lm_head(sd_model* m, PartView prev, int B, int T, int Tp, hipStr
 static void run_draft_heads(sd_model* m, sd_kv* kv, int B, uint32_t seq_mask, float* head_logits_out, hipStream_t s) {
     const sd_config& c = m->cfg;
     const int d = c.d_model, H = c.n_medusa;
-    const PartView none = {nullptr, 0, d, nullptr, 256, 0};
+    const PartView none = {nullptr, 0, d, nullptr, 0};
     launch_norm_pack(m->x, none, m->final_norm, c.rms_eps, m->xn, m->h_rows, B, d, 1, kv->last_row, s);
     PartView pm = run_gemm(m, m->xn, m->medusa_w, m->part, 1, m->KBd, m->NBmed, H * d, s);
     const int MBh = pow2_blocks(H * B);

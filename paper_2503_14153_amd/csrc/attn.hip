@@ -359,20 +359,17 @@ void launch_tree_attn(const void* q_packed, const void* kc, const void* vc, cons
 
 // ------------------------------------------------------------------------------------------
 // Merge the split-KV partials and emit the packed bf16 operand of the O-projection.
-// one thread per (seq, head, query t, 8 consecutive output dims); the parts are read in batches
+// one thread per (seq, head, query t, 8 consecutive output dims), grid (chunks of t x dims, head, seq);
+// the parts are read in batches
 // of eight whose loads are all issued before any is used (a part index past the end re-reads
 // the last part with weight zero, so no load sits behind a branch)
 __global__ void k_attn_merge(const float* __restrict__ opart, const float2* __restrict__ mlpart,
-                             bf16x8* __restrict__ xp, int B, int nh, int hd, int Tp, int nparts, int MB) {
+                             bf16x8* __restrict__ xp, int nh, int hd, int e8_shift, int Tp, int nparts, int MB) {
     constexpr int PB = 8;
-    int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    int e8n = hd / 8;
-    int total = B * nh * Tp * e8n;
-    if (idx >= total) return;
-    int e8 = idx % e8n;
-    int t = (idx / e8n) % Tp;
-    int h = (idx / (e8n * Tp)) % nh;
-    int b = idx / (e8n * Tp * nh);
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;      // hd / 8 = 1 << e8_shift pieces per query row
+    const int e8 = idx & ((1 << e8_shift) - 1), t = idx >> e8_shift;
+    if (t >= Tp) return;
+    const int h = blockIdx.y, b = blockIdx.z;
     size_t base = ((size_t)b * nh + h) * nparts;
     float M = NEG_INF, den = 0.f, o[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     for (int p0 = 0; p0 < nparts; p0 += PB) {
@@ -417,7 +414,7 @@ __global__ void k_attn_merge(const float* __restrict__ opart, const float2* __re
 
 void launch_attn_merge(const float* opart, const float2* mlpart, void* x_packed, int B, int nh, int hd, int Tp,
                        int nparts, int MB, hipStream_t s) {
-    int total = B * nh * Tp * (hd / 8);
-    hipLaunchKernelGGL(k_attn_merge, dim3((total + 255) / 256), dim3(256), 0, s, opart, mlpart, (bf16x8*)x_packed,
-                       B, nh, hd, Tp, nparts, MB);
+    const int e8_shift = hd == 128 ? 4 : 3;            // head_dim is 128 or 64
+    hipLaunchKernelGGL(k_attn_merge, dim3((Tp * (hd / 8) + 255) / 256, nh, B), dim3(256), 0, s, opart, mlpart,
+                       (bf16x8*)x_packed, nh, hd, e8_shift, Tp, nparts, MB);
 }

@@ -446,7 +446,6 @@ PartView launch_gemm(const GemmPlan& p, const void* Xp, const void* Wp, const vo
     pv.base = out;
     pv.ld = p.NB * 32;
     pv.slot_stride = (size_t)p.MB * 32 * pv.ld;
-    pv.group_cols = 256;
     pv.cnt = p.uniform ? nullptr : p.cnt_dev;         // NULL: nmax slots everywhere, the consumer need not look it up
     pv.nmax = p.slots;
     const int MT = p.MB < SK_MAX_MT ? p.MB : SK_MAX_MT;

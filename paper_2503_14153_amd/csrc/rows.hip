@@ -167,13 +167,15 @@ void launch_norm_pack(float* x, PartView pv, const void* gain, float eps, void* 
 // Sum the QKV partials, rotate q and k to the row's position, and write q (fragment order,
 // two-term expansion), k and v (tree scratch, block layouts, bf16). Thread (m, h, a, which)
 // owns dims [8a, 8a+8) and their rotary partners [hd/2 + 8a, +8) of q (which=0), k (1) or v (2).
-__global__ void k_rope_kv(PartView pv, RowTable rt, bf16x8* __restrict__ qp, uint16_t* __restrict__ kt, uint16_t* __restrict__ vt, int B, int Tp,
-                          int nh, int hd) {
-    const int na = hd / 16;
-    int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= B * Tp * nh * na * 3) return;
-    const int a = idx % na, h = (idx / na) % nh, which = (idx / (na * nh)) % 3, m = idx / (na * nh * 3);
-    const int b = m / Tp, t = m % Tp, d = nh * hd, half = hd / 2;
+// grid (chunks of (h, a) x which, t, b): no index needs a division.
+__global__ void k_rope_kv(PartView pv, RowTable rt, bf16x8* __restrict__ qp, uint16_t* __restrict__ kt, uint16_t* __restrict__ vt, int Tp,
+                          int nh, int hd, int na_shift) {
+    const int which = blockIdx.x % 3;                   // a constant divisor: a multiplication
+    const int ha = (blockIdx.x / 3) * blockDim.x + threadIdx.x;
+    const int a = ha & ((1 << na_shift) - 1), h = ha >> na_shift;      // hd / 16 = 1 << na_shift
+    if (h >= nh) return;
+    const int t = blockIdx.y, b = blockIdx.z, m = b * Tp + t;
+    const int d = nh * hd, half = hd / 2;
     float4 s0 = make_float4(0, 0, 0, 0), s1 = s0, s2 = s0, s3 = s0;       // dims 8a..8a+7, half+8a..+7
     const int col0 = which * d + h * hd + a * 8;
     const float* p0 = pv.base + (size_t)m * pv.ld + col0;
@@ -227,18 +229,17 @@ __global__ void k_rope_kv(PartView pv, RowTable rt, bf16x8* __restrict__ qp, uin
 
 void launch_rope_kv(PartView pv, RowTable rt, void* q_packed, void* kt, void* vt, int B, int Tp, int nh, int hd,
                     hipStream_t s) {
-    int total = B * Tp * nh * (hd / 16) * 3;
-    hipLaunchKernelGGL(k_rope_kv, dim3((total + 255) / 256), dim3(256), 0, s, pv, rt,
-                       (bf16x8*)q_packed, (uint16_t*)kt, (uint16_t*)vt, B, Tp, nh, hd);
+    const int na_shift = hd == 128 ? 3 : 2;            // head_dim is 128 or 64
+    hipLaunchKernelGGL(k_rope_kv, dim3(((nh << na_shift) + 255) / 256 * 3, Tp, B), dim3(256), 0, s, pv, rt,
+                       (bf16x8*)q_packed, (uint16_t*)kt, (uint16_t*)vt, Tp, nh, hd, na_shift);
 }
 
 // ------------------------------------------------------------------------------------------
 // act = silu(gate) * up from the gate/up partials (gate in columns [0,F), up in [Fpad, Fpad+F)).
-__global__ void k_swiglu_pack(PartView pv, int F, int Fpad, bf16x8* __restrict__ act, int M, int MB) {
-    int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    int ng = F / 8;
-    if (idx >= M * ng) return;
-    int grp = idx % ng, m = idx / ng;
+// grid (chunks of 8-column groups, row)
+__global__ void k_swiglu_pack(PartView pv, int F, int Fpad, bf16x8* __restrict__ act, int MB) {
+    const int grp = blockIdx.x * blockDim.x + threadIdx.x, m = blockIdx.y;
+    if (grp >= F / 8) return;
     float gsum[8] = {0, 0, 0, 0, 0, 0, 0, 0}, usum[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     const int ng_ = part_count(pv, grp * 8), nu_ = part_count(pv, Fpad + grp * 8);
     for (int sp = 0; sp < ng_; ++sp) {
@@ -264,8 +265,7 @@ __global__ void k_swiglu_pack(PartView pv, int F, int Fpad, bf16x8* __restrict__
 }
 
 void launch_swiglu_pack(PartView pv, int F, int Fpad, void* act_packed, int M, int MB, hipStream_t s) {
-    int total = M * (F / 8);
-    hipLaunchKernelGGL(k_swiglu_pack, dim3((total + 255) / 256), dim3(256), 0, s, pv, F, Fpad, (bf16x8*)act_packed, M,
+    hipLaunchKernelGGL(k_swiglu_pack, dim3((F / 8 + 255) / 256, M), dim3(256), 0, s, pv, F, Fpad, (bf16x8*)act_packed,
                        MB);
 }
 

@@ -82,12 +82,11 @@ struct PartView {
     const float* base;
     size_t slot_stride;      // floats between slots
     int ld;                  // floats between rows
-    const int32_t* cnt;      // [ceil(ld / group_cols)] slots per column group, or NULL
-    int group_cols;
+    const int32_t* cnt;      // [ceil(ld / 256)] slots per 256-column group, or NULL
     int nmax;
 };
 #ifdef __HIPCC__
-static __device__ inline int part_count(const PartView& p, int col) { return p.cnt ? p.cnt[col / p.group_cols] : p.nmax; }
+static __device__ inline int part_count(const PartView& p, int col) { return p.cnt ? p.cnt[col >> 8] : p.nmax; }
 #endif
 
 // How one GEMM shape is launched (made once per shape at model creation).
