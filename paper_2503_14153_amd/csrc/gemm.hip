@@ -73,11 +73,12 @@ struct SkIter { int kb, ng, valid, last; };
 // after the first position: the next iteration starts at (ng, kb), covers min(R, rest of the segment)
 // steps and is the segment's last if the segment ends within it.
 struct SkWalk { int u, u1, ng, kb; };
-static __device__ inline SkWalk sk_walk_init(int g, int upw, int rem, int KB) {
+// kb_magic = ceil(2^32 / KB): u / KB = high word of u * kb_magic for every u < 2^32 / KB (units number < 2^20)
+static __device__ inline SkWalk sk_walk_init(int g, int upw, int rem, int KB, uint32_t kb_magic) {
     SkWalk w;
     w.u = g * upw + (g < rem ? g : rem);               // workgroup g takes upw units, the first `rem` one more
     w.u1 = w.u + upw + (g < rem ? 1 : 0);
-    w.ng = w.u / KB;
+    w.ng = KB == 1 ? w.u : (int)__umulhi((uint32_t)w.u, kb_magic);
     w.kb = w.u - w.ng * KB;
     return w;
 }
@@ -102,7 +103,7 @@ template <int MT>
 __global__ __launch_bounds__(512, 2) void k_gemm_sk(const bf16x8* __restrict__ Xp, const bf16x8* __restrict__ Wp,
                                                     const bf16x8* __restrict__ zfrag, float* __restrict__ out,
                                                     int KB, int NB, int ldo, size_t slot_stride, int upw, int rem,
-                                                    const int32_t* __restrict__ slot0_tab) {
+                                                    uint32_t kb_magic, const int32_t* __restrict__ slot0_tab) {
     static_assert(MT == 1 || MT == 2, "four row blocks: k_gemm_sk_wide");
     constexpr int R = 16;                            // ring depth
     constexpr int XK = 8 / MT;                       // contraction blocks per chunk
@@ -113,7 +114,7 @@ __global__ __launch_bounds__(512, 2) void k_gemm_sk(const bf16x8* __restrict__ X
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int g = blockIdx.x;
-    SkWalk walk = sk_walk_init(g, upw, rem, KB);
+    SkWalk walk = sk_walk_init(g, upw, rem, KB, kb_magic);
     const int slot0 = slot0_tab[g];                    // slot of this workgroup's first segment (later ones: 0)
     int nseg = 0;
 
@@ -239,7 +240,7 @@ __global__ __launch_bounds__(SKW_THREADS, 1) void k_gemm_sk_wide(const bf16x8* _
                                                                  const bf16x8* __restrict__ Wp,
                                                                  const bf16x8* __restrict__ zfrag,
                                                                  float* __restrict__ out, int KB, int NB, int ldo,
-                                                                 size_t slot_stride, int upw, int rem,
+                                                                 size_t slot_stride, int upw, int rem, uint32_t kb_magic,
                                                                  const int32_t* __restrict__ slot0_tab, int x_kb_units) {
     constexpr int MT = 4, CB = 2, R = SKW_R, XK = 2, CPI = R / XK, XF = XK * MT * 2, XP = XF * 64 / SKW_THREADS;
     static_assert(CPI == 3, "three chunks per ring length, three LDS buffers");
@@ -247,7 +248,7 @@ __global__ __launch_bounds__(SKW_THREADS, 1) void k_gemm_sk_wide(const bf16x8* _
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int g = blockIdx.x;
-    SkWalk walk = sk_walk_init(g, upw, rem, KB);
+    SkWalk walk = sk_walk_init(g, upw, rem, KB, kb_magic);
     const int slot0 = slot0_tab[g];                    // slot of this workgroup's first segment (later ones: 0)
     int nseg = 0;
     // the wave's two fragments of a contraction block lie side by side (2 KiB)
@@ -450,12 +451,13 @@ PartView launch_gemm(const GemmPlan& p, const void* Xp, const void* Wp, const vo
     pv.nmax = p.slots;
     const int MT = p.MB < SK_MAX_MT ? p.MB : SK_MAX_MT;
     const int x_kb_units = p.MB * 2 * 64;
+    const uint32_t kb_magic = (uint32_t)((0x100000000ull + (uint64_t)p.KB - 1) / (uint64_t)p.KB);
     const int passes = p.MB / MT;
     for (int r = 0; r < passes; ++r) {                 // passes of MT row blocks
         const bf16x8* xp = (const bf16x8*)Xp + (size_t)r * MT * 2 * 64;
         float* o = out + (size_t)r * MT * 32 * pv.ld;
         hipEvent_t e0 = r == 0 ? ev0 : nullptr, e1 = r == passes - 1 ? ev1 : nullptr;
-#define SK_ARGS xp, (const bf16x8*)Wp, (const bf16x8*)zfrag, o, p.KB, p.NB, pv.ld, pv.slot_stride, p.upw, p.rem, p.slot0_dev
+#define SK_ARGS xp, (const bf16x8*)Wp, (const bf16x8*)zfrag, o, p.KB, p.NB, pv.ld, pv.slot_stride, p.upw, p.rem, kb_magic, p.slot0_dev
 #define SK_LAUNCH(MT_)                                                                                     \
         do {                                                                                               \
             if (e0 || e1)                                                                                  \
