@@ -201,11 +201,13 @@ __global__ __launch_bounds__(512, 2) void k_gemm_sk(const bf16x8* __restrict__ X
                 float* o = out + (size_t)slot * slot_stride + (size_t)nb * 32 + (lane & 31);
                 const int gq = lane >> 5;
 #pragma unroll
+                // write-through stores: the tiles are consumed by other XCDs anyway, and lines left dirty
+                // in this XCD's L2 would only be written back at the end of the kernel, lengthening it
                 for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         int m = mt * 32 + 8 * (v >> 2) + 4 * gq + (v & 3);
-                        o[(size_t)m * ldo] = acc[mt][v];
+                        __hip_atomic_store(&o[(size_t)m * ldo], acc[mt][v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     }
             }
 #pragma unroll
@@ -367,7 +369,7 @@ __global__ __launch_bounds__(SKW_THREADS, 1) void k_gemm_sk_wide(const bf16x8* _
 #pragma unroll
                         for (int v = 0; v < 16; ++v) {
                             int m = mt * 32 + 8 * (v >> 2) + 4 * gq + (v & 3);
-                            o[(size_t)m * ldo] = acc[mt][cb][v];
+                            __hip_atomic_store(&o[(size_t)m * ldo], acc[mt][cb][v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         }
                 }
             }
