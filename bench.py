@@ -41,8 +41,11 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=256)
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", default="7b", choices=["7b", "7b-long", "13b", "7b-h10", "tiny", "labels"],
-                    help="labels = the training-side label construction alone (not the headline step)")
+    ap.add_argument("--workload", default="7b", choices=["7b", "7b-long", "7b-batch8", "13b", "7b-h10", "tiny", "labels"],
+                    help="labels = the training-side label construction alone (not the headline step); "
+                         "7b-batch8 = eight ragged sequences, the model's own drafts, step time only")
+    ap.add_argument("--draft-schedule", default="after_verdict", choices=["after_verdict", "all_nodes"],
+                    help="all_nodes = draft heads on every tree row inside the verifying pass (measured slower here)")
     ap.add_argument("--layers", type=int, default=None, help="cut the depth (debugging only; result is labelled)")
     ap.add_argument("--draft", default="planted", choices=["planted", "random"])
     ap.add_argument("--decoding", default="greedy", choices=["greedy", "sampling"],
@@ -54,10 +57,11 @@ def parse():
     return ap.parse_args()
 
 
-def weight_bytes(m) -> float:
+def weight_bytes(m, lm_head_reads: int = 2) -> float:
     d, F, V, L, H = m.d_model, m.d_ffn, m.vocab, m.n_layers, m.n_medusa
-    # every projection once + LM head twice (tree rows, then the draft-head rows) + draft heads
-    return 2.0 * (L * (4 * d * d + 3 * d * F) + 2 * V * d + H * d * d)
+    # every projection once + LM head twice (tree rows, then the draft-head rows) + draft heads; with the
+    # heads on every tree row the LM head is read once per 128-row chunk of head rows instead
+    return 2.0 * (L * (4 * d * d + 3 * d * F) + lm_head_reads * V * d + H * d * d)
 
 
 def main():
@@ -75,6 +79,8 @@ def main():
     if args.workload == "labels":
         return bench_labels(args, torch, wl, sd)
     W = wl.preset(args.workload, args.layers)
+    if W.batch > 1:
+        return bench_batch(args, torch, wl, sd, W)
     shape = dataclasses.replace(W.model, dtype="bf16")
     T, H, k = W.tree_nodes, shape.n_medusa, shape.topk
     prompt_len = W.prompt_len if args.workload != "7b-long" else W.prompt_len
@@ -140,6 +146,7 @@ def main():
     tok_host = torch.empty((1, H + 1), dtype=torch.int32).pin_memory()
     forced = torch.zeros((1, H, k), dtype=torch.int32, device="cuda")     # fixed buffer: graphs replay on it
     model.set_graph_mode(args.graph)
+    model.set_draft_schedule(args.draft_schedule)
     state = {"e": 0, "emitted": 0, "diverged": 0, "resets": 0, "i": 0}
     typical = dict(temperature=0.8, epsilon=0.09, delta=0.3)
     n_u = args.steps + args.warmup + args.profile_steps
@@ -227,7 +234,8 @@ def main():
                            typical=dict(typical, u=0.5) if args.decoding == "sampling" else None)
 
     kv_bytes = (prompt_len + state["e"] / 2) * 2.0 * shape.d_model * 2 * shape.n_layers
-    step_bytes = weight_bytes(shape) + kv_bytes
+    lm_reads = 2 if args.draft_schedule == "after_verdict" else 1 + -(-H * ((T + 31) // 32 * 32) // 128)
+    step_bytes = weight_bytes(shape, lm_reads) + kv_bytes
     res = {
         "metric": "verified_tree_tokens_per_s", "value": args.steps * T / elapsed, "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -235,6 +243,7 @@ def main():
         "config": {"workload": f"{W.name}: {shape.n_layers}-layer d={shape.d_model} Llama-shaped decoder, "
                                f"{H} draft heads top-{k}, {T}-node tree, batch 1, Zipf prompt {prompt_len}, "
                                f"KV cap {W.kv_cap}, 20% stop ids",
+                   "draft_schedule": args.draft_schedule,
                    "decoding": args.decoding, "typical_acceptance": typical if args.decoding == "sampling" else None,
                    "draft_mode": args.draft if args.decoding == "greedy" else "own heads",
                    "planted_accuracy_by_depth": list(p_depth) if (args.draft == "planted" and args.decoding == "greedy") else None},
@@ -253,6 +262,74 @@ def main():
         "cpu_baseline": cpu,
     }
     print(json.dumps(res))
+
+
+def bench_batch(args, torch, wl, sd, W):
+    """A batch of ragged sequences (configs[3] shape): real prefill of Zipf prompts with lengths drawn in
+    [1024, 4096], then speculative steps on the model's own (random-head) drafts. Step time and the per-kernel
+    figures only: there is no planted stream, so acceptance is that of untrained heads."""
+    shape = dataclasses.replace(W.model, dtype="bf16")
+    B, T, H, k = W.batch, W.tree_nodes, shape.n_medusa, shape.topk
+    Tp = (T + 31) // 32 * 32
+    model = sd.Model(shape, wl.make_weights(shape, device="cuda"), max_rows=B * Tp)
+    torch.cuda.empty_cache()
+    kv = sd.KVCache(model, B, W.kv_cap)
+    rng = np.random.Generator(np.random.Philox(key=wl.SEEDS["kvlen"]))
+    lens = [int(x) for x in rng.integers(1024, 4097, size=B)]
+    prompt = np.concatenate([wl.zipf_prompt(shape.vocab, n, seed=wl.SEEDS["prompt"] + b) for b, n in enumerate(lens)])
+    stop_words = torch.from_numpy(wl.pack_mask_words(wl.stop_set(shape.vocab, W.stop_frac)).view(np.int32)).cuda()
+    tree = sd.Tree(*wl.default_tree(T, H, k), H, k)
+    t0 = time.perf_counter()
+    sd.prefill(model, kv, torch.from_numpy(prompt).cuda(), lens)
+    torch.cuda.synchronize()
+    prefill_s = time.perf_counter() - t0
+    root0, cand0 = (t.clone() for t in kv.get_draft())
+    out = sd.StepOutput(
+        torch.empty(B, dtype=torch.int32, device="cuda"), torch.empty((B, H + 1), dtype=torch.int32, device="cuda"),
+        torch.empty((B, H + 1), dtype=torch.int32, device="cuda"), torch.empty(B, dtype=torch.int32, device="cuda"))
+    model.set_graph_mode(args.graph)
+    model.set_draft_schedule(args.draft_schedule)
+    room = (W.kv_cap - 1 - max(lens)) // (H + 1)           # steps before the longest sequence could fill its cache
+    state = {"left": room, "emitted": 0}
+
+    def run_steps(n):
+        for _ in range(n):
+            if state["left"] <= 0:
+                kv.set_len(lens)
+                kv.set_draft(root0, cand0)
+                state["left"] = room
+            sd.spec_step(model, kv, tree, stop_words, out=out)
+            state["emitted"] += sum(kv.len())              # synchronises the stream
+            state["left"] -= 1
+
+    run_steps(args.warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_steps(args.steps)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    model.profile_begin(200000)
+    run_steps(args.profile_steps)
+    prof = model.profile_end()
+    g, a = prof["gemm"], prof["attn"]
+    gemm_gbs = g["bytes"] / max(g["ms"], 1e-9) / 1e6
+    print(json.dumps({
+        "metric": "verified_tree_tokens_per_s", "value": args.steps * B * T / elapsed, "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{W.name}: {shape.n_layers}-layer d={shape.d_model} Llama-shaped decoder, {H} draft "
+                               f"heads top-{k}, {T}-node trees, batch {B}, Zipf prompts of {lens} tokens, KV cap "
+                               f"{W.kv_cap}, 20% stop ids",
+                   "draft_schedule": args.draft_schedule, "decoding": "greedy", "draft_mode": "own heads"},
+        "prefill_tokens_per_s": sum(lens) / prefill_s, "hip_graphs": args.graph,
+        "roofline": {"kernel": "k_gemm_sk (weight-streaming MFMA GEMM, all projections)", "bound": "hbm",
+                     "achieved": gemm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gemm_gbs / HBM_PEAK_GBS,
+                     "traffic": None, "avg_launch_us": g["ms"] / max(g["launches"], 1) * 1e3,
+                     "launches_per_step": g["launches"] / args.profile_steps,
+                     "algorithmic_bytes_per_launch": g["bytes"] / max(g["launches"], 1)},
+        "attention": {"kernel": "k_tree_attn", "achieved_GBs": a["bytes"] / max(a["ms"], 1e-9) / 1e6,
+                      "avg_launch_us": a["ms"] / max(a["launches"], 1) * 1e3},
+        "cpu_baseline": None}))
 
 
 def bench_labels(args, torch, wl, sd):

@@ -222,6 +222,20 @@ int sd_sample_tokens(const float* logits, int32_t n_rows, int32_t ld, int32_t vo
 int sd_build_labels(const int32_t* l0, int32_t batch, int32_t seq, int32_t n_heads, int32_t frag_id,
                     int32_t pad_id, int32_t ignore_id, int32_t no_frag, int32_t* labels, void* stream);
 
+/* Where in a step the draft heads run (Section III-B: every head predicts from the base model's
+ * last hidden state at one position; which positions get evaluated is a schedule, not part of
+ * the method, and both give the same candidates up to summation order).
+ *   SD_DRAFT_AFTER_VERDICT (default): after the verdict, on the one row of every sequence that
+ *     was kept last: H head rows per sequence through the shared LM head, a second read of it.
+ *   SD_DRAFT_ALL_NODES: inside the verifying pass, on all tree rows (the schedule of a
+ *     single-pass multi-head decoder): H * T head rows per sequence go through the LM head, and
+ *     the H rows of the last kept node are ranked afterwards. sd_greedy_step and sd_prefill
+ *     always use the first schedule (they have one candidate row).
+ * Returns SD_ERR_NULL / SD_ERR_SHAPE (unknown value); takes effect from the next step.          */
+#define SD_DRAFT_AFTER_VERDICT 0
+#define SD_DRAFT_ALL_NODES     1
+int sd_set_draft_schedule(sd_model* m, int32_t schedule);
+
 /* Graph mode (off by default). When on, sd_spec_step / sd_greedy_step capture their kernel
  * sequence into a HIP graph the first time a given combination of (cache, tree, split-KV
  * geometry, stop mask, output and candidate pointers) is seen and replay it afterwards: one

@@ -15,7 +15,7 @@ EXPORTED_SYMBOLS = [
     "sd_kv_set_len", "sd_kv_write_rows", "sd_kv_read_rows", "sd_kv_set_draft", "sd_kv_get_draft",
     "sd_tree_create", "sd_tree_destroy", "sd_prefill", "sd_spec_step", "sd_greedy_step", "sd_verify_tree",
     "sd_spec_step_typical", "sd_verify_tree_typical", "sd_sample_tokens", "sd_build_labels",
-    "sd_set_graph_mode", "sd_profile_begin", "sd_profile_end", "sd_last_error", "sd_version",
+    "sd_set_graph_mode", "sd_set_draft_schedule", "sd_profile_begin", "sd_profile_end", "sd_last_error", "sd_version",
 ]
 
 SD_ERR = {-1: "SD_ERR_NULL", -2: "SD_ERR_SHAPE", -3: "SD_ERR_BAD_TREE", -4: "SD_ERR_KV_FULL", -5: "SD_ERR_HIP",
@@ -95,6 +95,7 @@ def lib() -> C.CDLL:
         L.sd_build_labels.argtypes = [C.c_void_p] + [C.c_int32] * 7 + [C.c_void_p, C.c_void_p]
         L.sd_profile_begin.argtypes = [C.c_void_p, C.c_int32]
         L.sd_set_graph_mode.argtypes = [C.c_void_p, C.c_int32]
+        L.sd_set_draft_schedule.argtypes = [C.c_void_p, C.c_int32]
         L.sd_profile_end.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64),
                                      C.POINTER(C.c_double)]
         _LIB = L
@@ -151,6 +152,10 @@ class Model:
 
     def set_graph_mode(self, on: bool):
         _check(lib().sd_set_graph_mode(self.handle, 1 if on else 0))
+
+    def set_draft_schedule(self, schedule: str):
+        """"after_verdict" (default) or "all_nodes": where in a step the draft heads run."""
+        _check(lib().sd_set_draft_schedule(self.handle, {"after_verdict": 0, "all_nodes": 1}[schedule]))
 
     def profile_begin(self, max_launches: int = 65536):
         _check(lib().sd_profile_begin(self.handle, max_launches))

@@ -67,6 +67,8 @@ struct sd_model {
     float *x, *part, *logits, *hlogits, *hf, *h_rows, *opart;
     float2* mlpart;
     void *xn, *attn_x, *act, *q, *kt, *vt;
+    void* xh;                                // draft-head rows of every tree row, in 128-row operand chunks
+    int draft_schedule = SD_DRAFT_AFTER_VERDICT;
     RowTable rt;
     int32_t *am, *g_parent, *g_depth, *g_rank;
     float4* row_stats;                     // [Mp]: per tree row, statistics for typical acceptance
@@ -230,9 +232,8 @@ extern "C" int sd_model_create(const sd_config* cfg, const sd_weights* w, int32_
             for (int si = 0; si < 6; ++si) {
                 const int* sh = shapes[si];
                 // beyond MBmax only the LM head is used (draft-head rows); the draft-head
-                // projection itself always has one row block
+                // projection has one row block, or the step's when the heads run on every tree row
                 if (mb > m->MBmax && si != 4) continue;
-                if (si == 5 && mb > 1) continue;
                 bool dup = false;
                 for (const GemmPlan& q : m->plans) dup |= q.MB == mb && q.KB == sh[0] && q.NB == sh[1];
                 if (dup) continue;
@@ -262,6 +263,7 @@ extern "C" int sd_model_create(const sd_config* cfg, const sd_weights* w, int32_
     size_t w_tok = wtake((size_t)Mp * 4), w_pos = wtake((size_t)Mp * 4), w_anc = wtake((size_t)Mp * SD_ANC_WORDS * 4);
     size_t w_cs = wtake((size_t)Mp * (hd / 2) * 8), w_am = wtake((size_t)Mp * 4), w_g = wtake(3 * 4);
     size_t w_rs = wtake((size_t)Mp * 16);
+    size_t w_xh = wtake(align_up((size_t)H * Mp, 128) * d * 4);
     size_t w_zs = wtake((size_t)ceil_div(V, 32) * 4), w_zf = wtake(1024);
     e = hipMalloc((void**)&m->work, wz);
     if (e == hipSuccess) e = hipMalloc((void**)&m->plan_cnt, cnt_all.size() * 4);
@@ -284,6 +286,7 @@ extern "C" int sd_model_create(const sd_config* cfg, const sd_weights* w, int32_
     m->opart = (float*)(Wk + w_opart); m->mlpart = (float2*)(Wk + w_ml);
     m->xn = Wk + w_xn; m->attn_x = Wk + w_attn; m->act = Wk + w_act; m->q = Wk + w_q;
     m->kt = Wk + w_kt; m->vt = Wk + w_vt;
+    m->xh = Wk + w_xh;
     m->rt.tok = (int32_t*)(Wk + w_tok); m->rt.pos = (int32_t*)(Wk + w_pos); m->rt.anc = (uint32_t*)(Wk + w_anc);
     m->rt.cs = (float2*)(Wk + w_cs);
     m->am = (int32_t*)(Wk + w_am);
@@ -357,6 +360,14 @@ extern "C" int sd_build_labels(const int32_t* l0, int32_t batch, int32_t seq, in
     launch_build_labels(l0, batch, seq, n_heads, frag_id, pad_id, ignore_id, no_frag == SD_LABELS_KEEP_ALL, labels,
                         (hipStream_t)stream);
     HIP_TRY(hipGetLastError());
+    return SD_OK;
+}
+
+extern "C" int sd_set_draft_schedule(sd_model* m, int32_t schedule) {
+    if (!m) return fail(SD_ERR_NULL, "sd_set_draft_schedule: NULL model");
+    if (schedule != SD_DRAFT_AFTER_VERDICT && schedule != SD_DRAFT_ALL_NODES)
+        return fail(SD_ERR_SHAPE, "sd_set_draft_schedule: unknown schedule %d", schedule);
+    m->draft_schedule = schedule;
     return SD_OK;
 }
 
@@ -622,10 +633,11 @@ static PartView run_layers(sd_model* m, sd_kv* kv, int B, int Tp, int n_hi, hipS
 }
 
 // final norm + LM head on all rows + arg-max of the first T rows of every sequence
-static void run_lm_head(sd_model* m, PartView prev, int B, int T, int Tp, hipStream_t s) {
+// (keep_h: also leaves the normalised rows in m->hf as fp32, for draft heads on every row)
+static void run_lm_head(sd_model* m, PartView prev, int B, int T, int Tp, hipStream_t s, bool keep_h = false) {
     const sd_config& c = m->cfg;
     const int M = B * Tp, MB = pow2_blocks(M);
-    launch_norm_pack(m->x, prev, m->final_norm, c.rms_eps, m->xn, nullptr, M, c.d_model, MB, nullptr, s);
+    launch_norm_pack(m->x, prev, m->final_norm, c.rms_eps, m->xn, keep_h ? m->hf : nullptr, M, c.d_model, MB, nullptr, s);
     PartView pl = run_gemm(m, m->xn, m->lm_head, m->part, MB, m->KBd, m->NBv, c.vocab, s);
     launch_reduce_slots(pl, m->logits, M, s);
     launch_argmax(m->logits, m->Vpad, c.vocab, m->am, B, T, Tp, s);
@@ -639,10 +651,31 @@ static void run_draft_heads(sd_model* m, sd_kv* kv, int B, uint32_t seq_mask, fl
     launch_norm_pack(m->x, none, m->final_norm, c.rms_eps, m->xn, m->h_rows, B, d, 1, kv->last_row, s);
     PartView pm = run_gemm(m, m->xn, m->medusa_w, m->part, 1, m->KBd, m->NBmed, H * d, s);
     const int MBh = pow2_blocks(H * B);
-    launch_medusa_act(pm, m->h_rows, m->medusa_b, B, H, d, m->xn, MBh, s);
+    launch_medusa_act(pm, m->h_rows, m->medusa_b, B, H, d, m->xn, MBh * 32, MBh, MBh, s);
     PartView pl = run_gemm(m, m->xn, m->lm_head, m->part, MBh, m->KBd, m->NBv, c.vocab, s);
     launch_reduce_slots(pl, m->hlogits, H * B, s);
     launch_topk(m->hlogits, m->Vpad, c.vocab, c.topk, kv->cand, B, H, seq_mask, s);
+    if (head_logits_out) launch_copy_head_logits(m->hlogits, m->Vpad, head_logits_out, c.vocab, B, H, s);
+}
+
+// The other schedule: the draft heads run on all B*Tp rows of the verifying pass (m->xn and m->hf
+// still hold the final norm's output), the shared LM head on all H*B*Tp head rows in chunks of 128
+// rows, and only the H rows of every sequence's last kept row (kv->last_row, set by the verdict) are
+// summed out of the partial tiles and ranked.
+static void run_draft_heads_all_rows(sd_model* m, sd_kv* kv, int B, int Tp, float* head_logits_out, hipStream_t s) {
+    const sd_config& c = m->cfg;
+    const int d = c.d_model, H = c.n_medusa, M = B * Tp, MB = pow2_blocks(M), R = H * M, CH = 128;
+    PartView pm = run_gemm(m, m->xn, m->medusa_w, m->part, MB, m->KBd, m->NBmed, H * d, s);
+    const int n_chunks = ceil_div(R, CH), MBlast = pow2_blocks(R - (n_chunks - 1) * CH);
+    launch_medusa_act(pm, m->hf, m->medusa_b, M, H, d, m->xh, CH, CH / 32, MBlast, s);
+    for (int ch = 0; ch < n_chunks; ++ch) {
+        const int rows = std::min(CH, R - ch * CH);
+        const char* xc = (const char*)m->xh + (size_t)ch * CH * d * 4;
+        PartView pl = run_gemm(m, xc, m->lm_head, m->part, ch == n_chunks - 1 ? MBlast : CH / 32, m->KBd, m->NBv,
+                               c.vocab, s);
+        launch_reduce_selected(pl, m->hlogits, kv->last_row, B, H, M, ch * CH, rows, s);
+    }
+    launch_topk(m->hlogits, m->Vpad, c.vocab, c.topk, kv->cand, B, H, 0xffffffffu, s);
     if (head_logits_out) launch_copy_head_logits(m->hlogits, m->Vpad, head_logits_out, c.vocab, B, H, s);
 }
 
@@ -721,7 +754,8 @@ static int step_common(sd_model* m, sd_kv* kv, const int32_t* parent, const int3
     launch_build_rows_tree(m->rt, parent, depth, rank, kv->root_tok, cand, kv->kv_len, B, T, Tp, H, c.topk, c.head_dim,
                            c.rope_theta, m->embed, c.d_model, c.vocab, m->x, s);
     PartView prev = run_layers(m, kv, B, Tp, n_hi, s);
-    run_lm_head(m, prev, B, T, Tp, s);
+    const bool all_rows = m->draft_schedule == SD_DRAFT_ALL_NODES && T > 1;
+    run_lm_head(m, prev, B, T, Tp, s, all_rows);
     if (io->logits) launch_copy_logits(m->logits, m->Vpad, io->logits, c.vocab, B, T, Tp, s);
     if (io->argmax) launch_copy_rows_i32(m->am, io->argmax, B, T, Tp, s);
     VerifyArgs va;
@@ -744,7 +778,8 @@ static int step_common(sd_model* m, sd_kv* kv, const int32_t* parent, const int3
                            B * Tp, s);
     launch_kv_commit(m->kt, m->vt, kv->kc, kv->vc, slots, n_accept, kv->n_old, c.n_layers, B, c.n_heads, c.head_dim,
                      Tp / 32, kv->cap_blocks, H + 1, H + 1, s);
-    run_draft_heads(m, kv, B, 0xffffffffu, io->head_logits, s);
+    if (all_rows) run_draft_heads_all_rows(m, kv, B, Tp, io->head_logits, s);
+    else run_draft_heads(m, kv, B, 0xffffffffu, io->head_logits, s);
     };
 
     if (m->use_graphs && !m->prof.on && !ty) {
@@ -754,7 +789,8 @@ static int step_common(sd_model* m, sd_kv* kv, const int32_t* parent, const int3
                                      (uint64_t)(uintptr_t)n_accept, (uint64_t)(uintptr_t)tokens,
                                      (uint64_t)(uintptr_t)slots, (uint64_t)(uintptr_t)io->n_accept_raw,
                                      (uint64_t)(uintptr_t)io->logits, (uint64_t)(uintptr_t)io->argmax,
-                                     (uint64_t)(uintptr_t)io->head_logits, (uint64_t)(uintptr_t)cand};
+                                     (uint64_t)(uintptr_t)io->head_logits, (uint64_t)(uintptr_t)cand,
+                                     (uint64_t)m->draft_schedule};
         hipGraphExec_t exec = nullptr;
         for (const sd_model::StepGraph& g : m->graphs)
             if (g.key == key) { exec = g.exec; break; }

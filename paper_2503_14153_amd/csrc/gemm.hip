@@ -405,6 +405,31 @@ void launch_reduce_slots(PartView pv, float* dst, int rows, hipStream_t s) {
     hipLaunchKernelGGL(k_reduce_slots, dim3((pv.ld / 4 + 255) / 256, rows), dim3(256), 0, s, pv, dst, rows);
 }
 
+// Sums the slots of selected rows only: output row (i, b), i < H, b < B, is row i*M + sel[b] of a
+// row-chunked GEMM sequence; this launch covers the chunk holding rows [row0, row0 + rows) and
+// writes dst row i*B + b when that row lies in it.
+__global__ void k_reduce_selected(PartView pv, float* __restrict__ dst, const int32_t* __restrict__ sel, int B, int M,
+                                  int row0, int rows) {
+    const int c4 = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    const int i = blockIdx.y / B, b = blockIdx.y % B;
+    const int s = sel[b];
+    if (c4 >= pv.ld || s < 0 || s >= M) return;
+    const int m = i * M + s - row0;
+    if (m < 0 || m >= rows) return;
+    const int n = part_count(pv, c4);
+    float4 a = make_float4(0, 0, 0, 0);
+    for (int sp = 0; sp < n; ++sp) {
+        float4 v = *(const float4*)(pv.base + (size_t)sp * pv.slot_stride + (size_t)m * pv.ld + c4);
+        a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
+    }
+    *(float4*)(dst + (size_t)blockIdx.y * pv.ld + c4) = a;
+}
+void launch_reduce_selected(PartView pv, float* dst, const int32_t* sel, int B, int H, int M, int row0, int rows,
+                            hipStream_t s) {
+    hipLaunchKernelGGL(k_reduce_selected, dim3((pv.ld / 4 + 255) / 256, H * B), dim3(256), 0, s, pv, dst, sel, B, M, row0,
+                       rows);
+}
+
 // ------------------------------------------------------------------------------------------
 #define SK_MAX_WG 256       // one workgroup of 8 waves per CU
 #define SK_MAX_MT 4         // row blocks per pass

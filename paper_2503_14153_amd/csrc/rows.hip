@@ -272,8 +272,11 @@ void launch_swiglu_pack(PartView pv, int F, int Fpad, void* act_packed, int M, i
 // ------------------------------------------------------------------------------------------
 // Draft heads, activation stage: row (i, b) = h_b + silu(W_i h_b + bias_i), packed as the
 // operand of the shared LM-head GEMM. part columns [i*d, (i+1)*d) hold W_i h_b for row b.
+// The i*B + b output rows are laid out in chunks of `chunk_rows` rows (a power of two >= 32, or
+// >= H*B for a single operand): chunk c is a packed activation of its own, `chunk_rows * d * 2`
+// elements after the previous one, with MB row blocks (MBlast in the last chunk).
 __global__ void k_medusa_act(PartView pv, const float* __restrict__ h_rows, MedusaBias bias, int B, int H, int d,
-                             bf16x8* __restrict__ xp, int MB) {
+                             bf16x8* __restrict__ xp, int chunk_rows, int MB, int MBlast) {
     int idx = blockIdx.x * blockDim.x + threadIdx.x;
     int ng = d / 8;
     if (idx >= H * B * ng) return;
@@ -294,13 +297,16 @@ __global__ void k_medusa_act(PartView pv, const float* __restrict__ h_rows, Medu
         f[e] = h_rows[(size_t)b * d + grp * 8 + e] + zz / (1.f + __expf(-zz));
     }
     split_hilo(f, hi, lo);
-    const size_t u = xpack_index(i * B + b, grp * 8, MB) >> 3;
+    const int row = i * B + b, chunk = row / chunk_rows, last = (H * B - 1) / chunk_rows;
+    const size_t u = ((size_t)chunk * chunk_rows * d * 2 + xpack_index(row - chunk * chunk_rows, grp * 8,
+                                                                       chunk == last ? MBlast : MB)) >> 3;
     xp[u] = hi;
     xp[u + XPART / 8] = lo;
 }
 
 void launch_medusa_act(PartView pv, const float* h_rows, const MedusaBias& bias, int B, int H, int d, void* x_packed,
-                       int MB, hipStream_t s) {
+                       int chunk_rows, int MB, int MBlast, hipStream_t s) {
     int total = H * B * (d / 8);
-    hipLaunchKernelGGL(k_medusa_act, dim3((total + 255) / 256), dim3(256), 0, s, pv, h_rows, bias, B, H, d, (bf16x8*)x_packed, MB);
+    hipLaunchKernelGGL(k_medusa_act, dim3((total + 255) / 256), dim3(256), 0, s, pv, h_rows, bias, B, H, d,
+                       (bf16x8*)x_packed, chunk_rows, MB, MBlast);
 }

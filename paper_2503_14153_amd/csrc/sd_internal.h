@@ -131,6 +131,9 @@ void gemm_plan_make(GemmPlan* p, int MB, int KB, int NB, int32_t* cnt_host, int3
 PartView launch_gemm(const GemmPlan& p, const void* Xp, const void* Wp, const void* zfrag, float* out, hipStream_t s,
                      hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 void launch_reduce_slots(PartView pv, float* dst, int rows, hipStream_t s);
+// dst row i*B + b = summed row (i*M + sel[b]) - row0 of pv when it lies in [0, rows); i < H, b < B
+void launch_reduce_selected(PartView pv, float* dst, const int32_t* sel, int B, int H, int M, int row0, int rows,
+                            hipStream_t s);
 
 void launch_build_rows_tree(RowTable rt, const int32_t* parent, const int32_t* depth, const int32_t* rank,
                             const int32_t* root_tok, const int32_t* cand, const int32_t* kv_len,
@@ -150,8 +153,9 @@ void launch_tree_attn(const void* q_packed, const void* kc, const void* vc, cons
 void launch_attn_merge(const float* opart, const float2* mlpart, void* x_packed, int B, int nh, int hd,
                        int Tp, int nparts, int MB, hipStream_t s);
 void launch_swiglu_pack(PartView pv, int F, int Fpad, void* act_packed, int M, int MB, hipStream_t s);
+// output rows i*B + b in chunks of chunk_rows rows, each a packed activation of MB (last: MBlast) row blocks
 void launch_medusa_act(PartView pv, const float* h_rows, const MedusaBias& bias, int B, int H, int d,
-                       void* x_packed, int MB, hipStream_t s);
+                       void* x_packed, int chunk_rows, int MB, int MBlast, hipStream_t s);
 void launch_argmax(const float* logits, int ld, int V, int32_t* am, int B, int T, int Tp, hipStream_t s);
 void launch_topk(const float* logits, int ld, int V, int k, int32_t* out, int B, int H, uint32_t seq_mask,
                  hipStream_t s);

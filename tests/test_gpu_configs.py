@@ -49,11 +49,12 @@ def _random_draft(shape, B, seed):
 
 
 def _run_batch_steps(sd, shape, B, T, lens, cap, n_steps, tree_np=None, plant=True, fallback="keep_all",
-                     weights_device="cpu"):
+                     weights_device="cpu", schedule="after_verdict"):
     weights = wl.make_weights(shape, device=weights_device)
     w64 = lockstep.weights_to_f64(weights)
     Tp = (T + 31) // 32 * 32
     model = sd.Model(shape, {k: v.cuda() for k, v in weights.items()}, B * Tp, fallback)
+    model.set_draft_schedule(schedule)
     kv = sd.KVCache(model, B, cap)
     stop = wl.stop_set(shape.vocab, 0.2)
     words = torch.from_numpy(wl.pack_mask_words(stop).view(np.int32)).cuda()
