@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # (FETCH_SIZE, WRITE_SIZE), scaled by what the same counters read for sd_calib's 1 GiB copy
 # kernel (1 FETCH unit = 2 KiB, 1 WRITE unit = 1 KiB): profiles/k_gemm_sk_7b_pmc_traffic.txt.
 # Only valid for the default workload; other workloads report null.
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = 122.5e6
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = 123.1e6
 # same counters for k_build_labels at the `labels` workload: profiles/k_build_labels_256x8192_kernel_trace_and_traffic.txt
 LABELS_TRAFFIC_BYTES_PER_LAUNCH = 100.9e6
 
