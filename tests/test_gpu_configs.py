@@ -216,6 +216,18 @@ def test_tree_sizes_beyond_128_nodes(sd, T):
     assert max(rep.raw) >= 2
 
 
+def test_library_limits_fifteen_heads_top32_odd_vocabulary(sd):
+    """The most draft heads (15) and candidates per head (32) the library takes, on a 256-node tree, with a
+    vocabulary of odd size (1007: the last 32-column block of the LM head holds 15 real columns) and a
+    chain of 16 nodes deep enough to use every head."""
+    shape = dataclasses.replace(_shape("tiny"), n_medusa=15, topk=32, vocab=1007)
+    rep = _run_batch_steps(sd, shape, 1, 256, [45], 128, n_steps=3)
+    print(f"\n[tiny H=15 k=32 V=1007 T=256] {rep}")
+    assert max(rep.raw) >= 2
+    rep = _run_batch_steps(sd, shape, 1, 16, [45], 128, n_steps=2, tree_np=wl.chain_tree(16))
+    print(f"\n[tiny H=15 chain] {rep}")
+
+
 @pytest.mark.parametrize("kind", ["root_only", "chain", "ragged33", "full_k3"])
 def test_degenerate_trees(sd, kind):
     shape = _shape("tiny")
