@@ -199,7 +199,12 @@ __global__ __launch_bounds__(512, 2) void k_gemm_sk(const bf16x8* __restrict__ X
             const int nb = cur.ng * 8 + wave;
             if (nb < NB) {
                 float* o = out + (size_t)slot * slot_stride + (size_t)nb * 32 + (lane & 31);
-                const int gq = lane >> 5;
+                // the row stride and the lane's row group are made opaque here so that the row offsets
+                // m * ldo are computed where they are used: hoisted out of the loop (which the compiler
+                // does otherwise) they occupy registers for the whole kernel, 64 of them here and some
+                // 150 in the 128-row kernel
+                int gq = lane >> 5, ldo_here = ldo;
+                asm volatile("" : "+v"(gq), "+s"(ldo_here));
 #pragma unroll
                 // write-through stores: the tiles are consumed by other XCDs anyway, and lines left dirty
                 // in this XCD's L2 would only be written back at the end of the kernel, lengthening it
@@ -207,7 +212,7 @@ __global__ __launch_bounds__(512, 2) void k_gemm_sk(const bf16x8* __restrict__ X
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         int m = mt * 32 + 8 * (v >> 2) + 4 * gq + (v & 3);
-                        __hip_atomic_store(&o[(size_t)m * ldo], acc[mt][v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        __hip_atomic_store(&o[(size_t)m * ldo_here], acc[mt][v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     }
             }
 #pragma unroll
@@ -363,13 +368,14 @@ __global__ __launch_bounds__(SKW_THREADS, 1) void k_gemm_sk_wide(const bf16x8* _
                 const int nb = cur.ng * 8 + wave * CB + cb;
                 if (nb < NB) {
                     float* o = out + (size_t)slot * slot_stride + (size_t)nb * 32 + (lane & 31);
-                    const int gq = lane >> 5;
+                    int gq = lane >> 5, ldo_here = ldo;            // opaque, as in k_gemm_sk: no hoisted row offsets
+                    asm volatile("" : "+v"(gq), "+s"(ldo_here));
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                         for (int v = 0; v < 16; ++v) {
                             int m = mt * 32 + 8 * (v >> 2) + 4 * gq + (v & 3);
-                            __hip_atomic_store(&o[(size_t)m * ldo], acc[mt][cb][v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            __hip_atomic_store(&o[(size_t)m * ldo_here], acc[mt][cb][v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         }
                 }
             }
