@@ -51,6 +51,8 @@ def parse():
     ap.add_argument("--decoding", default="greedy", choices=["greedy", "sampling"],
                     help="sampling = typical acceptance and a sampled next root at temperature 0.8 (the paper's "
                          "second decoding setting); drafts are then the model's own heads'")
+    ap.add_argument("--sync-every", type=int, default=16,
+                    help="steps launched between host synchronisations (1 = wait for every step before the next)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=32)
     ap.add_argument("--graph", action="store_true", help="replay captured HIP graphs instead of launching every kernel (measured: no gain, the step is not host-bound)")
@@ -143,7 +145,6 @@ def main():
     out = sd.StepOutput(
         torch.empty(1, dtype=torch.int32, device="cuda"), torch.empty((1, H + 1), dtype=torch.int32, device="cuda"),
         torch.empty((1, H + 1), dtype=torch.int32, device="cuda"), torch.empty(1, dtype=torch.int32, device="cuda"))
-    tok_host = torch.empty((1, H + 1), dtype=torch.int32).pin_memory()
     forced = torch.zeros((1, H, k), dtype=torch.int32, device="cuda")     # fixed buffer: graphs replay on it
     model.set_graph_mode(args.graph)
     model.set_draft_schedule(args.draft_schedule)
@@ -152,44 +153,68 @@ def main():
     n_u = args.steps + args.warmup + args.profile_steps
     u_dev = torch.from_numpy(np.random.default_rng(wl.SEEDS["force"] + 1).random(n_u).astype(np.float32)).cuda()
 
-    def run_steps_sampling(n):
-        # nothing to compare the sampled stream with: e only tracks the committed length
-        for _ in range(n):
-            e, i = state["e"], state["i"]
-            if prompt_len + e + H + 1 > W.kv_cap - 1:
-                reset()
-                state["resets"] += 1
-                e = state["e"] = 0
-            sd.spec_step_typical(model, kv, tree, stop_words, u_dev[i: i + 1], out=out, **typical)
-            n_acc = kv.len()[0] - prompt_len - e      # synchronises the stream
-            state["e"] = e + n_acc
-            state["emitted"] += n_acc
-            state["i"] = i + 1
+    # The loop does not wait for a step before launching the next: the planted candidates of step i are picked on
+    # the device from the number of tokens emitted so far (a device counter), and the emitted tokens are logged on
+    # the device. Every `sync_every` steps the host synchronises, reads the committed length back (which also
+    # refreshes the library's bound on it), checks the logged tokens against the plain-greedy stream and decides
+    # whether the cache or the planted table could run out within the next window.
+    SYNC = max(1, args.sync_every)
+    e_dev = torch.zeros(1, dtype=torch.int64, device="cuda")
+    tok_log = torch.zeros((SYNC, H + 1), dtype=torch.int32, device="cuda")
+    nacc_log = torch.zeros(SYNC, dtype=torch.int32, device="cuda")
+    room = min(n_table, W.kv_cap - 1 - prompt_len) - (H + 1)          # e may not exceed this when a step starts
+    assert room > SYNC * (H + 1), "sync window too long for this cache"
+
+    def restart():
+        reset()
+        e_dev.zero_()
+        state["e"] = 0
+
+    def close_window(n_in_window):
+        """Synchronise, account for the window's steps, restart where needed."""
+        if n_in_window == 0:
+            return
+        torch.cuda.synchronize()
+        n_now = kv.len()[0]
+        nacc = nacc_log[:n_in_window].cpu().numpy()
+        e = state["e"]
+        if args.decoding == "greedy":
+            toks = tok_log[:n_in_window].cpu().numpy()
+            for j in range(n_in_window):
+                if not np.array_equal(toks[j, :nacc[j]], truth[e: e + nacc[j]]):
+                    state["diverged"] += 1          # an arg-max flipped between the two GPU runs
+                    restart()
+                    return
+                e += int(nacc[j])
+                state["emitted"] += int(nacc[j])
+        else:                                       # nothing to compare a sampled stream with
+            e += int(nacc.sum())
+            state["emitted"] += int(nacc.sum())
+        assert n_now == prompt_len + e, "device length and logged acceptances disagree"
+        state["e"] = e
+        if e + SYNC * (H + 1) > room:
+            restart()
+            state["resets"] += 1
 
     def run_steps(n):
-        if args.decoding == "sampling":
-            return run_steps_sampling(n)
-        for _ in range(n):
-            e = state["e"]
-            if e >= n_table or prompt_len + e + H + 1 > W.kv_cap - 1:
-                reset()
-                state["resets"] += 1
-                e = state["e"] = 0
-            forced.copy_(table_dev[e: e + 1])
-            sd.spec_step(model, kv, tree, stop_words, forced_cand=forced, out=out)
-            tok_host.copy_(out.tokens, non_blocking=True)
-            n_now = kv.len()[0]                     # synchronises the stream
-            n_acc = n_now - prompt_len - e
-            if not np.array_equal(tok_host[0, :n_acc].numpy(), truth[e: e + n_acc]):
-                state["diverged"] += 1              # an arg-max flipped between the two GPU runs
-                reset()
-                state["e"] = 0
-                continue
-            state["e"] = e + n_acc
-            state["emitted"] += n_acc
+        done = 0
+        while done < n:
+            w = min(SYNC, n - done)
+            for j in range(w):
+                if args.decoding == "sampling":
+                    i = state["i"]
+                    sd.spec_step_typical(model, kv, tree, stop_words, u_dev[i: i + 1], out=out, **typical)
+                    state["i"] = i + 1
+                else:
+                    torch.index_select(table_dev, 0, e_dev, out=forced)
+                    sd.spec_step(model, kv, tree, stop_words, forced_cand=forced, out=out)
+                    tok_log[j].copy_(out.tokens[0])
+                    e_dev.add_(out.n_accept)
+                nacc_log[j: j + 1].copy_(out.n_accept)
+            close_window(w)
+            done += w
 
-    reset()
-    state["e"] = 0
+    restart()
     run_steps(args.warmup)
     torch.cuda.synchronize()
     state["emitted"] = 0
@@ -252,6 +277,7 @@ def main():
         "prefill_tokens_per_s": prompt_len / prefill_s,
         "step_hbm_frac": step_bytes / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9),
         "diverged_resets": state["diverged"], "sampling_replay_mismatches": replay_mismatches, "hip_graphs": args.graph,
+        "sync_every": SYNC,
         "roofline": {"kernel": "k_gemm_sk (weight-streaming MFMA GEMM, all projections)", "bound": "hbm",
                      "achieved": gemm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gemm_gbs / HBM_PEAK_GBS,
                      "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH if (args.workload == "7b" and args.layers is None) else None, "avg_launch_us": gemm_avg_us,
