@@ -44,7 +44,7 @@ def parse():
     ap.add_argument("--workload", default="7b", choices=["7b", "7b-long", "7b-batch8", "13b", "7b-h10", "tiny", "labels"],
                     help="labels = the training-side label construction alone (not the headline step); "
                          "7b-batch8 = eight ragged sequences, the model's own drafts, step time only")
-    ap.add_argument("--draft-schedule", default="after_verdict", choices=["after_verdict", "all_nodes"],
+    ap.add_argument("--draft-schedule", default="after_accept", choices=["after_accept", "all_nodes"],
                     help="all_nodes = draft heads on every tree row inside the verifying pass (measured slower here)")
     ap.add_argument("--layers", type=int, default=None, help="cut the depth (debugging only; result is labelled)")
     ap.add_argument("--draft", default="planted", choices=["planted", "random"])
@@ -260,7 +260,7 @@ def main():
                            typical=dict(typical, u=0.5) if args.decoding == "sampling" else None)
 
     kv_bytes = (prompt_len + state["e"] / 2) * 2.0 * shape.d_model * 2 * shape.n_layers
-    lm_reads = 2 if args.draft_schedule == "after_verdict" else 1 + -(-H * ((T + 31) // 32 * 32) // 128)
+    lm_reads = 2 if args.draft_schedule == "after_accept" else 1 + -(-H * ((T + 31) // 32 * 32) // 128)
     step_bytes = weight_bytes(shape, lm_reads) + kv_bytes
     res = {
         "metric": "verified_tree_tokens_per_s", "value": args.steps * T / elapsed, "unit": "tokens/s",

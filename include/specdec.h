@@ -225,14 +225,14 @@ int sd_build_labels(const int32_t* l0, int32_t batch, int32_t seq, int32_t n_hea
 /* Where in a step the draft heads run (Section III-B: every head predicts from the base model's
  * last hidden state at one position; which positions get evaluated is a schedule, not part of
  * the method, and both give the same candidates up to summation order).
- *   SD_DRAFT_AFTER_VERDICT (default): after the verdict, on the one row of every sequence that
+ *   SD_DRAFT_AFTER_ACCEPT (default): after acceptance, on the one row of every sequence that
  *     was kept last: H head rows per sequence through the shared LM head, a second read of it.
  *   SD_DRAFT_ALL_NODES: inside the verifying pass, on all tree rows (the schedule of a
  *     single-pass multi-head decoder): H * T head rows per sequence go through the LM head, and
  *     the H rows of the last kept node are ranked afterwards. sd_greedy_step and sd_prefill
  *     always use the first schedule (they have one candidate row).
  * Returns SD_ERR_NULL / SD_ERR_SHAPE (unknown value); takes effect from the next step.          */
-#define SD_DRAFT_AFTER_VERDICT 0
+#define SD_DRAFT_AFTER_ACCEPT 0
 #define SD_DRAFT_ALL_NODES     1
 int sd_set_draft_schedule(sd_model* m, int32_t schedule);
 

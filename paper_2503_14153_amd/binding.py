@@ -154,8 +154,8 @@ class Model:
         _check(lib().sd_set_graph_mode(self.handle, 1 if on else 0))
 
     def set_draft_schedule(self, schedule: str):
-        """"after_verdict" (default) or "all_nodes": where in a step the draft heads run."""
-        _check(lib().sd_set_draft_schedule(self.handle, {"after_verdict": 0, "all_nodes": 1}[schedule]))
+        """"after_accept" (default) or "all_nodes": where in a step the draft heads run."""
+        _check(lib().sd_set_draft_schedule(self.handle, {"after_accept": 0, "all_nodes": 1}[schedule]))
 
     def profile_begin(self, max_launches: int = 65536):
         _check(lib().sd_profile_begin(self.handle, max_launches))

@@ -68,7 +68,7 @@ struct sd_model {
     float2* mlpart;
     void *xn, *attn_x, *act, *q, *kt, *vt;
     void* xh;                                // draft-head rows of every tree row, in 128-row operand chunks
-    int draft_schedule = SD_DRAFT_AFTER_VERDICT;
+    int draft_schedule = SD_DRAFT_AFTER_ACCEPT;
     RowTable rt;
     int32_t *am, *g_parent, *g_depth, *g_rank;
     float4* row_stats;                     // [Mp]: per tree row, statistics for typical acceptance
@@ -365,7 +365,7 @@ extern "C" int sd_build_labels(const int32_t* l0, int32_t batch, int32_t seq, in
 
 extern "C" int sd_set_draft_schedule(sd_model* m, int32_t schedule) {
     if (!m) return fail(SD_ERR_NULL, "sd_set_draft_schedule: NULL model");
-    if (schedule != SD_DRAFT_AFTER_VERDICT && schedule != SD_DRAFT_ALL_NODES)
+    if (schedule != SD_DRAFT_AFTER_ACCEPT && schedule != SD_DRAFT_ALL_NODES)
         return fail(SD_ERR_SHAPE, "sd_set_draft_schedule: unknown schedule %d", schedule);
     m->draft_schedule = schedule;
     return SD_OK;
@@ -660,7 +660,7 @@ static void run_draft_heads(sd_model* m, sd_kv* kv, int B, uint32_t seq_mask, fl
 
 // The other schedule: the draft heads run on all B*Tp rows of the verifying pass (m->xn and m->hf
 // still hold the final norm's output), the shared LM head on all H*B*Tp head rows in chunks of 128
-// rows, and only the H rows of every sequence's last kept row (kv->last_row, set by the verdict) are
+// rows, and only the H rows of every sequence's last kept row (kv->last_row, set by the acceptance kernel) are
 // summed out of the partial tiles and ranked.
 static void run_draft_heads_all_rows(sd_model* m, sd_kv* kv, int B, int Tp, float* head_logits_out, hipStream_t s) {
     const sd_config& c = m->cfg;

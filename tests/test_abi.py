@@ -76,7 +76,7 @@ def test_error_codes_match_the_binding():
     assert d["SD_OK"] == 0
     for code, name in binding.SD_ERR.items():
         assert d[name] == code and code < 0
-    assert d["SD_DRAFT_AFTER_VERDICT"] == 0 and d["SD_DRAFT_ALL_NODES"] == 1
+    assert d["SD_DRAFT_AFTER_ACCEPT"] == 0 and d["SD_DRAFT_ALL_NODES"] == 1
     assert d["SD_LABELS_KEEP_BASE"] == 0 and d["SD_LABELS_KEEP_ALL"] == 1
 
 

@@ -49,7 +49,7 @@ def _random_draft(shape, B, seed):
 
 
 def _run_batch_steps(sd, shape, B, T, lens, cap, n_steps, tree_np=None, plant=True, fallback="keep_all",
-                     weights_device="cpu", schedule="after_verdict"):
+                     weights_device="cpu", schedule="after_accept"):
     weights = wl.make_weights(shape, device=weights_device)
     w64 = lockstep.weights_to_f64(weights)
     Tp = (T + 31) // 32 * 32

@@ -70,7 +70,7 @@ def test_two_schedules_agree(sd):
     sd.prefill(model, kv_b, toks, [len(prompt)])
     worst = 0.0
     for step in range(8):
-        model.set_draft_schedule("after_verdict")
+        model.set_draft_schedule("after_accept")
         a = sd.spec_step(model, kv_a, tree, words, want_head_logits=True)
         model.set_draft_schedule("all_nodes")
         b = sd.spec_step(model, kv_b, tree, words, want_head_logits=True)
