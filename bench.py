@@ -92,7 +92,7 @@ def main():
     cpu_keep = None
     if not args.no_cpu_baseline:
         names = ["embed", "lm_head", "final_norm"] + [f"medusa{i}.{x}" for i in range(H) for x in "wb"]
-        names += [n for n in weights if n.split(".")[0] in ("l0", "l1", "l2", "l3", "l4", "l5")]
+        names += [n for n in weights if n.split(".")[0] in tuple(f"l{i}" for i in range(8))]
         cpu_keep = {n: weights[n].cpu() for n in names}
     model = sd.Model(shape, weights, max_rows=max(128, ((T + 31) // 32) * 32))   # 128: prompt chunks of 128 rows
     del weights
@@ -407,7 +407,7 @@ def cpu_baseline(wl, shape, cpu_keep, T, tree_np, stop, n_cache, typical=None):
     from oracle import specdec_oracle as orc
 
     w64 = {n: t.double().numpy() for n, t in cpu_keep.items()}
-    depth_hi = min(6, shape.n_layers)
+    depth_hi = min(8, shape.n_layers)
     depth_lo = max(1, depth_hi // 2)
 
     def one_step(L):
@@ -425,7 +425,7 @@ def cpu_baseline(wl, shape, cpu_keep, T, tree_np, stop, n_cache, typical=None):
         return time.perf_counter() - t0
 
     one_step(1)                                      # warm-up: BLAS threads, page faults
-    reps = 9
+    reps = 21
     t_lo = sorted(one_step(depth_lo) for _ in range(reps))[reps // 2]
     t_hi = sorted(one_step(depth_hi) for _ in range(reps))[reps // 2]
     if depth_hi > depth_lo:
