@@ -95,7 +95,6 @@ def test_two_schedules_agree(sd):
 
 
 def test_unknown_schedule_is_refused(sd):
-    import ctypes as C
     shape = _bf16_shape("tiny")
     _, weights, w64, model, kv, prompt, stop, words, tree_np, tree = _setup(sd, shape, 8, 64, 16)
     assert sd.lib().sd_set_draft_schedule(model.handle, 7) != 0

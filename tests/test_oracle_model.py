@@ -7,7 +7,6 @@ mathematical formulation (complex rotation), a closed form, or explicit loops on
 import math
 
 import numpy as np
-import pytest
 import torch
 import torch.nn.functional as F
 
