@@ -192,6 +192,37 @@ def test_errors_leave_state_untouched(sd):
     assert e.value.name == "SD_ERR_KV_FULL" and kv.len() == [20]
 
 
+def test_step_that_exactly_fits_the_cache(sd):
+    """cap = prompt + H + 1 (not a multiple of the 32-row cache blocks): the step is accepted, matches the
+    oracle up to the last cache row, and the one after it is refused without touching anything."""
+    shape = _bf16_shape("tiny")
+    cap = 21 + shape.n_medusa + 1
+    lockstep, weights, w64, model, kv, prompt, stop, words, tree_np, tree = _setup(sd, shape, 21, cap, 16)
+    rep = lockstep.Report()
+    st, root, cand = _prefill_both(sd, lockstep, model, kv, w64, shape, prompt, cap, rep, 0.05)
+    truth = orc.prefill(w64, shape, prompt, cap + 8)
+    for _ in range(shape.n_medusa + 1):
+        orc.greedy_step(w64, shape, truth)
+
+    def plant(s):                                  # the whole chain is right: H + 1 tokens unless a stop cuts it
+        c = np.array(s.cand, np.int32).copy()
+        for i in range(shape.n_medusa):
+            want = truth.emitted[1 + i]
+            dup = np.nonzero(c[i] == want)[0]
+            if dup.size:
+                c[i, dup[0]] = c[i, 0]
+            c[i, 0] = want
+        return c
+
+    rep = lockstep.lockstep_spec(model, kv, tree, tree_np, stop, words, w64, shape, st, 1, "keep_all", plant, rep=rep)
+    assert rep.steps == 1 and rep.raw[0] == shape.n_medusa + 1
+    n = kv.len()[0]
+    assert n == 21 + rep.accepted[0] <= cap
+    with pytest.raises(sd.SpecDecError) as e:
+        sd.spec_step(model, kv, tree, words)
+    assert e.value.name == "SD_ERR_KV_FULL" and kv.len() == [n]
+
+
 def test_graph_mode_replays_equal_eager(sd):
     """Graph mode: the captured step, replayed many times with eager work and synchronisations
     in between, gives bit-identical outputs to the eager path (same deterministic kernels)."""
