@@ -136,6 +136,42 @@ def test_tiny_shape_lockstep_32_steps(sd, fallback):
     assert st.emitted == truth[: len(st.emitted)]          # lossless, by the oracle's own stream
 
 
+def test_tiny_shape_against_the_fp32_oracle(sd):
+    """configs[0] as specified (fp32 weights, fp32 cache) on the oracle's side, against the device path,
+    which stores weights and K/V rows as bf16: the storage rounding itself stays inside the logits bounds
+    (2e-2 max-abs, 1e-2 relative), so the tiny configuration is met without an fp32 device path."""
+    import dataclasses
+    shape32 = wl.preset("tiny").model
+    assert shape32.dtype == "f32"
+    from tests import lockstep
+    weights = wl.make_weights(shape32)
+    assert weights["l0.wqkv"].dtype == torch.float32
+    w64 = lockstep.weights_to_f64(weights)
+    model = sd.Model(dataclasses.replace(shape32, dtype="bf16"), {k: v.bfloat16().cuda() for k, v in weights.items()}, 64)
+    kv = sd.KVCache(model, 1, 256)
+    prompt = wl.zipf_prompt(shape32.vocab, 64)
+    stop = wl.stop_set(shape32.vocab, 0.2)
+    words = torch.from_numpy(wl.pack_mask_words(stop).view(np.int32)).cuda()
+    tree_np = wl.default_tree(16, shape32.n_medusa, shape32.topk)
+    tree = sd.Tree(*tree_np, shape32.n_medusa, shape32.topk)
+    rep = lockstep.Report()
+    st, root, cand = _prefill_both(sd, lockstep, model, kv, w64, shape32, prompt, 256, rep, 0.05)
+    g = orc.prefill(w64, shape32, prompt, 256)
+    for _ in range(150):
+        orc.greedy_step(w64, shape32, g)
+    truth = g.emitted
+    rng = np.random.default_rng(wl.SEEDS["force"])
+
+    def plant(s):
+        e = len(s.emitted)
+        return wl.plant_drafts(s.cand, np.array(truth[e + 1: e + 1 + shape32.n_medusa]), (0.9, 0.8, 0.7), rng)
+
+    rep = lockstep.lockstep_spec(model, kv, tree, tree_np, stop, words, w64, shape32, st, 32, "keep_all", plant, rep=rep)
+    print(f"\n[tiny, fp32 oracle] {rep}")
+    assert rep.steps == 32 and max(rep.accepted) >= 3
+    assert st.emitted == truth[: len(st.emitted)]
+
+
 def test_7b_width_two_layers_lockstep(sd):
     """Full 7B width and vocabulary, depth cut to 2 layers: prefill 100 tokens (two ragged
     chunks), then speculative steps on the 64-node tree with random heads and planted drafts."""
