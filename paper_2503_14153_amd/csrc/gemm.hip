@@ -15,6 +15,8 @@
 // cores idle most of the time in an HBM-bound kernel, each activation enters as a two-term
 // bf16 expansion x = hi + lo (two MFMAs per weight fragment), which keeps ~16 mantissa bits
 // of x and makes the product exact up to fp32 accumulation.
+#include <cstdio>
+#include <cstdlib>
 #include "sd_internal.h"
 
 // ------------------------------------------------------------------------------------------
@@ -45,9 +47,8 @@ void launch_pack_weight(const void* src, void* dst, int N, int K, int nb_offset,
 }
 
 // ------------------------------------------------------------------------------------------
-// Balanced streaming ("stream-K") over MT = 1 or 2 row blocks of 32 rows (this kernel) or four (the
-// kernel after it); more rows are done in passes of four row blocks (the weights are then streamed
-// once per pass).
+// Balanced streaming ("stream-K") over MT = 1, 2 or 8 row blocks of 32 rows (this kernel) or four (the
+// kernel after it).
 //
 // The work of one GEMM is the list of units (column group of 256 outputs, contraction block),
 // contraction block fastest; workgroup g of G takes the contiguous range [g*U/G, (g+1)*U/G),
@@ -100,12 +101,15 @@ static __device__ inline SkIter sk_walk_next(SkWalk& w, int KB) {
 }
 
 template <int MT>
-__global__ __launch_bounds__(512, 2) void k_gemm_sk(const bf16x8* __restrict__ Xp, const bf16x8* __restrict__ Wp,
+__global__ __launch_bounds__(512, MT == 8 ? 1 : 2) void k_gemm_sk(const bf16x8* __restrict__ Xp, const bf16x8* __restrict__ Wp,
                                                     const bf16x8* __restrict__ zfrag, float* __restrict__ out,
                                                     int KB, int NB, int ldo, size_t slot_stride, int upw, int rem,
                                                     uint32_t kb_magic, const int32_t* __restrict__ slot0_tab) {
-    static_assert(MT == 1 || MT == 2, "four row blocks: k_gemm_sk_wide");
-    constexpr int R = 16;                            // ring depth
+    static_assert(MT == 1 || MT == 2 || MT == 8, "four row blocks: k_gemm_sk_wide");
+    // ring depth. Eight row blocks: the 128 accumulators leave two waves per SIMD room for a ring of
+    // 4 steps (210 registers), and a step then holds 16 MFMAs, so 4 steps cover the same time as 16 do
+    // with two row blocks (rings of 6 and 8 steps measured slower: 62.3 and 62.8 us against 59.8)
+    constexpr int R = MT == 8 ? 4 : 16;
     constexpr int XK = 8 / MT;                       // contraction blocks per chunk
     constexpr int CPI = R / XK;                      // chunks per outer iteration (2 or 4)
     constexpr int XF = 16;                           // fragments per chunk = XK * MT * 2
@@ -228,27 +232,24 @@ __global__ __launch_bounds__(512, 2) void k_gemm_sk(const bf16x8* __restrict__ X
 }
 
 // ------------------------------------------------------------------------------------------
-// Four row blocks (128 rows per pass). The kernel above, instantiated for four row blocks, needs
-// more registers than two waves per SIMD can have (it spills) and issues eight LDS fragment reads
-// and eight MFMAs, in dependent pairs, per weight fragment: it is bound by those, not by HBM.
+// Four row blocks (128 rows). The kernel above at four row blocks issues eight LDS fragment reads and
+// eight MFMAs per weight fragment and is bound by those, not by HBM; the form below measured a little
+// faster there (54.1 against 54.8 us per launch at the 13B shape), the one above at eight row blocks.
 // Here a workgroup is four waves, one per SIMD, so that a wave may hold up to 512 registers; wave
 // w owns column blocks 2w and 2w+1 of the same 256-column group, every activation fragment read
 // from LDS feeds two weight fragments (half the LDS traffic per weight byte), and the four MFMAs
 // of a row block alternate between its two accumulators, so that none waits for the one before
 // it. Units, ring, segments, zero page and slots exactly as above.
-// PASSES: the activation holds more row blocks than one launch multiplies; x_kb_units = 16-byte units
-// between contraction blocks of the packed activation (all its row blocks).
 #define SKW_THREADS 256
 #ifndef SKW_R
 #define SKW_R 6
 #endif
-template <bool PASSES>
 __global__ __launch_bounds__(SKW_THREADS, 1) void k_gemm_sk_wide(const bf16x8* __restrict__ Xp,
                                                                  const bf16x8* __restrict__ Wp,
                                                                  const bf16x8* __restrict__ zfrag,
                                                                  float* __restrict__ out, int KB, int NB, int ldo,
                                                                  size_t slot_stride, int upw, int rem, uint32_t kb_magic,
-                                                                 const int32_t* __restrict__ slot0_tab, int x_kb_units) {
+                                                                 const int32_t* __restrict__ slot0_tab) {
     constexpr int MT = 4, CB = 2, R = SKW_R, XK = 2, CPI = R / XK, XF = XK * MT * 2, XP = XF * 64 / SKW_THREADS;
     static_assert(CPI == 3, "three chunks per ring length, three LDS buffers");
     __shared__ bf16x8 xs[3][XF * 64];
@@ -271,13 +272,11 @@ __global__ __launch_bounds__(SKW_THREADS, 1) void k_gemm_sk_wide(const bf16x8* _
         steps = steps < 0 ? 0 : (steps > XK ? XK : steps);
         constexpr int PER_KB = MT * 2 * 64;
         const int limit = steps * PER_KB;
-        const int kb_units = PASSES ? x_kb_units : PER_KB;
-        const bf16x8* base = Xp + (size_t)(I.kb + c * XK) * kb_units;
+        const bf16x8* base = Xp + (size_t)(I.kb + c * XK) * PER_KB;
 #pragma unroll
         for (int p = 0; p < XP; ++p) {
             const int i = p * SKW_THREADS + tid;
-            const bf16x8* src = PASSES ? base + (size_t)(i / PER_KB) * kb_units + (i % PER_KB) : base + i;
-            dst[p] = *((i < limit) ? src : zl);
+            dst[p] = *((i < limit) ? base + i : zl);
         }
     };
     auto xstore = [&](const bf16x8(&src)[XP], int buf) {
@@ -438,7 +437,6 @@ void launch_reduce_selected(PartView pv, float* dst, const int32_t* sel, int B, 
 
 // ------------------------------------------------------------------------------------------
 #define SK_MAX_WG 256       // one workgroup of 8 waves per CU
-#define SK_MAX_MT 4         // row blocks per pass
 #ifndef SK_SMALL_U
 #define SK_SMALL_U (16 * SK_MAX_WG * 2)   // (column groups x contraction blocks) up to which half the workgroups are used
 #endif
@@ -482,36 +480,25 @@ PartView launch_gemm(const GemmPlan& p, const void* Xp, const void* Wp, const vo
     pv.slot_stride = (size_t)p.MB * 32 * pv.ld;
     pv.cnt = p.uniform ? nullptr : p.cnt_dev;         // NULL: nmax slots everywhere, the consumer need not look it up
     pv.nmax = p.slots;
-    const int MT = p.MB < SK_MAX_MT ? p.MB : SK_MAX_MT;
-    const int x_kb_units = p.MB * 2 * 64;
     const uint32_t kb_magic = (uint32_t)((0x100000000ull + (uint64_t)p.KB - 1) / (uint64_t)p.KB);
-    const int passes = p.MB / MT;
-    for (int r = 0; r < passes; ++r) {                 // passes of MT row blocks
-        const bf16x8* xp = (const bf16x8*)Xp + (size_t)r * MT * 2 * 64;
-        float* o = out + (size_t)r * MT * 32 * pv.ld;
-        hipEvent_t e0 = r == 0 ? ev0 : nullptr, e1 = r == passes - 1 ? ev1 : nullptr;
-#define SK_ARGS xp, (const bf16x8*)Wp, (const bf16x8*)zfrag, o, p.KB, p.NB, pv.ld, pv.slot_stride, p.upw, p.rem, kb_magic, p.slot0_dev
-#define SK_LAUNCH(MT_)                                                                                     \
-        do {                                                                                               \
-            if (e0 || e1)                                                                                  \
-                hipExtLaunchKernelGGL((k_gemm_sk<MT_>), dim3(p.G), dim3(512), 0, s, e0, e1, 0, SK_ARGS);   \
-            else                                                                                           \
-                hipLaunchKernelGGL((k_gemm_sk<MT_>), dim3(p.G), dim3(512), 0, s, SK_ARGS);                 \
-        } while (0)
-#define SK_LAUNCH_WIDE(PASSES_)                                                                             \
-        do {                                                                                               \
-            if (e0 || e1)                                                                                  \
-                hipExtLaunchKernelGGL((k_gemm_sk_wide<PASSES_>), dim3(p.G), dim3(SKW_THREADS), 0, s, e0, e1, 0, SK_ARGS, x_kb_units); \
-            else                                                                                           \
-                hipLaunchKernelGGL((k_gemm_sk_wide<PASSES_>), dim3(p.G), dim3(SKW_THREADS), 0, s, SK_ARGS, x_kb_units); \
-        } while (0)
-        if (MT == 1) SK_LAUNCH(1);
-        else if (MT == 2) SK_LAUNCH(2);
-        else if (p.MB == MT) SK_LAUNCH_WIDE(false);
-        else SK_LAUNCH_WIDE(true);
-#undef SK_LAUNCH_WIDE
+#define SK_ARGS (const bf16x8*)Xp, (const bf16x8*)Wp, (const bf16x8*)zfrag, out, p.KB, p.NB, pv.ld, pv.slot_stride, p.upw, p.rem, kb_magic, p.slot0_dev
+#define SK_LAUNCH(KERNEL_, THREADS_)                                                                       \
+    do {                                                                                                   \
+        if (ev0 || ev1)                                                                                    \
+            hipExtLaunchKernelGGL(KERNEL_, dim3(p.G), dim3(THREADS_), 0, s, ev0, ev1, 0, SK_ARGS);         \
+        else                                                                                               \
+            hipLaunchKernelGGL(KERNEL_, dim3(p.G), dim3(THREADS_), 0, s, SK_ARGS);                         \
+    } while (0)
+    switch (p.MB) {                                    // the plan's row blocks: 1, 2, 4 or 8, one pass each
+    case 1: SK_LAUNCH(k_gemm_sk<1>, 512); break;
+    case 2: SK_LAUNCH(k_gemm_sk<2>, 512); break;
+    case 4: SK_LAUNCH(k_gemm_sk_wide, SKW_THREADS); break;
+    case 8: SK_LAUNCH(k_gemm_sk<8>, 512); break;
+    default:
+        fprintf(stderr, "libspecdec: internal error: GEMM plan with %d row blocks\n", p.MB);
+        abort();
+    }
 #undef SK_LAUNCH
 #undef SK_ARGS
-    }
     return pv;
 }

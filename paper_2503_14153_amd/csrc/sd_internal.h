@@ -126,8 +126,8 @@ void launch_pack_weight(const void* src, void* dst, int N, int K, int nb_offset,
 void gemm_plan_make(GemmPlan* p, int MB, int KB, int NB, int32_t* cnt_host, int32_t* slot0_host);
 // out must hold plan.slots * (MB*32) * (NB*32) floats; zfrag: 1 KiB of zeros (device);
 // returns the view consumers read
-// ev0 / ev1 (both or neither): events that receive the kernel's own start and end time stamps
-// (first pass's start, last pass's end), for per-kernel timing without launch gaps
+// ev0 / ev1 (both or neither): events that receive the kernel's own start and end time stamps,
+// for per-kernel timing without launch gaps
 PartView launch_gemm(const GemmPlan& p, const void* Xp, const void* Wp, const void* zfrag, float* out, hipStream_t s,
                      hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 void launch_reduce_slots(PartView pv, float* dst, int rows, hipStream_t s);
