@@ -94,7 +94,7 @@ def main():
         names = ["embed", "lm_head", "final_norm"] + [f"medusa{i}.{x}" for i in range(H) for x in "wb"]
         names += [n for n in weights if n.split(".")[0] in tuple(f"l{i}" for i in range(8))]
         cpu_keep = {n: weights[n].cpu() for n in names}
-    model = sd.Model(shape, weights, max_rows=max(128, ((T + 31) // 32) * 32))   # 128: prompt chunks of 128 rows
+    model = sd.Model(shape, weights, max_rows=256)       # 256: prompt chunks of 256 rows
     del weights
     torch.cuda.empty_cache()
     kv = sd.KVCache(model, 1, W.kv_cap)

@@ -687,7 +687,7 @@ extern "C" int sd_prefill(sd_model* m, sd_kv* kv, const int32_t* tokens, const i
     const int B = kv->B;
     hipStream_t s = (hipStream_t)stream;
     int Tp = (m->max_rows / B) / 32 * 32;
-    if (Tp > 128) Tp = 128;                            // prompt chunks of up to 128 rows (one pass of the 128-row GEMM)
+    if (Tp > 256) Tp = 256;                            // prompt chunks of up to 256 rows (the widest GEMM)
     if (Tp < 32) return fail(SD_ERR_SHAPE, "sd_prefill: max_rows %d too small for batch %d", m->max_rows, B);
     int maxlen = 0;
     for (int b = 0; b < B; ++b) {

@@ -262,10 +262,11 @@ def test_prompt_of_one_token_and_continued_prefill(sd):
     assert kv.len() == [1] and int(kv.get_draft()[0][0]) == st.root_tok
 
 
-@pytest.mark.parametrize("name,prompt_len,max_rows", [("tiny", 300, 128), ("tiny", 129, 96), ("7b", 200, 128)])
-def test_prefill_in_chunks_of_up_to_128_rows(sd, name, prompt_len, max_rows):
-    """Prompt chunks follow the model's max_rows (128 -> 128 + 128 + 44 rows, 96 -> 96 + 33): committed K/V rows and
-    the draft state after the prompt against the oracle's causal forward."""
+@pytest.mark.parametrize("name,prompt_len,max_rows", [("tiny", 300, 128), ("tiny", 129, 96), ("7b", 200, 128),
+                                                      ("tiny", 600, 256), ("7b", 300, 256)])
+def test_prefill_in_chunks_of_up_to_256_rows(sd, name, prompt_len, max_rows):
+    """Prompt chunks follow the model's max_rows (128 -> 128 + 128 + 44 rows, 96 -> 96 + 33, 256 -> 256 + 256 + 88
+    or 256 + 44): committed K/V rows and the draft state after the prompt against the oracle's causal forward."""
     shape = _shape(name, 2)
     weights = wl.make_weights(shape)
     w64 = lockstep.weights_to_f64(weights)
