@@ -67,7 +67,7 @@ struct sd_model {
     float *x, *part, *logits, *hlogits, *hf, *h_rows, *opart;
     float2* mlpart;
     void *xn, *attn_x, *act, *q, *kt, *vt;
-    void* xh;                                // draft-head rows of every tree row, in 128-row operand chunks
+    void* xh;                                // draft-head rows of every tree row, in 256-row operand chunks
     int draft_schedule = SD_DRAFT_AFTER_ACCEPT;
     RowTable rt;
     int32_t *am, *g_parent, *g_depth, *g_rank;
@@ -263,7 +263,7 @@ extern "C" int sd_model_create(const sd_config* cfg, const sd_weights* w, int32_
     size_t w_tok = wtake((size_t)Mp * 4), w_pos = wtake((size_t)Mp * 4), w_anc = wtake((size_t)Mp * SD_ANC_WORDS * 4);
     size_t w_cs = wtake((size_t)Mp * (hd / 2) * 8), w_am = wtake((size_t)Mp * 4), w_g = wtake(3 * 4);
     size_t w_rs = wtake((size_t)Mp * 16);
-    size_t w_xh = wtake(align_up((size_t)H * Mp, 128) * d * 4);
+    size_t w_xh = wtake(align_up((size_t)H * Mp, 256) * d * 4);
     size_t w_zs = wtake((size_t)ceil_div(V, 32) * 4), w_zf = wtake(1024);
     e = hipMalloc((void**)&m->work, wz);
     if (e == hipSuccess) e = hipMalloc((void**)&m->plan_cnt, cnt_all.size() * 4);
@@ -659,12 +659,12 @@ static void run_draft_heads(sd_model* m, sd_kv* kv, int B, uint32_t seq_mask, fl
 }
 
 // The other schedule: the draft heads run on all B*Tp rows of the verifying pass (m->xn and m->hf
-// still hold the final norm's output), the shared LM head on all H*B*Tp head rows in chunks of 128
+// still hold the final norm's output), the shared LM head on all H*B*Tp head rows in chunks of 256
 // rows, and only the H rows of every sequence's last kept row (kv->last_row, set by the acceptance kernel) are
 // summed out of the partial tiles and ranked.
 static void run_draft_heads_all_rows(sd_model* m, sd_kv* kv, int B, int Tp, float* head_logits_out, hipStream_t s) {
     const sd_config& c = m->cfg;
-    const int d = c.d_model, H = c.n_medusa, M = B * Tp, MB = pow2_blocks(M), R = H * M, CH = 128;
+    const int d = c.d_model, H = c.n_medusa, M = B * Tp, MB = pow2_blocks(M), R = H * M, CH = 256;
     PartView pm = run_gemm(m, m->xn, m->medusa_w, m->part, MB, m->KBd, m->NBmed, H * d, s);
     const int n_chunks = ceil_div(R, CH), MBlast = pow2_blocks(R - (n_chunks - 1) * CH);
     launch_medusa_act(pm, m->hf, m->medusa_b, M, H, d, m->xh, CH, CH / 32, MBlast, s);

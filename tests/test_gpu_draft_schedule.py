@@ -47,10 +47,10 @@ def test_tiny_shape_lockstep_all_nodes(sd):
 
 
 @pytest.mark.parametrize("name,B,T,lens,cap", [
-    ("7b", 1, 64, [300], 512),                            # 256 head rows: two full chunks
+    ("7b", 1, 64, [300], 512),                            # 256 head rows: one full chunk
     ("7b-batch8", 8, 32, [64, 100, 150, 200, 260, 300, 350, 400], 512),   # 1024 head rows
-    ("13b", 1, 129, [300], 512),                          # 5 x 160 = 800 rows: last chunk of one row block
-    ("7b-h10", 1, 200, [200], 512),                       # 10 x 224 = 2240 rows: last chunk of two row blocks
+    ("13b", 1, 129, [300], 512),                         # 5 x 160 = 800 rows: three chunks of 256 and one of 32
+    ("7b-h10", 1, 200, [200], 512),                      # 10 x 224 = 2240 rows: eight chunks of 256 and one of 192
 ])
 def test_all_nodes_schedule_matches_oracle(sd, name, B, T, lens, cap):
     shape = _shape(name)
