@@ -1,5 +1,5 @@
 """GPU parity of the other draft-head schedule: heads on every tree row inside the verifying pass
-(H * T rows per sequence through the shared LM head in 128-row chunks, the last kept node's rows
+(H * T rows per sequence through the shared LM head in 256-row chunks, the last kept node's rows
 ranked afterwards). The oracle is the same step: what a step computes does not depend on the
 schedule, so logits, verdict, committed K/V, head logits and next candidates are held to the
 same bars as the default schedule, and the two schedules are compared with each other."""
