@@ -63,7 +63,8 @@ __global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp
                                                    const bf16x8* Kt, const bf16x8* Vt, const int32_t* __restrict__ kv_len,
                                                    const uint32_t* __restrict__ anc, float* __restrict__ opart,
                                                    float2* __restrict__ mlpart, int nh, int Tp, int cap_blocks,
-                                                   int ncparts, int per, int tree_sep, float scale_log2) {
+                                                   int ncparts, int per, int tree_sep, float scale_log2,
+                                                   int xcd_stride, int nseq) {
     constexpr int KK = HD / 16;        // contraction steps of QK^T = K fragments per block
     constexpr int EB = HD / 32;        // 32-wide output blocks of PV
     constexpr int NV = 2 * EB;         // V fragments per block
@@ -76,14 +77,30 @@ __global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp
     __shared__ __attribute__((aligned(1024))) bf16x8 lds[QF * 64 + 4 * WAVE_UNITS];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, tl = lane & 31;
-    const int part = blockIdx.x;
     const int TB = Tp / 32, TG = TB / TBW;
-    const int h = blockIdx.y / TG, tg = blockIdx.y % TG;
-    const int b = blockIdx.z;
+    const int nparts = ncparts + (tree_sep ? 1 : 0);
+    int part, h, tg, b;
+    if (xcd_stride == 0) {                             // grid (part, head x query group, sequence)
+        part = blockIdx.x;
+        h = blockIdx.y / TG;
+        tg = blockIdx.y % TG;
+        b = blockIdx.z;
+    } else {
+        // Several query groups: one-dimensional grid in which the query groups of one (sequence, head, part)
+        // lie xcd_stride workgroups apart. Workgroups are dealt to the eight XCDs round-robin and the stride
+        // is a multiple of eight, so the groups that read the same K/V blocks share an L2 and those blocks
+        // come from HBM once. Workgroups of the padding leave at once.
+        tg = blockIdx.x / xcd_stride;
+        const int combo = blockIdx.x - tg * xcd_stride;
+        if (combo >= nparts * nh * nseq) return;
+        part = combo % nparts;
+        const int hb = combo / nparts;
+        h = hb % nh;
+        b = hb / nh;
+    }
     bf16x8* qs = lds;
     const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) bf16x8*)lds);
     const uint32_t myq_addr = __builtin_amdgcn_readfirstlane(lds_addr + wave * QW * 1024);
-    const int nparts = ncparts + (tree_sep ? 1 : 0);
     const bool has_cache = part < ncparts;
     const int ntree = (part == nparts - 1) ? tg * TBW + TBW : 0;   // later tree blocks hold no ancestors
 
@@ -339,9 +356,15 @@ void launch_tree_attn(const void* q_packed, const void* kc, const void* vc, cons
     const float scale_log2 = 1.4426950408889634f / sqrtf((float)hd);
     const int TB = Tp / 32;
     const int TBW = (TB % 2 == 0) ? 2 : 1;
-    dim3 grid(ncparts + (tree_sep ? 1 : 0), nh * (TB / TBW), B);
+    const int nparts = ncparts + (tree_sep ? 1 : 0), TG = TB / TBW;
+    dim3 grid(nparts, nh * TG, B);
+    int xcd_stride = 0;
+    if (TG > 1) {                                      // query groups of one head on one XCD (see the kernel)
+        xcd_stride = (nparts * nh * B + 7) / 8 * 8;
+        grid = dim3(xcd_stride * TG, 1, 1);
+    }
 #define ATT_ARGS (const bf16x8*)q_packed, (const bf16x8*)kc, (const bf16x8*)vc, (const bf16x8*)kt, (const bf16x8*)vt, \
-                 kv_len, anc, opart, mlpart, nh, Tp, cap_blocks, ncparts, per, tree_sep, scale_log2
+                 kv_len, anc, opart, mlpart, nh, Tp, cap_blocks, ncparts, per, tree_sep, scale_log2, xcd_stride, B
 #define ATT(HD_, TBW_, AW_)                                                                                          \
     do {                                                                                                        \
         if (ev0 || ev1)                                                                                         \
