@@ -182,6 +182,107 @@ def test_medusa_head_block_matches_torch_formulation():
     assert list(cand[1]) == list(torch.topk(torch.from_numpy(got[1]), shape.topk).indices.numpy())
 
 
+# ---- the draft-head block pinned against what the mathematics fixes (Section III-B: the heads sit on the
+# ---- base model's last hidden state, i.e. on what the LM head consumes). None of these re-type the formula:
+# ---- each one picks weights for which the block has a value known in advance.
+def _tiny_f64_heads():
+    shape, w = _tiny()
+    return shape, {k: v.double() for k, v in w.items()}
+
+
+def test_medusa_head_with_zero_weights_is_the_base_lm_head():
+    """W_i = 0, b_i = 0: SiLU(0) = 0, so every head's logits ARE the base logits lm_head @ h, bit for bit."""
+    shape, w = _tiny_f64_heads()
+    h = RNG.standard_normal(shape.d_model)
+    for i in range(shape.n_medusa):
+        w[f"medusa{i}.w"] = torch.zeros_like(w[f"medusa{i}.w"])
+        w[f"medusa{i}.b"] = torch.zeros_like(w[f"medusa{i}.b"])
+    base = w["lm_head"].numpy() @ h
+    got = orc.medusa_logits(w, shape, h)
+    for i in range(shape.n_medusa):
+        assert np.array_equal(got[i], base)
+
+
+def test_medusa_head_bias_saturates_silu_on_both_sides():
+    """W_i = 0 and a bias far in SiLU's linear range: SiLU(40) = 40 to 2e-16, so logits = lm_head @ (h + b);
+    far in its flat range, SiLU(-40) = -2e-16: logits = base logits. A bias added outside the SiLU, a missing
+    residual or a missing bias each fail one of the two."""
+    shape, w = _tiny_f64_heads()
+    h = RNG.standard_normal(shape.d_model)
+    lm = w["lm_head"].numpy()
+    for i in range(shape.n_medusa):
+        w[f"medusa{i}.w"] = torch.zeros_like(w[f"medusa{i}.w"])
+    bias = 40.0 + RNG.random(shape.d_model)
+    for i in range(shape.n_medusa):
+        w[f"medusa{i}.b"] = torch.from_numpy(bias * (i + 1))
+    got = orc.medusa_logits(w, shape, h)
+    for i in range(shape.n_medusa):
+        assert np.allclose(got[i], lm @ (h + bias * (i + 1)), rtol=0, atol=1e-12)
+    for i in range(shape.n_medusa):
+        w[f"medusa{i}.b"] = torch.from_numpy(-bias)
+    got = orc.medusa_logits(w, shape, h)
+    for i in range(shape.n_medusa):
+        assert np.allclose(got[i], lm @ h, rtol=0, atol=1e-12)
+
+
+def test_medusa_head_on_a_one_hot_row_with_identity_lm_head_by_hand():
+    """d = V = 4, lm_head = I, h = e_2: head i's logits are e_2 + SiLU(column 2 of W_i + b_i), and with
+    pre-activations 0, ln 3 and -ln 3 the SiLU values are 0, (3/4) ln 3 and -(1/4) ln 3 (sigmoid(ln 3) = 3/4)."""
+    shape = wl.ModelShape(1, 4, 1, 4, 16, 4, 2, 2, "f32", 1e4)
+    ln3 = math.log(3.0)
+    W0 = np.zeros((4, 4)); W0[:, 2] = [ln3, 0.0, -ln3, 2 * ln3]          # what e_2 selects
+    W0[:, 0] = 7.0                                                      # must not matter for h = e_2
+    b0 = np.array([0.0, ln3, 0.0, -3 * ln3])                             # pre-activations: ln3, ln3, -ln3, -ln3
+    W1 = np.zeros((4, 4)); W1[1, 2] = -ln3
+    b1 = np.zeros(4)
+    w = {"lm_head": np.eye(4), "medusa0.w": W0, "medusa0.b": b0, "medusa1.w": W1, "medusa1.b": b1}
+    got = orc.medusa_logits(w, shape, np.array([0.0, 0.0, 1.0, 0.0]))
+    want0 = np.array([0.75 * ln3, 0.75 * ln3, 1.0 - 0.25 * ln3, -0.25 * ln3])
+    want1 = np.array([0.0, -0.25 * ln3, 1.0, 0.0])
+    assert np.allclose(got[0], want0, rtol=0, atol=1e-15)
+    assert np.allclose(got[1], want1, rtol=0, atol=1e-15)
+    # a transposed W_i would read row 2 of W0 instead of its column 2
+    assert not np.allclose(got[0], np.array([0.0, 0.0, 1.0, 0.0]) + orc.silu(W0[2] + b0))
+
+
+def test_draft_heads_read_the_final_norm_output_of_the_last_kept_row():
+    """With W_i = 0 and b_i = 0 a head's logits equal the base logits of the row it reads. So after a
+    prefill the heads' candidates must be the base model's own top-k at the last prompt row, and after a
+    speculative step the top-k at the last KEPT node: heads fed the un-normalised residual stream, another
+    row, or another node would give other lists (the final norm rescales rows by different factors, and
+    the LM head of x is not the LM head of norm(x) * gain once the gain is not constant)."""
+    shape, w = _tiny_f64_heads()
+    w["final_norm"] = torch.from_numpy(0.5 + RNG.random(shape.d_model))  # a gain that is not constant
+    for i in range(shape.n_medusa):
+        w[f"medusa{i}.w"] = torch.zeros_like(w[f"medusa{i}.w"])
+        w[f"medusa{i}.b"] = torch.zeros_like(w[f"medusa{i}.b"])
+    prompt = wl.zipf_prompt(shape.vocab, 12)
+    st = orc.prefill(w, shape, prompt, 64)
+    kv0 = orc.KVCache.empty(shape, 64)
+    logits, _, _, _ = orc.forward_rows(w, shape, prompt, np.arange(12), np.tril(np.ones((12, 12), bool)), kv0)
+    want = orc.topk_ids(logits[-1], shape.topk)
+    assert st.root_tok == want[0]
+    for i in range(shape.n_medusa):
+        assert list(st.cand[i]) == list(want)
+    # one speculative step whose drafts are the base model's own continuation, so several nodes are kept
+    tree = wl.default_tree(8, shape.n_medusa, shape.topk)
+    stop = np.zeros(shape.vocab, bool)
+    g = orc.prefill(w, shape, prompt, 64)
+    truth = []
+    for _ in range(shape.n_medusa + 1):
+        truth.append(int(orc.greedy_step(w, shape, g).tokens[0]))
+    cand = np.array(st.cand, copy=True)
+    for dpt in range(shape.n_medusa):
+        cand[dpt, 0] = truth[dpt + 1]
+    rec = orc.spec_step(w, shape, st, tree, stop, "keep_all", cand_override=cand)
+    assert rec.n_accept >= 2
+    last = rec.src_slots[-1]
+    want = orc.topk_ids(rec.logits[last], shape.topk)
+    for i in range(shape.n_medusa):
+        assert np.allclose(rec.head_logits[i], rec.logits[last], rtol=0, atol=1e-12)   # (rows @ W) vs (W @ row) rounding
+        assert list(rec.next_cand[i]) == list(want)
+
+
 def test_kv_storage_rounding_is_torch_bfloat16_and_only_for_bf16():
     a = RNG.standard_normal((7, 3, 16)) * np.array([1e-3, 1.0, 300.0])[None, :, None]
     want = torch.from_numpy(a).float().bfloat16().double().numpy()
