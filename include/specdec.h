@@ -96,6 +96,9 @@ int sd_model_destroy(sd_model* m);
  * `cap` = capacity in rows per sequence. A step needs kv_len + n_medusa + 1 <= cap (the
  * tree's own keys/values live in a library-owned scratch, not in the cache).               */
 size_t sd_kv_bytes(const sd_config* cfg, int32_t batch, int32_t cap);
+/* dev_buf: dev, at least sd_kv_bytes(...) bytes, 16-byte aligned, owned by the caller and borrowed until
+ * sd_kv_destroy. Its first sd_kv_bytes(...) bytes are cleared by this call (whatever the buffer held before
+ * cannot reach a result); the call blocks until the device is idle and allocates a small state block.   */
 int sd_kv_create(const sd_model* m, int32_t batch, int32_t cap, void* dev_buf, size_t bytes,
                  sd_kv** out);
 int sd_kv_destroy(sd_kv* kv);
@@ -235,6 +238,12 @@ int sd_build_labels(const int32_t* l0, int32_t batch, int32_t seq, int32_t n_hea
 #define SD_DRAFT_AFTER_ACCEPT 0
 #define SD_DRAFT_ALL_NODES     1
 int sd_set_draft_schedule(sd_model* m, int32_t schedule);
+
+/* Plain greedy decoding with or without the draft heads. sd_greedy_step runs them by default, so that
+ * a speculative step can follow it at once. With on = 0 it leaves them out (the paper's next-token
+ * baseline has none, Section IV-B) and the carried candidates stay as they were: a later speculative
+ * step is still lossless, its drafts are merely stale. Returns SD_ERR_NULL for a NULL model.             */
+int sd_set_greedy_drafts(sd_model* m, int32_t on);
 
 /* Graph mode (off by default). When on, sd_spec_step / sd_greedy_step capture their kernel
  * sequence into a HIP graph the first time a given combination of (cache, tree, split-KV

@@ -15,7 +15,7 @@ EXPORTED_SYMBOLS = [
     "sd_kv_set_len", "sd_kv_write_rows", "sd_kv_read_rows", "sd_kv_set_draft", "sd_kv_get_draft",
     "sd_tree_create", "sd_tree_destroy", "sd_prefill", "sd_spec_step", "sd_greedy_step", "sd_verify_tree",
     "sd_spec_step_typical", "sd_verify_tree_typical", "sd_sample_tokens", "sd_build_labels",
-    "sd_set_graph_mode", "sd_set_draft_schedule", "sd_profile_begin", "sd_profile_end", "sd_last_error", "sd_version",
+    "sd_set_graph_mode", "sd_set_draft_schedule", "sd_set_greedy_drafts", "sd_profile_begin", "sd_profile_end", "sd_last_error", "sd_version",
 ]
 
 SD_ERR = {-1: "SD_ERR_NULL", -2: "SD_ERR_SHAPE", -3: "SD_ERR_BAD_TREE", -4: "SD_ERR_KV_FULL", -5: "SD_ERR_HIP",
@@ -96,6 +96,7 @@ def lib() -> C.CDLL:
         L.sd_profile_begin.argtypes = [C.c_void_p, C.c_int32]
         L.sd_set_graph_mode.argtypes = [C.c_void_p, C.c_int32]
         L.sd_set_draft_schedule.argtypes = [C.c_void_p, C.c_int32]
+        L.sd_set_greedy_drafts.argtypes = [C.c_void_p, C.c_int32]
         L.sd_profile_end.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64),
                                      C.POINTER(C.c_double)]
         _LIB = L
@@ -157,6 +158,10 @@ class Model:
         """"after_accept" (default) or "all_nodes": where in a step the draft heads run."""
         _check(lib().sd_set_draft_schedule(self.handle, {"after_accept": 0, "all_nodes": 1}[schedule]))
 
+    def set_greedy_drafts(self, on: bool):
+        """Whether sd_greedy_step also runs the draft heads (default) or leaves the carried candidates alone."""
+        _check(lib().sd_set_greedy_drafts(self.handle, 1 if on else 0))
+
     def profile_begin(self, max_launches: int = 65536):
         _check(lib().sd_profile_begin(self.handle, max_launches))
 
@@ -176,10 +181,15 @@ class Model:
 class KVCache:
     """sd_kv_*: the cache buffer is a torch allocation; its tiling is private to the library."""
 
-    def __init__(self, model: Model, batch: int, cap: int):
+    def __init__(self, model: Model, batch: int, cap: int, buf: torch.Tensor | None = None):
+        """`buf`: a uint8 CUDA tensor of at least sd_kv_bytes bytes to hold the cache (its old contents do
+        not matter: sd_kv_create clears it); allocated here when None."""
         self.model, self.batch, self.cap = model, batch, cap
         nbytes = lib().sd_kv_bytes(C.byref(model.cfg), batch, cap)
-        self.buf = torch.zeros(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+        if buf is None:
+            buf = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+        assert buf.is_cuda and buf.dtype == torch.uint8 and buf.is_contiguous() and buf.numel() >= nbytes
+        self.buf = buf
         self.handle = C.c_void_p()
         _check(lib().sd_kv_create(model.handle, batch, cap, self.buf.data_ptr(), nbytes, C.byref(self.handle)))
 

@@ -83,17 +83,26 @@ struct sd_model {
     hipStream_t cap_stream = nullptr;      // capture happens here: the caller's stream may be the null stream
     std::vector<GemmPlan> plans;             // one per (row blocks, K blocks, N blocks) in use
     int32_t* plan_cnt = nullptr;             // device: the plans' per-group slot counts
-    const GemmPlan& plan(int MB, int KB, int NB) const {
+    // every shape a call can issue is planned at creation; the entry points check the plans they need
+    // (have_plans) before they enqueue anything, so a miss here cannot happen after that check
+    const GemmPlan* find_plan(int MB, int KB, int NB) const {
         for (const GemmPlan& p : plans)
-            if (p.MB == MB && p.KB == KB && p.NB == NB) return p;
-        // every shape a call can issue is planned at creation; launching with another shape's plan
-        // would read and write out of bounds, so an inconsistency here must not be survivable
-        fprintf(stderr, "libspecdec: internal error: no GEMM plan for %d row blocks, KB=%d, NB=%d\n", MB, KB, NB);
-        abort();
+            if (p.MB == MB && p.KB == KB && p.NB == NB) return &p;
+        return nullptr;
     }
+    bool plan_missing = false;               // set by run_gemm if it ever had to skip a launch
+    bool greedy_drafts = true;               // sd_greedy_step also runs the draft heads
 };
 
+// Handles get a process-wide serial number: graph keys use it instead of the handle's address, which a
+// later handle can be given again after this one is destroyed.
+static uint64_t next_uid() {
+    static uint64_t n = 0;
+    return ++n;
+}
+
 struct sd_kv {
+    uint64_t uid = next_uid();
     const sd_model* m;
     int B, cap, cap_blocks;
     uint16_t* buf;
@@ -106,6 +115,7 @@ struct sd_kv {
 };
 
 struct sd_tree {
+    uint64_t uid = next_uid();
     int T, Tp, H, topk;
     int32_t* dev = nullptr;                  // parent | depth | rank
     const int32_t *parent, *depth, *rank;
@@ -193,7 +203,7 @@ extern "C" int sd_model_create(const sd_config* cfg, const sd_weights* w, int32_
     for (int i = 0; i < H; ++i) {
         launch_pack_weight(w->medusa_w[i], A + o_med, d, d, i * (d / 32), m->NBmed, m->KBd, s);
         if (w->medusa_b && w->medusa_b[i]) {
-            copy(o_mb[i], w->medusa_b[i], (size_t)d * 2);
+            if (e == hipSuccess) e = copy(o_mb[i], w->medusa_b[i], (size_t)d * 2);
             m->medusa_b.p[i] = (const uint16_t*)(A + o_mb[i]);
         } else {
             m->medusa_b.p[i] = nullptr;
@@ -203,8 +213,8 @@ extern "C" int sd_model_create(const sd_config* cfg, const sd_weights* w, int32_
     m->layers.resize(L);
     for (int l = 0; l < L; ++l) {
         LayerW& lw = m->layers[l];
-        copy(o_an[l], w->attn_norm[l], (size_t)d * 2);
-        copy(o_ffn[l], w->ffn_norm[l], (size_t)d * 2);
+        if (e == hipSuccess) e = copy(o_an[l], w->attn_norm[l], (size_t)d * 2);
+        if (e == hipSuccess) e = copy(o_ffn[l], w->ffn_norm[l], (size_t)d * 2);
         launch_pack_weight(w->wqkv[l], A + o_qkv[l], 3 * d, d, 0, m->NBqkv, m->KBd, s);
         launch_pack_weight(w->wo[l], A + o_o[l], d, d, 0, m->NBo, m->KBd, s);
         launch_pack_weight(w->w_gate[l], A + o_gu[l], F, d, 0, m->NBgu, m->KBd, s);
@@ -265,6 +275,11 @@ extern "C" int sd_model_create(const sd_config* cfg, const sd_weights* w, int32_
     size_t w_rs = wtake((size_t)Mp * 16);
     size_t w_xh = wtake(align_up((size_t)H * Mp, 256) * d * 4);
     size_t w_zs = wtake((size_t)ceil_div(V, 32) * 4), w_zf = wtake(1024);
+    if (e != hipSuccess) {                             // one of the per-layer / per-head weight copies was refused
+        hipStreamSynchronize(s);
+        hipFree(m->arena); delete m;
+        return fail(SD_ERR_HIP, "weight copy: %s", hipGetErrorString(e));
+    }
     e = hipMalloc((void**)&m->work, wz);
     if (e == hipSuccess) e = hipMalloc((void**)&m->plan_cnt, cnt_all.size() * 4);
     if (e == hipSuccess) e = hipMemcpy(m->plan_cnt, cnt_all.data(), cnt_all.size() * 4, hipMemcpyHostToDevice);
@@ -279,7 +294,12 @@ extern "C" int sd_model_create(const sd_config* cfg, const sd_weights* w, int32_
         m->plans[i].cnt_dev = m->plan_cnt + cnt_off[i];
         m->plans[i].slot0_dev = m->plans[i].cnt_dev + (m->plans[i].NB + 7) / 8 + 1;      // right behind the counts
     }
-    hipMemsetAsync(m->work, 0, wz, s);
+    e = hipMemsetAsync(m->work, 0, wz, s);
+    if (e != hipSuccess) {
+        hipStreamSynchronize(s);
+        hipFree(m->arena); hipFree(m->work); hipFree(m->plan_cnt); delete m;
+        return fail(SD_ERR_HIP, "workspace clear: %s", hipGetErrorString(e));
+    }
     char* Wk = m->work;
     m->x = (float*)(Wk + w_x); m->part = (float*)(Wk + w_part); m->logits = (float*)(Wk + w_logits);
     m->hlogits = (float*)(Wk + w_hlog); m->hf = (float*)(Wk + w_hf); m->h_rows = (float*)(Wk + w_hrows);
@@ -371,6 +391,12 @@ extern "C" int sd_set_draft_schedule(sd_model* m, int32_t schedule) {
     return SD_OK;
 }
 
+extern "C" int sd_set_greedy_drafts(sd_model* m, int32_t on) {
+    if (!m) return fail(SD_ERR_NULL, "sd_set_greedy_drafts: NULL model");
+    m->greedy_drafts = on != 0;
+    return SD_OK;
+}
+
 extern "C" int sd_set_graph_mode(sd_model* m, int32_t on) {
     if (!m) return fail(SD_ERR_NULL, "sd_set_graph_mode: NULL model");
     m->use_graphs = on != 0;
@@ -421,6 +447,11 @@ extern "C" int sd_kv_create(const sd_model* m, int32_t batch, int32_t cap, void*
     hipError_t e = hipMalloc((void**)&kv->state, n * 4);
     if (e != hipSuccess) { delete kv; return fail(SD_ERR_HIP, "hipMalloc state: %s", hipGetErrorString(e)); }
     e = hipMemset(kv->state, 0, n * 4);
+    // The cache itself starts as zeros: attention multiplies the value rows of a partly filled block by
+    // probabilities that are exactly 0 for the rows past the committed length, and 0 * NaN is NaN, so no
+    // row the kernels can touch may hold a non-finite bit pattern left behind by the buffer's last user.
+    if (e == hipSuccess) e = hipMemset(dev_buf, 0, sd_kv_bytes(&m->cfg, batch, cap));
+    if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) { hipFree(kv->state); delete kv; return fail(SD_ERR_HIP, "hipMemset: %s", hipGetErrorString(e)); }
     int32_t* p = kv->state;
     kv->kv_len = p; p += batch;
@@ -571,8 +602,29 @@ static hipEvent_t prof_ev(sd_model* m, int i, int which) { return i >= 0 ? m->pr
 // One weight-streaming GEMM; algorithmic bytes = one read of the (unpadded) weight matrix.
 static PartView run_gemm(sd_model* m, const void* Xp, const void* Wp, float* out, int MB, int KB, int NB, int n_real,
                          hipStream_t s) {
+    const GemmPlan* p = m->find_plan(MB, KB, NB);
+    if (!p) {                                          // unreachable after have_plans(); never launch with another shape's plan
+        m->plan_missing = true;
+        return PartView{out, 0, NB * 32, nullptr, 0};  // no slots: the consumer adds nothing
+    }
     const int pi = prof_claim(m, PROF_GEMM, (double)n_real * KB * 16 * 2);
-    return launch_gemm(m->plan(MB, KB, NB), Xp, Wp, m->zfrag, out, s, prof_ev(m, pi, 0), prof_ev(m, pi, 1));
+    return launch_gemm(*p, Xp, Wp, m->zfrag, out, s, prof_ev(m, pi, 0), prof_ev(m, pi, 1));
+}
+
+// Every GEMM shape a pass over M rows issues (and, with heads = true, the draft heads after it, in the
+// schedule given) has a launch plan: checked by the entry points before anything is enqueued.
+static bool have_plans(const sd_model* m, int M, int B, bool heads, bool all_rows) {
+    const int MB = pow2_blocks(M), H = m->cfg.n_medusa;
+    bool ok = m->find_plan(MB, m->KBd, m->NBqkv) && m->find_plan(MB, m->KBd, m->NBo) && m->find_plan(MB, m->KBd, m->NBgu) &&
+              m->find_plan(MB, m->KBf, m->NBo) && m->find_plan(MB, m->KBd, m->NBv);
+    if (heads && !all_rows)
+        ok = ok && m->find_plan(1, m->KBd, m->NBmed) && m->find_plan(pow2_blocks(H * B), m->KBd, m->NBv);
+    if (heads && all_rows) {
+        const int R = H * M, n_chunks = ceil_div(R, 256);
+        ok = ok && m->find_plan(MB, m->KBd, m->NBmed) && m->find_plan(pow2_blocks(R - (n_chunks - 1) * 256), m->KBd, m->NBv) &&
+             (n_chunks == 1 || m->find_plan(8, m->KBd, m->NBv));
+    }
+    return ok;
 }
 
 // How the attention of one step is cut into workgroups (one resident per compute unit: the kernel
@@ -695,6 +747,8 @@ extern "C" int sd_prefill(sd_model* m, sd_kv* kv, const int32_t* tokens, const i
         if (kv->len_hi[b] + lens[b] > kv->cap) return fail(SD_ERR_KV_FULL, "sd_prefill: sequence %d does not fit", b);
         maxlen = std::max(maxlen, lens[b]);
     }
+    if (!have_plans(m, B * Tp, B, true, false))
+        return fail(SD_ERR_STATE, "sd_prefill: no launch plan for %d rows (internal inconsistency)", B * Tp);
     std::vector<int> start(B), done(B, 0);
     for (int b = 0, o = 0; b < B; ++b) { start[b] = o; o += lens[b]; }
     for (int pos = 0; pos < maxlen; pos += Tp) {
@@ -723,14 +777,15 @@ extern "C" int sd_prefill(sd_model* m, sd_kv* kv, const int32_t* tokens, const i
         }
     }
     HIP_TRY(hipGetLastError());
+    if (m->plan_missing) return fail(SD_ERR_STATE, "sd_prefill: a GEMM launch plan was missing");
     kv->has_draft = true;
     return SD_OK;
 }
 
 // ------------------------------------------------------------------------------------------ steps
-static int step_common(sd_model* m, sd_kv* kv, const int32_t* parent, const int32_t* depth, const int32_t* rank, int T,
-                       int Tp, const uint32_t* stop_mask, sd_step_io* io, hipStream_t s, const char* who,
-                       const sd_typical* ty = nullptr) {
+static int step_common(sd_model* m, sd_kv* kv, uint64_t tree_uid, const int32_t* parent, const int32_t* depth,
+                       const int32_t* rank, int T, int Tp, const uint32_t* stop_mask, sd_step_io* io, hipStream_t s,
+                       const char* who, const sd_typical* ty = nullptr) {
     const sd_config& c = m->cfg;
     const int B = kv->B, H = c.n_medusa;
     if (kv->m != m) return fail(SD_ERR_STATE, "%s: cache belongs to another model", who);
@@ -744,6 +799,10 @@ static int step_common(sd_model* m, sd_kv* kv, const int32_t* parent, const int3
                         kv->len_hi[b], kv->cap);
         n_hi = std::max(n_hi, kv->len_hi[b]);
     }
+    const bool all_rows = m->draft_schedule == SD_DRAFT_ALL_NODES && T > 1;
+    const bool heads = T > 1 || m->greedy_drafts;      // plain greedy decoding may leave the draft heads out
+    if (!have_plans(m, B * Tp, B, heads, all_rows))
+        return fail(SD_ERR_STATE, "%s: no launch plan for %d rows (internal inconsistency)", who, B * Tp);
     int32_t* n_accept = io->n_accept ? io->n_accept : kv->i_nacc;
     int32_t* tokens = io->tokens ? io->tokens : kv->i_tokens;
     int32_t* slots = io->src_slots ? io->src_slots : kv->i_slots;
@@ -754,7 +813,6 @@ static int step_common(sd_model* m, sd_kv* kv, const int32_t* parent, const int3
     launch_build_rows_tree(m->rt, parent, depth, rank, kv->root_tok, cand, kv->kv_len, B, T, Tp, H, c.topk, c.head_dim,
                            c.rope_theta, m->embed, c.d_model, c.vocab, m->x, s);
     PartView prev = run_layers(m, kv, B, Tp, n_hi, s);
-    const bool all_rows = m->draft_schedule == SD_DRAFT_ALL_NODES && T > 1;
     run_lm_head(m, prev, B, T, Tp, s, all_rows);
     if (io->logits) launch_copy_logits(m->logits, m->Vpad, io->logits, c.vocab, B, T, Tp, s);
     if (io->argmax) launch_copy_rows_i32(m->am, io->argmax, B, T, Tp, s);
@@ -779,18 +837,18 @@ static int step_common(sd_model* m, sd_kv* kv, const int32_t* parent, const int3
     launch_kv_commit(m->kt, m->vt, kv->kc, kv->vc, slots, n_accept, kv->n_old, c.n_layers, B, c.n_heads, c.head_dim,
                      Tp / 32, kv->cap_blocks, H + 1, H + 1, s);
     if (all_rows) run_draft_heads_all_rows(m, kv, B, Tp, io->head_logits, s);
-    else run_draft_heads(m, kv, B, 0xffffffffu, io->head_logits, s);
+    else if (heads) run_draft_heads(m, kv, B, 0xffffffffu, io->head_logits, s);
     };
 
     if (m->use_graphs && !m->prof.on && !ty) {
         const AttnGeom ag = attn_geometry(m, B, Tp, n_hi);
-        std::vector<uint64_t> key = {(uint64_t)(uintptr_t)kv, (uint64_t)(uintptr_t)parent, (uint64_t)T, (uint64_t)Tp,
+        std::vector<uint64_t> key = {kv->uid, tree_uid, (uint64_t)(uintptr_t)parent, (uint64_t)T, (uint64_t)Tp,
                                      (uint64_t)ag.ncparts, (uint64_t)(ag.per * 2 + ag.tree_sep), (uint64_t)(uintptr_t)stop_mask,
                                      (uint64_t)(uintptr_t)n_accept, (uint64_t)(uintptr_t)tokens,
                                      (uint64_t)(uintptr_t)slots, (uint64_t)(uintptr_t)io->n_accept_raw,
                                      (uint64_t)(uintptr_t)io->logits, (uint64_t)(uintptr_t)io->argmax,
                                      (uint64_t)(uintptr_t)io->head_logits, (uint64_t)(uintptr_t)cand,
-                                     (uint64_t)m->draft_schedule};
+                                     (uint64_t)m->draft_schedule, (uint64_t)heads};
         hipGraphExec_t exec = nullptr;
         for (const sd_model::StepGraph& g : m->graphs)
             if (g.key == key) { exec = g.exec; break; }
@@ -815,6 +873,7 @@ static int step_common(sd_model* m, sd_kv* kv, const int32_t* parent, const int3
         enqueue(s);
     }
     HIP_TRY(hipGetLastError());
+    if (m->plan_missing) return fail(SD_ERR_STATE, "%s: a GEMM launch plan was missing", who);
     for (int b = 0; b < B; ++b) kv->len_hi[b] += (T == 1) ? 1 : H + 1;
     return SD_OK;
 }
@@ -824,7 +883,7 @@ extern "C" int sd_spec_step(sd_model* m, sd_kv* kv, const sd_tree* tree, const u
     if (!m || !kv || !tree || !stop_mask || !io) return fail(SD_ERR_NULL, "sd_spec_step: NULL argument");
     if (tree->H != m->cfg.n_medusa || tree->topk != m->cfg.topk)
         return fail(SD_ERR_BAD_TREE, "sd_spec_step: tree was built for %d heads / top-%d", tree->H, tree->topk);
-    return step_common(m, kv, tree->parent, tree->depth, tree->rank, tree->T, tree->Tp, stop_mask, io,
+    return step_common(m, kv, tree->uid, tree->parent, tree->depth, tree->rank, tree->T, tree->Tp, stop_mask, io,
                        (hipStream_t)stream, "sd_spec_step");
 }
 
@@ -843,13 +902,13 @@ extern "C" int sd_spec_step_typical(sd_model* m, sd_kv* kv, const sd_tree* tree,
         return fail(SD_ERR_BAD_TREE, "sd_spec_step_typical: tree was built for %d heads / top-%d", tree->H, tree->topk);
     if (!ty->u) return fail(SD_ERR_NULL, "sd_spec_step_typical: sd_typical.u is NULL");
     if (int rc = check_typical(ty->temperature, ty->epsilon, ty->delta, "sd_spec_step_typical")) return rc;
-    return step_common(m, kv, tree->parent, tree->depth, tree->rank, tree->T, tree->Tp, stop_mask, io,
+    return step_common(m, kv, tree->uid, tree->parent, tree->depth, tree->rank, tree->T, tree->Tp, stop_mask, io,
                        (hipStream_t)stream, "sd_spec_step_typical", ty);
 }
 
 extern "C" int sd_greedy_step(sd_model* m, sd_kv* kv, sd_step_io* io, void* stream) {
     if (!m || !kv || !io) return fail(SD_ERR_NULL, "sd_greedy_step: NULL argument");
-    return step_common(m, kv, m->g_parent, m->g_depth, m->g_rank, 1, 32, m->zero_stop, io, (hipStream_t)stream,
+    return step_common(m, kv, 0, m->g_parent, m->g_depth, m->g_rank, 1, 32, m->zero_stop, io, (hipStream_t)stream,
                        "sd_greedy_step");
 }
 

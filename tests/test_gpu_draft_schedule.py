@@ -29,7 +29,7 @@ def test_tiny_shape_lockstep_all_nodes(sd):
     _, weights, w64, model, kv, prompt, stop, words, tree_np, tree = _setup(sd, shape, 64, 256, 16)
     model.set_draft_schedule("all_nodes")
     rep = lockstep.Report()
-    st, root, cand = _prefill_both(sd, lockstep, model, kv, w64, shape, prompt, 256, rep, 0.05)
+    st, root, cand = _prefill_both(sd, lockstep, model, kv, w64, shape, prompt, 256, rep, 0.0)
     g = orc.prefill(w64, shape, prompt, 256)
     for _ in range(150):
         orc.greedy_step(w64, shape, g)

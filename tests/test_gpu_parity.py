@@ -118,7 +118,7 @@ def test_tiny_shape_lockstep_32_steps(sd, fallback):
     shape = _bf16_shape("tiny")
     lockstep, weights, w64, model, kv, prompt, stop, words, tree_np, tree = _setup(sd, shape, 64, 256, 16, fallback)
     rep = lockstep.Report()
-    st, root, cand = _prefill_both(sd, lockstep, model, kv, w64, shape, prompt, 256, rep, 0.05)
+    st, root, cand = _prefill_both(sd, lockstep, model, kv, w64, shape, prompt, 256, rep, 0.0)
     # the plain-greedy continuation, for planting drafts
     g = orc.prefill(w64, shape, prompt, 256)
     for _ in range(150):
@@ -155,7 +155,9 @@ def test_tiny_shape_against_the_fp32_oracle(sd):
     tree_np = wl.default_tree(16, shape32.n_medusa, shape32.topk)
     tree = sd.Tree(*tree_np, shape32.n_medusa, shape32.topk)
     rep = lockstep.Report()
-    st, root, cand = _prefill_both(sd, lockstep, model, kv, w64, shape32, prompt, 256, rep, 0.05)
+    # the oracle's rows are not rounded here: half a bfloat16 spacing of storage rounding plus the effect of
+    # the bf16 weights on the rows themselves, bounded like the logits
+    st, root, cand = _prefill_both(sd, lockstep, model, kv, w64, shape32, prompt, 256, rep, lockstep.LOGIT_MAX_ABS)
     g = orc.prefill(w64, shape32, prompt, 256)
     for _ in range(150):
         orc.greedy_step(w64, shape32, g)
@@ -166,7 +168,8 @@ def test_tiny_shape_against_the_fp32_oracle(sd):
         e = len(s.emitted)
         return wl.plant_drafts(s.cand, np.array(truth[e + 1: e + 1 + shape32.n_medusa]), (0.9, 0.8, 0.7), rng)
 
-    rep = lockstep.lockstep_spec(model, kv, tree, tree_np, stop, words, w64, shape32, st, 32, "keep_all", plant, rep=rep)
+    rep = lockstep.lockstep_spec(model, kv, tree, tree_np, stop, words, w64, shape32, st, 32, "keep_all", plant,
+                                 kv_tol=lockstep.LOGIT_MAX_ABS, rep=rep)
     print(f"\n[tiny, fp32 oracle] {rep}")
     assert rep.steps == 32 and max(rep.accepted) >= 3
     assert st.emitted == truth[: len(st.emitted)]
@@ -178,8 +181,8 @@ def test_7b_width_two_layers_lockstep(sd):
     shape = _bf16_shape("7b", 2)
     lockstep, weights, w64, model, kv, prompt, stop, words, tree_np, tree = _setup(sd, shape, 100, 160, 64)
     rep = lockstep.Report()
-    st, root, cand = _prefill_both(sd, lockstep, model, kv, w64, shape, prompt, 160, rep, 0.08)
-    assert root == st.root_tok or True
+    st, root, cand = _prefill_both(sd, lockstep, model, kv, w64, shape, prompt, 160, rep, 0.0)
+    assert root == st.root_tok
     g = orc.prefill(w64, shape, prompt, 160)
     for _ in range(24):
         orc.greedy_step(w64, shape, g)
@@ -190,8 +193,8 @@ def test_7b_width_two_layers_lockstep(sd):
         e = len(s.emitted)
         return wl.plant_drafts(s.cand, np.array(truth[e + 1: e + 1 + shape.n_medusa]), (0.9, 0.85, 0.8, 0.75), rng)
 
-    rep = lockstep.lockstep_spec(model, kv, tree, tree_np, stop, words, w64, shape, st, 2, "keep_all", None, 0.08, rep)
-    rep = lockstep.lockstep_spec(model, kv, tree, tree_np, stop, words, w64, shape, st, 4, "keep_all", plant, 0.08, rep)
+    rep = lockstep.lockstep_spec(model, kv, tree, tree_np, stop, words, w64, shape, st, 2, "keep_all", None, 0.0, rep)
+    rep = lockstep.lockstep_spec(model, kv, tree, tree_np, stop, words, w64, shape, st, 4, "keep_all", plant, 0.0, rep)
     print(f"\n[7b-L2] {rep}")
     assert max(rep.accepted) >= 2
     assert st.emitted == truth[: len(st.emitted)]
@@ -201,7 +204,7 @@ def test_greedy_step_matches_oracle(sd):
     shape = _bf16_shape("tiny")
     lockstep, weights, w64, model, kv, prompt, stop, words, tree_np, tree = _setup(sd, shape, 40, 128, 16)
     rep = lockstep.Report()
-    st, root, cand = _prefill_both(sd, lockstep, model, kv, w64, shape, prompt, 128, rep, 0.05)
+    st, root, cand = _prefill_both(sd, lockstep, model, kv, w64, shape, prompt, 128, rep, 0.0)
     for i in range(8):
         kv.set_draft([st.root_tok], np.asarray(st.cand)[None])
         out = sd.greedy_step(model, kv, want_logits=True)
@@ -210,7 +213,7 @@ def test_greedy_step_matches_oracle(sd):
         lockstep.check_logits(out.logits[0].cpu().numpy().astype(np.float64), rec.logits, rep)
         assert int(out.n_accept[0]) == 1 and int(out.tokens[0, 0]) == rec.tokens[0] and int(out.src_slots[0, 0]) == 0
         assert kv.len() == [st.kv.n]
-        lockstep.compare_kv_rows(kv, st, shape, st.kv.n - 1, st.kv.n, rep, 0.05)
+        lockstep.compare_kv_rows(kv, st, shape, st.kv.n - 1, st.kv.n, rep)
 
 
 def test_errors_leave_state_untouched(sd):
@@ -235,7 +238,7 @@ def test_step_that_exactly_fits_the_cache(sd):
     cap = 21 + shape.n_medusa + 1
     lockstep, weights, w64, model, kv, prompt, stop, words, tree_np, tree = _setup(sd, shape, 21, cap, 16)
     rep = lockstep.Report()
-    st, root, cand = _prefill_both(sd, lockstep, model, kv, w64, shape, prompt, cap, rep, 0.05)
+    st, root, cand = _prefill_both(sd, lockstep, model, kv, w64, shape, prompt, cap, rep, 0.0)
     truth = orc.prefill(w64, shape, prompt, cap + 8)
     for _ in range(shape.n_medusa + 1):
         orc.greedy_step(w64, shape, truth)
@@ -292,3 +295,77 @@ def test_graph_mode_replays_equal_eager(sd):
     for a, b in zip(eager, graph):
         assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1]) and torch.equal(a[2], b[2]) and torch.equal(a[3], b[3])
         assert a[4] == b[4]
+
+
+def test_graph_mode_survives_a_destroyed_and_recreated_cache(sd):
+    """Graph keys name a cache by a serial number, not by its handle's address: a cache that is destroyed and
+    replaced by one of another capacity (whose handle may get the same address, and whose buffer does here)
+    must not replay the first one's graph. Each cache's graph-mode steps equal its own eager steps."""
+    shape = _bf16_shape("tiny")
+    lockstep, weights, w64, model, kv, prompt, stop, words, tree_np, tree = _setup(sd, shape, 40, 256, 16)
+    kv.close()
+    buf = torch.empty(sd.lib().sd_kv_bytes(model.cfg, 1, 256) + 16, dtype=torch.uint8, device="cuda")
+    forced = torch.zeros((1, shape.n_medusa, shape.topk), dtype=torch.int32, device="cuda")
+    rng = np.random.default_rng(5)
+    cands = [torch.from_numpy(np.stack([rng.permutation(shape.vocab)[: shape.topk] for _ in range(shape.n_medusa)])
+                              .astype(np.int32))[None] for _ in range(4)]
+    out = None
+    for cap in (256, 96, 160):
+        res = {}
+        for graphs in (False, True):
+            cache = sd.KVCache(model, 1, cap, buf=buf)
+            model.set_graph_mode(graphs)
+            sd.prefill(model, cache, torch.from_numpy(prompt).cuda(), [40])
+            got = []
+            for c in cands:
+                forced.copy_(c)
+                out = sd.spec_step(model, cache, tree, words, want_logits=True, want_argmax=True, forced_cand=forced,
+                                   out=out)
+                torch.cuda.synchronize()
+                got.append((out.logits.clone(), out.tokens.clone(), out.n_accept.clone(), cache.len()))
+            res[graphs] = got
+            cache.close()
+        model.set_graph_mode(False)
+        for a, b in zip(res[False], res[True]):
+            assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1]) and torch.equal(a[2], b[2]) and a[3] == b[3]
+
+
+def test_cache_buffer_full_of_nans_cannot_reach_the_logits(sd):
+    """A caller's cache buffer may hold anything (here: every 16-bit word a bfloat16 NaN). sd_kv_create clears
+    it, so the value rows past the committed length inside a partly filled block, which attention multiplies
+    by probabilities of exactly zero, are zeros and not NaNs. Prefill 45 rows (a partly filled second block)
+    and one step, against the oracle."""
+    shape = _bf16_shape("tiny")
+    lockstep, weights, w64, model, kv, prompt, stop, words, tree_np, tree = _setup(sd, shape, 45, 128, 16)
+    kv.close()
+    nbytes = sd.lib().sd_kv_bytes(model.cfg, 1, 128)
+    buf = torch.full((nbytes // 2,), 0x7FC0, dtype=torch.int16, device="cuda").view(torch.uint8)
+    cache = sd.KVCache(model, 1, 128, buf=buf)
+    rep = lockstep.Report()
+    st, root, cand = _prefill_both(sd, lockstep, model, cache, w64, shape, prompt, 128, rep, 0.0)
+    assert root == st.root_tok
+    rep = lockstep.lockstep_spec(model, cache, tree, tree_np, stop, words, w64, shape, st, 2, "keep_all", rep=rep)
+    assert rep.steps == 2 and np.isfinite(rep.max_abs)
+
+
+def test_greedy_step_without_draft_heads(sd):
+    """sd_set_greedy_drafts(0): the plain next-token step gives the same token and logits and leaves the
+    carried candidates untouched."""
+    shape = _bf16_shape("tiny")
+    lockstep, weights, w64, model, kv, prompt, stop, words, tree_np, tree = _setup(sd, shape, 40, 128, 16)
+    sd.prefill(model, kv, torch.from_numpy(prompt).cuda(), [40])
+    root0, cand0 = kv.get_draft()
+    root0, cand0 = root0.clone(), cand0.clone()
+    a = sd.greedy_step(model, kv, want_logits=True)
+    torch.cuda.synchronize()
+    root_a, cand_a = [t.clone() for t in kv.get_draft()]
+    kv.set_len([40])
+    kv.set_draft(root0, cand0)
+    model.set_greedy_drafts(False)
+    b = sd.greedy_step(model, kv, want_logits=True)
+    torch.cuda.synchronize()
+    root_b, cand_b = [t.clone() for t in kv.get_draft()]
+    model.set_greedy_drafts(True)
+    assert torch.equal(a.logits, b.logits) and torch.equal(a.tokens, b.tokens) and torch.equal(root_a, root_b)
+    assert torch.equal(cand_b, cand0) and kv.len() == [41]
+    assert not torch.equal(cand_a, cand0)                  # with the heads on, the candidates had moved on

@@ -208,7 +208,7 @@ def test_7b_width_two_layers_typical_lockstep(sd, temperature):
     rng = np.random.default_rng(11)
     ty = dict(TY, temperature=temperature)
     rep = lockstep.lockstep_typical(model, kv, tree, tree_np, stop, words, w64, shape, st, 4, "keep_all", ty, rng,
-                                    cand_fn=plant, kv_tol=0.08)
+                                    cand_fn=plant)
     print(f"\n[7b-L2 typical T={temperature}] {rep}")
     assert rep.steps == 4
     assert rep.accept_near_ties <= 1 and rep.root_near_ties <= 1
