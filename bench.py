@@ -55,6 +55,7 @@ def parse():
                     help="steps launched between host synchronisations (1 = wait for every step before the next)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=32)
+    ap.add_argument("--no-fused", action="store_true", help="one launch per stage instead of the persistent layer kernel")
     ap.add_argument("--graph", action="store_true", help="replay captured HIP graphs instead of launching every kernel (measured: no gain, the step is not host-bound)")
     return ap.parse_args()
 
@@ -148,6 +149,7 @@ def main():
         torch.empty((1, H + 1), dtype=torch.int32, device="cuda"), torch.empty(1, dtype=torch.int32, device="cuda"))
     forced = torch.zeros((1, H, k), dtype=torch.int32, device="cuda")     # fixed buffer: graphs replay on it
     model.set_graph_mode(args.graph)
+    model.set_fused(not args.no_fused)
     model.set_draft_schedule(args.draft_schedule)
     state = {"e": 0, "emitted": 0, "diverged": 0, "resets": 0, "i": 0}
     typical = dict(temperature=0.8, epsilon=0.09, delta=0.3)
@@ -315,6 +317,7 @@ def bench_batch(args, torch, wl, sd, W):
         torch.empty(B, dtype=torch.int32, device="cuda"), torch.empty((B, H + 1), dtype=torch.int32, device="cuda"),
         torch.empty((B, H + 1), dtype=torch.int32, device="cuda"), torch.empty(B, dtype=torch.int32, device="cuda"))
     model.set_graph_mode(args.graph)
+    model.set_fused(not args.no_fused)
     model.set_draft_schedule(args.draft_schedule)
     room = (W.kv_cap - 1 - max(lens)) // (H + 1)           # steps before the longest sequence could fill its cache
     state = {"left": room, "emitted": 0}

@@ -245,6 +245,22 @@ int sd_set_draft_schedule(sd_model* m, int32_t schedule);
  * step is still lossless, its drafts are merely stale. Returns SD_ERR_NULL for a NULL model.             */
 int sd_set_greedy_drafts(sd_model* m, int32_t on);
 
+/* The persistent layer kernel (on by default where the device can hold its 256 workgroups of 512 threads at once,
+ * and for passes of 32, 64 or 256 rows): all stages of the verifying pass between two attention launches run as
+ * phases of one launch, separated by barriers across the grid, instead of one launch per stage; results are
+ * bit-identical either way. sd_set_fused(m, 0) selects one launch per stage.
+ * Every wait of that kernel is bounded (default 50 ms; sd_set_sync_timeout: 0 .. 10 s, in microseconds). If a
+ * wait runs out, the kernel still ends, the outputs enqueued since are invalid, and the next sd_kv_len on a cache
+ * of this model returns SD_ERR_HIP once (after which decoding can go on, e.g. with sd_set_fused(m, 0)).           */
+int sd_set_fused(sd_model* m, int32_t on);
+int sd_set_sync_timeout(sd_model* m, int64_t microseconds);
+/* Diagnostic: time stamps of the persistent layer kernel. dev_buf: dev, [launches][24][256] uint64, or NULL to
+ * switch it off; launch l of a pass (0 .. n_layers) writes, for each of its 256 workgroups w, buf[l][i][w] = the
+ * device's 100 MHz real-time counter when the workgroup finished the work of a phase (even i) and when it left the
+ * barrier after it (odd i), in the order the phases run; entries of phases a launch does not run keep their old
+ * contents. Launches beyond bytes / 49152 are not recorded. The caller owns the buffer and keeps it alive while set. */
+int sd_set_layer_timeline(sd_model* m, void* dev_buf, size_t bytes);
+
 /* Graph mode (off by default). When on, sd_spec_step / sd_greedy_step capture their kernel
  * sequence into a HIP graph the first time a given combination of (cache, tree, split-KV
  * geometry, stop mask, output and candidate pointers) is seen and replay it afterwards: one

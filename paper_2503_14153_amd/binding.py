@@ -15,7 +15,7 @@ EXPORTED_SYMBOLS = [
     "sd_kv_set_len", "sd_kv_write_rows", "sd_kv_read_rows", "sd_kv_set_draft", "sd_kv_get_draft",
     "sd_tree_create", "sd_tree_destroy", "sd_prefill", "sd_spec_step", "sd_greedy_step", "sd_verify_tree",
     "sd_spec_step_typical", "sd_verify_tree_typical", "sd_sample_tokens", "sd_build_labels",
-    "sd_set_graph_mode", "sd_set_draft_schedule", "sd_set_greedy_drafts", "sd_profile_begin", "sd_profile_end", "sd_last_error", "sd_version",
+    "sd_set_graph_mode", "sd_set_draft_schedule", "sd_set_greedy_drafts", "sd_set_fused", "sd_set_sync_timeout", "sd_set_layer_timeline", "sd_profile_begin", "sd_profile_end", "sd_last_error", "sd_version",
 ]
 
 SD_ERR = {-1: "SD_ERR_NULL", -2: "SD_ERR_SHAPE", -3: "SD_ERR_BAD_TREE", -4: "SD_ERR_KV_FULL", -5: "SD_ERR_HIP",
@@ -97,6 +97,9 @@ def lib() -> C.CDLL:
         L.sd_set_graph_mode.argtypes = [C.c_void_p, C.c_int32]
         L.sd_set_draft_schedule.argtypes = [C.c_void_p, C.c_int32]
         L.sd_set_greedy_drafts.argtypes = [C.c_void_p, C.c_int32]
+        L.sd_set_fused.argtypes = [C.c_void_p, C.c_int32]
+        L.sd_set_sync_timeout.argtypes = [C.c_void_p, C.c_int64]
+        L.sd_set_layer_timeline.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
         L.sd_profile_end.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64),
                                      C.POINTER(C.c_double)]
         _LIB = L
@@ -161,6 +164,22 @@ class Model:
     def set_greedy_drafts(self, on: bool):
         """Whether sd_greedy_step also runs the draft heads (default) or leaves the carried candidates alone."""
         _check(lib().sd_set_greedy_drafts(self.handle, 1 if on else 0))
+
+    def set_fused(self, on: bool):
+        """The persistent layer kernel (default) or one launch per stage; results are bit-identical."""
+        _check(lib().sd_set_fused(self.handle, 1 if on else 0))
+
+    def set_layer_timeline(self, buf: torch.Tensor | None):
+        """Diagnostic time stamps of the layer kernel into an int64 CUDA tensor [launches, 24, 256] (None: off)."""
+        if buf is None:
+            _check(lib().sd_set_layer_timeline(self.handle, None, 0))
+        else:
+            assert buf.is_cuda and buf.dtype == torch.int64 and buf.is_contiguous()
+            _check(lib().sd_set_layer_timeline(self.handle, buf.data_ptr(), buf.numel() * 8))
+        self._timeline = buf
+
+    def set_sync_timeout(self, microseconds: int):
+        _check(lib().sd_set_sync_timeout(self.handle, int(microseconds)))
 
     def profile_begin(self, max_launches: int = 65536):
         _check(lib().sd_profile_begin(self.handle, max_launches))

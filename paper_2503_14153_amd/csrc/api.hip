@@ -90,6 +90,18 @@ struct sd_model {
             if (p.MB == MB && p.KB == KB && p.NB == NB) return &p;
         return nullptr;
     }
+    // persistent layer kernel (fused.hip)
+    bool fused_ok = false;                   // the device holds its 256 workgroups at once and the buffers exist
+    bool use_fused = false;                  // sd_set_fused
+    bool fused_dirty = false;                // launched since the host last looked at the give-up flag
+    float *part_o = nullptr, *part_gu = nullptr, *part_dn = nullptr, *part_q = nullptr;   // one per GEMM of a launch
+    void* xn2 = nullptr;                     // second packed operand (norm before the feed-forward block)
+    float *ssq_a = nullptr, *ssq_f = nullptr;   // [d / 16][Mp] partial sums of squares of the two deferred norms
+    unsigned* sync_ctr = nullptr;            // [(n_layers + 1)][FUSED_SYNC_WORDS] barrier counters, + the give-up flag
+    unsigned* sync_abort = nullptr;
+    unsigned long long sync_timeout_ticks = 5000000ull;     // 50 ms of the 100 MHz counter
+    unsigned long long* timeline = nullptr;  // caller's buffer for the layer kernel's time stamps, or NULL
+    size_t timeline_launches = 0;
     bool plan_missing = false;               // set by run_gemm if it ever had to skip a launch
     bool greedy_drafts = true;               // sd_greedy_step also runs the draft heads
 };
@@ -275,6 +287,17 @@ extern "C" int sd_model_create(const sd_config* cfg, const sd_weights* w, int32_
     size_t w_rs = wtake((size_t)Mp * 16);
     size_t w_xh = wtake(align_up((size_t)H * Mp, 256) * d * 4);
     size_t w_zs = wtake((size_t)ceil_div(V, 32) * 4), w_zf = wtake(1024);
+    size_t w_ssqa = wtake((size_t)align_up(d / 16, 4) * Mp * 4), w_ssqf = wtake((size_t)align_up(d / 16, 4) * Mp * 4);
+    size_t w_xn2 = wtake((size_t)Mp * d * 4);
+    // the persistent layer kernel: partial sums of each of its four GEMMs in a buffer of their own, a second
+    // packed operand, and the barrier counters of every launch of a pass
+    int dev_now = 0;
+    const bool fused_fits = hipGetDevice(&dev_now) == hipSuccess && fused_max_resident(dev_now) >= 256;
+    size_t w_po = 0, w_pgu = 0, w_pdn = 0, w_pq = 0, w_sync = 0;
+    if (fused_fits) {
+        w_po = wtake(pf * 4); w_pgu = wtake(pf * 4); w_pdn = wtake(pf * 4); w_pq = wtake(pf * 4);
+        w_sync = wtake(((size_t)(L + 1) * FUSED_SYNC_WORDS + 64) * 4);
+    }
     if (e != hipSuccess) {                             // one of the per-layer / per-head weight copies was refused
         hipStreamSynchronize(s);
         hipFree(m->arena); delete m;
@@ -314,6 +337,15 @@ extern "C" int sd_model_create(const sd_config* cfg, const sd_weights* w, int32_
     m->g_parent = (int32_t*)(Wk + w_g); m->g_depth = m->g_parent + 1; m->g_rank = m->g_parent + 2;
     m->zero_stop = (uint32_t*)(Wk + w_zs);
     m->zfrag = Wk + w_zf;
+    m->ssq_a = (float*)(Wk + w_ssqa); m->ssq_f = (float*)(Wk + w_ssqf);
+    m->xn2 = Wk + w_xn2;
+    if (fused_fits) {
+        m->part_o = (float*)(Wk + w_po); m->part_gu = (float*)(Wk + w_pgu); m->part_dn = (float*)(Wk + w_pdn);
+        m->part_q = (float*)(Wk + w_pq);
+        m->sync_ctr = (unsigned*)(Wk + w_sync);
+        m->sync_abort = m->sync_ctr + (size_t)(L + 1) * FUSED_SYNC_WORDS;
+        m->fused_ok = true;
+    }
     launch_fill_i32(m->g_parent, -1, 1, s);
     e = hipStreamSynchronize(s);
     if (e == hipSuccess) e = hipGetLastError();
@@ -388,6 +420,42 @@ extern "C" int sd_set_draft_schedule(sd_model* m, int32_t schedule) {
     if (schedule != SD_DRAFT_AFTER_ACCEPT && schedule != SD_DRAFT_ALL_NODES)
         return fail(SD_ERR_SHAPE, "sd_set_draft_schedule: unknown schedule %d", schedule);
     m->draft_schedule = schedule;
+    return SD_OK;
+}
+
+extern "C" int sd_set_fused(sd_model* m, int32_t on) {
+    if (!m) return fail(SD_ERR_NULL, "sd_set_fused: NULL model");
+    m->use_fused = on != 0;
+    return SD_OK;
+}
+
+extern "C" int sd_set_layer_timeline(sd_model* m, void* dev_buf, size_t bytes) {
+    if (!m) return fail(SD_ERR_NULL, "sd_set_layer_timeline: NULL model");
+    if (dev_buf && (((uintptr_t)dev_buf) & 7)) return fail(SD_ERR_SHAPE, "sd_set_layer_timeline: buffer must be 8-byte aligned");
+    m->timeline = (unsigned long long*)dev_buf;
+    m->timeline_launches = dev_buf ? bytes / ((size_t)24 * 256 * 8) : 0;
+    return SD_OK;
+}
+
+extern "C" int sd_set_sync_timeout(sd_model* m, int64_t microseconds) {
+    if (!m) return fail(SD_ERR_NULL, "sd_set_sync_timeout: NULL model");
+    if (microseconds < 0 || microseconds > 10000000) return fail(SD_ERR_SHAPE, "sd_set_sync_timeout: 0 .. 10 s");
+    m->sync_timeout_ticks = (unsigned long long)microseconds * 100ull;
+    return SD_OK;
+}
+
+// Has a workgroup of the persistent kernel given up a wait since the last look? Called where the host has just
+// synchronised the stream anyway. The flag is cleared, so one failure is reported once.
+static int check_fused_abort(sd_model* m, const char* who) {
+    if (!m->fused_dirty || !m->sync_abort) return SD_OK;
+    unsigned flag = 0;
+    HIP_TRY(hipMemcpy(&flag, m->sync_abort, 4, hipMemcpyDeviceToHost));
+    m->fused_dirty = false;
+    if (flag) {
+        HIP_TRY(hipMemset(m->sync_abort, 0, 4));
+        return fail(SD_ERR_HIP, "%s: a wait between workgroups inside the layer kernel ran out of time; the results "
+                    "enqueued since the last successful check are invalid", who);
+    }
     return SD_OK;
 }
 
@@ -479,6 +547,7 @@ extern "C" int sd_kv_len(sd_kv* kv, int32_t* out_len, void* stream) {
     HIP_TRY(hipMemcpyAsync(out_len, kv->kv_len, kv->B * 4, hipMemcpyDeviceToHost, (hipStream_t)stream));
     HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
     for (int b = 0; b < kv->B; ++b) kv->len_hi[b] = out_len[b];
+    if (int rc = check_fused_abort(const_cast<sd_model*>(kv->m), "sd_kv_len")) return rc;
     return SD_OK;
 }
 
@@ -600,15 +669,20 @@ static int prof_claim(sd_model* m, int cls, double bytes) {
 static hipEvent_t prof_ev(sd_model* m, int i, int which) { return i >= 0 ? m->prof.ev[2 * i + which] : nullptr; }
 
 // One weight-streaming GEMM; algorithmic bytes = one read of the (unpadded) weight matrix.
+static SkRowScale row_scale(const sd_model* m, const float* ssq) {
+    return SkRowScale{ssq, m->cfg.d_model / 16, 1.f / (float)m->cfg.d_model, m->cfg.rms_eps};
+}
+static const SkRowScale NO_SCALE = {nullptr, 0, 0.f, 0.f};
+
 static PartView run_gemm(sd_model* m, const void* Xp, const void* Wp, float* out, int MB, int KB, int NB, int n_real,
-                         hipStream_t s) {
+                         hipStream_t s, SkRowScale sc = NO_SCALE) {
     const GemmPlan* p = m->find_plan(MB, KB, NB);
     if (!p) {                                          // unreachable after have_plans(); never launch with another shape's plan
         m->plan_missing = true;
         return PartView{out, 0, NB * 32, nullptr, 0};  // no slots: the consumer adds nothing
     }
     const int pi = prof_claim(m, PROF_GEMM, (double)n_real * KB * 16 * 2);
-    return launch_gemm(*p, Xp, Wp, m->zfrag, out, s, prof_ev(m, pi, 0), prof_ev(m, pi, 1));
+    return launch_gemm(*p, Xp, Wp, m->zfrag, out, s, prof_ev(m, pi, 0), prof_ev(m, pi, 1), sc);
 }
 
 // Every GEMM shape a pass over M rows issues (and, with heads = true, the draft heads after it, in the
@@ -662,10 +736,17 @@ static PartView run_layers(sd_model* m, sd_kv* kv, int B, int Tp, int n_hi, hipS
     const AttnGeom ag = attn_geometry(m, B, Tp, n_hi);
     PartView prev = {nullptr, 0, d, nullptr, 0};
     const size_t t_stride = (size_t)B * nh * TB * 32 * hd;     // elements per layer of tree scratch
+    const bool deferred = false;   // one launch per stage: the norm kernel that scales its rows itself measured faster
     for (int l = 0; l < c.n_layers; ++l) {
         const LayerW& lw = m->layers[l];
-        launch_norm_pack(m->x, prev, lw.attn_norm, c.rms_eps, m->xn, nullptr, M, d, MB, nullptr, s);
-        PartView pq = run_gemm(m, m->xn, lw.wqkv, m->part, MB, m->KBd, m->NBqkv, 3 * d, s);
+        PartView pq;
+        if (deferred) {                                    // the norm's 1 / rms factor is applied by the GEMM (row_ops.h)
+            launch_norm_tile(m->x, prev, lw.attn_norm, m->xn, m->ssq_a, M, d, MB, s);
+            pq = run_gemm(m, m->xn, lw.wqkv, m->part, MB, m->KBd, m->NBqkv, 3 * d, s, row_scale(m, m->ssq_a));
+        } else {
+            launch_norm_pack(m->x, prev, lw.attn_norm, c.rms_eps, m->xn, nullptr, M, d, MB, nullptr, s);
+            pq = run_gemm(m, m->xn, lw.wqkv, m->part, MB, m->KBd, m->NBqkv, 3 * d, s);
+        }
         uint16_t* kt = (uint16_t*)m->kt + l * t_stride;
         uint16_t* vt = (uint16_t*)m->vt + l * t_stride;
         launch_rope_kv(pq, m->rt, m->q, kt, vt, B, Tp, nh, hd, s);
@@ -676,12 +757,102 @@ static PartView run_layers(sd_model* m, sd_kv* kv, int B, int Tp, int n_hi, hipS
                          prof_ev(m, pa, 0), prof_ev(m, pa, 1));
         launch_attn_merge(m->opart, m->mlpart, m->attn_x, B, nh, hd, Tp, ag.nparts, MB, s);
         PartView po = run_gemm(m, m->attn_x, lw.wo, m->part, MB, m->KBd, m->NBo, d, s);
-        launch_norm_pack(m->x, po, lw.ffn_norm, c.rms_eps, m->xn, nullptr, M, d, MB, nullptr, s);
-        PartView pg = run_gemm(m, m->xn, lw.wgu, m->part, MB, m->KBd, m->NBgu, 2 * c.d_ffn, s);
+        PartView pg;
+        if (deferred) {
+            launch_norm_tile(m->x, po, lw.ffn_norm, m->xn, m->ssq_f, M, d, MB, s);
+            pg = run_gemm(m, m->xn, lw.wgu, m->part, MB, m->KBd, m->NBgu, 2 * c.d_ffn, s, row_scale(m, m->ssq_f));
+        } else {
+            launch_norm_pack(m->x, po, lw.ffn_norm, c.rms_eps, m->xn, nullptr, M, d, MB, nullptr, s);
+            pg = run_gemm(m, m->xn, lw.wgu, m->part, MB, m->KBd, m->NBgu, 2 * c.d_ffn, s);
+        }
         launch_swiglu_pack(pg, c.d_ffn, m->Fpad, m->act, M, MB, s);
         prev = run_gemm(m, m->act, lw.wdown, m->part, MB, m->KBf, m->NBo, d, s);
     }
     return prev;
+}
+
+// ---- the same pass through the persistent layer kernel: one launch per layer besides attention
+static FusedGemm fused_gemm(const sd_model* m, int MB, int KB, int NB, const void* X, const void* W, float* out) {
+    const GemmPlan* p = m->find_plan(MB, KB, NB);          // present: have_plans() ran before
+    FusedGemm g;
+    g.X = (const bf16x8*)X; g.W = (const bf16x8*)W; g.out = out;
+    g.KB = KB; g.NB = NB; g.ldo = NB * 32;
+    g.slot_stride = (size_t)MB * 32 * g.ldo;
+    g.upw = p->upw; g.rem = p->rem; g.G = p->G; g.nmax = p->slots;
+    g.kb_magic = (uint32_t)((0x100000000ull + (uint64_t)KB - 1) / (uint64_t)KB);
+    g.slot0 = p->slot0_dev;
+    g.cnt = p->uniform ? nullptr : p->cnt_dev;
+    g.sc = NO_SCALE;
+    return g;
+}
+static bool fused_eligible(const sd_model* m, int M) {
+    const int MB = pow2_blocks(M);
+    return m->use_fused && m->fused_ok && (MB == 1 || MB == 2 || MB == 8);
+}
+// Layers 0..L-1 and, with want_lm, the final norm and the LM-head GEMM, whose partial sums the returned view
+// describes (without want_lm: the last down projection's, still to be added to m->x).
+static PartView run_forward_fused(sd_model* m, sd_kv* kv, int B, int Tp, int n_hi, bool want_lm, hipStream_t s) {
+    const sd_config& c = m->cfg;
+    const int M = B * Tp, MB = pow2_blocks(M), d = c.d_model, nh = c.n_heads, hd = c.head_dim, TB = Tp / 32, L = c.n_layers;
+    const AttnGeom ag = attn_geometry(m, B, Tp, n_hi);
+    const size_t t_stride = (size_t)B * nh * TB * 32 * hd;
+    launch_fill_i32((int32_t*)m->sync_ctr, 0, (L + 1) * FUSED_SYNC_WORDS, s);
+    m->fused_dirty = true;
+    FusedArgs a;
+    memset(&a, 0, sizeof(a));
+    a.M = M; a.MB = MB; a.B = B; a.Tp = Tp; a.d = d; a.nh = nh; a.hd = hd; a.F = c.d_ffn; a.Fpad = m->Fpad;
+    a.nparts = ag.nparts; a.eps = c.rms_eps;
+    a.x = m->x; a.opart = m->opart; a.mlpart = m->mlpart; a.att = (bf16x8*)m->attn_x;
+    a.xn_f = (bf16x8*)m->xn2; a.act = (bf16x8*)m->act; a.xn_a = (bf16x8*)m->xn;
+    a.ssq_f = m->ssq_f; a.ssq_a = m->ssq_a;
+    a.rt = m->rt; a.q = (bf16x8*)m->q; a.zfrag = (const bf16x8*)m->zfrag;
+    a.sync.abort_flag = m->sync_abort; a.sync.timeout_ticks = m->sync_timeout_ticks;
+    const double w_attn_side = (double)(3 * d) * m->KBd * 32.0, w_ffn_side = ((double)d * m->KBd + 2.0 * c.d_ffn * m->KBd + (double)d * m->KBf) * 32.0;
+    PartView last = {nullptr, 0, d, nullptr, 0};
+    for (int l = 0; l <= L; ++l) {                         // launch l: the end of layer l-1 and the start of layer l
+        double bytes = 0.0;
+        a.phases = 0;
+        a.sync.counters = m->sync_ctr + (size_t)l * FUSED_SYNC_WORDS;
+        if (l > 0) {
+            const LayerW& lw = m->layers[l - 1];
+            a.phases |= FUSED_GEMM_O | FUSED_GEMM_GU | FUSED_GEMM_DN;
+            a.g_o = fused_gemm(m, MB, m->KBd, m->NBo, m->attn_x, lw.wo, m->part_o);
+            a.gain_f = (const uint16_t*)lw.ffn_norm;
+            a.g_gu = fused_gemm(m, MB, m->KBd, m->NBgu, m->xn2, lw.wgu, m->part_gu);
+            a.g_gu.sc = row_scale(m, m->ssq_f);
+            a.g_dn = fused_gemm(m, MB, m->KBf, m->NBo, m->act, lw.wdown, m->part_dn);
+            bytes += w_ffn_side;
+            last = PartView{a.g_dn.out, a.g_dn.slot_stride, a.g_dn.ldo, a.g_dn.cnt, a.g_dn.nmax};
+        }
+        a.prev = PartView{nullptr, 0, d, nullptr, 0};
+        if (l < L) {
+            const LayerW& lw = m->layers[l];
+            a.phases |= FUSED_GEMM_Q | FUSED_ROPE;
+            a.gain_a = (const uint16_t*)lw.attn_norm;
+            a.g_q = fused_gemm(m, MB, m->KBd, m->NBqkv, m->xn, lw.wqkv, m->part_q);
+            a.g_q.sc = row_scale(m, m->ssq_a);
+            a.kt = (uint16_t*)m->kt + l * t_stride;
+            a.vt = (uint16_t*)m->vt + l * t_stride;
+            bytes += w_attn_side;
+        } else if (want_lm) {
+            a.phases |= FUSED_GEMM_Q;
+            a.gain_a = (const uint16_t*)m->final_norm;
+            a.g_q = fused_gemm(m, MB, m->KBd, m->NBv, m->xn, m->lm_head, m->part_q);
+            a.g_q.sc = row_scale(m, m->ssq_a);
+            bytes += (double)c.vocab * m->KBd * 32.0;
+            last = PartView{a.g_q.out, a.g_q.slot_stride, a.g_q.ldo, a.g_q.cnt, a.g_q.nmax};
+        }
+        a.timeline = (m->timeline && (size_t)l < m->timeline_launches) ? m->timeline + (size_t)l * 24 * 256 : nullptr;
+        const int pi = prof_claim(m, PROF_GEMM, bytes);
+        launch_layer(a, 256, s, prof_ev(m, pi, 0), prof_ev(m, pi, 1));
+        if (l < L) {
+            const int pa = prof_claim(m, PROF_ATTN, (double)B * (n_hi + Tp) * 2.0 * d * 2.0);
+            launch_tree_attn(m->q, kv->kc + l * kv->layer_stride, kv->vc + l * kv->layer_stride, a.kt, a.vt, kv->kv_len,
+                             m->rt.anc, m->opart, m->mlpart, B, nh, hd, Tp, kv->cap_blocks, ag.ncparts, ag.per, ag.tree_sep, s,
+                             prof_ev(m, pa, 0), prof_ev(m, pa, 1));
+        }
+    }
+    return last;
 }
 
 // final norm + LM head on all rows + arg-max of the first T rows of every sequence
@@ -689,10 +860,34 @@ static PartView run_layers(sd_model* m, sd_kv* kv, int B, int Tp, int n_hi, hipS
 static void run_lm_head(sd_model* m, PartView prev, int B, int T, int Tp, hipStream_t s, bool keep_h = false) {
     const sd_config& c = m->cfg;
     const int M = B * Tp, MB = pow2_blocks(M);
-    launch_norm_pack(m->x, prev, m->final_norm, c.rms_eps, m->xn, keep_h ? m->hf : nullptr, M, c.d_model, MB, nullptr, s);
-    PartView pl = run_gemm(m, m->xn, m->lm_head, m->part, MB, m->KBd, m->NBv, c.vocab, s);
+    PartView pl;
+    if (false) {                                           // (the deferred form, kept for comparison)
+        launch_norm_tile(m->x, prev, m->final_norm, m->xn, m->ssq_a, M, c.d_model, MB, s);
+        pl = run_gemm(m, m->xn, m->lm_head, m->part, MB, m->KBd, m->NBv, c.vocab, s, row_scale(m, m->ssq_a));
+    } else {                                               // the normalised rows themselves are wanted (m->hf), or 128 rows
+        launch_norm_pack(m->x, prev, m->final_norm, c.rms_eps, m->xn, keep_h ? m->hf : nullptr, M, c.d_model, MB, nullptr, s);
+        pl = run_gemm(m, m->xn, m->lm_head, m->part, MB, m->KBd, m->NBv, c.vocab, s);
+    }
     launch_reduce_slots(pl, m->logits, M, s);
     launch_argmax(m->logits, m->Vpad, c.vocab, m->am, B, T, Tp, s);
+}
+
+// The whole verifying pass: layers, and with want_lm the final norm, the LM head and the arg-max of the first T rows
+// of every sequence (logits in m->logits, arg-max in m->am).
+static void run_forward(sd_model* m, sd_kv* kv, int B, int T, int Tp, int n_hi, bool want_lm, bool keep_h, hipStream_t s) {
+    if (fused_eligible(m, B * Tp)) {
+        // (when the final norm's rows themselves are wanted, the last stage runs as kernels of its own)
+        PartView pl = run_forward_fused(m, kv, B, Tp, n_hi, want_lm && !keep_h, s);
+        if (want_lm && keep_h) {
+            run_lm_head(m, pl, B, T, Tp, s, true);
+        } else if (want_lm) {
+            launch_reduce_slots(pl, m->logits, B * Tp, s);
+            launch_argmax(m->logits, m->Vpad, m->cfg.vocab, m->am, B, T, Tp, s);
+        }
+        return;
+    }
+    PartView prev = run_layers(m, kv, B, Tp, n_hi, s);
+    if (want_lm) run_lm_head(m, prev, B, T, Tp, s, keep_h);
 }
 
 // draft heads at row last_row[b] of every sequence -> cand (sequences in seq_mask only)
@@ -765,13 +960,12 @@ extern "C" int sd_prefill(sd_model* m, sd_kv* kv, const int32_t* tokens, const i
         }
         launch_build_rows_chain(m->rt, tokens, ca, kv->kv_len, B, Tp, c.head_dim, c.rope_theta, m->embed, c.d_model,
                                 c.vocab, m->x, s);
-        PartView prev = run_layers(m, kv, B, Tp, n_hi, s);
+        run_forward(m, kv, B, Tp, Tp, n_hi, fin != 0, false, s);
         launch_prefill_commit_setup(ca, B, Tp, kv->i_slots, kv->i_nacc, kv->n_old, kv->kv_len, kv->last_row, s);
         launch_kv_commit(m->kt, m->vt, kv->kc, kv->vc, kv->i_slots, kv->i_nacc, kv->n_old, c.n_layers, B, c.n_heads,
                          c.head_dim, Tp / 32, kv->cap_blocks, Tp, Tp, s);
         for (int b = 0; b < B; ++b) kv->len_hi[b] += ca.len[b];
         if (fin) {
-            run_lm_head(m, prev, B, Tp, Tp, s);
             launch_pick_root(m->am, kv->last_row, kv->root_tok, B, fin, s);
             run_draft_heads(m, kv, B, fin, nullptr, s);
         }
@@ -812,8 +1006,7 @@ static int step_common(sd_model* m, sd_kv* kv, uint64_t tree_uid, const int32_t*
     auto enqueue = [&](hipStream_t s) {
     launch_build_rows_tree(m->rt, parent, depth, rank, kv->root_tok, cand, kv->kv_len, B, T, Tp, H, c.topk, c.head_dim,
                            c.rope_theta, m->embed, c.d_model, c.vocab, m->x, s);
-    PartView prev = run_layers(m, kv, B, Tp, n_hi, s);
-    run_lm_head(m, prev, B, T, Tp, s, all_rows);
+    run_forward(m, kv, B, T, Tp, n_hi, true, all_rows, s);
     if (io->logits) launch_copy_logits(m->logits, m->Vpad, io->logits, c.vocab, B, T, Tp, s);
     if (io->argmax) launch_copy_rows_i32(m->am, io->argmax, B, T, Tp, s);
     VerifyArgs va;
@@ -848,7 +1041,8 @@ static int step_common(sd_model* m, sd_kv* kv, uint64_t tree_uid, const int32_t*
                                      (uint64_t)(uintptr_t)slots, (uint64_t)(uintptr_t)io->n_accept_raw,
                                      (uint64_t)(uintptr_t)io->logits, (uint64_t)(uintptr_t)io->argmax,
                                      (uint64_t)(uintptr_t)io->head_logits, (uint64_t)(uintptr_t)cand,
-                                     (uint64_t)m->draft_schedule, (uint64_t)heads};
+                                     (uint64_t)m->draft_schedule, (uint64_t)heads,
+                                     (uint64_t)(m->use_fused ? 1 : 0) | ((uint64_t)m->sync_timeout_ticks << 1)};
         hipGraphExec_t exec = nullptr;
         for (const sd_model::StepGraph& g : m->graphs)
             if (g.key == key) { exec = g.exec; break; }

@@ -16,6 +16,7 @@
 //     the waves merge through LDS, the workgroups' partial (max, sum, O) triples are merged
 //     by a second small kernel, which also emits the packed bf16 operand of the O-projection.
 #include "sd_internal.h"
+#include "row_ops.h"
 
 #define NEG_INF (-__builtin_inff())
 
@@ -381,58 +382,14 @@ void launch_tree_attn(const void* q_packed, const void* kc, const void* vc, cons
 }
 
 // ------------------------------------------------------------------------------------------
-// Merge the split-KV partials and emit the packed bf16 operand of the O-projection.
-// one thread per (seq, head, query t, 8 consecutive output dims), grid (chunks of t x dims, head, seq);
-// the parts are read in batches
-// of eight whose loads are all issued before any is used (a part index past the end re-reads
-// the last part with weight zero, so no load sits behind a branch)
+// Merge the split-KV partials and emit the packed bf16 operand of the O-projection (body: row_ops.h).
+// one thread per (seq, head, query t, 8 consecutive output dims), grid (chunks of t x dims, head, seq)
 __global__ void k_attn_merge(const float* __restrict__ opart, const float2* __restrict__ mlpart,
                              bf16x8* __restrict__ xp, int nh, int hd, int e8_shift, int Tp, int nparts, int MB) {
-    constexpr int PB = 8;
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;      // hd / 8 = 1 << e8_shift pieces per query row
     const int e8 = idx & ((1 << e8_shift) - 1), t = idx >> e8_shift;
     if (t >= Tp) return;
-    const int h = blockIdx.y, b = blockIdx.z;
-    size_t base = ((size_t)b * nh + h) * nparts;
-    float M = NEG_INF, den = 0.f, o[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    for (int p0 = 0; p0 < nparts; p0 += PB) {
-        float2 ml[PB];
-        float4 a[PB], c[PB];
-#pragma unroll
-        for (int i = 0; i < PB; ++i) {
-            const int p = min(p0 + i, nparts - 1);
-            ml[i] = mlpart[(base + p) * Tp + t];
-            const float4* src = (const float4*)(opart + ((base + p) * Tp + t) * hd + e8 * 8);
-            a[i] = src[0];
-            c[i] = src[1];
-        }
-        float Mb = M;
-#pragma unroll
-        for (int i = 0; i < PB; ++i)
-            if (p0 + i < nparts && ml[i].y != 0.f) Mb = fmaxf(Mb, ml[i].x);       // an empty part has sum 0
-        if (Mb == NEG_INF) continue;
-        const float sold = exp2f(M - Mb);              // 0 when nothing was merged yet
-        den *= sold;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) o[j] *= sold;
-#pragma unroll
-        for (int i = 0; i < PB; ++i) {
-            const float w = (p0 + i < nparts && ml[i].y != 0.f) ? exp2f(ml[i].x - Mb) : 0.f;
-            den += w * ml[i].y;
-            o[0] += w * a[i].x; o[1] += w * a[i].y; o[2] += w * a[i].z; o[3] += w * a[i].w;
-            o[4] += w * c[i].x; o[5] += w * c[i].y; o[6] += w * c[i].z; o[7] += w * c[i].w;
-        }
-        M = Mb;
-    }
-    float inv = den > 0.f ? 1.f / den : 0.f;
-    bf16x8 hi, lo;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) o[i] *= inv;
-    split_hilo(o, hi, lo);
-    int m = b * Tp + t, k = h * hd + e8 * 8;
-    const size_t u = xpack_index(m, k, MB) >> 3;
-    xp[u] = hi;
-    xp[u + XPART / 8] = lo;
+    attn_merge_item<false>(opart, mlpart, xp, nh, hd, Tp, nparts, MB, /*b=*/blockIdx.z, /*h=*/blockIdx.y, t, e8);
 }
 
 void launch_attn_merge(const float* opart, const float2* mlpart, void* x_packed, int B, int nh, int hd, int Tp,

@@ -3,8 +3,7 @@
 // weight-streaming GEMMs, reduce the GEMMs' split partial sums, and emit the next GEMM's
 // operand directly in MFMA fragment order (bf16), so no separate conversion pass exists.
 #include "sd_internal.h"
-
-static __device__ inline float bf16_bits_to_float(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+#include "row_ops.h"
 
 // ------------------------------------------------------------------------------------------
 // Rotary angle table entry, in float64 so that positions up to ~17k lose nothing.
@@ -92,69 +91,14 @@ void launch_build_rows_chain(RowTable rt, const int32_t* tokens, const ChainArgs
 }
 
 // ------------------------------------------------------------------------------------------
-// x += sum of split partials (residual add of the previous projection), then
-// xn = x * rsqrt(mean(x^2) + eps) * gain, written as bf16 in fragment order.
-// One workgroup per row; a thread owns groups of 8 consecutive columns.
-#define NP_THREADS 512
-#define NP_MAXG 2   // d <= 8 * NP_THREADS * NP_MAXG = 8192
+// RMSNorm with the residual add of the previous projection's partial sums (body: row_ops.h). One workgroup per row.
 __global__ __launch_bounds__(NP_THREADS) void k_norm_pack(float* __restrict__ x, PartView pv,
                                                           const uint16_t* __restrict__ gain, float eps,
                                                           bf16x8* __restrict__ xn, float* __restrict__ hf, int d,
                                                           int MB, const int32_t* __restrict__ gather) {
-    const int m = blockIdx.x;
-    const int src = gather ? gather[m] : m;
-    float* xr = x + (size_t)src * d;
-    const int ngroups = d >> 3;
-    float v[NP_MAXG][8];
-    float ss = 0.f;
-#pragma unroll
-    for (int gi = 0; gi < NP_MAXG; ++gi) {
-        int grp = gi * NP_THREADS + threadIdx.x;
-        if (grp < ngroups) {
-            float4 a = *(const float4*)(xr + grp * 8), c = *(const float4*)(xr + grp * 8 + 4);
-            float t[8] = {a.x, a.y, a.z, a.w, c.x, c.y, c.z, c.w};
-            const int nsplit = pv.nmax > 0 ? part_count(pv, grp * 8) : 0;
-#pragma unroll 4
-            for (int sp = 0; sp < nsplit; ++sp) {
-                const float* p = pv.base + (size_t)sp * pv.slot_stride + (size_t)src * pv.ld + grp * 8;
-                float4 pa = *(const float4*)p, pc = *(const float4*)(p + 4);
-                t[0] += pa.x; t[1] += pa.y; t[2] += pa.z; t[3] += pa.w;
-                t[4] += pc.x; t[5] += pc.y; t[6] += pc.z; t[7] += pc.w;
-            }
-            if (nsplit > 0) {
-                *(float4*)(xr + grp * 8) = make_float4(t[0], t[1], t[2], t[3]);
-                *(float4*)(xr + grp * 8 + 4) = make_float4(t[4], t[5], t[6], t[7]);
-            }
-#pragma unroll
-            for (int i = 0; i < 8; ++i) { v[gi][i] = t[i]; ss += t[i] * t[i]; }
-        }
-    }
     __shared__ float red[NP_THREADS / 64];
-    for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
-    __syncthreads();
-    ss = 0.f;
-#pragma unroll
-    for (int w = 0; w < NP_THREADS / 64; ++w) ss += red[w];
-    const float r = rsqrtf(ss / (float)d + eps);
-#pragma unroll
-    for (int gi = 0; gi < NP_MAXG; ++gi) {
-        int grp = gi * NP_THREADS + threadIdx.x;
-        if (grp < ngroups) {
-            bf16x8 hi, lo;
-            float f[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) f[i] = v[gi][i] * r * bf16_bits_to_float(gain[grp * 8 + i]);
-            split_hilo(f, hi, lo);
-            const size_t u = xpack_index(m, grp * 8, MB) >> 3;
-            xn[u] = hi;
-            xn[u + XPART / 8] = lo;
-            if (hf) {
-                *(float4*)(hf + (size_t)m * d + grp * 8) = make_float4(f[0], f[1], f[2], f[3]);
-                *(float4*)(hf + (size_t)m * d + grp * 8 + 4) = make_float4(f[4], f[5], f[6], f[7]);
-            }
-        }
-    }
+    const int m = blockIdx.x;
+    norm_pack_row<false>(x, pv, gain, eps, xn, hf, d, MB, gather ? gather[m] : m, m, red);
 }
 
 void launch_norm_pack(float* x, PartView pv, const void* gain, float eps, void* xn_packed, float* hf_out, int M, int d,
@@ -163,10 +107,23 @@ void launch_norm_pack(float* x, PartView pv, const void* gain, float eps, void* 
                        (const uint16_t*)gain, eps, (bf16x8*)xn_packed, hf_out, d, MB, gather);
 }
 
+// RMSNorm with the scale deferred to the consuming GEMM (body: row_ops.h): one wave per tile of 32 rows x 16 columns.
+__global__ __launch_bounds__(256) void k_norm_tile(float* __restrict__ x, PartView pv, const uint16_t* __restrict__ gain,
+                                                   bf16x8* __restrict__ xn, float* __restrict__ ssq_part, int d, int MB,
+                                                   int Mp, int n_items) {
+    const int item = blockIdx.x * 4 + (threadIdx.x >> 6), nkb = d >> 4;
+    if (item >= n_items) return;
+    norm_tile<false>(x, pv, gain, xn, ssq_part, d, MB, Mp, item / nkb, item % nkb, threadIdx.x & 63);
+}
+void launch_norm_tile(float* x, PartView pv, const void* gain, void* xn_packed, float* ssq_part, int M, int d, int MB,
+                      hipStream_t s) {
+    const int n_items = (M / 32) * (d / 16);
+    hipLaunchKernelGGL(k_norm_tile, dim3((n_items + 3) / 4), dim3(256), 0, s, x, pv, (const uint16_t*)gain,
+                       (bf16x8*)xn_packed, ssq_part, d, MB, MB * 32, n_items);
+}
+
 // ------------------------------------------------------------------------------------------
-// Sum the QKV partials, rotate q and k to the row's position, and write q (fragment order,
-// two-term expansion), k and v (tree scratch, block layouts, bf16). Thread (m, h, a, which)
-// owns dims [8a, 8a+8) and their rotary partners [hd/2 + 8a, +8) of q (which=0), k (1) or v (2).
+// Rotary embedding and the tree K/V write from the QKV partial sums (body: row_ops.h).
 // grid (chunks of (h, a) x which, t, b): no index needs a division.
 __global__ void k_rope_kv(PartView pv, RowTable rt, bf16x8* __restrict__ qp, uint16_t* __restrict__ kt, uint16_t* __restrict__ vt, int Tp,
                           int nh, int hd, int na_shift) {
@@ -174,57 +131,7 @@ __global__ void k_rope_kv(PartView pv, RowTable rt, bf16x8* __restrict__ qp, uin
     const int ha = (blockIdx.x / 3) * blockDim.x + threadIdx.x;
     const int a = ha & ((1 << na_shift) - 1), h = ha >> na_shift;      // hd / 16 = 1 << na_shift
     if (h >= nh) return;
-    const int t = blockIdx.y, b = blockIdx.z, m = b * Tp + t;
-    const int d = nh * hd, half = hd / 2;
-    float4 s0 = make_float4(0, 0, 0, 0), s1 = s0, s2 = s0, s3 = s0;       // dims 8a..8a+7, half+8a..+7
-    const int col0 = which * d + h * hd + a * 8;
-    const float* p0 = pv.base + (size_t)m * pv.ld + col0;
-    const int nsplit = part_count(pv, col0);           // a head's columns share one 256-column group
-    for (int sp = 0; sp < nsplit; ++sp) {
-        const float* p = p0 + (size_t)sp * pv.slot_stride;
-        float4 x0 = *(const float4*)p, x1 = *(const float4*)(p + 4);
-        float4 x2 = *(const float4*)(p + half), x3 = *(const float4*)(p + half + 4);
-        s0.x += x0.x; s0.y += x0.y; s0.z += x0.z; s0.w += x0.w;
-        s1.x += x1.x; s1.y += x1.y; s1.z += x1.z; s1.w += x1.w;
-        s2.x += x2.x; s2.y += x2.y; s2.z += x2.z; s2.w += x2.w;
-        s3.x += x3.x; s3.y += x3.y; s3.z += x3.z; s3.w += x3.w;
-    }
-    float lo[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
-    float hi[8] = {s2.x, s2.y, s2.z, s2.w, s3.x, s3.y, s3.z, s3.w};
-    const int TB = Tp / 32;
-    const size_t head_off = ((size_t)b * nh + h) * TB * (32 * hd);
-    if (which == 2) {                                   // values: not rotated, scattered bf16
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            __bf16 w1 = (__bf16)lo[i], w2 = (__bf16)hi[i];
-            vt[head_off + vblk_index(t, a * 8 + i, hd)] = __builtin_bit_cast(uint16_t, w1);
-            vt[head_off + vblk_index(t, half + a * 8 + i, hd)] = __builtin_bit_cast(uint16_t, w2);
-        }
-        return;
-    }
-    float r1[8], r2[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        float2 cs = rt.cs[(size_t)m * half + a * 8 + i];
-        r1[i] = lo[i] * cs.x - hi[i] * cs.y;
-        r2[i] = hi[i] * cs.x + lo[i] * cs.y;
-    }
-    if (which == 0) {                                   // queries: two-term expansion
-        bf16x8 h1, l1, h2, l2;
-        split_hilo(r1, h1, l1);
-        split_hilo(r2, h2, l2);
-        size_t q1i = 2 * head_off + qblk_index(t, a * 8, hd), q2i = 2 * head_off + qblk_index(t, half + a * 8, hd);
-        qp[q1i >> 3] = h1;
-        qp[(q1i >> 3) + 64] = l1;
-        qp[q2i >> 3] = h2;
-        qp[(q2i >> 3) + 64] = l2;
-    } else {                                            // keys: bf16, the cache's storage type
-        bf16x8 k1, k2;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) { k1[i] = (__bf16)r1[i]; k2[i] = (__bf16)r2[i]; }
-        ((bf16x8*)kt)[(head_off + kblk_index(t, a * 8, hd)) >> 3] = k1;
-        ((bf16x8*)kt)[(head_off + kblk_index(t, half + a * 8, hd)) >> 3] = k2;
-    }
+    rope_kv_item<false>(pv, rt, qp, kt, vt, Tp, nh, hd, which, h, a, blockIdx.y, blockIdx.z);
 }
 
 void launch_rope_kv(PartView pv, RowTable rt, void* q_packed, void* kt, void* vt, int B, int Tp, int nh, int hd,
@@ -235,33 +142,11 @@ void launch_rope_kv(PartView pv, RowTable rt, void* q_packed, void* kt, void* vt
 }
 
 // ------------------------------------------------------------------------------------------
-// act = silu(gate) * up from the gate/up partials (gate in columns [0,F), up in [Fpad, Fpad+F)).
-// grid (chunks of 8-column groups, row)
+// SwiGLU from the gate/up partial sums (body: row_ops.h). grid (chunks of 8-column groups, row)
 __global__ void k_swiglu_pack(PartView pv, int F, int Fpad, bf16x8* __restrict__ act, int MB) {
     const int grp = blockIdx.x * blockDim.x + threadIdx.x, m = blockIdx.y;
     if (grp >= F / 8) return;
-    float gsum[8] = {0, 0, 0, 0, 0, 0, 0, 0}, usum[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    const int ng_ = part_count(pv, grp * 8), nu_ = part_count(pv, Fpad + grp * 8);
-    for (int sp = 0; sp < ng_; ++sp) {
-        const float* p = pv.base + (size_t)sp * pv.slot_stride + (size_t)m * pv.ld + grp * 8;
-        float4 a = *(const float4*)p, c = *(const float4*)(p + 4);
-        gsum[0] += a.x; gsum[1] += a.y; gsum[2] += a.z; gsum[3] += a.w;
-        gsum[4] += c.x; gsum[5] += c.y; gsum[6] += c.z; gsum[7] += c.w;
-    }
-    for (int sp = 0; sp < nu_; ++sp) {
-        const float* p = pv.base + (size_t)sp * pv.slot_stride + (size_t)m * pv.ld + Fpad + grp * 8;
-        float4 ua = *(const float4*)p, uc = *(const float4*)(p + 4);
-        usum[0] += ua.x; usum[1] += ua.y; usum[2] += ua.z; usum[3] += ua.w;
-        usum[4] += uc.x; usum[5] += uc.y; usum[6] += uc.z; usum[7] += uc.w;
-    }
-    bf16x8 hi, lo;
-    float f[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) f[i] = gsum[i] / (1.f + __expf(-gsum[i])) * usum[i];
-    split_hilo(f, hi, lo);
-    const size_t u = xpack_index(m, grp * 8, MB) >> 3;
-    act[u] = hi;
-    act[u + XPART / 8] = lo;
+    swiglu_item<false>(pv, F, Fpad, act, MB, m, grp);
 }
 
 void launch_swiglu_pack(PartView pv, int F, int Fpad, void* act_packed, int M, int MB, hipStream_t s) {

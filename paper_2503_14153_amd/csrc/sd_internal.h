@@ -89,6 +89,16 @@ struct PartView {
 static __device__ inline int part_count(const PartView& p, int col) { return p.cnt ? p.cnt[col >> 8] : p.nmax; }
 #endif
 
+// Rows whose RMSNorm scale is applied AFTER the contraction (the operand holds x * gain, see row_ops.h):
+// ssq [ceil(n_parts / 4)][Mp][4] partial sums of squares of every row (Mp = the GEMM's padded row count, part p of
+// row m at ((p / 4) * Mp + m) * 4 + p % 4; parts beyond n_parts are zero); every output of row m is multiplied by
+// 1 / sqrt(sum_p ssq[p][m] * inv_d + eps).
+struct SkRowScale {
+    const float* ssq;        // NULL: no scaling
+    int n_parts;
+    float inv_d, eps;
+};
+
 // How one GEMM shape is launched (made once per shape at model creation).
 struct GemmPlan {
     int MB, KB, NB;
@@ -98,6 +108,51 @@ struct GemmPlan {
     int uniform;             // 1: every column group has exactly `slots` contributors
     int32_t* cnt_dev;        // [NG] contributors per column group (device)
     int32_t* slot0_dev;      // [G] slot of every workgroup's first segment (device)
+};
+
+// ---- the persistent layer kernel (fused.hip) -----------------------------------------------
+// One weight-streaming GEMM as a phase: its plan, operands and the buffer of its partial sums.
+struct FusedGemm {
+    const bf16x8* X;         // packed activations (written by an earlier phase of the same launch)
+    const bf16x8* W;         // packed weights
+    float* out;              // partial sums [slot][row][col]
+    size_t slot_stride;
+    int KB, NB, ldo, upw, rem, G, nmax;
+    uint32_t kb_magic;
+    const int32_t* slot0;    // [G]
+    const int32_t* cnt;      // [NG] or NULL (nmax slots everywhere)
+    SkRowScale sc;           // deferred RMS scale of the rows (the GEMMs that follow a norm), or ssq NULL
+};
+struct FusedSync {
+    unsigned* counters;      // this launch's barrier counters: 9 words 256 bytes apart, zero at launch
+    unsigned* abort_flag;    // set to 1 by a workgroup whose wait ran out
+    unsigned long long timeout_ticks;   // of the 100 MHz real-time counter
+};
+// what a launch runs, in this order; each GEMM comes with the row-wise phase that produces its operand
+enum {
+    FUSED_GEMM_O = 1,        // merge of the attention parts, O projection
+    FUSED_GEMM_GU = 2,       // residual + norm (feed-forward), gate/up projection
+    FUSED_GEMM_DN = 4,       // SwiGLU, down projection
+    FUSED_GEMM_Q = 8,        // residual + norm (attention, or the final one), QKV projection or LM head
+    FUSED_ROPE = 16          // rotary embedding and the tree K/V write
+};
+#define FUSED_SYNC_WORDS 1024    // counters of one launch (9 used, spaced 64 words)
+struct FusedArgs {
+    uint32_t phases;         // FUSED_* bits
+    int M, MB, B, Tp, d, nh, hd, F, Fpad, nparts;
+    float eps;
+    float* x;                // residual stream [M][d]
+    const float* opart; const float2* mlpart;      // attention parts (merge)
+    bf16x8* att;             // merged attention output, operand of g_o
+    FusedGemm g_o, g_gu, g_dn, g_q;
+    const uint16_t* gain_f; bf16x8* xn_f; float* ssq_f;   // norm before the feed-forward block -> operand of g_gu
+    bf16x8* act;             // SwiGLU output, operand of g_dn
+    const uint16_t* gain_a; bf16x8* xn_a; float* ssq_a;   // norm before attention (or the final norm) -> operand of g_q
+    PartView prev;           // what NORM_A adds when the launch starts with it
+    RowTable rt; bf16x8* q; uint16_t* kt; uint16_t* vt;   // rotary phase outputs
+    const bf16x8* zfrag;
+    FusedSync sync;
+    unsigned long long* timeline;   // NULL, or [24][gridDim.x] time stamps (100 MHz): entry to each phase, end of launch
 };
 
 #define SD_MAX_BATCH 32
@@ -128,8 +183,13 @@ void gemm_plan_make(GemmPlan* p, int MB, int KB, int NB, int32_t* cnt_host, int3
 // returns the view consumers read
 // ev0 / ev1 (both or neither): events that receive the kernel's own start and end time stamps,
 // for per-kernel timing without launch gaps
+// sc: deferred RMS scale of the rows (ssq NULL: none; not available at four row blocks)
 PartView launch_gemm(const GemmPlan& p, const void* Xp, const void* Wp, const void* zfrag, float* out, hipStream_t s,
-                     hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
+                     hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr, SkRowScale sc = SkRowScale{nullptr, 0, 0.f, 0.f});
+// persistent layer kernel: G workgroups (all must be resident at once), a.MB in {1, 2, 8}
+void launch_layer(const FusedArgs& a, int G, hipStream_t s, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
+// how many of its workgroups the device can hold at once (0 on error)
+int fused_max_resident(int device);
 void launch_reduce_slots(PartView pv, float* dst, int rows, hipStream_t s);
 // dst row i*B + b = summed row (i*M + sel[b]) - row0 of pv when it lies in [0, rows); i < H, b < B
 void launch_reduce_selected(PartView pv, float* dst, const int32_t* sel, int B, int H, int M, int row0, int rows,
@@ -144,6 +204,9 @@ void launch_build_rows_chain(RowTable rt, const int32_t* tokens, const ChainArgs
                              hipStream_t s);
 void launch_norm_pack(float* x, PartView pv, const void* gain, float eps, void* xn_packed, float* hf_out,
                       int M, int d, int MB, const int32_t* gather, hipStream_t s);
+// RMSNorm with the scale deferred: operand = x * gain, ssq_part = partial sums of squares in SkRowScale's layout
+void launch_norm_tile(float* x, PartView pv, const void* gain, void* xn_packed, float* ssq_part, int M, int d, int MB,
+                      hipStream_t s);
 void launch_rope_kv(PartView pv, RowTable rt, void* q_packed, void* kt, void* vt, int B, int Tp, int nh, int hd,
                     hipStream_t s);
 void launch_tree_attn(const void* q_packed, const void* kc, const void* vc, const void* kt, const void* vt,

@@ -100,6 +100,9 @@ def test_null_arguments_are_refused_before_any_device_call(lib):
     assert lib.sd_set_draft_schedule(null, 0) == d["SD_ERR_NULL"]
     assert lib.sd_set_graph_mode(null, 1) == d["SD_ERR_NULL"]
     assert lib.sd_set_greedy_drafts(null, 1) == d["SD_ERR_NULL"]
+    assert lib.sd_set_fused(null, 1) == d["SD_ERR_NULL"]
+    assert lib.sd_set_sync_timeout(null, 5) == d["SD_ERR_NULL"]
+    assert lib.sd_set_layer_timeline(null, null, 0) == d["SD_ERR_NULL"]
     assert lib.sd_profile_begin(null, 16) == d["SD_ERR_NULL"]
     assert lib.sd_model_create(null, null, 64, null, null) == d["SD_ERR_NULL"]
     # destroying nothing is allowed

@@ -84,7 +84,7 @@ def _plant_along_a_path(cand, truth, tree_np, depth_want, pick):
 
 
 def _run_batch_steps(sd, shape, B, T, lens, cap, n_steps, tree_np=None, plant=True, fallback="keep_all",
-                     weights_device="cpu", schedule="after_accept"):
+                     weights_device="cpu", schedule="after_accept", fused=False):
     """Lock-step speculative steps of a batch against one oracle state per sequence.
 
     Drafts: the oracle's own greedy continuation of every sequence is planted along one root path of the tree,
@@ -99,6 +99,7 @@ def _run_batch_steps(sd, shape, B, T, lens, cap, n_steps, tree_np=None, plant=Tr
     H = shape.n_medusa
     model = sd.Model(shape, {k: v.cuda() for k, v in weights.items()}, B * Tp, fallback)
     model.set_draft_schedule(schedule)
+    model.set_fused(fused)
     kv = sd.KVCache(model, B, cap)
     stop0 = wl.stop_set(shape.vocab, 0.2)
     tree_np = tree_np or wl.default_tree(T, shape.n_medusa, shape.topk)
