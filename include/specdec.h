@@ -203,6 +203,19 @@ int sd_verify_tree_typical(const sd_tree* tree, int32_t batch, int32_t n_medusa,
                            float epsilon, float delta, const uint32_t* stop_mask, float* row_stats,
                            int32_t* n_accept, int32_t* n_accept_raw, int32_t* tokens, int32_t* src_slots,
                            void* stream);
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): sd_verify_tree_typical without its row_stats argument. The per-node
+ * statistics live in a static device array inside the library (64 KiB per GPU, held until the process
+ * ends) instead of a buffer the caller brings; the call allocates nothing and calls no allocating routine.
+ * Arguments and outputs as sd_verify_tree_typical. Limit: batch * tree nodes <= 4096, SD_ERR_SHAPE beyond
+ * (nothing is enqueued). All calls on one GPU share that GPU's array: two calls whose kernels may overlap
+ * in time there (different streams, or threads) race on it; calls on one stream are safe. The first call
+ * on a device looks the array's address up; use it from one device context per thread as the other calls. */
+int sd_verify_tree_typical_static(const sd_tree* tree, int32_t batch, int32_t n_medusa, int32_t trunc_fallback,
+                                  int32_t vocab, const int32_t* tok, const float* logits, float temperature,
+                                  float epsilon, float delta, const uint32_t* stop_mask,
+                                  int32_t* n_accept, int32_t* n_accept_raw, int32_t* tokens, int32_t* src_slots,
+                                  void* stream);
 /* Inverse-CDF draws alone (the sampling half of Section IV-A's decoding setting): out[i] =
  * smallest id whose cumulative probability under softmax(logits[rows[i]] / temperature)
  * exceeds u[i]. logits dev [n_rows][ld] with ld >= vocab; rows, u, out dev [n], n <= 65535;

@@ -7,5 +7,5 @@ call does, and fails loudly if it has not been built (`python -m paper_2503_1415
 """
 from .binding import (  # noqa: F401
     KVCache, Model, build_labels, SpecDecError, StepOutput, Tree, greedy_step, lib, lib_path, prefill, sample_tokens, spec_step,
-    spec_step_typical, verify_tree, verify_tree_typical, EXPORTED_SYMBOLS,
+    spec_step_typical, verify_tree, verify_tree_typical, verify_tree_typical_static, EXPORTED_SYMBOLS,
 )

@@ -14,7 +14,7 @@ EXPORTED_SYMBOLS = [
     "sd_model_create", "sd_model_destroy", "sd_kv_bytes", "sd_kv_create", "sd_kv_destroy", "sd_kv_len",
     "sd_kv_set_len", "sd_kv_write_rows", "sd_kv_read_rows", "sd_kv_set_draft", "sd_kv_get_draft",
     "sd_tree_create", "sd_tree_destroy", "sd_prefill", "sd_spec_step", "sd_greedy_step", "sd_verify_tree",
-    "sd_spec_step_typical", "sd_verify_tree_typical", "sd_sample_tokens", "sd_build_labels",
+    "sd_spec_step_typical", "sd_verify_tree_typical", "sd_verify_tree_typical_static", "sd_sample_tokens", "sd_build_labels",
     "sd_set_graph_mode", "sd_set_draft_schedule", "sd_set_greedy_drafts", "sd_set_fused", "sd_set_sync_timeout", "sd_set_layer_timeline", "sd_profile_begin", "sd_profile_end", "sd_last_error", "sd_version",
 ]
 
@@ -90,6 +90,8 @@ def lib() -> C.CDLL:
                                            C.POINTER(_Typical), C.c_void_p]
         L.sd_verify_tree_typical.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                              C.c_void_p, C.c_float, C.c_float, C.c_float] + [C.c_void_p] * 7
+        L.sd_verify_tree_typical_static.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                                    C.c_void_p, C.c_float, C.c_float, C.c_float] + [C.c_void_p] * 6
         L.sd_sample_tokens.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
                                        C.c_float, C.c_void_p, C.c_void_p]
         L.sd_build_labels.argtypes = [C.c_void_p] + [C.c_int32] * 7 + [C.c_void_p, C.c_void_p]
@@ -382,6 +384,24 @@ def verify_tree_typical(tree: Tree, tok: torch.Tensor, logits: torch.Tensor, sto
                                         stats.data_ptr(), n_acc.data_ptr(), n_raw.data_ptr(), tokens.data_ptr(),
                                         slots.data_ptr(), _stream()))
     return n_acc, n_raw, tokens, slots, stats
+
+
+def verify_tree_typical_static(tree: Tree, tok: torch.Tensor, logits: torch.Tensor, stop_mask: torch.Tensor, out, *,
+                               temperature: float, epsilon: float, delta: float, trunc_fallback: str = "keep_all"):
+    """sd_verify_tree_typical_static: as verify_tree_typical, statistics in the library's static buffer.
+    `out` = (n_accept, n_accept_raw, tokens, src_slots), int32 CUDA tensors the caller made beforehand:
+    nothing is allocated here or in the library."""
+    batch, T, vocab = logits.shape
+    assert T == tree.T and tok.shape == (batch, T) and tok.dtype == torch.int32 and logits.dtype == torch.float32
+    assert tok.is_contiguous() and logits.is_contiguous() and tok.is_cuda and logits.is_cuda
+    n_acc, n_raw, tokens, slots = out
+    W = tree.n_medusa + 1
+    assert n_acc.numel() >= batch and n_raw.numel() >= batch and tokens.numel() >= batch * W and slots.numel() >= batch * W
+    _check(lib().sd_verify_tree_typical_static(tree.handle, batch, tree.n_medusa,
+                                               {"keep_all": 0, "keep_one": 1}[trunc_fallback], vocab, tok.data_ptr(),
+                                               logits.data_ptr(), temperature, epsilon, delta, stop_mask.data_ptr(),
+                                               n_acc.data_ptr(), n_raw.data_ptr(), tokens.data_ptr(), slots.data_ptr(),
+                                               _stream()))
 
 
 def sample_tokens(logits: torch.Tensor, rows: torch.Tensor, u: torch.Tensor, temperature: float) -> torch.Tensor:

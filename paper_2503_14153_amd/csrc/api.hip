@@ -1155,6 +1155,68 @@ extern "C" int sd_verify_tree_typical(const sd_tree* tree, int32_t batch, int32_
     return SD_OK;
 }
 
+// ------------------------------------------------------------------------------------------ no allocation
+// Per-node statistics of sd_verify_tree_typical_static: one copy per GPU, held until the process ends.
+#define SD_STATIC_ROWS 4096
+static __device__ __align__(256) float4 scratch[SD_STATIC_ROWS];
+// Device address of `scratch` on every GPU this process has used it on. The array's name is only a host-side
+// handle: the address a kernel can use comes from hipGetSymbolAddress, per device.
+#define SD_MAX_DEVICES 64
+static float4* g_scratch_dev[SD_MAX_DEVICES] = {};
+
+static int static_scratch(float4** out) {
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= SD_MAX_DEVICES) return fail(SD_ERR_SHAPE, "device ordinal %d not supported", dev);
+    float4* p = __atomic_load_n(&g_scratch_dev[dev], __ATOMIC_ACQUIRE);
+    if (!p) {                                          // first call on this device (two racing threads get the same answer)
+        void* addr = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&addr, HIP_SYMBOL(scratch)));
+        if (!addr) return fail(SD_ERR_HIP, "hipGetSymbolAddress returned no address");
+        p = (float4*)addr;
+        __atomic_store_n(&g_scratch_dev[dev], p, __ATOMIC_RELEASE);
+    }
+    *out = p;
+    return SD_OK;
+}
+
+extern "C" int sd_verify_tree_typical_static(const sd_tree* tree, int32_t batch, int32_t n_medusa,
+                                             int32_t trunc_fallback, int32_t vocab, const int32_t* tok,
+                                             const float* logits, float temperature, float epsilon, float delta,
+                                             const uint32_t* stop_mask, int32_t* n_accept, int32_t* n_accept_raw,
+                                             int32_t* tokens, int32_t* src_slots, void* stream) {
+    if (!tree || !tok || !logits || !stop_mask || !n_accept || !tokens || !src_slots)
+        return fail(SD_ERR_NULL, "sd_verify_tree_typical_static: NULL argument");
+    if (batch < 1 || batch > 65535) return fail(SD_ERR_SHAPE, "sd_verify_tree_typical_static: bad batch");
+    if ((int64_t)batch * tree->T > SD_STATIC_ROWS)
+        return fail(SD_ERR_SHAPE, "sd_verify_tree_typical_static: batch * tree nodes = %lld exceeds the %d rows of the "
+                    "static statistics buffer (use sd_verify_tree_typical with a buffer of your own)",
+                    (long long)batch * tree->T, SD_STATIC_ROWS);
+    if (vocab < 1 || vocab > 163840) return fail(SD_ERR_SHAPE, "sd_verify_tree_typical_static: bad vocab");
+    if (n_medusa != tree->H)
+        return fail(SD_ERR_BAD_TREE, "sd_verify_tree_typical_static: tree was built for %d heads", tree->H);
+    if (trunc_fallback != SD_TRUNC_KEEP_ALL && trunc_fallback != SD_TRUNC_KEEP_ONE)
+        return fail(SD_ERR_SHAPE, "sd_verify_tree_typical_static: bad trunc_fallback");
+    if (int rc = check_typical(temperature, epsilon, delta, "sd_verify_tree_typical_static")) return rc;
+    float4* stats = nullptr;
+    if (int rc = static_scratch(&stats)) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    const int T = tree->T;
+    // every row of the statistics that the acceptance kernel reads is written first by this launch, so nothing
+    // of the previous call's contents needs clearing
+    launch_row_stats(logits, vocab, vocab, stats, batch, T, T, 1.f / temperature, epsilon, delta, s);
+    VerifyArgs va;
+    memset(&va, 0, sizeof(va));
+    va.parent = tree->parent; va.depth = tree->depth; va.T = T; va.H = tree->H; va.fallback = trunc_fallback;
+    va.src_stride = T; va.Tp = tree->Tp; va.V = vocab;
+    va.tok = tok; va.am = tok; va.stop_mask = stop_mask;      // am is not read under typical acceptance
+    va.n_accept = n_accept; va.n_accept_raw = n_accept_raw; va.tokens = tokens; va.src_slots = src_slots;
+    va.logits = logits; va.ld = vocab; va.row_stats = stats; va.inv_temperature = 1.f / temperature;
+    launch_verify(va, batch, s);
+    HIP_TRY(hipGetLastError());
+    return SD_OK;
+}
+
 extern "C" int sd_sample_tokens(const float* logits, int32_t n_rows, int32_t ld, int32_t vocab, const int32_t* rows,
                                 const float* u, int32_t n, float temperature, int32_t* out, void* stream) {
     if (!logits || !rows || !u || !out) return fail(SD_ERR_NULL, "sd_sample_tokens: NULL argument");
