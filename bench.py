@@ -41,7 +41,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=256)
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", default="7b", choices=["7b", "7b-long", "7b-batch8", "13b", "7b-h10", "tiny", "labels"],
+    ap.add_argument("--workload", default="7b", choices=["7b", "7b-long", "7b-batch8", "13b", "7b-h10", "tiny", "labels", "kv-commit"],
                     help="labels = the training-side label construction alone (not the headline step); "
                          "7b-batch8 = eight ragged sequences, the model's own drafts, step time only")
     ap.add_argument("--draft-schedule", default="after_accept", choices=["after_accept", "all_nodes"],
@@ -81,6 +81,8 @@ def main():
     torch.cuda.set_device(0)
     if args.workload == "labels":
         return bench_labels(args, torch, wl, sd)
+    if args.workload == "kv-commit":
+        return bench_kv_commit(args, torch, wl, sd)
     W = wl.preset(args.workload, args.layers)
     if W.batch > 1:
         return bench_batch(args, torch, wl, sd, W)
@@ -359,6 +361,76 @@ def bench_batch(args, torch, wl, sd, W):
                      "algorithmic_bytes_per_launch": g["bytes"] / max(g["launches"], 1)},
         "attention": {"kernel": "k_tree_attn", "achieved_GBs": a["bytes"] / max(a["ms"], 1e-9) / 1e6,
                       "avg_launch_us": a["ms"] / max(a["launches"], 1) * 1e3},
+        "cpu_baseline": None}))
+
+
+def bench_kv_commit(args, torch, wl, sd):
+    """The commit of accepted K/V rows (the last stage of a step) under stress: the batched 7B shape (8 sequences
+    of 32-node trees, 32 layers, lengths in [1024, 4096]) with every sequence accepting H + 1 = 5 tree rows, and a
+    long list (all 32 tree rows of every sequence). In a step the stage moves at most 2.6 MB per sequence and is
+    bound by its launch; here it is timed alone, launch after launch, with HIP events on the launch stream.
+    Algorithmic bytes = rows * (K and V) * d * 2 bytes * layers, read once and written once."""
+    W = wl.preset("7b-batch8", args.layers)
+    shape = dataclasses.replace(W.model, dtype="bf16")
+    B, T, H, k = W.batch, W.tree_nodes, shape.n_medusa, shape.topk
+    Tp = (T + 31) // 32 * 32
+    model = sd.Model(shape, wl.make_weights(shape, device="cuda"), max_rows=B * Tp)
+    torch.cuda.empty_cache()
+    kv = sd.KVCache(model, B, W.kv_cap)
+    rng = np.random.Generator(np.random.Philox(key=wl.SEEDS["kvlen"]))
+    lens = [int(x) for x in rng.integers(1024, 4097 - 64, size=B)]
+    kv.set_len(lens)
+    roots = rng.integers(shape.vocab, size=B).astype(np.int32)
+    cand = np.stack([np.stack([rng.permutation(shape.vocab)[:k] for _ in range(H)]) for _ in range(B)]).astype(np.int32)
+    kv.set_draft(roots, cand)
+    tree_np = wl.default_tree(T, H, k)
+    tree = sd.Tree(*tree_np, H, k)
+    words = torch.zeros((shape.vocab + 31) // 32, dtype=torch.int32, device="cuda")
+    sd.spec_step(model, kv, tree, words)                  # fills the tree scratch of all sequences and layers
+    torch.cuda.synchronize()
+    results = {}
+    for label, width in (("accepted_chain", H + 1), ("all_tree_rows", Tp)):
+        # a root path of the tree for the short list (what a step commits), every row for the long one
+        if width == H + 1:
+            j = int(np.argmax(tree_np[1]))
+            path = []
+            while j >= 0:
+                path.append(j)
+                j = int(tree_np[0][j])
+            slots_row = (path[::-1] + [0] * width)[:width]
+        else:
+            slots_row = list(range(width))
+        slots = torch.tensor([slots_row] * B, dtype=torch.int32, device="cuda")
+        n_rows = torch.full((B,), width, dtype=torch.int32, device="cuda")
+        per_window = max(1, (W.kv_cap - max(lens)) // width - 1)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        total_ms, launches = 0.0, 0
+        for it in range(args.warmup + args.steps):
+            kv.set_len(lens)                              # synchronises; outside the timed launches
+            e0.record()
+            for _ in range(per_window):
+                sd.kv_commit_rows(model, kv, slots, n_rows)
+            e1.record()
+            torch.cuda.synchronize()
+            if it >= args.warmup:
+                total_ms += e0.elapsed_time(e1)
+                launches += per_window
+        us = total_ms / launches * 1e3 / 2                # two launches per call: the length bookkeeping and the copy
+        nbytes = 2.0 * B * width * 2 * shape.d_model * 2 * shape.n_layers
+        results[label] = {"rows_per_sequence": width, "us_per_call": total_ms / launches * 1e3,
+                          "algorithmic_bytes": nbytes, "achieved_GBs": nbytes / (total_ms / launches * 1e-3) / 1e9}
+        del us
+    best = results["all_tree_rows"]
+    print(json.dumps({
+        "metric": "kv_commit_GBps", "value": best["achieved_GBs"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": best["us_per_call"] / 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"kv-commit stress: {shape.n_layers}-layer d={shape.d_model} cache, batch {B}, lengths {lens}, "
+                               f"{Tp}-row tree scratch; per call the length bookkeeping kernel and the copy kernel"},
+        "variants": results,
+        "roofline": {"kernel": "k_kv_commit (stress variant, not the step)", "bound": "hbm", "achieved": best["achieved_GBs"],
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": best["achieved_GBs"] / HBM_PEAK_GBS, "traffic": None,
+                     "avg_launch_us": best["us_per_call"], "algorithmic_bytes_per_launch": best["algorithmic_bytes"]},
         "cpu_baseline": None}))
 
 

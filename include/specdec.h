@@ -195,6 +195,16 @@ int sd_verify_tree(const sd_tree* tree, int32_t batch, int32_t n_medusa, int32_t
                    int32_t* n_accept, int32_t* n_accept_raw, int32_t* tokens, int32_t* src_slots,
                    void* stream);
 
+/* Commit of key/value rows alone (the last stage of a step, Section III-B: the accepted tokens become part of the
+ * sequence): for every sequence b of `kv`, rows src_slots[b][0 .. n_rows[b]) of the tree rows that the LAST step or
+ * prefill chunk of this model over this cache's batch computed are appended to the cache, in that order, and the
+ * committed length grows by n_rows[b] (clamped to 0 .. width). src_slots: dev [batch][width], tree row numbers
+ * below the last pass's padded tree size (clamped); n_rows: dev [batch]. Keys are copied as they are (they were
+ * rotated for the position depth(node) after the old length: only meaningful when row j has depth j). SD_ERR_STATE
+ * without such a pass, SD_ERR_SHAPE for a bad width, SD_ERR_KV_FULL judged on width rows per sequence.              */
+int sd_kv_commit_rows(sd_model* m, sd_kv* kv, const int32_t* src_slots, const int32_t* n_rows, int32_t width,
+                      void* stream);
+
 /* Typical acceptance + fragment cut alone (Section III-B, Eq. 1): logits dev
  * [batch][T][vocab] = base logits of every node, tok dev [batch][T]. Writes row_stats (dev
  * [batch][T][4], required, layout as in sd_typical) and then the four outputs as above.     */

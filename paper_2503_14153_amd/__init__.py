@@ -6,6 +6,6 @@ for device memory and streams. Importing the package does not load the library; 
 call does, and fails loudly if it has not been built (`python -m paper_2503_14153_amd.build`).
 """
 from .binding import (  # noqa: F401
-    KVCache, Model, build_labels, SpecDecError, StepOutput, Tree, greedy_step, lib, lib_path, prefill, sample_tokens, spec_step,
+    KVCache, Model, build_labels, kv_commit_rows, SpecDecError, StepOutput, Tree, greedy_step, lib, lib_path, prefill, sample_tokens, spec_step,
     spec_step_typical, verify_tree, verify_tree_typical, verify_tree_typical_static, EXPORTED_SYMBOLS,
 )

@@ -14,7 +14,7 @@ EXPORTED_SYMBOLS = [
     "sd_model_create", "sd_model_destroy", "sd_kv_bytes", "sd_kv_create", "sd_kv_destroy", "sd_kv_len",
     "sd_kv_set_len", "sd_kv_write_rows", "sd_kv_read_rows", "sd_kv_set_draft", "sd_kv_get_draft",
     "sd_tree_create", "sd_tree_destroy", "sd_prefill", "sd_spec_step", "sd_greedy_step", "sd_verify_tree",
-    "sd_spec_step_typical", "sd_verify_tree_typical", "sd_verify_tree_typical_static", "sd_sample_tokens", "sd_build_labels",
+    "sd_kv_commit_rows", "sd_spec_step_typical", "sd_verify_tree_typical", "sd_verify_tree_typical_static", "sd_sample_tokens", "sd_build_labels",
     "sd_set_graph_mode", "sd_set_draft_schedule", "sd_set_greedy_drafts", "sd_set_fused", "sd_set_sync_timeout", "sd_set_layer_timeline", "sd_profile_begin", "sd_profile_end", "sd_last_error", "sd_version",
 ]
 
@@ -86,6 +86,7 @@ def lib() -> C.CDLL:
         L.sd_spec_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(_StepIO), C.c_void_p]
         L.sd_greedy_step.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(_StepIO), C.c_void_p]
         L.sd_verify_tree.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32] + [C.c_void_p] * 8
+        L.sd_kv_commit_rows.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
         L.sd_spec_step_typical.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(_StepIO),
                                            C.POINTER(_Typical), C.c_void_p]
         L.sd_verify_tree_typical.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
@@ -348,6 +349,15 @@ def greedy_step(model: Model, kv: KVCache, *, want_logits=False, want_head_logit
     out, io = _alloc_io(model, kv.batch, 1, want_logits, False, want_head_logits, None, out)
     _check(lib().sd_greedy_step(model.handle, kv.handle, C.byref(io), _stream()))
     return out
+
+
+def kv_commit_rows(model: Model, kv: KVCache, src_slots: torch.Tensor, n_rows: torch.Tensor) -> None:
+    """sd_kv_commit_rows: append tree rows of the last pass. src_slots int32 CUDA [batch, width], n_rows int32 CUDA [batch]."""
+    assert src_slots.dtype == n_rows.dtype == torch.int32 and src_slots.is_cuda and n_rows.is_cuda
+    assert src_slots.is_contiguous() and n_rows.is_contiguous()
+    assert src_slots.shape[0] == kv.batch and n_rows.numel() == kv.batch
+    _check(lib().sd_kv_commit_rows(model.handle, kv.handle, src_slots.data_ptr(), n_rows.data_ptr(), src_slots.shape[1],
+                                   _stream()))
 
 
 def verify_tree(tree: Tree, tok: torch.Tensor, am: torch.Tensor, stop_mask: torch.Tensor, vocab: int,

@@ -102,6 +102,7 @@ struct sd_model {
     unsigned long long sync_timeout_ticks = 5000000ull;     // 50 ms of the 100 MHz counter
     unsigned long long* timeline = nullptr;  // caller's buffer for the layer kernel's time stamps, or NULL
     size_t timeline_launches = 0;
+    int scratch_B = 0, scratch_Tp = 0;       // geometry of the tree K/V scratch as the last pass left it
     bool plan_missing = false;               // set by run_gemm if it ever had to skip a launch
     bool greedy_drafts = true;               // sd_greedy_step also runs the draft heads
 };
@@ -875,6 +876,8 @@ static void run_lm_head(sd_model* m, PartView prev, int B, int T, int Tp, hipStr
 // The whole verifying pass: layers, and with want_lm the final norm, the LM head and the arg-max of the first T rows
 // of every sequence (logits in m->logits, arg-max in m->am).
 static void run_forward(sd_model* m, sd_kv* kv, int B, int T, int Tp, int n_hi, bool want_lm, bool keep_h, hipStream_t s) {
+    m->scratch_B = B;
+    m->scratch_Tp = Tp;
     if (fused_eligible(m, B * Tp)) {
         // (when the final norm's rows themselves are wanted, the last stage runs as kernels of its own)
         PartView pl = run_forward_fused(m, kv, B, Tp, n_hi, want_lm && !keep_h, s);
@@ -1079,6 +1082,30 @@ extern "C" int sd_spec_step(sd_model* m, sd_kv* kv, const sd_tree* tree, const u
         return fail(SD_ERR_BAD_TREE, "sd_spec_step: tree was built for %d heads / top-%d", tree->H, tree->topk);
     return step_common(m, kv, tree->uid, tree->parent, tree->depth, tree->rank, tree->T, tree->Tp, stop_mask, io,
                        (hipStream_t)stream, "sd_spec_step");
+}
+
+// Commit stage alone: rows of the tree scratch, as the last pass over this cache's batch left them, appended to
+// every sequence.
+extern "C" int sd_kv_commit_rows(sd_model* m, sd_kv* kv, const int32_t* src_slots, const int32_t* n_rows, int32_t width,
+                                 void* stream) {
+    if (!m || !kv || !src_slots || !n_rows) return fail(SD_ERR_NULL, "sd_kv_commit_rows: NULL argument");
+    if (kv->m != m) return fail(SD_ERR_STATE, "sd_kv_commit_rows: cache belongs to another model");
+    if (m->scratch_B != kv->B || m->scratch_Tp < 32)
+        return fail(SD_ERR_STATE, "sd_kv_commit_rows: no pass over a batch of %d has left tree rows to commit", kv->B);
+    if (width < 1 || width > m->scratch_Tp)
+        return fail(SD_ERR_SHAPE, "sd_kv_commit_rows: width must be in 1..%d (the rows of the last pass)", m->scratch_Tp);
+    for (int b = 0; b < kv->B; ++b)
+        if (kv->len_hi[b] + width > kv->cap)
+            return fail(SD_ERR_KV_FULL, "sd_kv_commit_rows: sequence %d may exceed the cache (len <= %d, cap %d)", b,
+                        kv->len_hi[b], kv->cap);
+    hipStream_t s = (hipStream_t)stream;
+    const sd_config& c = m->cfg;
+    launch_commit_setup(n_rows, width, kv->B, kv->i_nacc, kv->n_old, kv->kv_len, s);
+    launch_kv_commit(m->kt, m->vt, kv->kc, kv->vc, src_slots, kv->i_nacc, kv->n_old, c.n_layers, kv->B, c.n_heads,
+                     c.head_dim, m->scratch_Tp / 32, kv->cap_blocks, width, width, s);
+    HIP_TRY(hipGetLastError());
+    for (int b = 0; b < kv->B; ++b) kv->len_hi[b] += width;
+    return SD_OK;
 }
 
 static int check_typical(float temperature, float epsilon, float delta, const char* who) {

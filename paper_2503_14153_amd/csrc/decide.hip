@@ -384,30 +384,69 @@ void launch_verify(const VerifyArgs& a, int B, hipStream_t s) {
 // Commit the kept nodes' K/V rows: tree-scratch row src_slots[j] -> cache row n_old + j, for
 // every layer and head. A kept node at chain index j was rotated for position n_old + j
 // already (depth = chain index), so this is a pure copy.
-// grid: x = head, y = j (0..H), z = layer * B + b; hd threads.
+// grid: x = head, y = layer * B + b, z = chunk of the rows; hd threads.
+//
+// Keys: a row's 16-byte pieces move as they are (chunk z: rows 8z .. 8z+7, thread = (row, piece)). Values: a 16-byte
+// piece of the value layout holds one dim of EIGHT rows (the four rows 4q .. 4q+3 of a quad in one half, the quad two
+// further on in the other), so a row cannot move as a piece; written one 2-byte element at a time, every element is
+// a partial write of a line of its own. Instead every 8-byte half piece (one quad of destination rows, thread = dim)
+// that receives at least one row is read, patched and written back whole (its other rows are committed rows, which
+// must survive, or rows past the new length, which nobody reads): chunk z takes the quads 2z and 2z+1 after the
+// first one. Only the workgroups of this (layer, sequence, head) touch its blocks, each its own quads and rows.
+#define KVC_QUADS 2
+#define KVC_ROWS 8
 __global__ void k_kv_commit(const uint16_t* __restrict__ kt, const uint16_t* __restrict__ vt, uint16_t* __restrict__ kc,
                             uint16_t* __restrict__ vc, const int32_t* __restrict__ src_slots,
                             const int32_t* __restrict__ n_accept, const int32_t* __restrict__ n_old, int B, int nh,
                             int hd, int TB, int cap_blocks, int W, size_t layer_stride_t, size_t layer_stride_c) {
-    const int h = blockIdx.x, j = blockIdx.y, l = blockIdx.z / B, b = blockIdx.z % B, e = threadIdx.x;
-    if (j >= n_accept[b]) return;
-    const int src = src_slots[(size_t)b * W + j];
-    const int dst = n_old[b] + j;
+    const int h = blockIdx.x, l = blockIdx.y / B, b = blockIdx.y % B, z = blockIdx.z, tid = threadIdx.x;
+    const int a = min(n_accept[b], W);
+    if (a <= 0) return;
+    const int n = n_old[b];
+    const int32_t* slots = src_slots + (size_t)b * W;
     const size_t toff = l * layer_stride_t + ((size_t)b * nh + h) * TB * (32 * hd);
     const size_t coff = l * layer_stride_c + ((size_t)b * nh + h) * cap_blocks * (32 * hd);
-    vc[coff + vblk_index(dst, e, hd)] = vt[toff + vblk_index(src, e, hd)];
-    if (e < hd / 8) {
-        const uint4* s4 = (const uint4*)(kt + toff + kblk_index(src, e * 8, hd));
-        uint4* d4 = (uint4*)(kc + coff + kblk_index(dst, e * 8, hd));
-        *d4 = *s4;
+    const int src_max = TB * 32 - 1;
+    // values: this chunk's quads of destination rows, thread = dim
+    const int q_first = (n >> 2) + z * KVC_QUADS, q_last = (n + a - 1) >> 2;
+#pragma unroll
+    for (int qi = 0; qi < KVC_QUADS; ++qi) {
+        const int q = q_first + qi;
+        if (q > q_last) break;
+        const size_t piece = coff + vblk_index(4 * q, tid, hd);         // first of the quad's four slots
+        typedef uint16_t u16x4 __attribute__((ext_vector_type(4)));
+        u16x4 v = *(const u16x4*)(vc + piece);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int j = 4 * q + r - n;
+            if (j >= 0 && j < a) {
+                const int src = min(max(slots[j], 0), src_max);
+                v[r] = vt[toff + vblk_index(src, tid, hd)];
+            }
+        }
+        *(u16x4*)(vc + piece) = v;
+    }
+    // keys: this chunk's rows, thread = (row, 16-byte piece)
+    const int pieces = hd / 8;                                           // 8 or 16
+    for (int idx = tid; idx < KVC_ROWS * pieces; idx += hd) {
+        const int j = z * KVC_ROWS + idx / pieces, e = idx % pieces;
+        if (j < a) {
+            const int src = min(max(slots[j], 0), src_max);
+            const uint4* s4 = (const uint4*)(kt + toff + kblk_index(src, e * 8, hd));
+            uint4* d4 = (uint4*)(kc + coff + kblk_index(n + j, e * 8, hd));
+            *d4 = *s4;
+        }
     }
 }
 
 void launch_kv_commit(const void* kt_all, const void* vt_all, void* kc_all, void* vc_all, const int32_t* src_slots,
                       const int32_t* n_accept, const int32_t* n_old, int L, int B, int nh, int hd, int TB,
                       int cap_blocks, int rows, int W, hipStream_t s) {
+    (void)rows;
     size_t lst = (size_t)B * nh * TB * 32 * hd, lsc = (size_t)B * nh * cap_blocks * 32 * hd;
-    hipLaunchKernelGGL(k_kv_commit, dim3(nh, rows, L * B), dim3(hd), 0, s, (const uint16_t*)kt_all,
+    const int quads = (W + 3) / 4 + 1;                                   // W rows from any old length touch at most this many
+    const int chunks = (quads + KVC_QUADS - 1) / KVC_QUADS;              // (and chunks * KVC_ROWS >= W)
+    hipLaunchKernelGGL(k_kv_commit, dim3(nh, L * B, chunks), dim3(hd), 0, s, (const uint16_t*)kt_all,
                        (const uint16_t*)vt_all, (uint16_t*)kc_all, (uint16_t*)vc_all, src_slots, n_accept, n_old, B, nh,
                        hd, TB, cap_blocks, W, lst, lsc);
 }
@@ -508,6 +547,21 @@ void launch_prefill_commit_setup(const ChainArgs& ca, int B, int Tp, int32_t* sr
                                  int32_t* n_old, int32_t* kv_len, int32_t* last_row, hipStream_t s) {
     hipLaunchKernelGGL(k_prefill_commit_setup, dim3(B), dim3(SD_MAX_TREE), 0, s, ca, B, Tp, src_slots, n_accept, n_old,
                        kv_len, last_row);
+}
+
+// commit stage alone: the count of every sequence clamped to [0, width], old length noted, new length set
+__global__ void k_commit_setup(const int32_t* __restrict__ n_rows, int width, int B, int32_t* __restrict__ n_accept,
+                               int32_t* __restrict__ n_old, int32_t* __restrict__ kv_len) {
+    const int b = threadIdx.x;
+    if (b >= B) return;
+    const int a = min(max(n_rows[b], 0), width), n = kv_len[b];
+    n_accept[b] = a;
+    n_old[b] = n;
+    kv_len[b] = n + a;
+}
+void launch_commit_setup(const int32_t* n_rows, int width, int B, int32_t* n_accept, int32_t* n_old, int32_t* kv_len,
+                         hipStream_t s) {
+    hipLaunchKernelGGL(k_commit_setup, dim3(1), dim3(SD_MAX_BATCH), 0, s, n_rows, width, B, n_accept, n_old, kv_len);
 }
 
 // root_tok[b] = arg-max at the last prompt row, for the sequences whose prompt just ended

@@ -239,6 +239,8 @@ void launch_copy_row_stats(const float4* src, float4* dst, int B, int T, int Tp,
 void launch_kv_commit(const void* kt_all, const void* vt_all, void* kc_all, void* vc_all,
                       const int32_t* src_slots, const int32_t* n_accept, const int32_t* n_old,
                       int L, int B, int nh, int hd, int TB, int cap_blocks, int rows, int W, hipStream_t s);
+void launch_commit_setup(const int32_t* n_rows, int width, int B, int32_t* n_accept, int32_t* n_old, int32_t* kv_len,
+                         hipStream_t s);
 void launch_kv_rows(void* kc, void* vc, void* k_rows, void* v_rows, int row0, int nrows, int nh, int hd,
                     int cap_blocks, int to_cache, hipStream_t s);
 void launch_copy_logits(const float* src, int ld, float* dst, int V, int B, int T, int Tp, hipStream_t s);

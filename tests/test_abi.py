@@ -97,6 +97,7 @@ def test_null_arguments_are_refused_before_any_device_call(lib):
     assert b"NULL" in lib.sd_last_error()
     assert lib.sd_greedy_step(null, null, null, null) == d["SD_ERR_NULL"]
     assert lib.sd_prefill(null, null, null, null, null) == d["SD_ERR_NULL"]
+    assert lib.sd_kv_commit_rows(null, null, null, null, 4, null) == d["SD_ERR_NULL"]
     assert lib.sd_set_draft_schedule(null, 0) == d["SD_ERR_NULL"]
     assert lib.sd_set_graph_mode(null, 1) == d["SD_ERR_NULL"]
     assert lib.sd_set_greedy_drafts(null, 1) == d["SD_ERR_NULL"]
