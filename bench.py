@@ -55,7 +55,7 @@ def parse():
                     help="steps launched between host synchronisations (1 = wait for every step before the next)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=32)
-    ap.add_argument("--no-fused", action="store_true", help="one launch per stage instead of the persistent layer kernel")
+    ap.add_argument("--fused", action="store_true", help="run the optional persistent layer kernel instead of one launch per stage (measured slower; off by default)")
     ap.add_argument("--graph", action="store_true", help="replay captured HIP graphs instead of launching every kernel (measured: no gain, the step is not host-bound)")
     return ap.parse_args()
 
@@ -117,16 +117,26 @@ def main():
     # ---------------------------------------------------------------- plain greedy on the same GPU
     max_emit = W.kv_cap - prompt_len - (H + 1) - 1
     n_truth = min(max_emit, (args.steps + args.warmup) * (H + 1) + H + 2)
+    model.set_fused(args.fused)
     gout = [sd.greedy_step(model, kv) for _ in range(4)]            # warm-up
     torch.cuda.synchronize()
-    n_timed = min(128, n_truth - 4)
-    t0 = time.perf_counter()
-    for i in range(n_timed):                       # same launch discipline as the speculative loop below
-        gout.append(sd.greedy_step(model, kv))
-        if (i + 1) % max(1, args.sync_every) == 0 or i + 1 == n_timed:
-            kv.len()
-    greedy_s = time.perf_counter() - t0
-    for _ in range(n_truth - 4 - n_timed):
+    n_timed = min(64, (n_truth - 4) // 2)
+
+    def timed_greedy(n):                           # same launch discipline as the speculative loop below
+        t0 = time.perf_counter()
+        for i in range(n):
+            gout.append(sd.greedy_step(model, kv))
+            if (i + 1) % max(1, args.sync_every) == 0 or i + 1 == n:
+                kv.len()
+        return time.perf_counter() - t0
+
+    # plain next-token decoding has no draft heads (the paper's NTP baseline): timed without them; with them (what a
+    # speculative step can follow at once) for comparison. The emitted tokens are the same either way.
+    model.set_greedy_drafts(False)
+    greedy_s = timed_greedy(n_timed)
+    model.set_greedy_drafts(True)
+    greedy_heads_s = timed_greedy(n_timed)
+    for _ in range(n_truth - 4 - 2 * n_timed):
         gout.append(sd.greedy_step(model, kv))
     torch.cuda.synchronize()
     truth = torch.stack([o.tokens[0, 0] for o in gout]).cpu().numpy()
@@ -151,7 +161,7 @@ def main():
         torch.empty((1, H + 1), dtype=torch.int32, device="cuda"), torch.empty(1, dtype=torch.int32, device="cuda"))
     forced = torch.zeros((1, H, k), dtype=torch.int32, device="cuda")     # fixed buffer: graphs replay on it
     model.set_graph_mode(args.graph)
-    model.set_fused(not args.no_fused)
+    model.set_fused(args.fused)
     model.set_draft_schedule(args.draft_schedule)
     state = {"e": 0, "emitted": 0, "diverged": 0, "resets": 0, "i": 0}
     typical = dict(temperature=0.8, epsilon=0.09, delta=0.3)
@@ -279,6 +289,7 @@ def main():
                    "planted_accuracy_by_depth": list(p_depth) if (args.draft == "planted" and args.decoding == "greedy") else None},
         "accepted_tokens_per_s": emitted / elapsed, "mean_accepted_len": emitted / args.steps,
         "greedy_tokens_per_s": n_timed / greedy_s, "speedup_vs_greedy": (emitted / elapsed) / (n_timed / greedy_s),
+        "greedy_with_draft_heads_tokens_per_s": n_timed / greedy_heads_s,
         "prefill_tokens_per_s": prompt_len / prefill_s,
         "step_hbm_frac": step_bytes / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9),
         "diverged_resets": state["diverged"], "sampling_replay_mismatches": replay_mismatches, "hip_graphs": args.graph,
@@ -319,7 +330,7 @@ def bench_batch(args, torch, wl, sd, W):
         torch.empty(B, dtype=torch.int32, device="cuda"), torch.empty((B, H + 1), dtype=torch.int32, device="cuda"),
         torch.empty((B, H + 1), dtype=torch.int32, device="cuda"), torch.empty(B, dtype=torch.int32, device="cuda"))
     model.set_graph_mode(args.graph)
-    model.set_fused(not args.no_fused)
+    model.set_fused(args.fused)
     model.set_draft_schedule(args.draft_schedule)
     room = (W.kv_cap - 1 - max(lens)) // (H + 1)           # steps before the longest sequence could fill its cache
     state = {"left": room, "emitted": 0}

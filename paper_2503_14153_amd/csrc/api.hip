@@ -858,7 +858,8 @@ static PartView run_forward_fused(sd_model* m, sd_kv* kv, int B, int Tp, int n_h
 
 // final norm + LM head on all rows + arg-max of the first T rows of every sequence
 // (keep_h: also leaves the normalised rows in m->hf as fp32, for draft heads on every row)
-static void run_lm_head(sd_model* m, PartView prev, int B, int T, int Tp, hipStream_t s, bool keep_h = false) {
+// need_logits: somebody reads m->logits afterwards (the caller's copy, sampling decoding); else only the arg-max
+static void run_lm_head(sd_model* m, PartView prev, int B, int T, int Tp, hipStream_t s, bool keep_h, bool need_logits) {
     const sd_config& c = m->cfg;
     const int M = B * Tp, MB = pow2_blocks(M);
     PartView pl;
@@ -869,28 +870,25 @@ static void run_lm_head(sd_model* m, PartView prev, int B, int T, int Tp, hipStr
         launch_norm_pack(m->x, prev, m->final_norm, c.rms_eps, m->xn, keep_h ? m->hf : nullptr, M, c.d_model, MB, nullptr, s);
         pl = run_gemm(m, m->xn, m->lm_head, m->part, MB, m->KBd, m->NBv, c.vocab, s);
     }
-    launch_reduce_slots(pl, m->logits, M, s);
-    launch_argmax(m->logits, m->Vpad, c.vocab, m->am, B, T, Tp, s);
+    (void)M;
+    launch_reduce_argmax(pl, need_logits ? m->logits : nullptr, c.vocab, m->am, B, T, Tp, s);
 }
 
 // The whole verifying pass: layers, and with want_lm the final norm, the LM head and the arg-max of the first T rows
 // of every sequence (logits in m->logits, arg-max in m->am).
-static void run_forward(sd_model* m, sd_kv* kv, int B, int T, int Tp, int n_hi, bool want_lm, bool keep_h, hipStream_t s) {
+static void run_forward(sd_model* m, sd_kv* kv, int B, int T, int Tp, int n_hi, bool want_lm, bool keep_h, bool need_logits,
+                        hipStream_t s) {
     m->scratch_B = B;
     m->scratch_Tp = Tp;
     if (fused_eligible(m, B * Tp)) {
         // (when the final norm's rows themselves are wanted, the last stage runs as kernels of its own)
         PartView pl = run_forward_fused(m, kv, B, Tp, n_hi, want_lm && !keep_h, s);
-        if (want_lm && keep_h) {
-            run_lm_head(m, pl, B, T, Tp, s, true);
-        } else if (want_lm) {
-            launch_reduce_slots(pl, m->logits, B * Tp, s);
-            launch_argmax(m->logits, m->Vpad, m->cfg.vocab, m->am, B, T, Tp, s);
-        }
+        if (want_lm && keep_h) run_lm_head(m, pl, B, T, Tp, s, true, need_logits);
+        else if (want_lm) launch_reduce_argmax(pl, need_logits ? m->logits : nullptr, m->cfg.vocab, m->am, B, T, Tp, s);
         return;
     }
     PartView prev = run_layers(m, kv, B, Tp, n_hi, s);
-    if (want_lm) run_lm_head(m, prev, B, T, Tp, s, keep_h);
+    if (want_lm) run_lm_head(m, prev, B, T, Tp, s, keep_h, need_logits);
 }
 
 // draft heads at row last_row[b] of every sequence -> cand (sequences in seq_mask only)
@@ -903,8 +901,7 @@ static void run_draft_heads(sd_model* m, sd_kv* kv, int B, uint32_t seq_mask, fl
     const int MBh = pow2_blocks(H * B);
     launch_medusa_act(pm, m->h_rows, m->medusa_b, B, H, d, m->xn, MBh * 32, MBh, MBh, s);
     PartView pl = run_gemm(m, m->xn, m->lm_head, m->part, MBh, m->KBd, m->NBv, c.vocab, s);
-    launch_reduce_slots(pl, m->hlogits, H * B, s);
-    launch_topk(m->hlogits, m->Vpad, c.vocab, c.topk, kv->cand, B, H, seq_mask, s);
+    launch_topk_parts(pl, head_logits_out ? m->hlogits : nullptr, c.vocab, c.topk, kv->cand, B, H, seq_mask, s);
     if (head_logits_out) launch_copy_head_logits(m->hlogits, m->Vpad, head_logits_out, c.vocab, B, H, s);
 }
 
@@ -963,7 +960,7 @@ extern "C" int sd_prefill(sd_model* m, sd_kv* kv, const int32_t* tokens, const i
         }
         launch_build_rows_chain(m->rt, tokens, ca, kv->kv_len, B, Tp, c.head_dim, c.rope_theta, m->embed, c.d_model,
                                 c.vocab, m->x, s);
-        run_forward(m, kv, B, Tp, Tp, n_hi, fin != 0, false, s);
+        run_forward(m, kv, B, Tp, Tp, n_hi, fin != 0, false, false, s);
         launch_prefill_commit_setup(ca, B, Tp, kv->i_slots, kv->i_nacc, kv->n_old, kv->kv_len, kv->last_row, s);
         launch_kv_commit(m->kt, m->vt, kv->kc, kv->vc, kv->i_slots, kv->i_nacc, kv->n_old, c.n_layers, B, c.n_heads,
                          c.head_dim, Tp / 32, kv->cap_blocks, Tp, Tp, s);
@@ -1009,7 +1006,7 @@ static int step_common(sd_model* m, sd_kv* kv, uint64_t tree_uid, const int32_t*
     auto enqueue = [&](hipStream_t s) {
     launch_build_rows_tree(m->rt, parent, depth, rank, kv->root_tok, cand, kv->kv_len, B, T, Tp, H, c.topk, c.head_dim,
                            c.rope_theta, m->embed, c.d_model, c.vocab, m->x, s);
-    run_forward(m, kv, B, T, Tp, n_hi, true, all_rows, s);
+    run_forward(m, kv, B, T, Tp, n_hi, true, all_rows, io->logits != nullptr || ty != nullptr, s);
     if (io->logits) launch_copy_logits(m->logits, m->Vpad, io->logits, c.vocab, B, T, Tp, s);
     if (io->argmax) launch_copy_rows_i32(m->am, io->argmax, B, T, Tp, s);
     VerifyArgs va;

@@ -52,24 +52,84 @@ void launch_argmax(const float* logits, int ld, int V, int32_t* am, int B, int T
 }
 
 // ------------------------------------------------------------------------------------------
+// The same arg-max straight from the LM-head GEMM's partial sums: a thread sums the slots of its columns (in slot
+// order, as k_reduce_slots does, so the logits are the same numbers), keeps the best, and writes the logits out
+// only when somebody wants them (WRITE: the caller asked for logits, or sampling decoding reads them). Saves a
+// launch and, without WRITE, the 8 MB write and re-read of the logits of a 64-row step.
+template <bool WRITE>
+__global__ __launch_bounds__(ARGMAX_THREADS) void k_reduce_argmax(PartView pv, float* __restrict__ logits, int V,
+                                                                  int32_t* __restrict__ am, int T, int Tp) {
+    const int b = blockIdx.x / T, j = blockIdx.x % T;
+    const int m = b * Tp + j;
+    float bv = NEG_INF;
+    int bi = 0x7fffffff;
+    for (int i = threadIdx.x * 4; i < pv.ld; i += ARGMAX_THREADS * 4) {
+        const int n = part_count(pv, i);
+        float4 a = make_float4(0, 0, 0, 0);
+        const float* p = pv.base + (size_t)m * pv.ld + i;
+#pragma unroll 4
+        for (int sp = 0; sp < n; ++sp) {
+            float4 v = *(const float4*)(p + (size_t)sp * pv.slot_stride);
+            a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
+        }
+        if (WRITE) *(float4*)(logits + (size_t)m * pv.ld + i) = a;
+        float vals[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (i + e < V && better(vals[e], i + e, bv, bi)) { bv = vals[e]; bi = i + e; }
+    }
+    wave_best(bv, bi);
+    __shared__ float sv[ARGMAX_THREADS / 64];
+    __shared__ int si[ARGMAX_THREADS / 64];
+    if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
+    __syncthreads();
+    if (threadIdx.x < 64) {
+        bv = threadIdx.x < ARGMAX_THREADS / 64 ? sv[threadIdx.x] : NEG_INF;
+        bi = threadIdx.x < ARGMAX_THREADS / 64 ? si[threadIdx.x] : 0x7fffffff;
+        wave_best(bv, bi);
+        if (threadIdx.x == 0) am[m] = bi;
+    }
+}
+
+void launch_reduce_argmax(PartView pv, float* logits_or_null, int V, int32_t* am, int B, int T, int Tp, hipStream_t s) {
+    if (logits_or_null)
+        hipLaunchKernelGGL(k_reduce_argmax<true>, dim3(B * T), dim3(ARGMAX_THREADS), 0, s, pv, logits_or_null, V, am, T, Tp);
+    else
+        hipLaunchKernelGGL(k_reduce_argmax<false>, dim3(B * T), dim3(ARGMAX_THREADS), 0, s, pv, logits_or_null, V, am, T, Tp);
+}
+
+// ------------------------------------------------------------------------------------------
 // Per-row top-k (descending logit, ties to the lower id). One workgroup of 1024 threads per
 // row keeps the whole row in registers (thread t owns ids t, t+1024, ...); each of the k
 // rounds is a thread-local scan plus one block-wide (value, id) reduction, after which the
 // owner retires the selected element.
 #define TOPK_THREADS 1024
-template <int NPT>
-__global__ __launch_bounds__(TOPK_THREADS) void k_topk(const float* __restrict__ logits, int ld, int V, int k,
+// PARTS: the row is not read from `logits` but summed from the partial sums of the LM-head GEMM (slot order, as
+// k_reduce_slots does) and, if `logits` is not NULL, written there as well.
+template <int NPT, bool PARTS>
+__global__ __launch_bounds__(TOPK_THREADS) void k_topk(float* __restrict__ logits, PartView pv, int ld, int V, int k,
                                                        int32_t* __restrict__ out, int B, int H, uint32_t seq_mask) {
     const int r = blockIdx.x;                 // row r = head i * B + sequence b
     const int i = r / B, b = r % B;
     if (!((seq_mask >> b) & 1u)) return;
-    const float* row = logits + (size_t)r * ld;
+    float* row = logits ? logits + (size_t)r * ld : nullptr;
     const int tid = threadIdx.x;
     float v[NPT];
 #pragma unroll
     for (int j = 0; j < NPT; ++j) {
         int c = j * TOPK_THREADS + tid;
-        v[j] = c < V ? row[c] : NEG_INF;
+        if (PARTS) {
+            float a = 0.f;
+            if (c < V) {
+                const int n = part_count(pv, c);
+                const float* p = pv.base + (size_t)r * pv.ld + c;
+                for (int sp = 0; sp < n; ++sp) a += p[(size_t)sp * pv.slot_stride];
+                if (row) row[c] = a;
+            }
+            v[j] = c < V ? a : NEG_INF;
+        } else {
+            v[j] = c < V ? row[c] : NEG_INF;
+        }
     }
     __shared__ float sv[TOPK_THREADS / 64];
     __shared__ int si[TOPK_THREADS / 64];
@@ -112,10 +172,11 @@ __global__ __launch_bounds__(TOPK_THREADS) void k_topk(const float* __restrict__
     }
 }
 
-void launch_topk(const float* logits, int ld, int V, int k, int32_t* out, int B, int H, uint32_t seq_mask,
-                 hipStream_t s) {
+template <bool PARTS>
+static void topk_dispatch(float* logits, PartView pv, int ld, int V, int k, int32_t* out, int B, int H, uint32_t seq_mask,
+                          hipStream_t s) {
     const int npt = (V + TOPK_THREADS - 1) / TOPK_THREADS;
-#define TOPK(N) hipLaunchKernelGGL((k_topk<N>), dim3(B * H), dim3(TOPK_THREADS), 0, s, logits, ld, V, k, out, B, H, seq_mask)
+#define TOPK(N) hipLaunchKernelGGL((k_topk<N, PARTS>), dim3(B * H), dim3(TOPK_THREADS), 0, s, logits, pv, ld, V, k, out, B, H, seq_mask)
     if (npt <= 1) TOPK(1);
     else if (npt <= 4) TOPK(4);
     else if (npt <= 16) TOPK(16);
@@ -123,6 +184,15 @@ void launch_topk(const float* logits, int ld, int V, int k, int32_t* out, int B,
     else if (npt <= 64) TOPK(64);
     else TOPK(160);          // vocabularies up to 163840 ids (validated at model creation)
 #undef TOPK
+}
+void launch_topk(const float* logits, int ld, int V, int k, int32_t* out, int B, int H, uint32_t seq_mask,
+                 hipStream_t s) {
+    topk_dispatch<false>(const_cast<float*>(logits), PartView{nullptr, 0, ld, nullptr, 0}, ld, V, k, out, B, H, seq_mask, s);
+}
+// top-k of rows that still lie in the LM-head GEMM's partial sums; logits_or_null [rows][pv.ld]: also write them
+void launch_topk_parts(PartView pv, float* logits_or_null, int V, int k, int32_t* out, int B, int H, uint32_t seq_mask,
+                       hipStream_t s) {
+    topk_dispatch<true>(logits_or_null, pv, pv.ld, V, k, out, B, H, seq_mask, s);
 }
 
 // ------------------------------------------------------------------------------------------

@@ -219,9 +219,14 @@ void launch_swiglu_pack(PartView pv, int F, int Fpad, void* act_packed, int M, i
 // output rows i*B + b in chunks of chunk_rows rows, each a packed activation of MB (last: MBlast) row blocks
 void launch_medusa_act(PartView pv, const float* h_rows, const MedusaBias& bias, int B, int H, int d,
                        void* x_packed, int chunk_rows, int MB, int MBlast, hipStream_t s);
+// arg-max of the first T rows of every sequence from the LM head's partial sums; logits_or_null: also write the
+// summed logits of those rows ([row][pv.ld])
+void launch_reduce_argmax(PartView pv, float* logits_or_null, int V, int32_t* am, int B, int T, int Tp, hipStream_t s);
 void launch_argmax(const float* logits, int ld, int V, int32_t* am, int B, int T, int Tp, hipStream_t s);
 void launch_topk(const float* logits, int ld, int V, int k, int32_t* out, int B, int H, uint32_t seq_mask,
                  hipStream_t s);
+void launch_topk_parts(PartView pv, float* logits_or_null, int V, int k, int32_t* out, int B, int H, uint32_t seq_mask,
+                       hipStream_t s);
 void launch_pick_root(const int32_t* am, const int32_t* last_row, int32_t* root_tok, int B, uint32_t seq_mask,
                       hipStream_t s);
 void launch_verify(const VerifyArgs& a, int B, hipStream_t s);
