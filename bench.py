@@ -86,9 +86,9 @@ def main():
     W = wl.preset(args.workload, args.layers)
     if W.batch > 1:
         return bench_batch(args, torch, wl, sd, W)
-    shape = dataclasses.replace(W.model, dtype="bf16")
+    shape = W.model                  # "tiny" is specified in float32 and runs on the float32 path; the others are bf16
     T, H, k = W.tree_nodes, shape.n_medusa, shape.topk
-    prompt_len = W.prompt_len if args.workload != "7b-long" else W.prompt_len
+    prompt_len = W.prompt_len
 
     # ---------------------------------------------------------------- inputs, resident in HBM
     weights = wl.make_weights(shape, device="cuda")
@@ -279,7 +279,7 @@ def main():
     res = {
         "metric": "verified_tree_tokens_per_s", "value": args.steps * T / elapsed, "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": shape.dtype, "data": "synthetic",
         "config": {"workload": f"{W.name}: {shape.n_layers}-layer d={shape.d_model} Llama-shaped decoder, "
                                f"{H} draft heads top-{k}, {T}-node tree, batch 1, Zipf prompt {prompt_len}, "
                                f"KV cap {W.kv_cap}, 20% stop ids",
@@ -303,6 +303,14 @@ def main():
                       "avg_launch_us": a["ms"] / max(a["launches"], 1) * 1e3},
         "cpu_baseline": cpu,
     }
+    if shape.dtype == "f32":
+        # the float32 path: plain vector-ALU kernels, launch-bound at this size; no per-kernel events are taken
+        Tp = (T + 31) // 32 * 32
+        flops = 2.0 * Tp * weight_bytes(shape, 1) / 2.0
+        res["roofline"] = {"kernel": "k_f32_linear (whole step; float32 vector-ALU path, launch-bound at this size)",
+                           "bound": "alu", "achieved": flops / (ms_per_step * 1e-3) / 1e12, "peak": 157.3,
+                           "unit": "TFLOP/s", "frac": flops / (ms_per_step * 1e-3) / 1e12 / 157.3, "traffic": None}
+        res["attention"] = None
     print(json.dumps(res))
 
 

@@ -18,9 +18,18 @@
  *   - `stream` is a hipStream_t passed as void*. Calls that take a stream are asynchronous
  *     on it; results are valid once the caller has synchronised the stream. A handle must
  *     be used from one thread and one stream at a time.
- *   - All weight matrices are row-major [out_features][in_features] (y = W x), bf16.
- *   - Only dtype = SD_DTYPE_BF16 is implemented; head_dim must be 64 or 128; d_model and
- *     d_ffn must be multiples of 16; n_medusa <= 15; topk <= 32; tree nodes <= 256.
+ *   - All weight matrices are row-major [out_features][in_features] (y = W x), in the element
+ *     type sd_config.dtype names.
+ *   - dtype = SD_DTYPE_BF16: weights and cache rows are bfloat16, products run on the matrix
+ *     cores with float32 accumulation: the production path, the one every performance figure is for.
+ *     dtype = SD_DTYPE_F32: weights, activations and cache rows are float32 and every product is
+ *     accumulated in float32 on the vector ALUs, with plain kernels: for configurations that are
+ *     specified in float32 (small ones: correctness, not speed). Same entry points, same integer
+ *     stages; differences: sd_kv_write_rows / sd_kv_read_rows move float32 rows, the draft heads
+ *     always run after acceptance (sd_set_draft_schedule is accepted and has no effect),
+ *     sd_set_fused has no effect, and sd_profile_end reports no launches.
+ *   - head_dim must be 64 or 128; d_model a multiple of 32, d_ffn of 16; n_medusa <= 15;
+ *     topk <= 32; tree nodes <= 256.
  */
 #ifndef SPECDEC_H
 #define SPECDEC_H
@@ -56,7 +65,7 @@ typedef struct sd_config {
     float rope_theta, rms_eps;
 } sd_config;
 
-/* Device pointers to the caller's weights (bf16). Per-layer arrays are host arrays of
+/* Device pointers to the caller's weights (bfloat16 or float32, as sd_config.dtype says). Per-layer arrays are host arrays of
  * n_layers (resp. n_medusa) device pointers. medusa_b may be NULL (no bias).
  * wqkv stacks q, k, v along the output axis: [3*d_model][d_model].                         */
 typedef struct sd_weights {
@@ -79,8 +88,9 @@ typedef struct sd_kv sd_kv;
 typedef struct sd_tree sd_tree;
 
 /* ---- model ------------------------------------------------------------------------------
- * sd_model_create copies every weight into a library-owned device arena, re-tiled so that one
- * wavefront load instruction fetches one contiguous 1 KiB MFMA operand fragment. The
+ * sd_model_create copies every weight into a library-owned device arena (bfloat16 models: re-tiled so
+ * that one wavefront load instruction fetches one contiguous 1 KiB MFMA operand fragment; float32
+ * models: as they are). The
  * caller's weight buffers are read on `stream` during this call only; the call synchronises
  * the stream before returning, after which the caller may free them. `max_rows` is the
  * largest batch * round_up(tree_nodes, 32) any later call will use (workspace is sized for
@@ -91,7 +101,7 @@ int sd_model_destroy(sd_model* m);
 
 /* ---- KV cache ---------------------------------------------------------------------------
  * The cache lives in ONE caller-allocated device buffer of sd_kv_bytes(...) bytes; its
- * internal tiling is private (keys and values are stored as ready-made MFMA fragments of
+ * internal tiling is private (bfloat16: keys and values are stored as ready-made MFMA fragments of
  * 32 cache rows), use sd_kv_write_rows / sd_kv_read_rows to move rows in natural layout.
  * `cap` = capacity in rows per sequence. A step needs kv_len + n_medusa + 1 <= cap (the
  * tree's own keys/values live in a library-owned scratch, not in the cache).               */
@@ -108,7 +118,8 @@ int sd_kv_len(sd_kv* kv, int32_t* out_len, void* stream);
  * declare rows written by sd_kv_write_rows as committed). Rows beyond len are ignored.     */
 int sd_kv_set_len(sd_kv* kv, const int32_t* len, void* stream);
 /* Copy `nrows` rows starting at cache row `row0` of sequence `seq`, layer `layer`, between
- * the cache and natural-layout device arrays k_rows / v_rows: bf16 [nrows][n_heads][head_dim].
+ * the cache and natural-layout device arrays k_rows / v_rows: [nrows][n_heads][head_dim] of the
+ * model's element type (bfloat16 or float32).
  * Keys are stored as given (they must already be rotated to their positions).              */
 int sd_kv_write_rows(sd_kv* kv, int32_t layer, int32_t seq, int32_t row0, int32_t nrows,
                      const void* k_rows, const void* v_rows, void* stream);

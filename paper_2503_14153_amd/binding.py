@@ -134,7 +134,8 @@ def _config(shape, trunc_fallback: str) -> _Config:
 
 
 class Model:
-    """sd_model_create / sd_model_destroy. `weights`: name -> bf16 CUDA tensor, [out, in]."""
+    """sd_model_create / sd_model_destroy. `weights`: name -> CUDA tensor [out, in] of the shape's dtype
+    (bfloat16 for "bf16", float32 for "f32": the float32 path keeps weights, activations and the cache in float32)."""
 
     def __init__(self, shape, weights: dict, max_rows: int, trunc_fallback: str = "keep_all"):
         self.shape = shape
@@ -144,9 +145,10 @@ class Model:
         def arr(names):
             return (C.c_void_p * len(names))(*[weights[n].data_ptr() for n in names])
 
+        self.torch_dtype = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
         for name, t in weights.items():
-            if not (t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous()):
-                raise ValueError(f"weight {name} must be a contiguous bf16 CUDA tensor")
+            if not (t.is_cuda and t.dtype == self.torch_dtype and t.is_contiguous()):
+                raise ValueError(f"weight {name} must be a contiguous {shape.dtype} CUDA tensor")
         keep = [arr([f"l{l}.{k}" for l in range(L)]) for k in ("attn_norm", "wqkv", "wo", "ffn_norm", "w_gate",
                                                              "w_up", "w_down")]
         mw = arr([f"medusa{i}.w" for i in range(H)])
@@ -169,7 +171,8 @@ class Model:
         _check(lib().sd_set_greedy_drafts(self.handle, 1 if on else 0))
 
     def set_fused(self, on: bool):
-        """The persistent layer kernel (default) or one launch per stage; results are bit-identical."""
+        """The optional persistent layer kernel (True) or one launch per stage (False, the default and the faster
+        of the two); the two agree within the parity tolerance, not bit for bit."""
         _check(lib().sd_set_fused(self.handle, 1 if on else 0))
 
     def set_layer_timeline(self, buf: torch.Tensor | None):
@@ -224,13 +227,14 @@ class KVCache:
         _check(lib().sd_kv_set_len(self.handle, _i32_array(lens), _stream()))
 
     def write_rows(self, layer, seq, row0, k_rows, v_rows):
-        assert k_rows.dtype == torch.bfloat16 and k_rows.is_cuda and k_rows.is_contiguous() and v_rows.is_contiguous()
+        assert k_rows.dtype == v_rows.dtype == self.model.torch_dtype and k_rows.is_cuda and v_rows.is_cuda
+        assert k_rows.is_contiguous() and v_rows.is_contiguous() and k_rows.shape == v_rows.shape
         _check(lib().sd_kv_write_rows(self.handle, layer, seq, row0, k_rows.shape[0], k_rows.data_ptr(),
                                       v_rows.data_ptr(), _stream()))
 
     def read_rows(self, layer, seq, row0, nrows):
         s = self.model.shape
-        k = torch.empty((nrows, s.n_heads, s.head_dim), dtype=torch.bfloat16, device="cuda")
+        k = torch.empty((nrows, s.n_heads, s.head_dim), dtype=self.model.torch_dtype, device="cuda")
         v = torch.empty_like(k)
         _check(lib().sd_kv_read_rows(self.handle, layer, seq, row0, nrows, k.data_ptr(), v.data_ptr(), _stream()))
         return k, v

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspecdec.so")
-SOURCES = ["api.hip", "gemm.hip", "fused.hip", "attn.hip", "rows.hip", "decide.hip", "labels.hip"]
+SOURCES = ["api.hip", "gemm.hip", "fused.hip", "attn.hip", "rows.hip", "decide.hip", "labels.hip", "f32.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-result", "-Wno-unused-value",
          # keep hipcc from forming packed-fp32 VALU ops (v_pk_*_f32): some of their forms have given wrong results
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

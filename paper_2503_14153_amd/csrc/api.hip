@@ -105,6 +105,14 @@ struct sd_model {
     int scratch_B = 0, scratch_Tp = 0;       // geometry of the tree K/V scratch as the last pass left it
     bool plan_missing = false;               // set by run_gemm if it ever had to skip a launch
     bool greedy_drafts = true;               // sd_greedy_step also runs the draft heads
+    // float32 path (dtype SD_DTYPE_F32; f32.hip): weights [out][in] as float, natural activation layouts
+    bool f32 = false;
+    struct F32Layer { const float *attn_norm, *wqkv, *wo, *ffn_norm, *wgu, *wdown; };
+    struct F32 {
+        const float *embed, *lm_head, *final_norm, *medusa_w, *medusa_b;
+        std::vector<F32Layer> layers;
+        float *xn, *qkv, *q, *attn, *gu, *act, *kt, *vt, *z, *xh;
+    } f;
 };
 
 // Handles get a process-wide serial number: graph keys use it instead of the handle's address, which a
@@ -121,6 +129,7 @@ struct sd_kv {
     uint16_t* buf;
     size_t layer_stride;                     // elements between layers, per K or V plane
     uint16_t *kc, *vc;                       // plane bases
+    float *kc32 = nullptr, *vc32 = nullptr;  // float32 models: planes [layer][seq][cap][d], layer_stride = B * cap * d
     int32_t* state = nullptr;                // device: kv_len, n_old, root_tok, last_row, cand, io scratch
     int32_t *kv_len, *n_old, *root_tok, *last_row, *cand, *i_nacc, *i_tokens, *i_slots;
     std::vector<int32_t> len_hi;             // host upper bound of the committed lengths
@@ -136,7 +145,7 @@ struct sd_tree {
 
 // ------------------------------------------------------------------------------------------ model
 static int check_config(const sd_config* c) {
-    if (c->dtype != SD_DTYPE_BF16) return fail(SD_ERR_SHAPE, "only dtype bf16 is implemented");
+    if (c->dtype != SD_DTYPE_BF16 && c->dtype != SD_DTYPE_F32) return fail(SD_ERR_SHAPE, "dtype must be SD_DTYPE_BF16 or SD_DTYPE_F32");
     if (c->head_dim != 64 && c->head_dim != 128) return fail(SD_ERR_SHAPE, "head_dim must be 64 or 128");
     if (c->n_layers < 1 || c->n_heads < 1 || c->vocab < 2 || c->vocab > 163840) return fail(SD_ERR_SHAPE, "bad sizes");
     if (c->d_model != c->n_heads * c->head_dim) return fail(SD_ERR_SHAPE, "d_model != n_heads * head_dim");
@@ -147,6 +156,101 @@ static int check_config(const sd_config* c) {
     if (c->trunc_fallback != SD_TRUNC_KEEP_ALL && c->trunc_fallback != SD_TRUNC_KEEP_ONE)
         return fail(SD_ERR_SHAPE, "bad trunc_fallback");
     if (!(c->rope_theta > 0.f) || !(c->rms_eps >= 0.f)) return fail(SD_ERR_SHAPE, "bad rope_theta / rms_eps");
+    return SD_OK;
+}
+
+// The float32 model: weights copied as they are ([out][in] float; gate and up stacked, the draft heads stacked, a
+// zero bias where none is given) and a workspace in natural row-major layouts. No launch plans, no packing.
+static int create_f32(const sd_config* cfg, const sd_weights* w, int max_rows, hipStream_t s, sd_model** out) {
+    const int L = cfg->n_layers, d = cfg->d_model, F = cfg->d_ffn, V = cfg->vocab, H = cfg->n_medusa, hd = cfg->head_dim;
+    sd_model* m = new (std::nothrow) sd_model();
+    if (!m) return fail(SD_ERR_HIP, "out of host memory");
+    m->cfg = *cfg;
+    m->f32 = true;
+    m->max_rows = max_rows;
+    m->MBmax = pow2_blocks(max_rows);
+    m->Vpad = ceil_div(V, 32) * 32;
+    const int Mp = m->MBmax * 32;
+    const int HBp = pow2_blocks(H * SD_MAX_BATCH > 256 ? 256 : H * SD_MAX_BATCH) * 32;
+    size_t sz = 0;
+    auto take = [&](size_t floats) { size_t o = sz; sz = align_up(sz + floats * 4, 256); return o; };
+    const size_t o_embed = take((size_t)V * d), o_lm = take((size_t)V * d), o_fn = take(d);
+    const size_t o_mw = take((size_t)H * d * d), o_mb = take((size_t)H * d);
+    std::vector<size_t> o_an(L), o_qkv(L), o_o(L), o_ffn(L), o_gu(L), o_dn(L);
+    for (int l = 0; l < L; ++l) {
+        o_an[l] = take(d); o_qkv[l] = take((size_t)3 * d * d); o_o[l] = take((size_t)d * d);
+        o_ffn[l] = take(d); o_gu[l] = take((size_t)2 * F * d); o_dn[l] = take((size_t)d * F);
+    }
+    hipError_t e = hipMalloc((void**)&m->arena, sz);
+    if (e != hipSuccess) { delete m; return fail(SD_ERR_HIP, "hipMalloc(%zu) for weights: %s", sz, hipGetErrorString(e)); }
+    char* A = m->arena;
+    auto copy = [&](size_t off, const void* src, size_t floats) {
+        if (e == hipSuccess) e = hipMemcpyAsync(A + off, src, floats * 4, hipMemcpyDeviceToDevice, s);
+        return (const float*)(A + off);
+    };
+    e = hipMemsetAsync(A + o_mb, 0, (size_t)H * d * 4, s);
+    m->f.embed = copy(o_embed, w->embed, (size_t)V * d);
+    m->f.lm_head = copy(o_lm, w->lm_head, (size_t)V * d);
+    m->f.final_norm = copy(o_fn, w->final_norm, d);
+    for (int i = 0; i < H; ++i) {
+        copy(o_mw + (size_t)i * d * d * 4, w->medusa_w[i], (size_t)d * d);
+        if (w->medusa_b && w->medusa_b[i]) copy(o_mb + (size_t)i * d * 4, w->medusa_b[i], d);
+    }
+    m->f.medusa_w = (const float*)(A + o_mw);
+    m->f.medusa_b = (const float*)(A + o_mb);
+    m->f.layers.resize(L);
+    for (int l = 0; l < L; ++l) {
+        sd_model::F32Layer& lw = m->f.layers[l];
+        lw.attn_norm = copy(o_an[l], w->attn_norm[l], d);
+        lw.wqkv = copy(o_qkv[l], w->wqkv[l], (size_t)3 * d * d);
+        lw.wo = copy(o_o[l], w->wo[l], (size_t)d * d);
+        lw.ffn_norm = copy(o_ffn[l], w->ffn_norm[l], d);
+        lw.wgu = copy(o_gu[l], w->w_gate[l], (size_t)F * d);
+        copy(o_gu[l] + (size_t)F * d * 4, w->w_up[l], (size_t)F * d);
+        lw.wdown = copy(o_dn[l], w->w_down[l], (size_t)d * F);
+    }
+    m->embed = m->f.embed;
+
+    size_t wz = 0;
+    auto wtake = [&](size_t bytes) { size_t o = wz; wz = align_up(wz + bytes, 256); return o; };
+    const size_t w_x = wtake((size_t)Mp * d * 4), w_logits = wtake((size_t)Mp * m->Vpad * 4);
+    const size_t w_hlog = wtake((size_t)HBp * m->Vpad * 4), w_hrows = wtake((size_t)SD_MAX_BATCH * d * 4);
+    const size_t w_xn = wtake((size_t)Mp * d * 4), w_qkv = wtake((size_t)Mp * 3 * d * 4), w_q = wtake((size_t)Mp * d * 4);
+    const size_t w_attn = wtake((size_t)Mp * d * 4), w_gu = wtake((size_t)Mp * 2 * F * 4), w_act = wtake((size_t)Mp * F * 4);
+    const size_t w_kt = wtake((size_t)L * Mp * d * 4), w_vt = wtake((size_t)L * Mp * d * 4);
+    const size_t w_z = wtake((size_t)SD_MAX_BATCH * H * d * 4), w_xh = wtake((size_t)HBp * d * 4);
+    const size_t w_tok = wtake((size_t)Mp * 4), w_pos = wtake((size_t)Mp * 4), w_anc = wtake((size_t)Mp * SD_ANC_WORDS * 4);
+    const size_t w_cs = wtake((size_t)Mp * (hd / 2) * 8), w_am = wtake((size_t)Mp * 4), w_g = wtake(3 * 4);
+    const size_t w_rs = wtake((size_t)Mp * 16), w_zs = wtake((size_t)ceil_div(V, 32) * 4);
+    if (e == hipSuccess) e = hipMalloc((void**)&m->work, wz);
+    if (e == hipSuccess) e = hipMemsetAsync(m->work, 0, wz, s);
+    if (e != hipSuccess) {
+        hipStreamSynchronize(s);
+        hipFree(m->arena);
+        if (m->work) hipFree(m->work);
+        delete m;
+        return fail(SD_ERR_HIP, "float32 model: weights or workspace: %s", hipGetErrorString(e));
+    }
+    char* Wk = m->work;
+    m->x = (float*)(Wk + w_x); m->logits = (float*)(Wk + w_logits); m->hlogits = (float*)(Wk + w_hlog);
+    m->h_rows = (float*)(Wk + w_hrows);
+    m->f.xn = (float*)(Wk + w_xn); m->f.qkv = (float*)(Wk + w_qkv); m->f.q = (float*)(Wk + w_q);
+    m->f.attn = (float*)(Wk + w_attn); m->f.gu = (float*)(Wk + w_gu); m->f.act = (float*)(Wk + w_act);
+    m->f.kt = (float*)(Wk + w_kt); m->f.vt = (float*)(Wk + w_vt); m->f.z = (float*)(Wk + w_z); m->f.xh = (float*)(Wk + w_xh);
+    m->rt.tok = (int32_t*)(Wk + w_tok); m->rt.pos = (int32_t*)(Wk + w_pos); m->rt.anc = (uint32_t*)(Wk + w_anc);
+    m->rt.cs = (float2*)(Wk + w_cs);
+    m->am = (int32_t*)(Wk + w_am);
+    m->row_stats = (float4*)(Wk + w_rs);
+    m->g_parent = (int32_t*)(Wk + w_g); m->g_depth = m->g_parent + 1; m->g_rank = m->g_parent + 2;
+    m->zero_stop = (uint32_t*)(Wk + w_zs);
+    launch_fill_i32(m->g_parent, -1, 1, s);
+    e = hipStreamSynchronize(s);
+    if (e == hipSuccess) e = hipGetLastError();
+    if (e != hipSuccess) {
+        hipFree(m->arena); hipFree(m->work); delete m;
+        return fail(SD_ERR_HIP, "float32 model: set-up failed: %s", hipGetErrorString(e));
+    }
+    *out = m;
     return SD_OK;
 }
 
@@ -169,6 +273,7 @@ extern "C" int sd_model_create(const sd_config* cfg, const sd_weights* w, int32_
         if (!w->medusa_w[i]) return fail(SD_ERR_NULL, "sd_model_create: NULL draft-head weight %d", i);
 
     hipStream_t s = (hipStream_t)stream;
+    if (cfg->dtype == SD_DTYPE_F32) return create_f32(cfg, w, max_rows, s, out);
     sd_model* m = new (std::nothrow) sd_model();
     if (!m) return fail(SD_ERR_HIP, "out of host memory");
     m->cfg = *cfg;
@@ -488,6 +593,8 @@ extern "C" int sd_model_destroy(sd_model* m) {
 // ------------------------------------------------------------------------------------------ KV cache
 extern "C" size_t sd_kv_bytes(const sd_config* cfg, int32_t batch, int32_t cap) {
     if (!cfg || batch < 1 || cap < 1) return 0;
+    if (cfg->dtype == SD_DTYPE_F32)
+        return (size_t)cfg->n_layers * 2 * batch * cap * cfg->n_heads * cfg->head_dim * 4;
     size_t blocks = (size_t)ceil_div(cap, 32);
     return (size_t)cfg->n_layers * 2 * batch * cfg->n_heads * blocks * 32 * cfg->head_dim * 2;
 }
@@ -510,6 +617,11 @@ extern "C" int sd_kv_create(const sd_model* m, int32_t batch, int32_t cap, void*
     kv->layer_stride = (size_t)batch * m->cfg.n_heads * kv->cap_blocks * 32 * m->cfg.head_dim;
     kv->kc = kv->buf;
     kv->vc = kv->buf + (size_t)m->cfg.n_layers * kv->layer_stride;
+    if (m->f32) {
+        kv->layer_stride = (size_t)batch * cap * m->cfg.d_model;
+        kv->kc32 = (float*)dev_buf;
+        kv->vc32 = kv->kc32 + (size_t)m->cfg.n_layers * kv->layer_stride;
+    }
     const int H = m->cfg.n_medusa, k = m->cfg.topk;
     const int W = std::max(H + 1, SD_MAX_TREE);
     size_t n = (size_t)batch * (4 + H * k + 1 + 2 * W);
@@ -569,6 +681,13 @@ static int kv_rows_common(sd_kv* kv, int layer, int seq, int row0, int nrows, vo
     if (layer < 0 || layer >= c.n_layers || seq < 0 || seq >= kv->B || row0 < 0 || nrows < 0 || row0 + nrows > kv->cap)
         return fail(SD_ERR_SHAPE, "sd_kv_*_rows: index out of range");
     if (nrows == 0) return SD_OK;
+    if (kv->m->f32) {
+        const size_t o = layer * kv->layer_stride + (size_t)seq * kv->cap * c.d_model;
+        launch_f32_kv_rows(kv->kc32 + o, kv->vc32 + o, (float*)k_rows, (float*)v_rows, row0, nrows, c.d_model, to_cache,
+                           (hipStream_t)stream);
+        HIP_TRY(hipGetLastError());
+        return SD_OK;
+    }
     size_t off = layer * kv->layer_stride + (size_t)seq * c.n_heads * kv->cap_blocks * 32 * c.head_dim;
     launch_kv_rows(kv->kc + off, kv->vc + off, k_rows, v_rows, row0, nrows, c.n_heads, c.head_dim, kv->cap_blocks,
                    to_cache, (hipStream_t)stream);
@@ -689,6 +808,7 @@ static PartView run_gemm(sd_model* m, const void* Xp, const void* Wp, float* out
 // Every GEMM shape a pass over M rows issues (and, with heads = true, the draft heads after it, in the
 // schedule given) has a launch plan: checked by the entry points before anything is enqueued.
 static bool have_plans(const sd_model* m, int M, int B, bool heads, bool all_rows) {
+    if (m->f32) return true;                           // the float32 kernels take any shape
     const int MB = pow2_blocks(M), H = m->cfg.n_medusa;
     bool ok = m->find_plan(MB, m->KBd, m->NBqkv) && m->find_plan(MB, m->KBd, m->NBo) && m->find_plan(MB, m->KBd, m->NBgu) &&
               m->find_plan(MB, m->KBf, m->NBo) && m->find_plan(MB, m->KBd, m->NBv);
@@ -787,6 +907,7 @@ static FusedGemm fused_gemm(const sd_model* m, int MB, int KB, int NB, const voi
     return g;
 }
 static bool fused_eligible(const sd_model* m, int M) {
+    if (m->f32) return false;
     const int MB = pow2_blocks(M);
     return m->use_fused && m->fused_ok && (MB == 1 || MB == 2 || MB == 8);
 }
@@ -857,6 +978,55 @@ static PartView run_forward_fused(sd_model* m, sd_kv* kv, int B, int Tp, int n_h
 }
 
 // final norm + LM head on all rows + arg-max of the first T rows of every sequence
+// ------------------------------------------------------------------------------------------ float32 pass
+static void commit_rows(sd_model* m, sd_kv* kv, const int32_t* slots, const int32_t* n_acc, int Tp, int W, hipStream_t s) {
+    const sd_config& c = m->cfg;
+    if (m->f32)
+        launch_f32_kv_commit(m->f.kt, m->f.vt, kv->kc32, kv->vc32, slots, n_acc, kv->n_old, c.n_layers, kv->B, c.d_model, Tp,
+                             kv->cap, W, s);
+    else
+        launch_kv_commit(m->kt, m->vt, kv->kc, kv->vc, slots, n_acc, kv->n_old, c.n_layers, kv->B, c.n_heads, c.head_dim,
+                         Tp / 32, kv->cap_blocks, W, W, s);
+}
+
+static void run_forward_f32(sd_model* m, sd_kv* kv, int B, int T, int Tp, bool want_lm, hipStream_t s) {
+    const sd_config& c = m->cfg;
+    const int M = B * Tp, d = c.d_model, F = c.d_ffn;
+    sd_model::F32& f = m->f;
+    for (int l = 0; l < c.n_layers; ++l) {
+        const sd_model::F32Layer& lw = f.layers[l];
+        float* kt = f.kt + (size_t)l * M * d;
+        float* vt = f.vt + (size_t)l * M * d;
+        launch_f32_rmsnorm(m->x, lw.attn_norm, c.rms_eps, f.xn, M, d, nullptr, s);
+        launch_f32_linear(f.xn, lw.wqkv, nullptr, f.qkv, M, 3 * d, d, d, 3 * d, 0, s);
+        launch_f32_rope_kv(f.qkv, m->rt, f.q, kt, vt, M, c.n_heads, c.head_dim, s);
+        launch_f32_attn(f.q, kv->kc32 + l * kv->layer_stride, kv->vc32 + l * kv->layer_stride, kt, vt, kv->kv_len, m->rt.anc,
+                        f.attn, B, c.n_heads, c.head_dim, Tp, kv->cap, s);
+        launch_f32_linear(f.attn, lw.wo, nullptr, m->x, M, d, d, d, d, 1, s);
+        launch_f32_rmsnorm(m->x, lw.ffn_norm, c.rms_eps, f.xn, M, d, nullptr, s);
+        launch_f32_linear(f.xn, lw.wgu, nullptr, f.gu, M, 2 * F, d, d, 2 * F, 0, s);
+        launch_f32_swiglu(f.gu, f.act, M, F, s);
+        launch_f32_linear(f.act, lw.wdown, nullptr, m->x, M, d, F, F, d, 1, s);
+    }
+    if (want_lm) {
+        launch_f32_rmsnorm(m->x, f.final_norm, c.rms_eps, f.xn, M, d, nullptr, s);
+        launch_f32_linear(f.xn, f.lm_head, nullptr, m->logits, M, c.vocab, d, d, m->Vpad, 0, s);
+        launch_argmax(m->logits, m->Vpad, c.vocab, m->am, B, T, Tp, s);
+    }
+}
+
+static void run_draft_heads_f32(sd_model* m, sd_kv* kv, int B, uint32_t seq_mask, float* head_logits_out, hipStream_t s) {
+    const sd_config& c = m->cfg;
+    const int d = c.d_model, H = c.n_medusa;
+    sd_model::F32& f = m->f;
+    launch_f32_rmsnorm(m->x, f.final_norm, c.rms_eps, m->h_rows, B, d, kv->last_row, s);
+    launch_f32_linear(m->h_rows, f.medusa_w, f.medusa_b, f.z, B, H * d, d, d, H * d, 0, s);
+    launch_f32_medusa_act(f.z, m->h_rows, f.xh, B, H, d, s);
+    launch_f32_linear(f.xh, f.lm_head, nullptr, m->hlogits, H * B, c.vocab, d, d, m->Vpad, 0, s);
+    launch_topk(m->hlogits, m->Vpad, c.vocab, c.topk, kv->cand, B, H, seq_mask, s);
+    if (head_logits_out) launch_copy_head_logits(m->hlogits, m->Vpad, head_logits_out, c.vocab, B, H, s);
+}
+
 // (keep_h: also leaves the normalised rows in m->hf as fp32, for draft heads on every row)
 // need_logits: somebody reads m->logits afterwards (the caller's copy, sampling decoding); else only the arg-max
 static void run_lm_head(sd_model* m, PartView prev, int B, int T, int Tp, hipStream_t s, bool keep_h, bool need_logits) {
@@ -880,6 +1050,7 @@ static void run_forward(sd_model* m, sd_kv* kv, int B, int T, int Tp, int n_hi, 
                         hipStream_t s) {
     m->scratch_B = B;
     m->scratch_Tp = Tp;
+    if (m->f32) { run_forward_f32(m, kv, B, T, Tp, want_lm, s); return; }
     if (fused_eligible(m, B * Tp)) {
         // (when the final norm's rows themselves are wanted, the last stage runs as kernels of its own)
         PartView pl = run_forward_fused(m, kv, B, Tp, n_hi, want_lm && !keep_h, s);
@@ -893,6 +1064,7 @@ static void run_forward(sd_model* m, sd_kv* kv, int B, int T, int Tp, int n_hi, 
 
 // draft heads at row last_row[b] of every sequence -> cand (sequences in seq_mask only)
 static void run_draft_heads(sd_model* m, sd_kv* kv, int B, uint32_t seq_mask, float* head_logits_out, hipStream_t s) {
+    if (m->f32) { run_draft_heads_f32(m, kv, B, seq_mask, head_logits_out, s); return; }
     const sd_config& c = m->cfg;
     const int d = c.d_model, H = c.n_medusa;
     const PartView none = {nullptr, 0, d, nullptr, 0};
@@ -958,12 +1130,11 @@ extern "C" int sd_prefill(sd_model* m, sd_kv* kv, const int32_t* tokens, const i
             if (left > 0 && left <= Tp) fin |= 1u << b;
             n_hi = std::max(n_hi, kv->len_hi[b]);
         }
-        launch_build_rows_chain(m->rt, tokens, ca, kv->kv_len, B, Tp, c.head_dim, c.rope_theta, m->embed, c.d_model,
-                                c.vocab, m->x, s);
+        launch_build_rows_chain(m->rt, tokens, ca, kv->kv_len, B, Tp, c.head_dim, c.rope_theta, m->embed, m->f32 ? 1 : 0,
+                                c.d_model, c.vocab, m->x, s);
         run_forward(m, kv, B, Tp, Tp, n_hi, fin != 0, false, false, s);
         launch_prefill_commit_setup(ca, B, Tp, kv->i_slots, kv->i_nacc, kv->n_old, kv->kv_len, kv->last_row, s);
-        launch_kv_commit(m->kt, m->vt, kv->kc, kv->vc, kv->i_slots, kv->i_nacc, kv->n_old, c.n_layers, B, c.n_heads,
-                         c.head_dim, Tp / 32, kv->cap_blocks, Tp, Tp, s);
+        commit_rows(m, kv, kv->i_slots, kv->i_nacc, Tp, Tp, s);
         for (int b = 0; b < B; ++b) kv->len_hi[b] += ca.len[b];
         if (fin) {
             launch_pick_root(m->am, kv->last_row, kv->root_tok, B, fin, s);
@@ -993,7 +1164,7 @@ static int step_common(sd_model* m, sd_kv* kv, uint64_t tree_uid, const int32_t*
                         kv->len_hi[b], kv->cap);
         n_hi = std::max(n_hi, kv->len_hi[b]);
     }
-    const bool all_rows = m->draft_schedule == SD_DRAFT_ALL_NODES && T > 1;
+    const bool all_rows = m->draft_schedule == SD_DRAFT_ALL_NODES && T > 1 && !m->f32;   // (float32: one schedule only)
     const bool heads = T > 1 || m->greedy_drafts;      // plain greedy decoding may leave the draft heads out
     if (!have_plans(m, B * Tp, B, heads, all_rows))
         return fail(SD_ERR_STATE, "%s: no launch plan for %d rows (internal inconsistency)", who, B * Tp);
@@ -1005,7 +1176,7 @@ static int step_common(sd_model* m, sd_kv* kv, uint64_t tree_uid, const int32_t*
     // everything the launch sequence depends on besides device-resident state
     auto enqueue = [&](hipStream_t s) {
     launch_build_rows_tree(m->rt, parent, depth, rank, kv->root_tok, cand, kv->kv_len, B, T, Tp, H, c.topk, c.head_dim,
-                           c.rope_theta, m->embed, c.d_model, c.vocab, m->x, s);
+                           c.rope_theta, m->embed, m->f32 ? 1 : 0, c.d_model, c.vocab, m->x, s);
     run_forward(m, kv, B, T, Tp, n_hi, true, all_rows, io->logits != nullptr || ty != nullptr, s);
     if (io->logits) launch_copy_logits(m->logits, m->Vpad, io->logits, c.vocab, B, T, Tp, s);
     if (io->argmax) launch_copy_rows_i32(m->am, io->argmax, B, T, Tp, s);
@@ -1027,8 +1198,7 @@ static int step_common(sd_model* m, sd_kv* kv, uint64_t tree_uid, const int32_t*
     if (ty)      // the next root is drawn from the base distribution at the last kept node
         launch_sample_root(m->logits, m->Vpad, c.vocab, kv->last_row, ty->u, va.inv_temperature, kv->root_tok, B,
                            B * Tp, s);
-    launch_kv_commit(m->kt, m->vt, kv->kc, kv->vc, slots, n_accept, kv->n_old, c.n_layers, B, c.n_heads, c.head_dim,
-                     Tp / 32, kv->cap_blocks, H + 1, H + 1, s);
+    commit_rows(m, kv, slots, n_accept, Tp, H + 1, s);
     if (all_rows) run_draft_heads_all_rows(m, kv, B, Tp, io->head_logits, s);
     else if (heads) run_draft_heads(m, kv, B, 0xffffffffu, io->head_logits, s);
     };
@@ -1096,10 +1266,8 @@ extern "C" int sd_kv_commit_rows(sd_model* m, sd_kv* kv, const int32_t* src_slot
             return fail(SD_ERR_KV_FULL, "sd_kv_commit_rows: sequence %d may exceed the cache (len <= %d, cap %d)", b,
                         kv->len_hi[b], kv->cap);
     hipStream_t s = (hipStream_t)stream;
-    const sd_config& c = m->cfg;
     launch_commit_setup(n_rows, width, kv->B, kv->i_nacc, kv->n_old, kv->kv_len, s);
-    launch_kv_commit(m->kt, m->vt, kv->kc, kv->vc, src_slots, kv->i_nacc, kv->n_old, c.n_layers, kv->B, c.n_heads,
-                     c.head_dim, m->scratch_Tp / 32, kv->cap_blocks, width, width, s);
+    commit_rows(m, kv, src_slots, kv->i_nacc, m->scratch_Tp, width, s);
     HIP_TRY(hipGetLastError());
     for (int b = 0; b < kv->B; ++b) kv->len_hi[b] += width;
     return SD_OK;

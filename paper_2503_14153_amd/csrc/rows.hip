@@ -14,9 +14,15 @@ static __device__ inline float2 rope_cs(int pos, int i, int hd, float theta) {
     return make_float2((float)c, (float)s);
 }
 
-static __device__ inline void embed_row(const uint16_t* __restrict__ embed, int tok, int d, float* __restrict__ xrow,
-                                        bool valid) {
-    const uint16_t* e = embed + (size_t)tok * d;
+// (embed_f32: the table holds float32 instead of bfloat16)
+static __device__ inline void embed_row(const void* __restrict__ embed, int embed_f32, int tok, int d,
+                                        float* __restrict__ xrow, bool valid) {
+    if (embed_f32) {
+        const float* e = (const float*)embed + (size_t)tok * d;
+        for (int i = threadIdx.x; i < d; i += blockDim.x) xrow[i] = valid ? e[i] : 0.f;
+        return;
+    }
+    const uint16_t* e = (const uint16_t*)embed + (size_t)tok * d;
     for (int i = threadIdx.x; i < d; i += blockDim.x) xrow[i] = valid ? bf16_bits_to_float(e[i]) : 0.f;
 }
 
@@ -26,8 +32,8 @@ static __device__ inline void embed_row(const uint16_t* __restrict__ embed, int 
 __global__ void k_build_rows_tree(RowTable rt, const int32_t* __restrict__ parent, const int32_t* __restrict__ depth,
                                   const int32_t* __restrict__ rank, const int32_t* __restrict__ root_tok,
                                   const int32_t* __restrict__ cand, const int32_t* __restrict__ kv_len, int T, int Tp,
-                                  int H, int topk, int hd, float theta, const uint16_t* __restrict__ embed, int d,
-                                  int V, float* __restrict__ x) {
+                                  int H, int topk, int hd, float theta, const void* __restrict__ embed, int embed_f32,
+                                  int d, int V, float* __restrict__ x) {
     const int m = blockIdx.x, b = m / Tp, j = m % Tp;
     const bool valid = j < T;
     int tok = 0, pos = kv_len[b];
@@ -47,21 +53,23 @@ __global__ void k_build_rows_tree(RowTable rt, const int32_t* __restrict__ paren
         for (int w = 0; w < SD_ANC_WORDS; ++w) rt.anc[(size_t)m * SD_ANC_WORDS + w] = a[w];
     }
     for (int i = threadIdx.x; i < hd / 2; i += blockDim.x) rt.cs[(size_t)m * (hd / 2) + i] = rope_cs(pos, i, hd, theta);
-    embed_row(embed, tok, d, x + (size_t)m * d, valid);
+    embed_row(embed, embed_f32, tok, d, x + (size_t)m * d, valid);
 }
 
 void launch_build_rows_tree(RowTable rt, const int32_t* parent, const int32_t* depth, const int32_t* rank,
                             const int32_t* root_tok, const int32_t* cand, const int32_t* kv_len, int B, int T, int Tp,
-                            int H, int topk, int hd, float theta, const void* embed, int d, int V, float* x, hipStream_t s) {
+                            int H, int topk, int hd, float theta, const void* embed, int embed_f32, int d, int V, float* x,
+                            hipStream_t s) {
     hipLaunchKernelGGL(k_build_rows_tree, dim3(B * Tp), dim3(256), 0, s, rt, parent, depth, rank, root_tok, cand,
-                       kv_len, T, Tp, H, topk, hd, theta, (const uint16_t*)embed, d, V, x);
+                       kv_len, T, Tp, H, topk, hd, theta, embed, embed_f32, d, V, x);
 }
 
 // Prompt chunk as a chain: row j of sequence b is prompt token off[b] + j at position
 // committed length + j and attends rows 0..j of the chunk.
 __global__ void k_build_rows_chain(RowTable rt, const int32_t* __restrict__ tokens, ChainArgs ca,
                                    const int32_t* __restrict__ kv_len, int Tp, int hd, float theta,
-                                   const uint16_t* __restrict__ embed, int d, int V, float* __restrict__ x) {
+                                   const void* __restrict__ embed, int embed_f32, int d, int V,
+                                   float* __restrict__ x) {
     const int m = blockIdx.x, b = m / Tp, j = m % Tp;
     const bool valid = j < ca.len[b];
     int tok = valid ? min(max(tokens[ca.off[b] + j], 0), V - 1) : 0;
@@ -81,13 +89,14 @@ __global__ void k_build_rows_chain(RowTable rt, const int32_t* __restrict__ toke
         for (int w = 0; w < SD_ANC_WORDS; ++w) rt.anc[(size_t)m * SD_ANC_WORDS + w] = a[w];
     }
     for (int i = threadIdx.x; i < hd / 2; i += blockDim.x) rt.cs[(size_t)m * (hd / 2) + i] = rope_cs(pos, i, hd, theta);
-    embed_row(embed, tok, d, x + (size_t)m * d, valid);
+    embed_row(embed, embed_f32, tok, d, x + (size_t)m * d, valid);
 }
 
 void launch_build_rows_chain(RowTable rt, const int32_t* tokens, const ChainArgs& ca, const int32_t* kv_len, int B,
-                             int Tp, int hd, float theta, const void* embed, int d, int V, float* x, hipStream_t s) {
+                             int Tp, int hd, float theta, const void* embed, int embed_f32, int d, int V, float* x,
+                             hipStream_t s) {
     hipLaunchKernelGGL(k_build_rows_chain, dim3(B * Tp), dim3(256), 0, s, rt, tokens, ca, kv_len, Tp, hd, theta,
-                       (const uint16_t*)embed, d, V, x);
+                       embed, embed_f32, d, V, x);
 }
 
 // ------------------------------------------------------------------------------------------

@@ -198,10 +198,26 @@ void launch_reduce_selected(PartView pv, float* dst, const int32_t* sel, int B, 
 void launch_build_rows_tree(RowTable rt, const int32_t* parent, const int32_t* depth, const int32_t* rank,
                             const int32_t* root_tok, const int32_t* cand, const int32_t* kv_len,
                             int B, int T, int Tp, int H, int topk, int hd, float theta,
-                            const void* embed, int d, int V, float* x, hipStream_t s);
+                            const void* embed, int embed_f32, int d, int V, float* x, hipStream_t s);
 void launch_build_rows_chain(RowTable rt, const int32_t* tokens, const ChainArgs& ca, const int32_t* kv_len,
-                             int B, int Tp, int hd, float theta, const void* embed, int d, int V, float* x,
-                             hipStream_t s);
+                             int B, int Tp, int hd, float theta, const void* embed, int embed_f32, int d, int V,
+                             float* x, hipStream_t s);
+// float32 device path (f32.hip): natural row-major layouts, vector-ALU arithmetic
+void launch_f32_rmsnorm(const float* x, const float* gain, float eps, float* y, int M, int d, const int32_t* gather,
+                        hipStream_t s);
+void launch_f32_linear(const float* X, const float* W, const float* bias, float* out, int M, int N, int K, int ldx, int ldo,
+                       int accumulate, hipStream_t s);
+void launch_f32_rope_kv(const float* qkv, RowTable rt, float* q, float* kt, float* vt, int M, int nh, int hd, hipStream_t s);
+void launch_f32_attn(const float* q, const float* kc, const float* vc, const float* kt, const float* vt,
+                     const int32_t* kv_len, const uint32_t* anc, float* out, int B, int nh, int hd, int Tp, int cap,
+                     hipStream_t s);
+void launch_f32_swiglu(const float* gu, float* act, int M, int F, hipStream_t s);
+void launch_f32_medusa_act(const float* z, const float* h, float* out, int B, int H, int d, hipStream_t s);
+void launch_f32_kv_commit(const float* kt, const float* vt, float* kc, float* vc, const int32_t* src_slots,
+                          const int32_t* n_accept, const int32_t* n_old, int L, int B, int d, int Tp, int cap, int W,
+                          hipStream_t s);
+void launch_f32_kv_rows(float* kc, float* vc, float* k_rows, float* v_rows, int row0, int nrows, int d, int to_cache,
+                        hipStream_t s);
 void launch_norm_pack(float* x, PartView pv, const void* gain, float eps, void* xn_packed, float* hf_out,
                       int M, int d, int MB, const int32_t* gather, hipStream_t s);
 // RMSNorm with the scale deferred: operand = x * gain, ssq_part = partial sums of squares in SkRowScale's layout

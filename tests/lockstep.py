@@ -100,7 +100,9 @@ def compare_kv_rows(kv: sd.KVCache, st: orc.DecodeState, shape, row0: int, row1:
         rep.kv_flipped = max(rep.kv_flipped, fk, fv)
         # differing entries are rounding decisions near a boundary (a few per cent at these error levels; another
         # rounding mode on either side, e.g. truncation, would make about half of them differ)
-        assert extra > 0 or max(fk, fv) < 0.25, f"layer {layer}: {max(fk, fv):.1%} of the committed K/V entries differ"
+        # (a float32 cache holds unrounded rows: nearly every entry differs from the float64 one in its last bits)
+        assert extra > 0 or shape.dtype == "f32" or max(fk, fv) < 0.25, \
+            f"layer {layer}: {max(fk, fv):.1%} of the committed K/V entries differ"
 
 
 def resync_kv_rows(kv: sd.KVCache, st: orc.DecodeState, shape, row0: int, seq: int = 0):
@@ -108,8 +110,8 @@ def resync_kv_rows(kv: sd.KVCache, st: orc.DecodeState, shape, row0: int, seq: i
     n = st.kv.n
     if n > row0:
         for layer in range(shape.n_layers):
-            k = torch.from_numpy(st.kv.k[layer, row0:n]).to(torch.bfloat16).cuda().contiguous()
-            v = torch.from_numpy(st.kv.v[layer, row0:n]).to(torch.bfloat16).cuda().contiguous()
+            k = torch.from_numpy(st.kv.k[layer, row0:n]).to(kv.model.torch_dtype).cuda().contiguous()
+            v = torch.from_numpy(st.kv.v[layer, row0:n]).to(kv.model.torch_dtype).cuda().contiguous()
             kv.write_rows(layer, seq, row0, k, v)
 
 

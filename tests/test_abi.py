@@ -148,12 +148,15 @@ def test_bad_configurations_are_refused_before_allocation(lib):
     ptrs = C.cast(one, C.POINTER(C.c_void_p))
     w = binding._Weights(1, 1, 1, ptrs, ptrs, ptrs, ptrs, ptrs, ptrs, ptrs, ptrs, ptrs)
     out = C.c_void_p()
-    for bad in (dict(dtype=0), dict(head_dim=96, d_model=384), dict(d_model=260), dict(d_ffn=100), dict(n_medusa=16),
+    for bad in (dict(dtype=2), dict(head_dim=96, d_model=384), dict(d_model=260), dict(d_ffn=100), dict(n_medusa=16),
                 dict(topk=33), dict(topk=0), dict(vocab=1), dict(trunc_fallback=5), dict(rope_theta=0.0)):
         cfg = binding._Config(**{**good, **bad})
         assert lib.sd_model_create(C.byref(cfg), C.byref(w), 64, None, C.byref(out)) == d["SD_ERR_SHAPE"], bad
         assert not out.value
     cfg = binding._Config(**good)
+    # cache sizes: bf16 rows in blocks of 32, float32 rows as they are
+    assert lib.sd_kv_bytes(C.byref(cfg), 2, 100) == 2 * 2 * 2 * 128 * 256 * 2
+    assert lib.sd_kv_bytes(C.byref(binding._Config(**{**good, "dtype": 0})), 2, 100) == 2 * 2 * 2 * 100 * 256 * 4
     assert lib.sd_model_create(C.byref(cfg), C.byref(w), 0, None, C.byref(out)) == d["SD_ERR_SHAPE"]
     assert lib.sd_model_create(C.byref(cfg), C.byref(w), 257, None, C.byref(out)) == d["SD_ERR_SHAPE"]
 

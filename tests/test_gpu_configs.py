@@ -31,8 +31,8 @@ def _fill_synthetic(kv, states, shape, lens):
     for b, n in enumerate(lens):
         for layer in range(shape.n_layers):
             dims = (n, shape.n_heads, shape.head_dim)
-            k = wl.synthetic_kv_rows(wl.SEEDS["kvfill"], f"k{b}.{layer}", dims, "bf16")
-            v = wl.synthetic_kv_rows(wl.SEEDS["kvfill"], f"v{b}.{layer}", dims, "bf16")
+            k = wl.synthetic_kv_rows(wl.SEEDS["kvfill"], f"k{b}.{layer}", dims, shape.dtype)
+            v = wl.synthetic_kv_rows(wl.SEEDS["kvfill"], f"v{b}.{layer}", dims, shape.dtype)
             kv.write_rows(layer, b, 0, k.cuda().contiguous(), v.cuda().contiguous())
             states[b].kv.k[layer, :n] = k.double().numpy()
             states[b].kv.v[layer, :n] = v.double().numpy()

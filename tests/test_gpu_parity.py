@@ -137,9 +137,9 @@ def test_tiny_shape_lockstep_32_steps(sd, fallback):
 
 
 def test_tiny_shape_against_the_fp32_oracle(sd):
-    """configs[0] as specified (fp32 weights, fp32 cache) on the oracle's side, against the device path,
-    which stores weights and K/V rows as bf16: the storage rounding itself stays inside the logits bounds
-    (2e-2 max-abs, 1e-2 relative), so the tiny configuration is met without an fp32 device path."""
+    """configs[0] as specified (fp32 weights, fp32 cache) on the oracle's side, against the bf16 device path
+    given the same weights rounded to bf16: the storage rounding itself stays inside the logits bounds
+    (2e-2 max-abs, 1e-2 relative). (The float32 device path proper is covered by test_gpu_f32.py.)"""
     import dataclasses
     shape32 = wl.preset("tiny").model
     assert shape32.dtype == "f32"
