@@ -27,13 +27,39 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
-# HBM-side bytes per k_gemm_sk<2> launch (read + written) from two rocprofv3 --pmc runs
-# (FETCH_SIZE, WRITE_SIZE), scaled by what the same counters read for sd_calib's 1 GiB copy
-# kernel (1 FETCH unit = 2 KiB, 1 WRITE unit = 1 KiB): profiles/k_gemm_sk_7b_pmc_traffic.txt.
-# Only valid for the default workload; other workloads report null.
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = 123.1e6
-# same counters for k_build_labels at the `labels` workload: profiles/k_build_labels_256x8192_kernel_trace_and_traffic.txt
-LABELS_TRAFFIC_BYTES_PER_LAUNCH = 100.9e6
+
+
+def kernel_source_hash(names) -> str:
+    """SHA-256 over the named HIP sources (names and contents, in sorted order)."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in sorted(names):
+        h.update(name.encode())
+        with open(os.path.join(ROOT, "paper_2503_14153_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def counted_traffic(profile: str, key: str):
+    """HBM-side bytes per launch (read + written) of one kernel, as two rocprofv3 --pmc runs counted them
+    (FETCH_SIZE, WRITE_SIZE, scaled by what the same counters read for sd_calib's 1 GiB copy kernel). The
+    counter summaries under profiles/ carry the figure on a line `<key>: <bytes>` together with the sources of the
+    kernel (`kernel_sources: a.hip b.h ...`) and their hash at the time (`kernel_source_sha256: ...`); a summary
+    taken with other sources is not this build's traffic, and the bench line then says null rather than repeat a
+    stale number."""
+    path = os.path.join(ROOT, "profiles", profile)
+    try:
+        with open(path) as f:
+            lines = [ln.strip() for ln in f]
+    except OSError:
+        return None
+    fields = dict(ln.split(": ", 1) for ln in lines if ": " in ln and " " not in ln.split(": ", 1)[0])
+    try:
+        if fields["kernel_source_sha256"] != kernel_source_hash(fields["kernel_sources"].split()):
+            return None
+        return float(fields[key])
+    except (KeyError, OSError, ValueError):
+        return None
 
 
 def parse():
@@ -116,7 +142,7 @@ def main():
 
     # ---------------------------------------------------------------- plain greedy on the same GPU
     max_emit = W.kv_cap - prompt_len - (H + 1) - 1
-    n_truth = min(max_emit, (args.steps + args.warmup) * (H + 1) + H + 2)
+    n_truth = min(max_emit, (max(args.steps + args.warmup, args.sync_every + 2) + 1) * (H + 1) + H + 2)
     model.set_fused(args.fused)
     gout = [sd.greedy_step(model, kv) for _ in range(4)]            # warm-up
     torch.cuda.synchronize()
@@ -296,7 +322,9 @@ def main():
         "sync_every": SYNC,
         "roofline": {"kernel": "k_gemm_sk (weight-streaming MFMA GEMM, all projections)", "bound": "hbm",
                      "achieved": gemm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gemm_gbs / HBM_PEAK_GBS,
-                     "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH if (args.workload == "7b" and args.layers is None) else None, "avg_launch_us": gemm_avg_us,
+                     "traffic": counted_traffic("k_gemm_sk_7b_pmc_traffic.txt", "k_gemm_sk_traffic_bytes_per_launch")
+                     if (args.workload == "7b" and args.layers is None and not args.fused) else None,
+                     "avg_launch_us": gemm_avg_us,
                      "launches_per_step": g["launches"] / args.profile_steps,
                      "algorithmic_bytes_per_launch": g["bytes"] / max(g["launches"], 1)},
         "attention": {"kernel": "k_tree_attn", "achieved_GBs": attn_gbs, "frac_hbm": attn_gbs / HBM_PEAK_GBS,
@@ -490,7 +518,7 @@ def bench_labels(args, torch, wl, sd):
         "vs_baseline": None, "dtype": "int32", "data": "synthetic",
         "config": {"workload": f"labels: {B} sequences x {S} positions, {H} heads, geometric fragments of mean 4 tokens"},
         "roofline": {"kernel": "k_build_labels", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": gbs / HBM_PEAK_GBS, "traffic": LABELS_TRAFFIC_BYTES_PER_LAUNCH, "avg_launch_us": ms * 1e3,
+                     "frac": gbs / HBM_PEAK_GBS, "traffic": counted_traffic("k_build_labels_256x8192_kernel_trace_and_traffic.txt", "k_build_labels_traffic_bytes_per_launch"), "avg_launch_us": ms * 1e3,
                      "algorithmic_bytes_per_launch": nbytes},
         "cpu_baseline": cpu}))
 

@@ -795,14 +795,14 @@ static SkRowScale row_scale(const sd_model* m, const float* ssq) {
 static const SkRowScale NO_SCALE = {nullptr, 0, 0.f, 0.f};
 
 static PartView run_gemm(sd_model* m, const void* Xp, const void* Wp, float* out, int MB, int KB, int NB, int n_real,
-                         hipStream_t s, SkRowScale sc = NO_SCALE) {
+                         hipStream_t s) {
     const GemmPlan* p = m->find_plan(MB, KB, NB);
     if (!p) {                                          // unreachable after have_plans(); never launch with another shape's plan
         m->plan_missing = true;
         return PartView{out, 0, NB * 32, nullptr, 0};  // no slots: the consumer adds nothing
     }
     const int pi = prof_claim(m, PROF_GEMM, (double)n_real * KB * 16 * 2);
-    return launch_gemm(*p, Xp, Wp, m->zfrag, out, s, prof_ev(m, pi, 0), prof_ev(m, pi, 1), sc);
+    return launch_gemm(*p, Xp, Wp, m->zfrag, out, s, prof_ev(m, pi, 0), prof_ev(m, pi, 1));
 }
 
 // Every GEMM shape a pass over M rows issues (and, with heads = true, the draft heads after it, in the
@@ -857,17 +857,10 @@ static PartView run_layers(sd_model* m, sd_kv* kv, int B, int Tp, int n_hi, hipS
     const AttnGeom ag = attn_geometry(m, B, Tp, n_hi);
     PartView prev = {nullptr, 0, d, nullptr, 0};
     const size_t t_stride = (size_t)B * nh * TB * 32 * hd;     // elements per layer of tree scratch
-    const bool deferred = false;   // one launch per stage: the norm kernel that scales its rows itself measured faster
     for (int l = 0; l < c.n_layers; ++l) {
         const LayerW& lw = m->layers[l];
-        PartView pq;
-        if (deferred) {                                    // the norm's 1 / rms factor is applied by the GEMM (row_ops.h)
-            launch_norm_tile(m->x, prev, lw.attn_norm, m->xn, m->ssq_a, M, d, MB, s);
-            pq = run_gemm(m, m->xn, lw.wqkv, m->part, MB, m->KBd, m->NBqkv, 3 * d, s, row_scale(m, m->ssq_a));
-        } else {
-            launch_norm_pack(m->x, prev, lw.attn_norm, c.rms_eps, m->xn, nullptr, M, d, MB, nullptr, s);
-            pq = run_gemm(m, m->xn, lw.wqkv, m->part, MB, m->KBd, m->NBqkv, 3 * d, s);
-        }
+        launch_norm_pack(m->x, prev, lw.attn_norm, c.rms_eps, m->xn, nullptr, M, d, MB, nullptr, s);
+        PartView pq = run_gemm(m, m->xn, lw.wqkv, m->part, MB, m->KBd, m->NBqkv, 3 * d, s);
         uint16_t* kt = (uint16_t*)m->kt + l * t_stride;
         uint16_t* vt = (uint16_t*)m->vt + l * t_stride;
         launch_rope_kv(pq, m->rt, m->q, kt, vt, B, Tp, nh, hd, s);
@@ -878,14 +871,8 @@ static PartView run_layers(sd_model* m, sd_kv* kv, int B, int Tp, int n_hi, hipS
                          prof_ev(m, pa, 0), prof_ev(m, pa, 1));
         launch_attn_merge(m->opart, m->mlpart, m->attn_x, B, nh, hd, Tp, ag.nparts, MB, s);
         PartView po = run_gemm(m, m->attn_x, lw.wo, m->part, MB, m->KBd, m->NBo, d, s);
-        PartView pg;
-        if (deferred) {
-            launch_norm_tile(m->x, po, lw.ffn_norm, m->xn, m->ssq_f, M, d, MB, s);
-            pg = run_gemm(m, m->xn, lw.wgu, m->part, MB, m->KBd, m->NBgu, 2 * c.d_ffn, s, row_scale(m, m->ssq_f));
-        } else {
-            launch_norm_pack(m->x, po, lw.ffn_norm, c.rms_eps, m->xn, nullptr, M, d, MB, nullptr, s);
-            pg = run_gemm(m, m->xn, lw.wgu, m->part, MB, m->KBd, m->NBgu, 2 * c.d_ffn, s);
-        }
+        launch_norm_pack(m->x, po, lw.ffn_norm, c.rms_eps, m->xn, nullptr, M, d, MB, nullptr, s);
+        PartView pg = run_gemm(m, m->xn, lw.wgu, m->part, MB, m->KBd, m->NBgu, 2 * c.d_ffn, s);
         launch_swiglu_pack(pg, c.d_ffn, m->Fpad, m->act, M, MB, s);
         prev = run_gemm(m, m->act, lw.wdown, m->part, MB, m->KBf, m->NBo, d, s);
     }
@@ -1032,15 +1019,8 @@ static void run_draft_heads_f32(sd_model* m, sd_kv* kv, int B, uint32_t seq_mask
 static void run_lm_head(sd_model* m, PartView prev, int B, int T, int Tp, hipStream_t s, bool keep_h, bool need_logits) {
     const sd_config& c = m->cfg;
     const int M = B * Tp, MB = pow2_blocks(M);
-    PartView pl;
-    if (false) {                                           // (the deferred form, kept for comparison)
-        launch_norm_tile(m->x, prev, m->final_norm, m->xn, m->ssq_a, M, c.d_model, MB, s);
-        pl = run_gemm(m, m->xn, m->lm_head, m->part, MB, m->KBd, m->NBv, c.vocab, s, row_scale(m, m->ssq_a));
-    } else {                                               // the normalised rows themselves are wanted (m->hf), or 128 rows
-        launch_norm_pack(m->x, prev, m->final_norm, c.rms_eps, m->xn, keep_h ? m->hf : nullptr, M, c.d_model, MB, nullptr, s);
-        pl = run_gemm(m, m->xn, m->lm_head, m->part, MB, m->KBd, m->NBv, c.vocab, s);
-    }
-    (void)M;
+    launch_norm_pack(m->x, prev, m->final_norm, c.rms_eps, m->xn, keep_h ? m->hf : nullptr, M, c.d_model, MB, nullptr, s);
+    PartView pl = run_gemm(m, m->xn, m->lm_head, m->part, MB, m->KBd, m->NBv, c.vocab, s);
     launch_reduce_argmax(pl, need_logits ? m->logits : nullptr, c.vocab, m->am, B, T, Tp, s);
 }
 
@@ -1073,7 +1053,10 @@ static void run_draft_heads(sd_model* m, sd_kv* kv, int B, uint32_t seq_mask, fl
     const int MBh = pow2_blocks(H * B);
     launch_medusa_act(pm, m->h_rows, m->medusa_b, B, H, d, m->xn, MBh * 32, MBh, MBh, s);
     PartView pl = run_gemm(m, m->xn, m->lm_head, m->part, MBh, m->KBd, m->NBv, c.vocab, s);
-    launch_topk_parts(pl, head_logits_out ? m->hlogits : nullptr, c.vocab, c.topk, kv->cand, B, H, seq_mask, s);
+    // (a top-k that sums the slots itself was measured: 54 us against 5 + 22 us for these two, its few workgroups
+    // pull the partial sums too slowly)
+    launch_reduce_slots(pl, m->hlogits, H * B, s);
+    launch_topk(m->hlogits, m->Vpad, c.vocab, c.topk, kv->cand, B, H, seq_mask, s);
     if (head_logits_out) launch_copy_head_logits(m->hlogits, m->Vpad, head_logits_out, c.vocab, B, H, s);
 }
 

@@ -104,32 +104,19 @@ void launch_reduce_argmax(PartView pv, float* logits_or_null, int V, int32_t* am
 // rounds is a thread-local scan plus one block-wide (value, id) reduction, after which the
 // owner retires the selected element.
 #define TOPK_THREADS 1024
-// PARTS: the row is not read from `logits` but summed from the partial sums of the LM-head GEMM (slot order, as
-// k_reduce_slots does) and, if `logits` is not NULL, written there as well.
-template <int NPT, bool PARTS>
-__global__ __launch_bounds__(TOPK_THREADS) void k_topk(float* __restrict__ logits, PartView pv, int ld, int V, int k,
+template <int NPT>
+__global__ __launch_bounds__(TOPK_THREADS) void k_topk(const float* __restrict__ logits, int ld, int V, int k,
                                                        int32_t* __restrict__ out, int B, int H, uint32_t seq_mask) {
     const int r = blockIdx.x;                 // row r = head i * B + sequence b
     const int i = r / B, b = r % B;
     if (!((seq_mask >> b) & 1u)) return;
-    float* row = logits ? logits + (size_t)r * ld : nullptr;
+    const float* row = logits + (size_t)r * ld;
     const int tid = threadIdx.x;
     float v[NPT];
 #pragma unroll
     for (int j = 0; j < NPT; ++j) {
         int c = j * TOPK_THREADS + tid;
-        if (PARTS) {
-            float a = 0.f;
-            if (c < V) {
-                const int n = part_count(pv, c);
-                const float* p = pv.base + (size_t)r * pv.ld + c;
-                for (int sp = 0; sp < n; ++sp) a += p[(size_t)sp * pv.slot_stride];
-                if (row) row[c] = a;
-            }
-            v[j] = c < V ? a : NEG_INF;
-        } else {
-            v[j] = c < V ? row[c] : NEG_INF;
-        }
+        v[j] = c < V ? row[c] : NEG_INF;
     }
     __shared__ float sv[TOPK_THREADS / 64];
     __shared__ int si[TOPK_THREADS / 64];
@@ -172,11 +159,10 @@ __global__ __launch_bounds__(TOPK_THREADS) void k_topk(float* __restrict__ logit
     }
 }
 
-template <bool PARTS>
-static void topk_dispatch(float* logits, PartView pv, int ld, int V, int k, int32_t* out, int B, int H, uint32_t seq_mask,
-                          hipStream_t s) {
+void launch_topk(const float* logits, int ld, int V, int k, int32_t* out, int B, int H, uint32_t seq_mask,
+                 hipStream_t s) {
     const int npt = (V + TOPK_THREADS - 1) / TOPK_THREADS;
-#define TOPK(N) hipLaunchKernelGGL((k_topk<N, PARTS>), dim3(B * H), dim3(TOPK_THREADS), 0, s, logits, pv, ld, V, k, out, B, H, seq_mask)
+#define TOPK(N) hipLaunchKernelGGL((k_topk<N>), dim3(B * H), dim3(TOPK_THREADS), 0, s, logits, ld, V, k, out, B, H, seq_mask)
     if (npt <= 1) TOPK(1);
     else if (npt <= 4) TOPK(4);
     else if (npt <= 16) TOPK(16);
@@ -184,15 +170,6 @@ static void topk_dispatch(float* logits, PartView pv, int ld, int V, int k, int3
     else if (npt <= 64) TOPK(64);
     else TOPK(160);          // vocabularies up to 163840 ids (validated at model creation)
 #undef TOPK
-}
-void launch_topk(const float* logits, int ld, int V, int k, int32_t* out, int B, int H, uint32_t seq_mask,
-                 hipStream_t s) {
-    topk_dispatch<false>(const_cast<float*>(logits), PartView{nullptr, 0, ld, nullptr, 0}, ld, V, k, out, B, H, seq_mask, s);
-}
-// top-k of rows that still lie in the LM-head GEMM's partial sums; logits_or_null [rows][pv.ld]: also write them
-void launch_topk_parts(PartView pv, float* logits_or_null, int V, int k, int32_t* out, int B, int H, uint32_t seq_mask,
-                       hipStream_t s) {
-    topk_dispatch<true>(logits_or_null, pv, pv.ld, V, k, out, B, H, seq_mask, s);
 }
 
 // ------------------------------------------------------------------------------------------

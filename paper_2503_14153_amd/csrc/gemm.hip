@@ -79,21 +79,6 @@ __global__ __launch_bounds__(512, MT == 8 ? 1 : 2) void k_gemm_sk(const bf16x8* 
     gm.issue_ring();
     gm.template run<false>(xs, SkRowScale{nullptr, 0, 0.f, 0.f}, nullptr);
 }
-// the same with the deferred RMS scale of the rows (the operand came from a norm_tile stage)
-template <int MT>
-__global__ __launch_bounds__(512, MT == 8 ? 1 : 2) void k_gemm_sk_scaled(const bf16x8* __restrict__ Xp, const bf16x8* __restrict__ Wp,
-                                                    const bf16x8* __restrict__ zfrag, float* __restrict__ out,
-                                                    int KB, int NB, int ldo, size_t slot_stride, int upw, int rem,
-                                                    uint32_t kb_magic, const int32_t* __restrict__ slot0_tab,
-                                                    SkRowScale sc) {
-    __shared__ bf16x8 xs[SK_LDS_UNITS];
-    __shared__ float scale_lds[SK_LDS_SCALE_FLOATS];
-    SkGemm<MT> gm;
-    gm.setup(Xp, Wp, zfrag, out, KB, NB, ldo, slot_stride, upw, rem, kb_magic, slot0_tab, blockIdx.x, gridDim.x);
-    gm.issue_x();
-    gm.issue_ring();
-    gm.template run<true>(xs, sc, scale_lds);
-}
 
 // ------------------------------------------------------------------------------------------
 // Four row blocks (128 rows). The kernel above at four row blocks issues eight LDS fragment reads and
@@ -337,7 +322,7 @@ void gemm_plan_make(GemmPlan* p, int MB, int KB, int NB, int32_t* cnt_host, int3
 }
 
 PartView launch_gemm(const GemmPlan& p, const void* Xp, const void* Wp, const void* zfrag, float* out, hipStream_t s,
-                     hipEvent_t ev0, hipEvent_t ev1, SkRowScale sc) {
+                     hipEvent_t ev0, hipEvent_t ev1) {
     PartView pv;
     pv.base = out;
     pv.ld = p.NB * 32;
@@ -354,10 +339,10 @@ PartView launch_gemm(const GemmPlan& p, const void* Xp, const void* Wp, const vo
             hipLaunchKernelGGL(KERNEL_, dim3(p.G), dim3(THREADS_), 0, s, SK_ARGS, ##__VA_ARGS__);          \
     } while (0)
     switch (p.MB) {                                    // the plan's row blocks: 1, 2, 4 or 8, one pass each
-    case 1: if (sc.ssq) SK_LAUNCH(k_gemm_sk_scaled<1>, 512, sc); else SK_LAUNCH(k_gemm_sk<1>, 512); break;
-    case 2: if (sc.ssq) SK_LAUNCH(k_gemm_sk_scaled<2>, 512, sc); else SK_LAUNCH(k_gemm_sk<2>, 512); break;
-    case 4: SK_LAUNCH(k_gemm_sk_wide, SKW_THREADS); break;      // no deferred row scale in this kernel (sc.ssq is NULL)
-    case 8: if (sc.ssq) SK_LAUNCH(k_gemm_sk_scaled<8>, 512, sc); else SK_LAUNCH(k_gemm_sk<8>, 512); break;
+    case 1: SK_LAUNCH(k_gemm_sk<1>, 512); break;
+    case 2: SK_LAUNCH(k_gemm_sk<2>, 512); break;
+    case 4: SK_LAUNCH(k_gemm_sk_wide, SKW_THREADS); break;
+    case 8: SK_LAUNCH(k_gemm_sk<8>, 512); break;
     default:                                           // plans are only ever made for 1, 2, 4 or 8 row blocks
         pv.nmax = 0;                                   // nothing launched, nothing for a consumer to read
         pv.cnt = nullptr;

@@ -116,21 +116,6 @@ void launch_norm_pack(float* x, PartView pv, const void* gain, float eps, void* 
                        (const uint16_t*)gain, eps, (bf16x8*)xn_packed, hf_out, d, MB, gather);
 }
 
-// RMSNorm with the scale deferred to the consuming GEMM (body: row_ops.h): one wave per tile of 32 rows x 16 columns.
-__global__ __launch_bounds__(256) void k_norm_tile(float* __restrict__ x, PartView pv, const uint16_t* __restrict__ gain,
-                                                   bf16x8* __restrict__ xn, float* __restrict__ ssq_part, int d, int MB,
-                                                   int Mp, int n_items) {
-    const int item = blockIdx.x * 4 + (threadIdx.x >> 6), nkb = d >> 4;
-    if (item >= n_items) return;
-    norm_tile<false>(x, pv, gain, xn, ssq_part, d, MB, Mp, item / nkb, item % nkb, threadIdx.x & 63);
-}
-void launch_norm_tile(float* x, PartView pv, const void* gain, void* xn_packed, float* ssq_part, int M, int d, int MB,
-                      hipStream_t s) {
-    const int n_items = (M / 32) * (d / 16);
-    hipLaunchKernelGGL(k_norm_tile, dim3((n_items + 3) / 4), dim3(256), 0, s, x, pv, (const uint16_t*)gain,
-                       (bf16x8*)xn_packed, ssq_part, d, MB, MB * 32, n_items);
-}
-
 // ------------------------------------------------------------------------------------------
 // Rotary embedding and the tree K/V write from the QKV partial sums (body: row_ops.h).
 // grid (chunks of (h, a) x which, t, b): no index needs a division.

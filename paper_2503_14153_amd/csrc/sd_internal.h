@@ -185,7 +185,7 @@ void gemm_plan_make(GemmPlan* p, int MB, int KB, int NB, int32_t* cnt_host, int3
 // for per-kernel timing without launch gaps
 // sc: deferred RMS scale of the rows (ssq NULL: none; not available at four row blocks)
 PartView launch_gemm(const GemmPlan& p, const void* Xp, const void* Wp, const void* zfrag, float* out, hipStream_t s,
-                     hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr, SkRowScale sc = SkRowScale{nullptr, 0, 0.f, 0.f});
+                     hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 // persistent layer kernel: G workgroups (all must be resident at once), a.MB in {1, 2, 8}
 void launch_layer(const FusedArgs& a, int G, hipStream_t s, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 // how many of its workgroups the device can hold at once (0 on error)
@@ -221,8 +221,6 @@ void launch_f32_kv_rows(float* kc, float* vc, float* k_rows, float* v_rows, int 
 void launch_norm_pack(float* x, PartView pv, const void* gain, float eps, void* xn_packed, float* hf_out,
                       int M, int d, int MB, const int32_t* gather, hipStream_t s);
 // RMSNorm with the scale deferred: operand = x * gain, ssq_part = partial sums of squares in SkRowScale's layout
-void launch_norm_tile(float* x, PartView pv, const void* gain, void* xn_packed, float* ssq_part, int M, int d, int MB,
-                      hipStream_t s);
 void launch_rope_kv(PartView pv, RowTable rt, void* q_packed, void* kt, void* vt, int B, int Tp, int nh, int hd,
                     hipStream_t s);
 void launch_tree_attn(const void* q_packed, const void* kc, const void* vc, const void* kt, const void* vt,
@@ -241,8 +239,6 @@ void launch_reduce_argmax(PartView pv, float* logits_or_null, int V, int32_t* am
 void launch_argmax(const float* logits, int ld, int V, int32_t* am, int B, int T, int Tp, hipStream_t s);
 void launch_topk(const float* logits, int ld, int V, int k, int32_t* out, int B, int H, uint32_t seq_mask,
                  hipStream_t s);
-void launch_topk_parts(PartView pv, float* logits_or_null, int V, int k, int32_t* out, int B, int H, uint32_t seq_mask,
-                       hipStream_t s);
 void launch_pick_root(const int32_t* am, const int32_t* last_row, int32_t* root_tok, int B, uint32_t seq_mask,
                       hipStream_t s);
 void launch_verify(const VerifyArgs& a, int B, hipStream_t s);
