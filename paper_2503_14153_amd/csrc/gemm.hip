@@ -46,8 +46,8 @@ void launch_pack_weight(const void* src, void* dst, int N, int K, int nb_offset,
 }
 
 // ------------------------------------------------------------------------------------------
-// Balanced streaming ("stream-K") over MT = 1, 2 or 8 row blocks of 32 rows (this kernel) or four (the
-// kernel after it).
+// Balanced streaming ("stream-K") over MT = 1 or 2 row blocks of 32 rows (this kernel; also the GEMM body of the
+// persistent layer kernel, there with eight row blocks as well) or four and eight (the kernel after it).
 //
 // The work of one GEMM is the list of units (column group of 256 outputs, contraction block),
 // contraction block fastest; workgroup g of G takes the contiguous range [g*U/G, (g+1)*U/G),
@@ -81,163 +81,99 @@ __global__ __launch_bounds__(512, MT == 8 ? 1 : 2) void k_gemm_sk(const bf16x8* 
 }
 
 // ------------------------------------------------------------------------------------------
-// Four row blocks (128 rows). The kernel above at four row blocks issues eight LDS fragment reads and
-// eight MFMAs per weight fragment and is bound by those, not by HBM; the form below measured a little
-// faster there (54.1 against 54.8 us per launch at the 13B shape), the one above at eight row blocks.
-// Here a workgroup is four waves, one per SIMD, so that a wave may hold up to 512 registers; wave
-// w owns column blocks 2w and 2w+1 of the same 256-column group, every activation fragment read
-// from LDS feeds two weight fragments (half the LDS traffic per weight byte), and the four MFMAs
-// of a row block alternate between its two accumulators, so that none waits for the one before
-// it. Units, ring, segments, zero page and slots exactly as above.
-#define SKW_THREADS 256
-#ifndef SKW_R
-#define SKW_R 6
-#endif
-__global__ __launch_bounds__(SKW_THREADS, 1) void k_gemm_sk_wide(const bf16x8* __restrict__ Xp,
-                                                                 const bf16x8* __restrict__ Wp,
-                                                                 const bf16x8* __restrict__ zfrag,
-                                                                 float* __restrict__ out, int KB, int NB, int ldo,
-                                                                 size_t slot_stride, int upw, int rem, uint32_t kb_magic,
-                                                                 const int32_t* __restrict__ slot0_tab) {
-    constexpr int MT = 4, CB = 2, R = SKW_R, XK = 2, CPI = R / XK, XF = XK * MT * 2, XP = XF * 64 / SKW_THREADS;
-    static_assert(CPI == 3, "three chunks per ring length, three LDS buffers");
-    __shared__ bf16x8 xs[3][XF * 64];
-
+// Eight (or four) row blocks with the operand roles swapped: the WEIGHT fragments of a step go through LDS and the
+// activations stay in registers. With many row blocks the kernel above reads every activation fragment from LDS
+// once per column block (16 one-KiB reads and 16 MFMAs per wave and step at eight row blocks: the LDS port and
+// the matrix cores are both needed all the time, and neither gets it). Here wave w owns ROW block w % MT and MT
+// column blocks of the group: its two activation fragments of a step (hi, lo) come straight from L2 into registers
+// (nobody else needs them), every wave still streams one weight fragment per step through its ring and drops it
+// into LDS, and each weight fragment read from LDS feeds two MFMAs: half the LDS bytes per MFMA, the MFMAs of a
+// step go to MT different accumulators. Units, segments, zero page, slots and partial tiles exactly as above.
+template <int MT>
+__global__ __launch_bounds__(512, 2) void k_gemm_sk_rows(const bf16x8* __restrict__ Xp, const bf16x8* __restrict__ Wp,
+                                                         const bf16x8* __restrict__ zfrag, float* __restrict__ out,
+                                                         int KB, int NB, int ldo, size_t slot_stride, int upw, int rem,
+                                                         uint32_t kb_magic, const int32_t* __restrict__ slot0_tab) {
+    static_assert(MT == 4 || MT == 8, "row blocks");
+    constexpr int R = 4;       // ring depth in steps; even (the LDS buffer of a step is i & 1); 6 measured slower
+    constexpr int CPW = MT;                             // column blocks per wave: 8 waves cover MT rows x 8 columns
+    __shared__ bf16x8 ws[2][8 * 64];                    // the eight weight fragments of two consecutive steps
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int g = blockIdx.x;
-    SkWalk walk = sk_walk_init(g, upw, rem, KB, kb_magic);
-    const int slot0 = slot0_tab[g];                    // slot of this workgroup's first segment (later ones: 0)
+    const int r = wave % MT, ch = wave / MT;
+    SkWalk walk = sk_walk_init(blockIdx.x, upw, rem, KB, kb_magic);
+    const int slot0 = slot0_tab[blockIdx.x];
     int nseg = 0;
-    // the wave's two fragments of a contraction block lie side by side (2 KiB)
-    auto wptr = [&](const SkIter& I, int cb) {
-        int nb = I.ng * 8 + wave * CB + cb;
+    SkIter cur = sk_walk_next<R>(walk, KB), nxt = sk_walk_next<R>(walk, KB);
+    if (cur.valid == 0) return;
+    const bf16x8* zl = zfrag + lane;
+    const size_t wstep = (size_t)NB * 64, xstep = (size_t)MT * 2 * 64;
+    auto wptr = [&](const SkIter& I) {
+        int nb = I.ng * 8 + wave;
         if (nb >= NB) nb = NB - 1;
         return Wp + ((size_t)I.kb * NB + nb) * 64 + lane;
     };
-    const size_t wstep = (size_t)NB * 64;
-    const bf16x8* zl = zfrag + lane;
-    auto xload = [&](bf16x8(&dst)[XP], const SkIter& I, int c) {
-        int steps = I.valid - c * XK;
-        steps = steps < 0 ? 0 : (steps > XK ? XK : steps);
-        constexpr int PER_KB = MT * 2 * 64;
-        const int limit = steps * PER_KB;
-        const bf16x8* base = Xp + (size_t)(I.kb + c * XK) * PER_KB;
-#pragma unroll
-        for (int p = 0; p < XP; ++p) {
-            const int i = p * SKW_THREADS + tid;
-            dst[p] = *((i < limit) ? base + i : zl);
-        }
-    };
-    auto xstore = [&](const bf16x8(&src)[XP], int buf) {
-#pragma unroll
-        for (int p = 0; p < XP; ++p) xs[buf][p * SKW_THREADS + tid] = src[p];
-    };
+    auto xptr = [&](const SkIter& I) { return Xp + ((size_t)I.kb * MT + r) * 2 * 64 + lane; };
 
-    SkIter cur = sk_walk_next<R>(walk, KB), nxt = sk_walk_next<R>(walk, KB), nx2 = sk_walk_next<R>(walk, KB);
-    if (cur.valid == 0) return;
-
-    f32x16 acc[MT][CB];
+    f32x16 acc[CPW];
 #pragma unroll
-    for (int i = 0; i < MT; ++i)
+    for (int j = 0; j < CPW; ++j)
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][cb][v] = 0.f;
-
-    bf16x8 w[R][CB], xr[CPI][XP];
-#pragma unroll
-    for (int c = 0; c < CPI; ++c) xload(xr[c], cur, c);
+        for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+    bf16x8 w[R], xh[R], xl[R];
     {
-        const bf16x8* wc[CB];
+        const bf16x8* wc = wptr(cur);
+        const bf16x8* xc = xptr(cur);
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb) wc[cb] = wptr(cur, cb);
-#pragma unroll
-        for (int i = 0; i < R; ++i)
-#pragma unroll
-            for (int cb = 0; cb < CB; ++cb)
-                w[i][cb] = __builtin_nontemporal_load((i < cur.valid) ? wc[cb] + (size_t)i * wstep : zl);
+        for (int i = 0; i < R; ++i) {
+            w[i] = __builtin_nontemporal_load((i < cur.valid) ? wc + (size_t)i * wstep : zl);
+            xh[i] = *((i < cur.valid) ? xc + (size_t)i * xstep : zl);
+            xl[i] = *((i < cur.valid) ? xc + (size_t)i * xstep + 64 : zl);
+        }
     }
-    // LDS holds three chunks: the one in use and the next two. Chunk t+2 is written at the start of
-    // chunk t (its buffer was last read during chunk t-1, which every wave left through a barrier),
-    // so the first fragments of chunk t+1 can be read before the barrier that ends chunk t, and
-    // neither the LDS writes nor those reads sit on the critical path behind a barrier.
-    xstore(xr[0], 0);
-    xstore(xr[1], 1);
-    xload(xr[0], nxt, 0);
-    xload(xr[1], nxt, 1);
-    __syncthreads();
-    bf16x8 ph[2], pl[2];
-    ph[0] = xs[0][lane];
-    pl[0] = xs[0][64 + lane];
-
     for (;;) {
-        const bf16x8* wn[CB];
+        const bf16x8* wn = wptr(nxt);
+        const bf16x8* xn = xptr(nxt);
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb) wn[cb] = wptr(nxt, cb);
-#pragma unroll
-        for (int c = 0; c < CPI; ++c) {
-            // chunk t+2 -> LDS; its staging slot is refilled with the chunk one ring length further on
-            constexpr int XQ = XK * MT;                            // (hi, lo) pairs per chunk, even
-            const int sl = (c + 2) % CPI;
-            xstore(xr[sl], sl);
-            if (c == 0) xload(xr[sl], nxt, 2);
-            else xload(xr[sl], nx2, c - 1);
-            // the pairs are read one ahead of the MFMAs that use them (pair 0 was read before the barrier)
-#pragma unroll
-            for (int q = 0; q < XQ; ++q) {
-                const int j = q / MT, mt = q % MT;
-                const int i = c * XK + j;                         // ring slot (compile-time)
-                if (q + 1 < XQ) {
-                    ph[(q + 1) & 1] = xs[c][((q + 1) * 2) * 64 + lane];
-                    pl[(q + 1) & 1] = xs[c][((q + 1) * 2 + 1) * 64 + lane];
-                } else {
-                    ph[0] = xs[(c + 1) % CPI][lane];
-                    pl[0] = xs[(c + 1) % CPI][64 + lane];
-                }
-#pragma unroll
-                for (int cb = 0; cb < CB; ++cb)
-                    acc[mt][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph[q & 1], w[i][cb], acc[mt][cb], 0, 0, 0);
-#pragma unroll
-                for (int cb = 0; cb < CB; ++cb)
-                    acc[mt][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pl[q & 1], w[i][cb], acc[mt][cb], 0, 0, 0);
-                if (mt == MT - 1) {
-#pragma unroll
-                    for (int cb = 0; cb < CB; ++cb)
-                        w[i][cb] = __builtin_nontemporal_load((i < nxt.valid) ? wn[cb] + (size_t)i * wstep : zl);
-                }
-            }
+        for (int i = 0; i < R; ++i) {
+            // Buffer i & 1 was last read in step i - 2; every wave has passed the barrier of step i - 1 since, and
+            // its reads of step i - 2 come before that barrier in program order.
+            ws[i & 1][wave * 64 + lane] = w[i];
             __syncthreads();
+#pragma unroll
+            for (int j = 0; j < CPW; ++j) {
+                const bf16x8 b = ws[i & 1][(ch * CPW + j) * 64 + lane];
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh[i], b, acc[j], 0, 0, 0);
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl[i], b, acc[j], 0, 0, 0);
+            }
+            w[i] = __builtin_nontemporal_load((i < nxt.valid) ? wn + (size_t)i * wstep : zl);
+            xh[i] = *((i < nxt.valid) ? xn + (size_t)i * xstep : zl);
+            xl[i] = *((i < nxt.valid) ? xn + (size_t)i * xstep + 64 : zl);
         }
         if (cur.last) {
             const int slot = nseg == 0 ? slot0 : 0;
             ++nseg;
+            int gq = lane >> 5, ldo_here = ldo;            // opaque, as in k_gemm_sk: no hoisted row offsets
+            asm volatile("" : "+v"(gq), "+s"(ldo_here));
 #pragma unroll
-            for (int cb = 0; cb < CB; ++cb) {
-                const int nb = cur.ng * 8 + wave * CB + cb;
+            for (int j = 0; j < CPW; ++j) {
+                const int nb = cur.ng * 8 + ch * CPW + j;
                 if (nb < NB) {
                     float* o = out + (size_t)slot * slot_stride + (size_t)nb * 32 + (lane & 31);
-                    int gq = lane >> 5, ldo_here = ldo;            // opaque, as in k_gemm_sk: no hoisted row offsets
-                    asm volatile("" : "+v"(gq), "+s"(ldo_here));
 #pragma unroll
-                    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) {
-                            int m = mt * 32 + 8 * (v >> 2) + 4 * gq + (v & 3);
-                            __hip_atomic_store(&o[(size_t)m * ldo_here], acc[mt][cb][v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        }
+                    for (int v = 0; v < 16; ++v) {
+                        const int m = r * 32 + 8 * (v >> 2) + 4 * gq + (v & 3);
+                        __hip_atomic_store(&o[(size_t)m * ldo_here], acc[j][v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
                 }
             }
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
+            for (int j = 0; j < CPW; ++j)
 #pragma unroll
-                for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[mt][cb][v] = 0.f;
+                for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
         }
         if (nxt.valid == 0) break;
         cur = nxt;
-        nxt = nx2;
-        nx2 = sk_walk_next<R>(walk, KB);
+        nxt = sk_walk_next<R>(walk, KB);
     }
 }
 
@@ -341,8 +277,8 @@ PartView launch_gemm(const GemmPlan& p, const void* Xp, const void* Wp, const vo
     switch (p.MB) {                                    // the plan's row blocks: 1, 2, 4 or 8, one pass each
     case 1: SK_LAUNCH(k_gemm_sk<1>, 512); break;
     case 2: SK_LAUNCH(k_gemm_sk<2>, 512); break;
-    case 4: SK_LAUNCH(k_gemm_sk_wide, SKW_THREADS); break;
-    case 8: SK_LAUNCH(k_gemm_sk<8>, 512); break;
+    case 4: SK_LAUNCH(k_gemm_sk_rows<4>, 512); break;
+    case 8: SK_LAUNCH(k_gemm_sk_rows<8>, 512); break;
     default:                                           // plans are only ever made for 1, 2, 4 or 8 row blocks
         pv.nmax = 0;                                   // nothing launched, nothing for a consumer to read
         pv.cnt = nullptr;

@@ -49,7 +49,7 @@ static __device__ inline SkIter sk_walk_next(SkWalk& w, int KB) {
 // A workgroup (or a whole launch) without units: has_work() is false, the other calls do nothing.
 template <int MT>
 struct SkGemm {
-    static_assert(MT == 1 || MT == 2 || MT == 8, "four row blocks: k_gemm_sk_wide");
+    static_assert(MT == 1 || MT == 2 || MT == 8, "four row blocks: k_gemm_sk_rows only");
     // ring depth. Eight row blocks: the 128 accumulators leave two waves per SIMD room for a ring of
     // 4 steps (210 registers), and a step then holds 16 MFMAs, so 4 steps cover the same time as 16 do
     // with two row blocks (rings of 6 and 8 steps measured slower: 62.3 and 62.8 us against 59.8)
