@@ -863,12 +863,19 @@ static PartView run_layers(sd_model* m, sd_kv* kv, int B, int Tp, int n_hi, hipS
         PartView pq = run_gemm(m, m->xn, lw.wqkv, m->part, MB, m->KBd, m->NBqkv, 3 * d, s);
         uint16_t* kt = (uint16_t*)m->kt + l * t_stride;
         uint16_t* vt = (uint16_t*)m->vt + l * t_stride;
-        launch_rope_kv(pq, m->rt, m->q, kt, vt, B, Tp, nh, hd, s);
+        // With one query group per head (trees of up to 64 nodes, plain decoding, short prompt chunks) the attention
+        // launch builds the queries and the tree's keys / values from the QKV partial sums itself: one launch
+        // less per layer (7B shape: batch of eight 32-node trees 11.17 -> 10.97 ms per step, plain decoding +3 %, the
+        // 64-node step level to -0.8 %). With several query groups every group would repeat that work, and at long
+        // contexts, where the tree blocks go to the last cache part, that part would become the straggler (16 k rows:
+        // attention 55 -> 64 us): there the stage stays a launch of its own.
+        const bool fr = Tp <= 64 && ag.tree_sep;
+        if (!fr) launch_rope_kv(pq, m->rt, m->q, kt, vt, B, Tp, nh, hd, s);
         // algorithmic bytes: one read of K and V of the committed rows (upper bound n_hi) + tree rows
         const int pa = prof_claim(m, PROF_ATTN, (double)B * (n_hi + Tp) * 2.0 * d * 2.0);
         launch_tree_attn(m->q, kv->kc + l * kv->layer_stride, kv->vc + l * kv->layer_stride, kt, vt, kv->kv_len,
                          m->rt.anc, m->opart, m->mlpart, B, nh, hd, Tp, kv->cap_blocks, ag.ncparts, ag.per, ag.tree_sep, s,
-                         prof_ev(m, pa, 0), prof_ev(m, pa, 1));
+                         prof_ev(m, pa, 0), prof_ev(m, pa, 1), fr ? &pq : nullptr, fr ? &m->rt : nullptr);
         launch_attn_merge(m->opart, m->mlpart, m->attn_x, B, nh, hd, Tp, ag.nparts, MB, s);
         PartView po = run_gemm(m, m->attn_x, lw.wo, m->part, MB, m->KBd, m->NBo, d, s);
         launch_norm_pack(m->x, po, lw.ffn_norm, c.rms_eps, m->xn, nullptr, M, d, MB, nullptr, s);

@@ -59,13 +59,18 @@ static __device__ __forceinline__ void acc_scale(float& x, float alpha) {
 template <int N> static __device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
 
 // AW = ancestor words a query row needs: 4 for trees of up to 128 nodes, 8 beyond
-template <int HD, int TBW, int AW>
+// FR ("from the projection"): there is no rotary-embedding launch before this one. The workgroup builds the queries
+// of its head itself, from the QKV projection's partial sums (slot sums, rotation, two-term expansion, straight into
+// the LDS area the loop reads them from), and the workgroup that reads the tree blocks first builds the tree's keys
+// and values the same way, writes them to the tree scratch (the commit stage needs them there) and reads them back
+// as blocks. One query group only (Tp = 32 * TBW). NS: the projection's slot count if the same everywhere, else 0.
+template <int HD, int TBW, int AW, int FR = 0, int NS = 0>
 __global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp, const bf16x8* Kc, const bf16x8* Vc,
                                                    const bf16x8* Kt, const bf16x8* Vt, const int32_t* __restrict__ kv_len,
                                                    const uint32_t* __restrict__ anc, float* __restrict__ opart,
                                                    float2* __restrict__ mlpart, int nh, int Tp, int cap_blocks,
                                                    int ncparts, int per, int tree_sep, float scale_log2,
-                                                   int xcd_stride, int nseq) {
+                                                   int xcd_stride, int nseq, PartView pv, RowTable rt) {
     constexpr int KK = HD / 16;        // contraction steps of QK^T = K fragments per block
     constexpr int EB = HD / 32;        // 32-wide output blocks of PV
     constexpr int NV = 2 * EB;         // V fragments per block
@@ -139,6 +144,33 @@ __global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp
         j = min(j, total - 1);
         return (j < ntree) ? vtb + (size_t)j * BLK : vcb + (size_t)min(c0 + j - ntree, cap_blocks - 1) * BLK;
     };
+    // FR: a workgroup whose items are tree blocks only (the tree has a part of its own) keeps the blocks it builds in
+    // LDS too (in the area the final merge uses, which is idle until the loop is over) and reads its operands from
+    // there: no wait for the stores to the scratch, no round trip to read them back.
+    bf16x8* const tkv = lds + QF * 64;                 // K blocks of the tree, then its V blocks
+    const bool tree_only = FR && ntree && !has_cache;  // (workgroup-uniform)
+    if constexpr (FR) {
+        static_assert(2 * TBW * BLK <= 4 * WAVE_UNITS, "the tree blocks fit the merge area");
+        if (ntree) {                                   // (workgroup-uniform) the tree's keys and values of this head
+            constexpr int NA = HD / 16;                // pieces of 8 dims + their rotary partners per row
+            uint16_t* ktw = (uint16_t*)const_cast<bf16x8*>(Kt);
+            uint16_t* vtw = (uint16_t*)const_cast<bf16x8*>(Vt);
+            uint16_t* kcp = tree_only ? (uint16_t*)tkv : nullptr;
+            uint16_t* vcp = tree_only ? (uint16_t*)(tkv + TBW * BLK) : nullptr;
+            constexpr int TPC = TBW * 32;              // = Tp here; compile-time trip counts: no guard between the items' loads
+            static_assert((2 * TPC * NA) % 256 == 0, "whole rounds");
+#pragma unroll
+            for (int u = 0; u < 2 * TPC * NA / 256; ++u) {
+                const int it = u * 256 + tid;
+                const int which = 1 + it / (TPC * NA), rem_ = it % (TPC * NA);
+                rope_kv_item<true, NS>(pv, rt, nullptr, ktw, vtw, TPC, nh, HD, which, h, rem_ % NA, rem_ / NA, b, 0, kcp, vcp);
+            }
+            if (!tree_only) {
+                wait_vm<0>();                          // the stores have reached L2 ...
+                __syncthreads();                       // ... of every wave, before any wave reads the blocks back
+            }
+        }
+    }
     bf16x8 kr[2][KK], vr[2][NV];
     auto request_k = [&](bf16x8(&kd)[KK], int j) {
         const bf16x8* kp = kaddr(j);
@@ -150,8 +182,29 @@ __global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp
 #pragma unroll
         for (int i = 0; i < NV; ++i) vd[i] = __builtin_nontemporal_load(vp + i * 64);
     };
-    request_k(kr[0], jw); request_v(vr[0], jw); request_k(kr[1], jw + 1); request_v(vr[1], jw + 1);
-    {   // queries of this (sequence, head, query group) -> LDS, a quarter per wave
+    auto lds_k = [&](bf16x8(&kd)[KK], int j) {
+        const bf16x8* kp = tkv + (size_t)min(j, total - 1) * BLK + lane;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) kd[kk] = kp[kk * 64];
+    };
+    auto lds_v = [&](bf16x8(&vd)[NV], int j) {
+        const bf16x8* vp = tkv + (size_t)(TBW + min(j, total - 1)) * BLK + lane;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) vd[i] = vp[i * 64];
+    };
+    if (!tree_only) { request_k(kr[0], jw); request_v(vr[0], jw); request_k(kr[1], jw + 1); request_v(vr[1], jw + 1); }
+    if constexpr (FR) {                                // queries of this head, built here, -> LDS
+        constexpr int NA = HD / 16;
+        const size_t q_unit0 = ((size_t)b * nh + h) * TB * (KK * 2 * 64);
+        constexpr int TPC = TBW * 32;
+        static_assert((TPC * NA) % 256 == 0 || TPC * NA < 256, "whole rounds, or a part of one");
+#pragma unroll
+        for (int u = 0; u < (TPC * NA + 255) / 256; ++u) {
+            const int it = u * 256 + tid;
+            if (TPC * NA >= 256 || it < TPC * NA)
+                rope_kv_item<true, NS>(pv, rt, (bf16x8*)lds, nullptr, nullptr, TPC, nh, HD, 0, h, it % NA, it / NA, b, q_unit0);
+        }
+    } else {   // queries of this (sequence, head, query group) -> LDS, a quarter per wave
         const bf16x8* qsrc = Qp + (((size_t)b * nh + h) * TB + tg * TBW) * (KK * 2 * 64) + lane;
 #pragma unroll
         for (int i = 0; i < QW; ++i) lds_dma16(qsrc + (wave * QW + i) * 64, myq_addr + i * 1024);
@@ -281,18 +334,26 @@ __global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp
     // the query loads in the instruction stream is not known here.)
     wait_vm<0>();
     __syncthreads();                                   // queries are in LDS
-    if (nit > 0) {
+    // the loop in two copies, so that each has loads of one kind in a straight line (a branch around a load makes the
+    // compiler wait for everything in flight)
+    auto run_items = [&](auto&& req_k, auto&& req_v) {
         for (int it = 0; it < nit; it += 2) {
 #pragma unroll
             for (int r = 0; r < 2; ++r) {
                 const bool live = it + r < nit;
                 f32x16 S[TBW];
                 if (live) qk(kr[r], S);
-                request_k(kr[r], jw + min(it + r + 2, nit - 1));   // past the wave's last item: that item again
+                req_k(kr[r], jw + min(it + r + 2, nit - 1));   // past the wave's last item: that item again
                 if (live) softmax_pv(vr[r], S, it + r);
-                request_v(vr[r], jw + min(it + r + 2, nit - 1));
+                req_v(vr[r], jw + min(it + r + 2, nit - 1));
             }
         }
+    };
+    if (FR && tree_only) {
+        lds_k(kr[0], jw); lds_v(vr[0], jw); lds_k(kr[1], jw + 1); lds_v(vr[1], jw + 1);
+        if (nit > 0) run_items(lds_k, lds_v);
+    } else if (nit > 0) {
+        run_items(request_k, request_v);
     }
 
     // ---- merge the four waves. Every wave parks its O tiles in its own part of LDS and its (max, sum)
@@ -350,10 +411,12 @@ __global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp
     }
 }
 
+// qkv: NULL (the queries and the tree's keys / values were made by launch_rope_kv), or the QKV projection's partial
+// sums: then this launch makes them itself (one query group only: Tp <= 64), and `rt` gives the rotation table
 void launch_tree_attn(const void* q_packed, const void* kc, const void* vc, const void* kt, const void* vt,
                       const int32_t* kv_len, const uint32_t* anc, float* opart, float2* mlpart, int B, int nh,
                       int hd, int Tp, int cap_blocks, int ncparts, int per, int tree_sep, hipStream_t s, hipEvent_t ev0,
-                      hipEvent_t ev1) {
+                      hipEvent_t ev1, const PartView* qkv, const RowTable* rt) {
     const float scale_log2 = 1.4426950408889634f / sqrtf((float)hd);
     const int TB = Tp / 32;
     const int TBW = (TB % 2 == 0) ? 2 : 1;
@@ -365,17 +428,28 @@ void launch_tree_attn(const void* q_packed, const void* kc, const void* vc, cons
         grid = dim3(xcd_stride * TG, 1, 1);
     }
 #define ATT_ARGS (const bf16x8*)q_packed, (const bf16x8*)kc, (const bf16x8*)vc, (const bf16x8*)kt, (const bf16x8*)vt, \
-                 kv_len, anc, opart, mlpart, nh, Tp, cap_blocks, ncparts, per, tree_sep, scale_log2, xcd_stride, B
-#define ATT(HD_, TBW_, AW_)                                                                                          \
+                 kv_len, anc, opart, mlpart, nh, Tp, cap_blocks, ncparts, per, tree_sep, scale_log2, xcd_stride, B, pv_arg, rt_arg
+#define ATT(HD_, TBW_, AW_, ...)                                                                                     \
     do {                                                                                                        \
         if (ev0 || ev1)                                                                                         \
-            hipExtLaunchKernelGGL((k_tree_attn<HD_, TBW_, AW_>), grid, dim3(256), 0, s, ev0, ev1, 0, ATT_ARGS); \
+            hipExtLaunchKernelGGL((k_tree_attn<HD_, TBW_, AW_, ##__VA_ARGS__>), grid, dim3(256), 0, s, ev0, ev1, 0, ATT_ARGS); \
         else                                                                                                    \
-            hipLaunchKernelGGL((k_tree_attn<HD_, TBW_, AW_>), grid, dim3(256), 0, s, ATT_ARGS);                 \
+            hipLaunchKernelGGL((k_tree_attn<HD_, TBW_, AW_, ##__VA_ARGS__>), grid, dim3(256), 0, s, ATT_ARGS);  \
     } while (0)
 #define ATT2(HD_, TBW_) do { if (Tp > 128) ATT(HD_, TBW_, 8); else ATT(HD_, TBW_, 4); } while (0)
-    if (hd == 128) { if (TBW == 2) ATT2(128, 2); else ATT2(128, 1); }
-    else           { if (TBW == 2) ATT2(64, 2);  else ATT2(64, 1); }
+    PartView pv_arg = {nullptr, 0, 0, nullptr, 0};
+    RowTable rt_arg = {nullptr, nullptr, nullptr, nullptr};
+    if (qkv && rt && TG == 1) {
+        pv_arg = *qkv;
+        rt_arg = *rt;
+        const bool four = qkv->cnt == nullptr && qkv->nmax == 4;     // the aligned QKV plan of the 7B and 13B shapes
+#define ATT_FR(HD_, TBW_) do { if (four) ATT(HD_, TBW_, 4, 1, 4); else ATT(HD_, TBW_, 4, 1, 0); } while (0)
+        if (hd == 128) { if (TBW == 2) ATT_FR(128, 2); else ATT_FR(128, 1); }
+        else           { if (TBW == 2) ATT_FR(64, 2);  else ATT_FR(64, 1); }
+#undef ATT_FR
+    }
+    else if (hd == 128) { if (TBW == 2) ATT2(128, 2); else ATT2(128, 1); }
+    else                { if (TBW == 2) ATT2(64, 2);  else ATT2(64, 1); }
 #undef ATT2
 #undef ATT
 #undef ATT_ARGS

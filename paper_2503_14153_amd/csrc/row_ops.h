@@ -172,17 +172,37 @@ static __device__ __forceinline__ void norm_tile(float* __restrict__ x, const Pa
 // expansion), k and v (tree scratch, block layouts, bf16). One item = (row t of sequence b, head h, piece a,
 // which): dims [8a, 8a+8) and their rotary partners [hd/2 + 8a, +8) of q (which = 0), k (1) or v (2).
 // Nothing written here is read again within the launch (the attention kernel is the consumer).
-template <bool BATCH>
+// NS > 0: every column group of the QKV projection has NS slots (its plan says so): all loads in a straight line.
+// q_unit0: subtracted from the 16-byte unit index of the query fragments (a caller that keeps one head's queries in a
+// buffer of its own, e.g. in LDS, passes that head's offset). k_copy / v_copy: if not NULL, this head's key / value
+// blocks are written there as well (block layouts, offsets within the head).
+template <bool BATCH, int NS = 0>
 static __device__ __forceinline__ void rope_kv_item(const PartView& pv, const RowTable& rt, bf16x8* __restrict__ qp,
                                                     uint16_t* __restrict__ kt, uint16_t* __restrict__ vt, int Tp, int nh,
-                                                    int hd, int which, int h, int a, int t, int b) {
+                                                    int hd, int which, int h, int a, int t, int b, size_t q_unit0 = 0,
+                                                    uint16_t* k_copy = nullptr, uint16_t* v_copy = nullptr) {
     const int m = b * Tp + t;
     const int d = nh * hd, half = hd / 2;
     const int col0 = which * d + h * hd + a * 8;
     const float* p0 = pv.base + (size_t)m * pv.ld + col0;
-    const int nsplit = part_count(pv, col0);           // a head's columns share one 256-column group
+    const int nsplit = NS > 0 ? NS : part_count(pv, col0);           // a head's columns share one 256-column group
     float lo[8] = {0, 0, 0, 0, 0, 0, 0, 0}, hi[8] = {0, 0, 0, 0, 0, 0, 0, 0};     // dims 8a..8a+7, half+8a..+7
-    if constexpr (BATCH) {
+    if constexpr (NS > 0) {
+        float4 x0[NS], x1[NS], x2[NS], x3[NS];
+#pragma unroll
+        for (int sp = 0; sp < NS; ++sp) {
+            const float* p = p0 + (size_t)sp * pv.slot_stride;
+            x0[sp] = *(const float4*)p; x1[sp] = *(const float4*)(p + 4);
+            x2[sp] = *(const float4*)(p + half); x3[sp] = *(const float4*)(p + half + 4);
+        }
+#pragma unroll
+        for (int sp = 0; sp < NS; ++sp) {
+            lo[0] += x0[sp].x; lo[1] += x0[sp].y; lo[2] += x0[sp].z; lo[3] += x0[sp].w;
+            lo[4] += x1[sp].x; lo[5] += x1[sp].y; lo[6] += x1[sp].z; lo[7] += x1[sp].w;
+            hi[0] += x2[sp].x; hi[1] += x2[sp].y; hi[2] += x2[sp].z; hi[3] += x2[sp].w;
+            hi[4] += x3[sp].x; hi[5] += x3[sp].y; hi[6] += x3[sp].z; hi[7] += x3[sp].w;
+        }
+    } else if constexpr (BATCH) {
         add_slots8<true>(lo, p0, pv.slot_stride, nsplit);
         add_slots8<true>(hi, p0 + half, pv.slot_stride, nsplit);
     } else {
@@ -204,6 +224,10 @@ static __device__ __forceinline__ void rope_kv_item(const PartView& pv, const Ro
             __bf16 w1 = (__bf16)lo[i], w2 = (__bf16)hi[i];
             vt[head_off + vblk_index(t, a * 8 + i, hd)] = __builtin_bit_cast(uint16_t, w1);
             vt[head_off + vblk_index(t, half + a * 8 + i, hd)] = __builtin_bit_cast(uint16_t, w2);
+            if (v_copy) {
+                v_copy[vblk_index(t, a * 8 + i, hd)] = __builtin_bit_cast(uint16_t, w1);
+                v_copy[vblk_index(t, half + a * 8 + i, hd)] = __builtin_bit_cast(uint16_t, w2);
+            }
         }
         return;
     }
@@ -219,16 +243,20 @@ static __device__ __forceinline__ void rope_kv_item(const PartView& pv, const Ro
         split_hilo(r1, h1, l1);
         split_hilo(r2, h2, l2);
         size_t q1i = 2 * head_off + qblk_index(t, a * 8, hd), q2i = 2 * head_off + qblk_index(t, half + a * 8, hd);
-        qp[q1i >> 3] = h1;
-        qp[(q1i >> 3) + 64] = l1;
-        qp[q2i >> 3] = h2;
-        qp[(q2i >> 3) + 64] = l2;
+        qp[(q1i >> 3) - q_unit0] = h1;
+        qp[(q1i >> 3) - q_unit0 + 64] = l1;
+        qp[(q2i >> 3) - q_unit0] = h2;
+        qp[(q2i >> 3) - q_unit0 + 64] = l2;
     } else {                                            // keys: bf16, the cache's storage type
         bf16x8 k1, k2;
 #pragma unroll
         for (int i = 0; i < 8; ++i) { k1[i] = (__bf16)r1[i]; k2[i] = (__bf16)r2[i]; }
         ((bf16x8*)kt)[(head_off + kblk_index(t, a * 8, hd)) >> 3] = k1;
         ((bf16x8*)kt)[(head_off + kblk_index(t, half + a * 8, hd)) >> 3] = k2;
+        if (k_copy) {
+            ((bf16x8*)k_copy)[kblk_index(t, a * 8, hd) >> 3] = k1;
+            ((bf16x8*)k_copy)[kblk_index(t, half + a * 8, hd) >> 3] = k2;
+        }
     }
 }
 

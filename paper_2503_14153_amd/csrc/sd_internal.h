@@ -226,7 +226,8 @@ void launch_rope_kv(PartView pv, RowTable rt, void* q_packed, void* kt, void* vt
 void launch_tree_attn(const void* q_packed, const void* kc, const void* vc, const void* kt, const void* vt,
                       const int32_t* kv_len, const uint32_t* anc, float* opart, float2* mlpart,
                       int B, int nh, int hd, int Tp, int cap_blocks, int ncparts, int per, int tree_sep,
-                      hipStream_t s, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
+                      hipStream_t s, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr, const PartView* qkv = nullptr,
+                      const RowTable* rt = nullptr);
 void launch_attn_merge(const float* opart, const float2* mlpart, void* x_packed, int B, int nh, int hd,
                        int Tp, int nparts, int MB, hipStream_t s);
 void launch_swiglu_pack(PartView pv, int F, int Fpad, void* act_packed, int M, int MB, hipStream_t s);
