@@ -203,6 +203,10 @@ def main():
     e_dev = torch.zeros(1, dtype=torch.int64, device="cuda")
     tok_log = torch.zeros((SYNC, H + 1), dtype=torch.int32, device="cuda")
     nacc_log = torch.zeros(SYNC, dtype=torch.int32, device="cuda")
+    # step j of a window writes its verdict straight into row j of the logs (no copies between the steps)
+    slot_log = torch.zeros((SYNC, H + 1), dtype=torch.int32, device="cuda")
+    raw_log = torch.zeros(SYNC, dtype=torch.int32, device="cuda")
+    outs = [sd.StepOutput(nacc_log[j: j + 1], tok_log[j: j + 1], slot_log[j: j + 1], raw_log[j: j + 1]) for j in range(SYNC)]
     room = min(n_table, W.kv_cap - 1 - prompt_len) - (H + 1)          # e may not exceed this when a step starts
     assert room > SYNC * (H + 1), "sync window too long for this cache"
 
@@ -244,14 +248,12 @@ def main():
             for j in range(w):
                 if args.decoding == "sampling":
                     i = state["i"]
-                    sd.spec_step_typical(model, kv, tree, stop_words, u_dev[i: i + 1], out=out, **typical)
+                    sd.spec_step_typical(model, kv, tree, stop_words, u_dev[i: i + 1], out=outs[j], **typical)
                     state["i"] = i + 1
                 else:
                     torch.index_select(table_dev, 0, e_dev, out=forced)
-                    sd.spec_step(model, kv, tree, stop_words, forced_cand=forced, out=out)
-                    tok_log[j].copy_(out.tokens[0])
-                    e_dev.add_(out.n_accept)
-                nacc_log[j: j + 1].copy_(out.n_accept)
+                    sd.spec_step(model, kv, tree, stop_words, forced_cand=forced, out=outs[j])
+                    e_dev.add_(outs[j].n_accept)
             close_window(w)
             done += w
 
