@@ -30,13 +30,19 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 
 
 def kernel_source_hash(names) -> str:
-    """SHA-256 over the named HIP sources (names and contents, in sorted order)."""
+    """SHA-256 over the code of the named HIP sources (in sorted order): `//` comments, trailing blanks and empty
+    lines do not count, so that rewording a comment does not orphan the counters taken with the same code."""
     import hashlib
+    import re
     h = hashlib.sha256()
     for name in sorted(names):
         h.update(name.encode())
-        with open(os.path.join(ROOT, "paper_2503_14153_amd", "csrc", name), "rb") as f:
-            h.update(f.read())
+        with open(os.path.join(ROOT, "paper_2503_14153_amd", "csrc", name), "r") as f:
+            for line in f:
+                code = re.sub(r"//.*$", "", line).rstrip()
+                if code:
+                    h.update(code.encode())
+                    h.update(b"\n")
     return h.hexdigest()
 
 

@@ -8,8 +8,9 @@
 // waves of the whole grid read one contiguous region of HBM, (2) keeps a ring of such loads in
 // flight per wave, refilled as it is consumed, (3) shares the small activation operand between
 // the waves of a workgroup through LDS, and (4) splits the contraction across workgroups so
-// that every one of 256 CUs streams the same number of weight bytes; the consumer kernel sums
-// the split partial results (deterministic, no atomics).
+// that every workgroup streams the same number of weight bytes (over all 256 CUs, or over fewer
+// when that lets every workgroup stay inside one column group: gemm_plan_make); the consumer
+// kernel sums the split partial results (deterministic, no atomics).
 //
 // Precision: the weights are bf16 by definition, the activations are not. Since the matrix
 // cores idle most of the time in an HBM-bound kernel, each activation enters as a two-term
