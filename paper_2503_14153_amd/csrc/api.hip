@@ -827,8 +827,11 @@ static bool have_plans(const sd_model* m, int M, int B, bool heads, bool all_row
 // parts of `per` 32-row blocks each, sized from the host's bound on the sequence lengths, and the
 // tree blocks go to a part of their own while the chip has room for it (short contexts) or to the
 // last cache part (long contexts).
+// tree_sep: parts that hold tree blocks only: 0 (the last cache part takes them), 1, or, when the attention launch
+// builds the tree's keys and values itself (one query group of two blocks: split_ok), one per tree block, so that the
+// building is shared by two workgroups.
 struct AttnGeom { int ncparts, per, tree_sep, nparts; };
-static AttnGeom attn_geometry(const sd_model* m, int B, int Tp, int n_hi) {
+static AttnGeom attn_geometry(const sd_model* m, int B, int Tp, int n_hi, bool split_ok = false) {
     const int nblk = ceil_div(n_hi, 32);
     const int TB = Tp / 32, TG = (TB % 2 == 0) ? TB / 2 : TB;
     const int groups = B * m->cfg.n_heads * TG;
@@ -838,9 +841,10 @@ static AttnGeom attn_geometry(const sd_model* m, int B, int Tp, int n_hi) {
     AttnGeom g;
     if (nblk == 0) { g.ncparts = 0; g.per = 1; g.tree_sep = 1; g.nparts = 1; return g; }
     const int by_work = ceil_div(nblk, 4);                 // at least one block per wave
-    if (P >= 2 && nblk <= 8 * (P - 1)) {                   // short: at most two blocks per wave, tree beside
-        g.tree_sep = 1;
-        g.ncparts = P - 1 < by_work ? P - 1 : by_work;
+    const int ntp = (split_ok && TB == 2 && P >= 3) ? 2 : 1;
+    if (P >= 2 && nblk <= 8 * (P - ntp)) {                 // short: at most two blocks per wave, tree beside
+        g.tree_sep = ntp;
+        g.ncparts = P - ntp < by_work ? P - ntp : by_work;
     } else {
         g.tree_sep = 0;
         g.ncparts = P < by_work ? P : by_work;
@@ -854,7 +858,7 @@ static AttnGeom attn_geometry(const sd_model* m, int B, int Tp, int n_hi) {
 static PartView run_layers(sd_model* m, sd_kv* kv, int B, int Tp, int n_hi, hipStream_t s) {
     const sd_config& c = m->cfg;
     const int M = B * Tp, MB = pow2_blocks(M), d = c.d_model, nh = c.n_heads, hd = c.head_dim, TB = Tp / 32;
-    const AttnGeom ag = attn_geometry(m, B, Tp, n_hi);
+    const AttnGeom ag = attn_geometry(m, B, Tp, n_hi, /*split_ok=*/Tp == 64);   // (one query group of two blocks)
     PartView prev = {nullptr, 0, d, nullptr, 0};
     const size_t t_stride = (size_t)B * nh * TB * 32 * hd;     // elements per layer of tree scratch
     for (int l = 0; l < c.n_layers; ++l) {
@@ -866,7 +870,7 @@ static PartView run_layers(sd_model* m, sd_kv* kv, int B, int Tp, int n_hi, hipS
         // With one query group per head (trees of up to 64 nodes, plain decoding, short prompt chunks) the attention
         // launch builds the queries and the tree's keys / values from the QKV partial sums itself: one launch
         // less per layer (7B shape: batch of eight 32-node trees 11.17 -> 10.97 ms per step, plain decoding +3 %, the
-        // 64-node step level to -0.8 %). With several query groups every group would repeat that work, and at long
+        // 64-node step 4.95 -> 4.89 ms once each of its two tree blocks has a workgroup of its own to build it). With several query groups every group would repeat that work, and at long
         // contexts, where the tree blocks go to the last cache part, that part would become the straggler (16 k rows:
         // attention 55 -> 64 us): there the stage stays a launch of its own.
         const bool fr = Tp <= 64 && ag.tree_sep;
@@ -1194,9 +1198,9 @@ static int step_common(sd_model* m, sd_kv* kv, uint64_t tree_uid, const int32_t*
     };
 
     if (m->use_graphs && !m->prof.on && !ty) {
-        const AttnGeom ag = attn_geometry(m, B, Tp, n_hi);
+        const AttnGeom ag = attn_geometry(m, B, Tp, n_hi, Tp == 64);
         std::vector<uint64_t> key = {kv->uid, tree_uid, (uint64_t)(uintptr_t)parent, (uint64_t)T, (uint64_t)Tp,
-                                     (uint64_t)ag.ncparts, (uint64_t)(ag.per * 2 + ag.tree_sep), (uint64_t)(uintptr_t)stop_mask,
+                                     (uint64_t)ag.ncparts, (uint64_t)(ag.per * 4 + ag.tree_sep), (uint64_t)(uintptr_t)stop_mask,
                                      (uint64_t)(uintptr_t)n_accept, (uint64_t)(uintptr_t)tokens,
                                      (uint64_t)(uintptr_t)slots, (uint64_t)(uintptr_t)io->n_accept_raw,
                                      (uint64_t)(uintptr_t)io->logits, (uint64_t)(uintptr_t)io->argmax,

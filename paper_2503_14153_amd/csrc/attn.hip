@@ -84,7 +84,7 @@ __global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, tl = lane & 31;
     const int TB = Tp / 32, TG = TB / TBW;
-    const int nparts = ncparts + (tree_sep ? 1 : 0);
+    const int nparts = ncparts + tree_sep;             // tree_sep: parts that hold tree blocks only (0, 1, or one per block)
     int part, h, tg, b;
     if (xcd_stride == 0) {                             // grid (part, head x query group, sequence)
         part = blockIdx.x;
@@ -108,7 +108,11 @@ __global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp
     const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) bf16x8*)lds);
     const uint32_t myq_addr = __builtin_amdgcn_readfirstlane(lds_addr + wave * QW * 1024);
     const bool has_cache = part < ncparts;
-    const int ntree = (part == nparts - 1) ? tg * TBW + TBW : 0;   // later tree blocks hold no ancestors
+    // Tree blocks of this part: all of them up to the query group's own (later ones hold no ancestors) in the last
+    // part, or, when every tree block has a part of its own (tree_sep >= 2, one query group), block part - ncparts.
+    const bool split_tree = tree_sep >= 2;
+    const int tb0 = (split_tree && part >= ncparts) ? part - ncparts : 0;
+    const int ntree = split_tree ? (part >= ncparts ? 1 : 0) : ((part == nparts - 1) ? tg * TBW + TBW : 0);
 
     // ancestor words of this lane's query rows: only the part with the tree blocks masks by them
     static_assert(SD_ANC_WORDS == 8 && (AW == 4 || AW == 8), "one or two 16-byte loads per row");
@@ -138,11 +142,11 @@ __global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp
     // item -> block address, always inside the tree scratch or the cache allocation
     auto kaddr = [&](int j) -> const bf16x8* {
         j = min(j, total - 1);
-        return (j < ntree) ? ktb + (size_t)j * BLK : kcb + (size_t)min(c0 + j - ntree, cap_blocks - 1) * BLK;
+        return (j < ntree) ? ktb + (size_t)(tb0 + j) * BLK : kcb + (size_t)min(c0 + j - ntree, cap_blocks - 1) * BLK;
     };
     auto vaddr = [&](int j) -> const bf16x8* {
         j = min(j, total - 1);
-        return (j < ntree) ? vtb + (size_t)j * BLK : vcb + (size_t)min(c0 + j - ntree, cap_blocks - 1) * BLK;
+        return (j < ntree) ? vtb + (size_t)(tb0 + j) * BLK : vcb + (size_t)min(c0 + j - ntree, cap_blocks - 1) * BLK;
     };
     // FR: a workgroup whose items are tree blocks only (the tree has a part of its own) keeps the blocks it builds in
     // LDS too (in the area the final merge uses, which is idle until the loop is over) and reads its operands from
@@ -158,12 +162,21 @@ __global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp
             uint16_t* kcp = tree_only ? (uint16_t*)tkv : nullptr;
             uint16_t* vcp = tree_only ? (uint16_t*)(tkv + TBW * BLK) : nullptr;
             constexpr int TPC = TBW * 32;              // = Tp here; compile-time trip counts: no guard between the items' loads
-            static_assert((2 * TPC * NA) % 256 == 0, "whole rounds");
+            static_assert((2 * 32 * NA) % 256 == 0, "whole rounds");
+            if (split_tree) {                          // the 32 rows of this part's block
 #pragma unroll
-            for (int u = 0; u < 2 * TPC * NA / 256; ++u) {
-                const int it = u * 256 + tid;
-                const int which = 1 + it / (TPC * NA), rem_ = it % (TPC * NA);
-                rope_kv_item<true, NS>(pv, rt, nullptr, ktw, vtw, TPC, nh, HD, which, h, rem_ % NA, rem_ / NA, b, 0, kcp, vcp);
+                for (int u = 0; u < 2 * 32 * NA / 256; ++u) {
+                    const int it = u * 256 + tid;
+                    const int which = 1 + it / (32 * NA), rem_ = it % (32 * NA);
+                    rope_kv_item<true, NS>(pv, rt, nullptr, ktw, vtw, TPC, nh, HD, which, h, rem_ % NA, tb0 * 32 + rem_ / NA, b, 0, kcp, vcp);
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < 2 * TPC * NA / 256; ++u) {
+                    const int it = u * 256 + tid;
+                    const int which = 1 + it / (TPC * NA), rem_ = it % (TPC * NA);
+                    rope_kv_item<true, NS>(pv, rt, nullptr, ktw, vtw, TPC, nh, HD, which, h, rem_ % NA, rem_ / NA, b, 0, kcp, vcp);
+                }
             }
             if (!tree_only) {
                 wait_vm<0>();                          // the stores have reached L2 ...
@@ -183,12 +196,12 @@ __global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp
         for (int i = 0; i < NV; ++i) vd[i] = __builtin_nontemporal_load(vp + i * 64);
     };
     auto lds_k = [&](bf16x8(&kd)[KK], int j) {
-        const bf16x8* kp = tkv + (size_t)min(j, total - 1) * BLK + lane;
+        const bf16x8* kp = tkv + (size_t)(tb0 + min(j, total - 1)) * BLK + lane;
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) kd[kk] = kp[kk * 64];
     };
     auto lds_v = [&](bf16x8(&vd)[NV], int j) {
-        const bf16x8* vp = tkv + (size_t)(TBW + min(j, total - 1)) * BLK + lane;
+        const bf16x8* vp = tkv + (size_t)(TBW + tb0 + min(j, total - 1)) * BLK + lane;
 #pragma unroll
         for (int i = 0; i < NV; ++i) vd[i] = vp[i * 64];
     };
@@ -262,7 +275,7 @@ __global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp
     auto softmax_pv = [&](const bf16x8(&vf)[NV], f32x16(&S)[TBW], int it) {
         const int j = jw + it;
         const bool tr = j < ntree;
-        const int blk = tr ? j : c0 + j - ntree;
+        const int blk = tr ? tb0 + j : c0 + j - ntree;
         const int left = n - blk * 32;
         const bool need_mask = tr || left < 32;                 // wave-uniform
         bf16x8 pf[TBW][2], pl[TBW][2];     // probabilities, two-term expansion
@@ -420,7 +433,7 @@ void launch_tree_attn(const void* q_packed, const void* kc, const void* vc, cons
     const float scale_log2 = 1.4426950408889634f / sqrtf((float)hd);
     const int TB = Tp / 32;
     const int TBW = (TB % 2 == 0) ? 2 : 1;
-    const int nparts = ncparts + (tree_sep ? 1 : 0), TG = TB / TBW;
+    const int nparts = ncparts + tree_sep, TG = TB / TBW;     // tree_sep: number of parts with tree blocks only
     dim3 grid(nparts, nh * TG, B);
     int xcd_stride = 0;
     if (TG > 1) {                                      // query groups of one head on one XCD (see the kernel)
