@@ -372,7 +372,7 @@ extern "C" int sd_model_create(const sd_config* cfg, const sd_weights* w, int32_
                 cnt_all.insert(cnt_all.end(), cnt.begin(), cnt.end());
                 cnt_all.insert(cnt_all.end(), slot0.begin(), slot0.end());
                 m->plans.push_back(pl);
-                pf = std::max(pf, (size_t)pl.slots * (mb * 32) * (size_t)sh[1] * 32);
+                pf = std::max(pf, (size_t)pl.slots_max * (mb * 32) * (size_t)sh[1] * 32);
             }
     }
     (void)ld_max;

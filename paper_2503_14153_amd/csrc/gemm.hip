@@ -85,96 +85,118 @@ __global__ __launch_bounds__(512, MT == 8 ? 1 : 2) void k_gemm_sk(const bf16x8* 
 // Eight (or four) row blocks with the operand roles swapped: the WEIGHT fragments of a step go through LDS and the
 // activations stay in registers. With many row blocks the kernel above reads every activation fragment from LDS
 // once per column block (16 one-KiB reads and 16 MFMAs per wave and step at eight row blocks: the LDS port and
-// the matrix cores are both needed all the time, and neither gets it). Here wave w owns ROW block w % MT and MT
-// column blocks of the group: its two activation fragments of a step (hi, lo) come straight from L2 into registers
-// (nobody else needs them), every wave still streams one weight fragment per step through its ring and drops it
-// into LDS, and each weight fragment read from LDS feeds two MFMAs: half the LDS bytes per MFMA, the MFMAs of a
-// step go to MT different accumulators. Units, segments, zero page, slots and partial tiles exactly as above.
-template <int MT>
-__global__ __launch_bounds__(512, 2) void k_gemm_sk_rows(const bf16x8* __restrict__ Xp, const bf16x8* __restrict__ Wp,
-                                                         const bf16x8* __restrict__ zfrag, float* __restrict__ out,
-                                                         int KB, int NB, int ldo, size_t slot_stride, int upw, int rem,
-                                                         uint32_t kb_magic, const int32_t* __restrict__ slot0_tab) {
-    static_assert(MT == 4 || MT == 8, "row blocks");
-    constexpr int R = 4;       // ring depth in steps; even (the LDS buffer of a step is i & 1); 6 measured slower
-    constexpr int CPW = MT;                             // column blocks per wave: 8 waves cover MT rows x 8 columns
-    __shared__ bf16x8 ws[2][8 * 64];                    // the eight weight fragments of two consecutive steps
+// the matrix cores are both needed all the time, and neither gets it). Here wave w owns ROW block w % MT and
+// CPW = CG * MT / 8 column blocks of a column group of CG blocks: its two activation fragments of a step (hi, lo)
+// come straight from L2 into registers (nobody else needs them), the first CG waves stream one weight fragment per
+// step through their rings and drop it into LDS, and each weight fragment read from LDS feeds two MFMAs.
+//
+// At these row counts the matrix cores, not the weight stream, set the pace, and what a step costs beyond its
+// MFMAs is the hand-over through LDS. So the split is always the aligned one (workgroup g = column group g / S,
+// segment g % S of the contraction: one partial tile per workgroup, slot = segment), the width of a column group is
+// chosen with the split (gemm_plan_make: narrower groups mean more workgroups and fewer slots), and a step is
+// software-pipelined around its one barrier:
+//   write the NEXT step's fragment to the other LDS buffer (its last readers passed the previous barrier);
+//   MFMAs of the first half of the column blocks (fragments already in registers), the ring's weight load among them;
+//   barrier; read the next step's first-half fragments;
+//   MFMAs of the second half, the two activation loads among them; read the next step's second-half fragments.
+// A wave that arrives at the barrier has its MFMAs queued and the reads it needs next already in flight; the
+// global loads are spread over the step because a wave cannot issue past a vector-memory instruction the address
+// unit has not taken yet (24 loads of 1 KiB per step at once held every wave's next MFMAs back).
+// Measured per step at 256 rows, column groups of six blocks (768 MFMA cycles): 1230 cycles with write, barrier,
+// read, MFMA in sequence; 1075 with the hand-over pipelined; 1030 with the loads spread as well.
+template <int MT, int CG>
+__global__ __launch_bounds__(512, 2) void k_gemm_rows(const bf16x8* __restrict__ Xp, const bf16x8* __restrict__ Wp,
+                                                      const bf16x8* __restrict__ zfrag, float* __restrict__ out,
+                                                      int KB, int NB, int ldo, size_t slot_stride, int S) {
+    static_assert((MT == 4 || MT == 8) && (CG * MT) % 16 == 0 && CG <= 8, "row blocks / column group");
+    constexpr int R = 4;                                // ring depth in steps; even (the LDS buffer of step i is i & 1)
+    constexpr int CPW = CG * MT / 8;                    // column blocks per wave: 8 waves cover MT rows x CG columns
+    constexpr int H = CPW / 2;                          // first half
+    __shared__ bf16x8 ws[2][CG * 64];                   // the weight fragments of two consecutive steps
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int r = wave % MT, ch = wave / MT;
-    SkWalk walk = sk_walk_init(blockIdx.x, upw, rem, KB, kb_magic);
-    const int slot0 = slot0_tab[blockIdx.x];
-    int nseg = 0;
-    SkIter cur = sk_walk_next<R>(walk, KB), nxt = sk_walk_next<R>(walk, KB);
-    if (cur.valid == 0) return;
-    const bf16x8* zl = zfrag + lane;
+    const int ng = blockIdx.x / S, seg = blockIdx.x - ng * S;
+    const int n = KB / S, kb0 = seg * n;                // this workgroup's steps: contraction blocks [kb0, kb0 + n)
+    const bool loader = wave < CG;
+    int nbw = ng * CG + wave;
+    if (nbw >= NB) nbw = NB - 1;                        // (a ragged last group: a duplicate fragment, never stored)
     const size_t wstep = (size_t)NB * 64, xstep = (size_t)MT * 2 * 64;
-    auto wptr = [&](const SkIter& I) {
-        int nb = I.ng * 8 + wave;
-        if (nb >= NB) nb = NB - 1;
-        return Wp + ((size_t)I.kb * NB + nb) * 64 + lane;
-    };
-    auto xptr = [&](const SkIter& I) { return Xp + ((size_t)I.kb * MT + r) * 2 * 64 + lane; };
+    const bf16x8* wp = Wp + ((size_t)kb0 * NB + nbw) * 64 + lane;
+    const bf16x8* xp = Xp + ((size_t)kb0 * MT + r) * 2 * 64 + lane;
+    const bf16x8* zl = zfrag + lane;                    // steps past n read zeros (no weight bytes, idle MFMA work)
 
     f32x16 acc[CPW];
 #pragma unroll
     for (int j = 0; j < CPW; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
-    bf16x8 w[R], xh[R], xl[R];
-    {
-        const bf16x8* wc = wptr(cur);
-        const bf16x8* xc = xptr(cur);
+    bf16x8 w[R], xh[R], xl[R], b[CPW];
 #pragma unroll
-        for (int i = 0; i < R; ++i) {
-            w[i] = __builtin_nontemporal_load((i < cur.valid) ? wc + (size_t)i * wstep : zl);
-            xh[i] = *((i < cur.valid) ? xc + (size_t)i * xstep : zl);
-            xl[i] = *((i < cur.valid) ? xc + (size_t)i * xstep + 64 : zl);
-        }
+    for (int i = 0; i < R; ++i) {
+        const bool ok = i < n;
+        if (loader) w[i] = __builtin_nontemporal_load(ok ? wp + (size_t)i * wstep : zl);
+        xh[i] = *(ok ? xp + (size_t)i * xstep : zl);
+        xl[i] = *(ok ? xp + (size_t)i * xstep + 64 : zl);
     }
-    for (;;) {
-        const bf16x8* wn = wptr(nxt);
-        const bf16x8* xn = xptr(nxt);
+    wp += R * wstep;
+    xp += R * xstep;
+    // step 0's fragments; its ring slot takes step R
+    if (loader) ws[0][wave * 64 + lane] = w[0];
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < CPW; ++j) b[j] = ws[0][(ch * CPW + j) * 64 + lane];
+    if (loader) w[0] = __builtin_nontemporal_load(R < n ? wp : zl);
+    for (int s0 = 0; s0 < n; s0 += R) {
 #pragma unroll
         for (int i = 0; i < R; ++i) {
-            // Buffer i & 1 was last read in step i - 2; every wave has passed the barrier of step i - 1 since, and
-            // its reads of step i - 2 come before that barrier in program order.
-            ws[i & 1][wave * 64 + lane] = w[i];
+            // entering step s0 + i: b holds its fragments (read from buffer i & 1), buffer (i + 1) & 1 is free
+            const bf16x8* wn = (s0 + R + i + 1 < n) ? wp + (size_t)(i + 1) * wstep : zl;   // step s0 + i + 1 + R
+            const bool xok = s0 + R + i < n;                                               // step s0 + i + R
+            const bf16x8* xhn = xok ? xp + (size_t)i * xstep : zl;
+            const bf16x8* xln = xok ? xp + (size_t)i * xstep + 64 : zl;
+            if (loader) ws[(i + 1) & 1][wave * 64 + lane] = w[(i + 1) % R];
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < H; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh[i], b[j], acc[j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (loader) w[(i + 1) % R] = __builtin_nontemporal_load(wn);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < H; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl[i], b[j], acc[j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
             __syncthreads();
 #pragma unroll
-            for (int j = 0; j < CPW; ++j) {
-                const bf16x8 b = ws[i & 1][(ch * CPW + j) * 64 + lane];
-                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh[i], b, acc[j], 0, 0, 0);
-                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl[i], b, acc[j], 0, 0, 0);
-            }
-            w[i] = __builtin_nontemporal_load((i < nxt.valid) ? wn + (size_t)i * wstep : zl);
-            xh[i] = *((i < nxt.valid) ? xn + (size_t)i * xstep : zl);
-            xl[i] = *((i < nxt.valid) ? xn + (size_t)i * xstep + 64 : zl);
+            for (int j = 0; j < H; ++j) b[j] = ws[(i + 1) & 1][(ch * CPW + j) * 64 + lane];
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = H; j < CPW; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh[i], b[j], acc[j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            xh[i] = *xhn;
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = H; j < CPW; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl[i], b[j], acc[j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            xl[i] = *xln;
+#pragma unroll
+            for (int j = H; j < CPW; ++j) b[j] = ws[(i + 1) & 1][(ch * CPW + j) * 64 + lane];
+            __builtin_amdgcn_sched_barrier(0);
         }
-        if (cur.last) {
-            const int slot = nseg == 0 ? slot0 : 0;
-            ++nseg;
-            int gq = lane >> 5, ldo_here = ldo;            // opaque, as in k_gemm_sk: no hoisted row offsets
-            asm volatile("" : "+v"(gq), "+s"(ldo_here));
+        wp += R * wstep;
+        xp += R * xstep;
+    }
+    int gq = lane >> 5, ldo_here = ldo;                // opaque, as in k_gemm_sk: no hoisted row offsets
+    asm volatile("" : "+v"(gq), "+s"(ldo_here));
 #pragma unroll
-            for (int j = 0; j < CPW; ++j) {
-                const int nb = cur.ng * 8 + ch * CPW + j;
-                if (nb < NB) {
-                    float* o = out + (size_t)slot * slot_stride + (size_t)nb * 32 + (lane & 31);
+    for (int j = 0; j < CPW; ++j) {
+        const int nb = ng * CG + ch * CPW + j;
+        if (nb < NB) {
+            float* o = out + (size_t)seg * slot_stride + (size_t)nb * 32 + (lane & 31);
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int m = r * 32 + 8 * (v >> 2) + 4 * gq + (v & 3);
-                        __hip_atomic_store(&o[(size_t)m * ldo_here], acc[j][v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    }
-                }
+            for (int v = 0; v < 16; ++v) {
+                const int m = r * 32 + 8 * (v >> 2) + 4 * gq + (v & 3);
+                __hip_atomic_store(&o[(size_t)m * ldo_here], acc[j][v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
-#pragma unroll
-            for (int j = 0; j < CPW; ++j)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
         }
-        if (nxt.valid == 0) break;
-        cur = nxt;
-        nxt = sk_walk_next<R>(walk, KB);
     }
 }
 
@@ -227,6 +249,36 @@ void launch_reduce_selected(PartView pv, float* dst, const int32_t* sel, int B, 
 #define SK_SMALL_U (16 * SK_MAX_WG * 2)   // (column groups x contraction blocks) up to which half the workgroups are used
 #endif
 
+// Four and eight row blocks (k_gemm_rows): the width of a column group, CG blocks, and the number of segments S the
+// contraction is split into, S a divisor of KB, at most 16. Cost of a candidate in shader cycles, from the kernel's
+// measured pace: a step costs its MFMAs (two waves per SIMD, 2 x CPW MFMAs of 32 cycles each) plus about 300 cycles
+// of hand-over; a workgroup runs KB / S steps (rounded up to the ring), the grid ceil(groups x S / 256) rounds; the S
+// partial tiles are written at the end of the kernel and read by the consumer at about 2500 bytes per cycle each
+// way. Narrow groups buy workgroups and few slots for the matrices with few columns (O and down projection at the
+// 7B shape, 256 rows: 4 blocks x 8 segments instead of 8 x 16: 22 us against 26, 41 against 43, and the consumer
+// reads half as much); six-block groups fill the chip where eight-block ones leave a quarter of it idle (QKV: 64
+// groups x 4 = 256 workgroups, 45 us against 55 with 48 x 4; gate/up 115 x 2 = 230 against 86 x 2 = 172: 76 against 89).
+static void gemm_plan_rows(GemmPlan* p) {
+    const int MT = p->MB;
+    static const int widths8[] = {8, 6, 4}, widths4[] = {8, 4};
+    const int* widths = MT == 8 ? widths8 : widths4;
+    const int n_widths = MT == 8 ? 3 : 2;
+    double best = 0;
+    for (int wi = 0; wi < n_widths; ++wi) {
+        const int CG = widths[wi], groups = (p->NB + CG - 1) / CG;
+        for (int S = 1; S <= 16 && S <= p->KB; ++S) {
+            if (p->KB % S) continue;
+            const int G = groups * S, rounds = (G + SK_MAX_WG - 1) / SK_MAX_WG;
+            const int steps = (p->KB / S + 3) / 4 * 4;
+            const double step_cycles = 16.0 * CG * MT + 300.0;
+            const double tile_bytes = (double)S * MT * 32 * p->NB * 32 * 4;
+            const double cost = rounds * steps * step_cycles + 2.0 * tile_bytes / 2500.0;
+            if (p->CG == 0 || cost < best) { best = cost; p->CG = CG; p->S = S; }
+        }
+    }
+    if (p->S > p->slots_max) p->slots_max = p->S;
+}
+
 void gemm_plan_make(GemmPlan* p, int MB, int KB, int NB, int32_t* cnt_host, int32_t* slot0_host) {
     p->MB = MB; p->KB = KB; p->NB = NB;
     p->cnt_dev = nullptr;
@@ -271,6 +323,10 @@ void gemm_plan_make(GemmPlan* p, int MB, int KB, int NB, int32_t* cnt_host, int3
     p->slots = slots;
     p->uniform = 1;                                   // every column group has the same number of contributors?
     for (int ng = 0; ng < p->NG; ++ng) p->uniform &= (cnt_host[ng] == slots);
+    p->CG = 0;
+    p->S = 0;
+    p->slots_max = slots;
+    if (MB >= 4) gemm_plan_rows(p);
 }
 
 PartView launch_gemm(const GemmPlan& p, const void* Xp, const void* Wp, const void* zfrag, float* out, hipStream_t s,
@@ -290,11 +346,32 @@ PartView launch_gemm(const GemmPlan& p, const void* Xp, const void* Wp, const vo
         else                                                                                               \
             hipLaunchKernelGGL(KERNEL_, dim3(p.G), dim3(THREADS_), 0, s, SK_ARGS, ##__VA_ARGS__);          \
     } while (0)
-    switch (p.MB) {                                    // the plan's row blocks: 1, 2, 4 or 8, one pass each
+    if (p.CG) {                                        // four / eight row blocks: the aligned split of k_gemm_rows
+        const int G = (p.NB + p.CG - 1) / p.CG * p.S;
+        pv.cnt = nullptr;
+        pv.nmax = p.S;
+#define ROWS_LAUNCH(MT_, CG_)                                                                              \
+    do {                                                                                                   \
+        if (ev0 || ev1)                                                                                    \
+            hipExtLaunchKernelGGL((k_gemm_rows<MT_, CG_>), dim3(G), dim3(512), 0, s, ev0, ev1, 0, (const bf16x8*)Xp, \
+                                  (const bf16x8*)Wp, (const bf16x8*)zfrag, out, p.KB, p.NB, pv.ld, pv.slot_stride, p.S); \
+        else                                                                                               \
+            hipLaunchKernelGGL((k_gemm_rows<MT_, CG_>), dim3(G), dim3(512), 0, s, (const bf16x8*)Xp, (const bf16x8*)Wp, \
+                               (const bf16x8*)zfrag, out, p.KB, p.NB, pv.ld, pv.slot_stride, p.S);         \
+    } while (0)
+        const int key = p.MB * 10 + p.CG;
+        if (key == 88) ROWS_LAUNCH(8, 8);
+        else if (key == 86) ROWS_LAUNCH(8, 6);
+        else if (key == 84) ROWS_LAUNCH(8, 4);
+        else if (key == 48) ROWS_LAUNCH(4, 8);
+        else if (key == 44) ROWS_LAUNCH(4, 4);
+        else pv.nmax = 0;                              // gemm_plan_rows makes no other: nothing launched, nothing to read
+#undef ROWS_LAUNCH
+        return pv;
+    }
+    switch (p.MB) {                                    // one or two row blocks
     case 1: SK_LAUNCH(k_gemm_sk<1>, 512); break;
     case 2: SK_LAUNCH(k_gemm_sk<2>, 512); break;
-    case 4: SK_LAUNCH(k_gemm_sk_rows<4>, 512); break;
-    case 8: SK_LAUNCH(k_gemm_sk_rows<8>, 512); break;
     default:                                           // plans are only ever made for 1, 2, 4 or 8 row blocks
         pv.nmax = 0;                                   // nothing launched, nothing for a consumer to read
         pv.cnt = nullptr;

@@ -106,6 +106,11 @@ struct GemmPlan {
     int upw, rem;            // units per workgroup; the first `rem` workgroups take one more
     int slots;               // slots the output buffer must hold
     int uniform;             // 1: every column group has exactly `slots` contributors
+    int CG, S;               // four / eight row blocks as launched by launch_gemm: column groups of CG blocks, each
+                             // split into S segments of the contraction (workgroup = group * S + segment, slot =
+                             // segment); 0 for one and two row blocks. The fields above then describe the balanced
+                             // split that the persistent layer kernel walks at eight row blocks.
+    int slots_max;           // slots the output buffer must hold for either
     int32_t* cnt_dev;        // [NG] contributors per column group (device)
     int32_t* slot0_dev;      // [G] slot of every workgroup's first segment (device)
 };
