@@ -136,16 +136,20 @@ void launch_rope_kv(PartView pv, RowTable rt, void* q_packed, void* kt, void* vt
 }
 
 // ------------------------------------------------------------------------------------------
-// SwiGLU from the gate/up partial sums (body: row_ops.h). grid (chunks of 8-column groups, row)
-__global__ void k_swiglu_pack(PartView pv, int F, int Fpad, bf16x8* __restrict__ act, int MB) {
-    const int grp = blockIdx.x * blockDim.x + threadIdx.x, m = blockIdx.y;
-    if (grp >= F / 8) return;
+// SwiGLU from the gate/up partial sums (body: row_ops.h). grid (chunks of four contraction blocks, row blocks):
+// a wave takes the 32 rows of a row block and the 16 columns of one contraction block of the packed result, lane =
+// row + 32 * (column group), so that its two stores are the two whole 1 KiB fragments (hi, lo) and the four waves of
+// a workgroup read 256 contiguous bytes of every row and slot.
+__global__ void k_swiglu_pack(PartView pv, int F, int Fpad, bf16x8* __restrict__ act, int MB, int M) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int m = blockIdx.y * 32 + (lane & 31), grp = (blockIdx.x * 4 + wave) * 2 + (lane >> 5);
+    if (grp >= F / 8 || m >= M) return;
     swiglu_item<false>(pv, F, Fpad, act, MB, m, grp);
 }
 
 void launch_swiglu_pack(PartView pv, int F, int Fpad, void* act_packed, int M, int MB, hipStream_t s) {
-    hipLaunchKernelGGL(k_swiglu_pack, dim3((F / 8 + 255) / 256, M), dim3(256), 0, s, pv, F, Fpad, (bf16x8*)act_packed,
-                       MB);
+    hipLaunchKernelGGL(k_swiglu_pack, dim3((F / 16 + 3) / 4, (M + 31) / 32), dim3(256), 0, s, pv, F, Fpad,
+                       (bf16x8*)act_packed, MB, M);
 }
 
 // ------------------------------------------------------------------------------------------
