@@ -842,7 +842,12 @@ static AttnGeom attn_geometry(const sd_model* m, int B, int Tp, int n_hi, bool s
     if (nblk == 0) { g.ncparts = 0; g.per = 1; g.tree_sep = 1; g.nparts = 1; return g; }
     const int by_work = ceil_div(nblk, 4);                 // at least one block per wave
     const int ntp = (split_ok && TB == 2 && P >= 3) ? 2 : 1;
-    if (P >= 2 && nblk <= 8 * (P - ntp)) {                 // short: at most two blocks per wave, tree beside
+    // The tree keeps parts of its own while the cache parts are short: up to eight blocks per cache part, or, when a
+    // single sequence has the chip (eight parts per head, of which the tree's one or two idle while the others stream),
+    // up to forty: there the launch without the rotary stage before it wins up to ~8 k rows (64-node tree, step at
+    // 1.5 / 3 / 6 k rows: 5.18 -> 5.06, 5.25 -> 5.20, 5.55 -> 5.47 ms; at 16 k rows 6.40 -> 6.45, so not there).
+    const int short_mult = P >= 8 ? 40 : 8;
+    if (P >= 2 && nblk <= short_mult * (P - ntp)) {        // short: the tree beside the cache parts
         // (two blocks per wave before another part is opened: every part repeats the queries' set-up and adds a term
         // to the merge; 7B shape, 64-node tree over 512-1800 rows: attention launch 18.4 -> 16.8 us, step -1 %)
         const int by_two = ceil_div(nblk, 8);
