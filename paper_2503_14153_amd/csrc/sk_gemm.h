@@ -63,6 +63,7 @@ struct SkGemm {
     const bf16x8 *Xp, *Wp, *zl;
     float* out;
     int KB, NB, ldo, tid, wave, lane, slot0;
+    const int32_t* slot0_at;
     size_t slot_stride, wstep;
     SkWalk walk;
     SkIter cur, nxt, nx2;
@@ -82,9 +83,9 @@ struct SkGemm {
         zl = zfrag + lane;
         cur = nxt = nx2 = SkIter{0, 0, 0, 0};
         slot0 = 0;
+        slot0_at = slot0_tab + (g < G ? g : 0);        // read once the ring has been issued (issue_ring)
         if (g < G) {
             walk = sk_walk_init(g, upw, rem, KB, kb_magic);
-            slot0 = slot0_tab[g];                      // slot of this workgroup's first segment (later ones: 0)
             cur = sk_walk_next<R>(walk, KB);
             nxt = sk_walk_next<R>(walk, KB);
             nx2 = sk_walk_next<R>(walk, KB);
@@ -112,6 +113,12 @@ struct SkGemm {
         const bf16x8* wc = wptr(cur);
 #pragma unroll
         for (int i = 0; i < R; ++i) w[i] = __builtin_nontemporal_load((i < cur.valid) ? wc + (size_t)i * wstep : zl);
+        // The slot of this workgroup's first segment (later ones: 0), wanted only when that segment ends. Read here,
+        // as a vector load behind the ring, so that nothing waits for it: read in setup it was a scalar load that the
+        // next wait for a kernel argument also waited for, a memory round trip before the first weight was requested.
+        int zero = 0;
+        asm volatile("" : "+v"(zero));              // (a vector register: the load is a vector load)
+        slot0 = slot0_at[zero];
     }
     __device__ __forceinline__ void issue_x() {
         if (!has_work()) return;
