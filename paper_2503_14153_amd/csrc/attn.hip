@@ -91,6 +91,15 @@ __global__ __launch_bounds__(256) void k_tree_attn(const bf16x8* __restrict__ Qp
         h = blockIdx.y / TG;
         tg = blockIdx.y % TG;
         b = blockIdx.z;
+    } else if (xcd_stride < 0) {
+        // One query group, a multiple of eight heads: grid (head, part, sequence). Workgroups are dealt to the eight
+        // XCDs round-robin, so the parts of a head share an L2: what every part of a head fetches alike (the queries;
+        // under FR the projection's partial sums they are built from, the same bytes for every part) comes from
+        // memory once per head instead of once per part.
+        h = blockIdx.x;
+        tg = 0;
+        part = blockIdx.y;
+        b = blockIdx.z;
     } else {
         // Several query groups: one-dimensional grid in which the query groups of one (sequence, head, part)
         // lie xcd_stride workgroups apart. Workgroups are dealt to the eight XCDs round-robin and the stride
@@ -439,6 +448,9 @@ void launch_tree_attn(const void* q_packed, const void* kc, const void* vc, cons
     if (TG > 1) {                                      // query groups of one head on one XCD (see the kernel)
         xcd_stride = (nparts * nh * B + 7) / 8 * 8;
         grid = dim3(xcd_stride * TG, 1, 1);
+    } else if (nh % 8 == 0 && nparts > 1) {            // parts of one head on one XCD
+        xcd_stride = -1;
+        grid = dim3(nh, nparts, B);
     }
 #define ATT_ARGS (const bf16x8*)q_packed, (const bf16x8*)kc, (const bf16x8*)vc, (const bf16x8*)kt, (const bf16x8*)vt, \
                  kv_len, anc, opart, mlpart, nh, Tp, cap_blocks, ncparts, per, tree_sep, scale_log2, xcd_stride, B, pv_arg, rt_arg
