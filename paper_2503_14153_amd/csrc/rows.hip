@@ -118,21 +118,24 @@ void launch_norm_pack(float* x, PartView pv, const void* gain, float eps, void* 
 
 // ------------------------------------------------------------------------------------------
 // Rotary embedding and the tree K/V write from the QKV partial sums (body: row_ops.h).
-// grid (chunks of (h, a) x which, t, b): no index needs a division.
+// grid (head x which, row block, sequence); a workgroup is one head's 32 rows of q, k or v: wave w takes the pieces
+// a = 2w and 2w + 1, lane = row + 32 * (a & 1), so that what a wave stores of q and k are whole 1 KiB fragments (the
+// query and key layouts put row r, dim group g of contraction step w at lane r + 32 g) and what it reads of a row and
+// slot are 64 contiguous bytes twice. (One thread per (h, a) of ONE row wrote the same bytes as 16-byte pieces 0.5-2
+// KiB apart; the values' layout is transposed, their 2-byte stores stay scattered either way.)
 __global__ void k_rope_kv(PartView pv, RowTable rt, bf16x8* __restrict__ qp, uint16_t* __restrict__ kt, uint16_t* __restrict__ vt, int Tp,
-                          int nh, int hd, int na_shift) {
-    const int which = blockIdx.x % 3;                   // a constant divisor: a multiplication
-    const int ha = (blockIdx.x / 3) * blockDim.x + threadIdx.x;
-    const int a = ha & ((1 << na_shift) - 1), h = ha >> na_shift;      // hd / 16 = 1 << na_shift
-    if (h >= nh) return;
-    rope_kv_item<false>(pv, rt, qp, kt, vt, Tp, nh, hd, which, h, a, blockIdx.y, blockIdx.z);
+                          int nh, int hd, int na) {
+    const int which = blockIdx.x % 3, h = blockIdx.x / 3;     // a constant divisor: a multiplication
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int t = blockIdx.y * 32 + (lane & 31);
+    for (int a = 2 * wave + (lane >> 5); a < na; a += 8)      // hd / 16 pieces: 8 (one round) or 4 (waves 0 and 1)
+        rope_kv_item<false>(pv, rt, qp, kt, vt, Tp, nh, hd, which, h, a, t, blockIdx.z);
 }
 
 void launch_rope_kv(PartView pv, RowTable rt, void* q_packed, void* kt, void* vt, int B, int Tp, int nh, int hd,
                     hipStream_t s) {
-    const int na_shift = hd == 128 ? 3 : 2;            // head_dim is 128 or 64
-    hipLaunchKernelGGL(k_rope_kv, dim3(((nh << na_shift) + 255) / 256 * 3, Tp, B), dim3(256), 0, s, pv, rt,
-                       (bf16x8*)q_packed, (uint16_t*)kt, (uint16_t*)vt, Tp, nh, hd, na_shift);
+    hipLaunchKernelGGL(k_rope_kv, dim3(nh * 3, Tp / 32, B), dim3(256), 0, s, pv, rt, (bf16x8*)q_packed, (uint16_t*)kt,
+                       (uint16_t*)vt, Tp, nh, hd, hd / 16);
 }
 
 // ------------------------------------------------------------------------------------------
