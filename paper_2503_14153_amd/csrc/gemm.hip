@@ -93,7 +93,7 @@ __global__ __launch_bounds__(512, MT == 8 ? 1 : 2) void k_gemm_sk(const bf16x8* 
 // At these row counts the matrix cores, not the weight stream, set the pace, and what a step costs beyond its
 // MFMAs is the hand-over through LDS. So the split is always the aligned one (workgroup g = column group g / S,
 // segment g % S of the contraction: one partial tile per workgroup, slot = segment), the width of a column group is
-// chosen with the split (gemm_plan_make: narrower groups mean more workgroups and fewer slots), and a step is
+// chosen with the split (gemm_plan_rows: narrower groups mean more workgroups and fewer slots), and a step is
 // software-pipelined around its one barrier:
 //   write the NEXT step's fragment to the other LDS buffer (its last readers passed the previous barrier);
 //   MFMAs of the first half of the column blocks (fragments already in registers), the ring's weight load among them;
