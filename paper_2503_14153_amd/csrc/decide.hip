@@ -433,7 +433,7 @@ void launch_verify(const VerifyArgs& a, int B, hipStream_t s) {
 // already (depth = chain index), so this is a pure copy.
 // grid: x = head, y = layer * B + b, z = chunk of the rows; hd threads.
 //
-// Keys: a row's 16-byte pieces move as they are (chunk z: rows 8z .. 8z+7, thread = (row, piece)). Values: a 16-byte
+// Keys: a row's 16-byte pieces move as they are (chunk z: rows 8z .. 8z+7, thread = (piece, row)). Values: a 16-byte
 // piece of the value layout holds one dim of EIGHT rows (the four rows 4q .. 4q+3 of a quad in one half, the quad two
 // further on in the other), so a row cannot move as a piece; written one 2-byte element at a time, every element is
 // a partial write of a line of its own. Instead every 8-byte half piece (one quad of destination rows, thread = dim)
@@ -473,10 +473,12 @@ __global__ void k_kv_commit(const uint16_t* __restrict__ kt, const uint16_t* __r
         }
         *(u16x4*)(vc + piece) = v;
     }
-    // keys: this chunk's rows, thread = (row, 16-byte piece)
+    // keys: this chunk's rows, thread = (16-byte piece, row), rows fastest: the same piece of neighbouring rows is 16
+    // bytes further on in the key layout, so eight threads write 128 contiguous bytes (and read them, where the kept
+    // nodes' slots are consecutive)
     const int pieces = hd / 8;                                           // 8 or 16
     for (int idx = tid; idx < KVC_ROWS * pieces; idx += hd) {
-        const int j = z * KVC_ROWS + idx / pieces, e = idx % pieces;
+        const int j = z * KVC_ROWS + idx % KVC_ROWS, e = idx / KVC_ROWS;
         if (j < a) {
             const int src = min(max(slots[j], 0), src_max);
             const uint4* s4 = (const uint4*)(kt + toff + kblk_index(src, e * 8, hd));
