@@ -876,12 +876,15 @@ static PartView run_layers(sd_model* m, sd_kv* kv, int B, int Tp, int n_hi, hipS
         uint16_t* kt = (uint16_t*)m->kt + l * t_stride;
         uint16_t* vt = (uint16_t*)m->vt + l * t_stride;
         // With one query group per head (trees of up to 64 nodes, plain decoding, short prompt chunks) the attention
-        // launch builds the queries and the tree's keys / values from the QKV partial sums itself: one launch
-        // less per layer (7B shape: batch of eight 32-node trees 11.17 -> 10.97 ms per step, plain decoding +3 %, the
-        // 64-node step 4.95 -> 4.89 ms once each of its two tree blocks has a workgroup of its own to build it). With several query groups every group would repeat that work, and at long
-        // contexts, where the tree blocks go to the last cache part, that part would become the straggler (16 k rows:
-        // attention 55 -> 64 us): there the stage stays a launch of its own.
-        const bool fr = Tp <= 64 && ag.tree_sep;
+        // launch builds the queries and the tree's keys / values from the QKV partial sums itself: one launch less per
+        // layer (7B shape: plain decoding +3 %, the 64-node step 4.95 -> 4.89 ms once each of its two tree blocks has a
+        // workgroup of its own to build it). With several query groups every group would repeat that work, and at long
+        // contexts, where the tree blocks go to the last of several cache parts, that part would become the straggler
+        // (16 k rows: attention 55 -> 64 us): there the stage stays a launch of its own. Where every (sequence, head) has
+        // ONE workgroup (a batch that fills the chip) all workgroups carry the same extra work, none is a straggler, and
+        // the launch saved is worth more than it costs (batch of eight 32-node trees: attention 65.4 -> 72.8 us, the
+        // 11.8 us launch gone, step -0.8 %).
+        const bool fr = Tp <= 64 && (ag.tree_sep || ag.ncparts == 1);
         if (!fr) launch_rope_kv(pq, m->rt, m->q, kt, vt, B, Tp, nh, hd, s);
         // algorithmic bytes: one read of K and V of the committed rows (upper bound n_hi) + tree rows
         const int pa = prof_claim(m, PROF_ATTN, (double)B * (n_hi + Tp) * 2.0 * d * 2.0);
