@@ -10,6 +10,8 @@ from __future__ import annotations
 
 from dataclasses import dataclass, field
 
+import contextlib
+
 import numpy as np
 import torch
 
@@ -67,6 +69,27 @@ def bf16_ulp(a: np.ndarray) -> np.ndarray:
     return 2.0 ** (np.floor(np.log2(m)) - 7)
 
 
+# The relative error with which an evaluation in float32 reaches a K/V entry before it is rounded to the storage
+# format: the HIP path's GEMM operands are two-term bfloat16 expansions (16 mantissa bits, error 2^-17 per activation,
+# independent in sign), which over a random-sign contraction leave 2^-17 / sqrt(3) of the result.
+KV_PRE_ROUNDING_EPS = 2.0 ** -17 / np.sqrt(3.0)
+
+
+@contextlib.contextmanager
+def perturbed_kv_rounding(eps: float, seed: int = 12345):
+    """Inside the block the oracle multiplies every K/V row by (1 + eps * N(0, 1)) BEFORE rounding it to the cache's
+    storage format; everything else stays float64. Two such evaluations differ exactly where the rounding decisions
+    of a bfloat16 cache differ, which is what separates ANY float32 implementation from the oracle once the depth is
+    large: the difference it leaves in the logits is the oracle's own sensitivity, the floor under every tolerance."""
+    orig = orc.kv_storage
+    rng = np.random.default_rng(seed)
+    orc.kv_storage = lambda a, dtype: orig(np.asarray(a) * (1.0 + eps * rng.standard_normal(np.shape(a))), dtype)
+    try:
+        yield
+    finally:
+        orc.kv_storage = orig
+
+
 KV_UNROUNDED = LOGIT_MAX_ABS / 2      # bound on the difference of the two sides' K/V entries BEFORE storage rounding
 
 
@@ -121,14 +144,15 @@ def resync_kv(kv: sd.KVCache, st: orc.DecodeState, shape, row0: int):
     kv.set_len([st.kv.n])
 
 
-def check_step_outputs(out, b: int, rec, tree_np, stop_np, fallback: str, shape, rep: Report):
+def check_step_outputs(out, b: int, rec, tree_np, stop_np, fallback: str, shape, rep: Report,
+                       logit_max_abs: float = LOGIT_MAX_ABS):
     """Compare sequence b of one GPU step with the oracle's record of the same step.
 
     Logits within tolerance; arg-max equal except at oracle near-ties; accepted length, tokens
     and source slots bit-exact against the oracle's rule applied to the arg-max the GPU saw.
     Returns (accepted length, accepted chain) as the GPU must have computed them."""
     parent, depth, rank = tree_np
-    check_logits(out.logits[b].cpu().numpy().astype(np.float64), rec.logits, rep)
+    check_logits(out.logits[b].cpu().numpy().astype(np.float64), rec.logits, rep, max_abs=logit_max_abs)
     am = out.argmax[b].cpu().numpy()
     flips = np.nonzero(am != rec.am)[0]
     for j in flips:

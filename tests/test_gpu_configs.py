@@ -84,7 +84,8 @@ def _plant_along_a_path(cand, truth, tree_np, depth_want, pick):
 
 
 def _run_batch_steps(sd, shape, B, T, lens, cap, n_steps, tree_np=None, plant=True, fallback="keep_all",
-                     weights_device="cpu", schedule="after_accept", fused=False):
+                     weights_device="cpu", schedule="after_accept", fused=False, weights=None,
+                     logit_max_abs=lockstep.LOGIT_MAX_ABS):
     """Lock-step speculative steps of a batch against one oracle state per sequence.
 
     Drafts: the oracle's own greedy continuation of every sequence is planted along one root path of the tree,
@@ -93,7 +94,7 @@ def _run_batch_steps(sd, shape, B, T, lens, cap, n_steps, tree_np=None, plant=Tr
     edited so that one chosen sequence is cut in the middle of its accepted run (its second token is made a
     stop token, the later ones are not). A sequence whose device path differs from the oracle's at a counted
     near-tie is resynchronised from the oracle."""
-    weights = wl.make_weights(shape, device=weights_device)
+    weights = weights if weights is not None else wl.make_weights(shape, device=weights_device)
     w64 = lockstep.weights_to_f64(weights)
     Tp = (T + 31) // 32 * 32
     H = shape.n_medusa
@@ -136,7 +137,7 @@ def _run_batch_steps(sd, shape, B, T, lens, cap, n_steps, tree_np=None, plant=Tr
         root, gcand = kv.get_draft()
         resync = False
         for b, rec in enumerate(recs):
-            n_acc, chain = lockstep.check_step_outputs(out, b, rec, tree_np, stop, fallback, shape, rep)
+            n_acc, chain = lockstep.check_step_outputs(out, b, rec, tree_np, stop, fallback, shape, rep, logit_max_abs)
             assert lens_now[b] == n_old[b] + n_acc
             rep.accepted.append(n_acc)
             rep.mid_cuts += int(2 <= n_acc < len(chain))
@@ -145,7 +146,7 @@ def _run_batch_steps(sd, shape, B, T, lens, cap, n_steps, tree_np=None, plant=Tr
             if n_acc == rec.n_accept and chain[:n_acc] == list(rec.src_slots):
                 lockstep.compare_kv_rows(kv, states[b], shape, n_old[b], n_old[b] + n_acc, rep, seq=b)
                 hl = out.head_logits[b].cpu().numpy().astype(np.float64)
-                assert np.abs(hl - rec.head_logits).max() <= 2 * lockstep.LOGIT_MAX_ABS
+                assert np.abs(hl - rec.head_logits).max() <= 2 * logit_max_abs
                 lockstep.check_cand(gcand[b].cpu().numpy(), rec.next_cand, rec.head_logits, rep)
             else:           # a counted near-tie flip (check_step_outputs has verified the margin): adopt the oracle's rows
                 lockstep.resync_kv_rows(kv, states[b], shape, n_old[b], seq=b)
@@ -221,6 +222,50 @@ def test_7b_full_depth_one_step(sd):
     assert shape.n_layers == 32
     rep = _run_batch_steps(sd, shape, 1, 64, [512], 2048, n_steps=1, weights_device="cuda", plant=False)
     print(f"\n[7b L32] {rep}")
+
+
+def _oracle_states(shape, lens, cap, roots, cand):
+    """One oracle state per sequence over the synthetic rows of _fill_synthetic, made one at a time."""
+    for b, n in enumerate(lens):
+        st = orc.DecodeState(orc.KVCache.empty(shape, cap))
+        for layer in range(shape.n_layers):
+            dims = (n, shape.n_heads, shape.head_dim)
+            st.kv.k[layer, :n] = wl.synthetic_kv_rows(wl.SEEDS["kvfill"], f"k{b}.{layer}", dims, shape.dtype).double().numpy()
+            st.kv.v[layer, :n] = wl.synthetic_kv_rows(wl.SEEDS["kvfill"], f"v{b}.{layer}", dims, shape.dtype).double().numpy()
+        st.kv.n = n
+        st.root_tok, st.cand = int(roots[b]), cand[b]
+        yield st
+
+
+@pytest.mark.timeout(900)
+def test_7b_batch_of_eight_full_depth_one_step(sd):
+    """configs[3] at its full depth: all 32 layers, eight ragged sequences with 32-node trees, i.e. the 256-row
+    GEMM kernels and one attention workgroup per (sequence, head) at the depth the benchmark runs them. One step on
+    the model's own drafts; the committed lengths are kept short (the oracle's attention is a Python loop over heads).
+
+    At this depth and row count the 2e-2 bound on single logits is below what the storage format allows: the oracle
+    itself, all float64, moves by more once its K/V rows carry the relative error of a float32 evaluation BEFORE
+    they are rounded to bfloat16 (a quarter of the last layers' K/V entries then round to the other neighbour). The
+    test measures that sensitivity on the same inputs and holds the device to it, and to the 1e-2 relative bound."""
+    shape = dataclasses.replace(wl.preset("7b-batch8").model, dtype="bf16")
+    assert shape.n_layers == 32
+    rng = np.random.Generator(np.random.Philox(key=wl.SEEDS["kvlen"] + 1))
+    lens = [int(x) for x in rng.integers(200, 901, size=8)]
+    weights = wl.make_weights(shape, device="cuda")
+    w64 = lockstep.weights_to_f64(weights)
+    tree_np = wl.default_tree(32, shape.n_medusa, shape.topk)
+    stop = wl.stop_set(shape.vocab, 0.2)
+    roots, cand = _random_draft(shape, 8, 99)
+    logits = []
+    for eps in (0.0, lockstep.KV_PRE_ROUNDING_EPS):
+        with lockstep.perturbed_kv_rounding(eps):
+            logits.append([orc.spec_step(w64, shape, st, tree_np, stop, "keep_all", cand_override=cand[b]).logits
+                           for b, st in enumerate(_oracle_states(shape, lens, 1024, roots, cand))])
+    sens = max(float(np.abs(a - b).max()) for a, b in zip(*logits))
+    rep = _run_batch_steps(sd, shape, 8, 32, lens, 1024, n_steps=1, plant=False, weights=weights,
+                           logit_max_abs=max(lockstep.LOGIT_MAX_ABS, sens))
+    print(f"\n[7b-batch8 L32] lens={lens} oracle's own sensitivity to K/V rounding {sens:.4f} {rep}")
+    assert rep.max_rel <= lockstep.LOGIT_REL / 5
 
 
 def test_ragged_batch_of_eight(sd):
