@@ -84,7 +84,7 @@ def _plant_along_a_path(cand, truth, tree_np, depth_want, pick):
 
 
 def _run_batch_steps(sd, shape, B, T, lens, cap, n_steps, tree_np=None, plant=True, fallback="keep_all",
-                     weights_device="cpu", schedule="after_accept", fused=False, weights=None,
+                     weights_device="cpu", schedule="after_accept", fused=False, weights=None, w64=None,
                      logit_max_abs=lockstep.LOGIT_MAX_ABS):
     """Lock-step speculative steps of a batch against one oracle state per sequence.
 
@@ -95,7 +95,7 @@ def _run_batch_steps(sd, shape, B, T, lens, cap, n_steps, tree_np=None, plant=Tr
     stop token, the later ones are not). A sequence whose device path differs from the oracle's at a counted
     near-tie is resynchronised from the oracle."""
     weights = weights if weights is not None else wl.make_weights(shape, device=weights_device)
-    w64 = lockstep.weights_to_f64(weights)
+    w64 = w64 if w64 is not None else lockstep.weights_to_f64(weights)
     Tp = (T + 31) // 32 * 32
     H = shape.n_medusa
     model = sd.Model(shape, {k: v.cuda() for k, v in weights.items()}, B * Tp, fallback)
@@ -237,6 +237,30 @@ def _oracle_states(shape, lens, cap, roots, cand):
         yield st
 
 
+def _full_depth_step_within_the_oracles_own_sensitivity(sd, shape, T, lens, cap):
+    """One speculative step at full depth on the model's own drafts, with the bound on single logits taken from the
+    oracle itself: its K/V rows are perturbed by the relative error of a float32 evaluation BEFORE they are rounded
+    to the storage format, everything else stays float64, and the largest move of a logit is what the rounding
+    decisions alone do to ANY implementation that is not the oracle bit for bit. The device gets that on top of the
+    bound its arithmetic is held to where such flips are rare (two layers, or 64 rows). Returns (report, sensitivity)."""
+    B = len(lens)
+    weights = wl.make_weights(shape, device="cuda")
+    w64 = lockstep.weights_to_f64(weights)
+    tree_np = wl.default_tree(T, shape.n_medusa, shape.topk)
+    stop = wl.stop_set(shape.vocab, 0.2)
+    roots, cand = _random_draft(shape, B, 99)
+    logits = []
+    for eps in (0.0, lockstep.KV_PRE_ROUNDING_EPS):
+        with lockstep.perturbed_kv_rounding(eps):
+            logits.append([orc.spec_step(w64, shape, st, tree_np, stop, "keep_all", cand_override=cand[b]).logits
+                           for b, st in enumerate(_oracle_states(shape, lens, cap, roots, cand))])
+    sens = max(float(np.abs(a - b).max()) for a, b in zip(*logits))
+    rep = _run_batch_steps(sd, shape, B, T, lens, cap, n_steps=1, plant=False, weights=weights, w64=w64,
+                           logit_max_abs=lockstep.LOGIT_MAX_ABS + sens)
+    assert rep.max_rel <= lockstep.LOGIT_REL / 5
+    return rep, sens
+
+
 @pytest.mark.timeout(900)
 def test_7b_batch_of_eight_full_depth_one_step(sd):
     """configs[3] at its full depth: all 32 layers, eight ragged sequences with 32-node trees, i.e. the 256-row
@@ -246,26 +270,24 @@ def test_7b_batch_of_eight_full_depth_one_step(sd):
     At this depth and row count the 2e-2 bound on single logits is below what the storage format allows: the oracle
     itself, all float64, moves by more once its K/V rows carry the relative error of a float32 evaluation BEFORE
     they are rounded to bfloat16 (a quarter of the last layers' K/V entries then round to the other neighbour). The
-    test measures that sensitivity on the same inputs and holds the device to it, and to the 1e-2 relative bound."""
+    test measures that sensitivity on the same inputs, allows it on top of the 2e-2, and holds the relative error to
+    a fifth of its bound."""
     shape = dataclasses.replace(wl.preset("7b-batch8").model, dtype="bf16")
     assert shape.n_layers == 32
     rng = np.random.Generator(np.random.Philox(key=wl.SEEDS["kvlen"] + 1))
     lens = [int(x) for x in rng.integers(200, 901, size=8)]
-    weights = wl.make_weights(shape, device="cuda")
-    w64 = lockstep.weights_to_f64(weights)
-    tree_np = wl.default_tree(32, shape.n_medusa, shape.topk)
-    stop = wl.stop_set(shape.vocab, 0.2)
-    roots, cand = _random_draft(shape, 8, 99)
-    logits = []
-    for eps in (0.0, lockstep.KV_PRE_ROUNDING_EPS):
-        with lockstep.perturbed_kv_rounding(eps):
-            logits.append([orc.spec_step(w64, shape, st, tree_np, stop, "keep_all", cand_override=cand[b]).logits
-                           for b, st in enumerate(_oracle_states(shape, lens, 1024, roots, cand))])
-    sens = max(float(np.abs(a - b).max()) for a, b in zip(*logits))
-    rep = _run_batch_steps(sd, shape, 8, 32, lens, 1024, n_steps=1, plant=False, weights=weights,
-                           logit_max_abs=max(lockstep.LOGIT_MAX_ABS, sens))
+    rep, sens = _full_depth_step_within_the_oracles_own_sensitivity(sd, shape, 32, lens, 1024)
     print(f"\n[7b-batch8 L32] lens={lens} oracle's own sensitivity to K/V rounding {sens:.4f} {rep}")
-    assert rep.max_rel <= lockstep.LOGIT_REL / 5
+
+
+@pytest.mark.timeout(900)
+def test_13b_full_depth_one_step(sd):
+    """configs[4] at its full depth: all 40 layers at d=5120, a 128-node tree (the 128-row GEMM kernels and the
+    attention kernel with two query groups per head) over a short committed context."""
+    shape = dataclasses.replace(wl.preset("13b").model, dtype="bf16")
+    assert shape.n_layers == 40
+    rep, sens = _full_depth_step_within_the_oracles_own_sensitivity(sd, shape, 128, [700], 1024)
+    print(f"\n[13b L40] oracle's own sensitivity to K/V rounding {sens:.4f} {rep}")
 
 
 def test_ragged_batch_of_eight(sd):
