@@ -431,59 +431,104 @@ void launch_verify(const VerifyArgs& a, int B, hipStream_t s) {
 // Commit the kept nodes' K/V rows: tree-scratch row src_slots[j] -> cache row n_old + j, for
 // every layer and head. A kept node at chain index j was rotated for position n_old + j
 // already (depth = chain index), so this is a pure copy.
-// grid: x = head, y = layer * B + b, z = chunk of the rows; hd threads.
-//
-// Keys: a row's 16-byte pieces move as they are (chunk z: rows 8z .. 8z+7, thread = (piece, row)). Values: a 16-byte
-// piece of the value layout holds one dim of EIGHT rows (the four rows 4q .. 4q+3 of a quad in one half, the quad two
-// further on in the other), so a row cannot move as a piece; written one 2-byte element at a time, every element is
-// a partial write of a line of its own. Instead every 8-byte half piece (one quad of destination rows, thread = dim)
-// that receives at least one row is read, patched and written back whole (its other rows are committed rows, which
-// must survive, or rows past the new length, which nobody reads): chunk z takes the quads 2z and 2z+1 after the
-// first one. Only the workgroups of this (layer, sequence, head) touch its blocks, each its own quads and rows.
-#define KVC_QUADS 2
-#define KVC_ROWS 8
-__global__ void k_kv_commit(const uint16_t* __restrict__ kt, const uint16_t* __restrict__ vt, uint16_t* __restrict__ kc,
-                            uint16_t* __restrict__ vc, const int32_t* __restrict__ src_slots,
-                            const int32_t* __restrict__ n_accept, const int32_t* __restrict__ n_old, int B, int nh,
-                            int hd, int TB, int cap_blocks, int W, size_t layer_stride_t, size_t layer_stride_c) {
-    const int h = blockIdx.x, l = blockIdx.y / B, b = blockIdx.y % B, z = blockIdx.z, tid = threadIdx.x;
-    const int a = min(n_accept[b], W);
+// grid: x = head, y = sequence, z = layer; eight waves that share a list of wave-sized tasks, every task a run of
+// whole 16-byte pieces that lie side by side in the cache:
+//   values: a 16-byte piece of the value layout holds one dim of EIGHT rows (a "group": of a 16-row half of a block,
+//     the four rows of one quad and of the quad two further on), so a row cannot move as a piece, and a piece
+//     written in parts (2-byte elements, or its 8-byte halves from two workgroups) leaves the memory partial lines.
+//     One task = one half x 32 dims: a lane owns one piece, reads it unless all of its eight rows are replaced
+//     (its other rows are committed rows, which must survive, or rows past the new length, which nobody reads), takes
+//     the new rows' elements and writes the piece whole: 1 KiB per wave, in order (writing only the 8-byte half that
+//     has new rows, where one does not, was measured and is slower, short lists included). The new rows' elements
+//     come from a copy in LDS of the scratch groups that hold a kept row, fetched once as whole pieces: picked out
+//     of global memory two bytes at a time they cost a cache lookup per element and lane, eight times the lookups
+//     of everything else here (mirror_groups = 0: no room for that copy, the elements are gathered from global
+//     memory).
+//   keys: a row's 16-byte pieces move as they are; one task = 8 rows x 8 pieces, rows fastest (the same piece of
+//     neighbouring rows is 16 bytes further on, so eight lanes write 128 contiguous bytes).
+// Every piece has one owner, and only this workgroup touches this layer's blocks of its (sequence, head).
+#define KVC_THREADS 512
+static __device__ inline int vgroup_of(int c) { return (c >> 5) * 4 + ((c >> 4) & 1) * 2 + ((c >> 2) & 1); }
+__global__ __launch_bounds__(KVC_THREADS) void k_kv_commit(
+    const uint16_t* __restrict__ kt, const uint16_t* __restrict__ vt, uint16_t* __restrict__ kc,
+    uint16_t* __restrict__ vc, const int32_t* __restrict__ src_slots, const int32_t* __restrict__ n_accept,
+    const int32_t* __restrict__ n_old, int nh, int hd, int TB, int cap_blocks, int W, int mirror_groups,
+    int L, int lpw, size_t layer_stride_t, size_t layer_stride_c) {
+    extern __shared__ __align__(16) uint16_t kvc_mirror[];          // [kept group][hd / 32][32 dims][8 rows]
+    __shared__ int s_slots[SD_MAX_TREE];
+    __shared__ uint32_t s_need;
+    const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const int l0 = blockIdx.z * lpw, l1 = min(l0 + lpw, L);
+    const int wave = tid >> 6, lane = tid & 63;
+    const int a = min(n_accept[b], W);                              // <= SD_MAX_TREE < KVC_THREADS
     if (a <= 0) return;
     const int n = n_old[b];
-    const int32_t* slots = src_slots + (size_t)b * W;
-    const size_t toff = l * layer_stride_t + ((size_t)b * nh + h) * TB * (32 * hd);
-    const size_t coff = l * layer_stride_c + ((size_t)b * nh + h) * cap_blocks * (32 * hd);
-    const int src_max = TB * 32 - 1;
-    // values: this chunk's quads of destination rows, thread = dim
-    const int q_first = (n >> 2) + z * KVC_QUADS, q_last = (n + a - 1) >> 2;
-#pragma unroll
-    for (int qi = 0; qi < KVC_QUADS; ++qi) {
-        const int q = q_first + qi;
-        if (q > q_last) break;
-        const size_t piece = coff + vblk_index(4 * q, tid, hd);         // first of the quad's four slots
-        typedef uint16_t u16x4 __attribute__((ext_vector_type(4)));
-        u16x4 v = *(const u16x4*)(vc + piece);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int j = 4 * q + r - n;
-            if (j >= 0 && j < a) {
-                const int src = min(max(slots[j], 0), src_max);
-                v[r] = vt[toff + vblk_index(src, tid, hd)];
-            }
-        }
-        *(u16x4*)(vc + piece) = v;
+    const int slot = tid < a ? min(max(src_slots[(size_t)b * W + tid], 0), TB * 32 - 1) : 0;
+    if (tid == 0) s_need = 0;
+    __syncthreads();
+    if (tid < a) {
+        s_slots[tid] = slot;
+        if (mirror_groups) atomicOr(&s_need, 1u << vgroup_of(slot));
     }
-    // keys: this chunk's rows, thread = (16-byte piece, row), rows fastest: the same piece of neighbouring rows is 16
-    // bytes further on in the key layout, so eight threads write 128 contiguous bytes (and read them, where the kept
-    // nodes' slots are consecutive)
-    const int pieces = hd / 8;                                           // 8 or 16
-    for (int idx = tid; idx < KVC_ROWS * pieces; idx += hd) {
-        const int j = z * KVC_ROWS + idx % KVC_ROWS, e = idx / KVC_ROWS;
-        if (j < a) {
-            const int src = min(max(slots[j], 0), src_max);
-            const uint4* s4 = (const uint4*)(kt + toff + kblk_index(src, e * 8, hd));
-            uint4* d4 = (uint4*)(kc + coff + kblk_index(n + j, e * 8, hd));
-            *d4 = *s4;
+    __syncthreads();
+    const size_t toff0 = ((size_t)b * nh + h) * TB * (32 * hd);
+    const size_t coff0 = ((size_t)b * nh + h) * cap_blocks * (32 * hd);
+    const int EB = hd / 32, KP = hd / 64;                  // wave tasks per 16-row half (values), per 8 rows (keys)
+    typedef uint16_t u16x8 __attribute__((ext_vector_type(8)));
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const uint32_t need = s_need;
+    const int half0 = n >> 4, nV = (((n + a - 1) >> 4) - half0 + 1) * EB;
+    const int NT = nV + ((a + 7) >> 3) * KP;
+    // The counts, the slots and the set of groups are the same for every layer: a workgroup reads them once and
+    // then goes through its layers (the same number of times for every wave: all of them reach the barriers).
+    for (int l = l0; l < l1; ++l) {
+        const size_t toff = l * layer_stride_t + toff0, coff = l * layer_stride_c + coff0;
+        if (mirror_groups) {                               // (at most min(a, groups of the scratch) <= mirror_groups bits)
+            if (l > l0) __syncthreads();                   // the previous layer's readers are done
+            for (int i = tid; i < TB * 4 * EB * 32; i += KVC_THREADS) {
+                const int grp = i / (EB * 32), eb = (i >> 5) % EB, er = i & 31;
+                if ((need >> grp) & 1u) {
+                    const int c = (grp >> 2) * 32 + ((grp >> 1) & 1) * 16 + (grp & 1) * 4;   // the group's first row
+                    const int at = ((__popc(need & ((1u << grp) - 1u)) * EB + eb) * 32 + er) * 8;
+                    *(u16x8*)(kvc_mirror + at) = *(const u16x8*)(vt + toff + vblk_index(c, eb * 32 + er, hd));
+                }
+            }
+            __syncthreads();
+        }
+        for (int tl = wave; tl < NT; tl += KVC_THREADS / 64) {
+            if (tl < nV) {
+                const int eb = tl % EB, er = lane & 31, e = eb * 32 + er;
+                const int row0 = (half0 + tl / EB) * 16 + (lane >> 5) * 4;   // the piece's rows: row0 + {0..3, 8..11}
+                const int lo = n - row0, hi = n + a - row0;                   // new rows: offsets lo <= r < hi
+                const bool any = (lo < 4 && hi > 0) || (lo < 12 && hi > 8);
+                const bool full = lo <= 0 && hi >= 12;
+                if (!any) continue;
+                uint16_t* piece = vc + coff + vblk_index(row0, e, hd);
+                u16x8 v = {0, 0, 0, 0, 0, 0, 0, 0}, g;
+                if (!full) v = *(const u16x8*)piece;
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {              // (any kept row's element where the piece's row stays)
+                    const int c = s_slots[min(max((q >> 2) * 8 + (q & 3) - lo, 0), a - 1)];
+                    if (mirror_groups) {
+                        const int cs = __popc(need & ((1u << vgroup_of(c)) - 1u));
+                        g[q] = kvc_mirror[((cs * EB + eb) * 32 + er) * 8 + ((c >> 3) & 1) * 4 + (c & 3)];
+                    } else {
+                        g[q] = vt[toff + vblk_index(c, e, hd)];
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    const int r = (q >> 2) * 8 + (q & 3);
+                    if (r >= lo && r < hi) v[q] = g[q];
+                }
+                *(u16x8*)piece = v;
+            } else {
+                const int tk = tl - nV;
+                const int j = (tk / KP) * 8 + (lane & 7), e = ((tk % KP) * 8 + (lane >> 3)) * 8;
+                if (j < a)
+                    *(u32x4*)(kc + coff + kblk_index(n + j, e, hd)) =
+                        *(const u32x4*)(kt + toff + kblk_index(s_slots[j], e, hd));
+            }
         }
     }
 }
@@ -493,11 +538,15 @@ void launch_kv_commit(const void* kt_all, const void* vt_all, void* kc_all, void
                       int cap_blocks, int rows, int W, hipStream_t s) {
     (void)rows;
     size_t lst = (size_t)B * nh * TB * 32 * hd, lsc = (size_t)B * nh * cap_blocks * 32 * hd;
-    const int quads = (W + 3) / 4 + 1;                                   // W rows from any old length touch at most this many
-    const int chunks = (quads + KVC_QUADS - 1) / KVC_QUADS;              // (and chunks * KVC_ROWS >= W)
-    hipLaunchKernelGGL(k_kv_commit, dim3(nh, L * B, chunks), dim3(hd), 0, s, (const uint16_t*)kt_all,
-                       (const uint16_t*)vt_all, (uint16_t*)kc_all, (uint16_t*)vc_all, src_slots, n_accept, n_old, B, nh,
-                       hd, TB, cap_blocks, W, lst, lsc);
+    // LDS copy of the scratch groups (8 rows x hd) with a kept row: at most one per row, at most all of them
+    int groups = W < TB * 4 ? W : TB * 4;
+    size_t mirror = (size_t)groups * 8 * hd * 2;
+    if (mirror > 60 * 1024) { groups = 0; mirror = 0; }  // (eight-block scratch at head_dim 128, 31 rows or more)
+    int lpw = (int)((size_t)B * nh * L / 1024);            // layers per workgroup: one while the launch is small
+    lpw = lpw < 1 ? 1 : lpw > L ? L : lpw;
+    hipLaunchKernelGGL(k_kv_commit, dim3(nh, B, (L + lpw - 1) / lpw), dim3(KVC_THREADS), mirror, s,
+                       (const uint16_t*)kt_all, (const uint16_t*)vt_all, (uint16_t*)kc_all, (uint16_t*)vc_all, src_slots,
+                       n_accept, n_old, nh, hd, TB, cap_blocks, W, groups, L, lpw, lst, lsc);
 }
 
 // ------------------------------------------------------------------------------------------

@@ -27,15 +27,19 @@ def _rows(kv, shape, b, row0, n):
     return [tuple(t.clone() for t in kv.read_rows(layer, b, row0, n)) for layer in range(shape.n_layers)]
 
 
-@pytest.mark.parametrize("name,T", [("tiny", 16), ("7b", 64)])
+@pytest.mark.parametrize("name,T", [("tiny", 16), ("7b", 64), ("7b-h10", 256)])
 def test_commit_stage_moves_rows_bit_exactly(sd, name, T):
+    """Lists of 1 to Tp rows: short ones (what a step commits), every row of the scratch (value pieces replaced
+    whole), and, with the 256-row scratch at head_dim 128, lists too long for the kernel's copy of the scratch in LDS
+    (it then gathers from global memory)."""
     shape = dataclasses.replace(wl.preset(name, 2).model, dtype="bf16")
-    B, cap, Tp = 2, 192, (T + 31) // 32 * 32
+    Tp = (T + 31) // 32 * 32
+    B, cap = (2 if Tp < 256 else 1), 160 + Tp            # (a pass takes at most 256 rows)
     weights = wl.make_weights(shape, device="cuda")
     model = sd.Model(shape, weights, B * Tp)
     kv = sd.KVCache(model, B, cap)
     rng = np.random.default_rng(12)
-    lens0 = [37, 50]
+    lens0 = [37, 50][:B]
     for b, n in enumerate(lens0):
         for layer in range(shape.n_layers):
             k = wl.synthetic_kv_rows(wl.SEEDS["kvfill"], f"k{b}.{layer}", (cap, shape.n_heads, shape.head_dim), "bf16").cuda()
@@ -65,10 +69,11 @@ def test_commit_stage_moves_rows_bit_exactly(sd, name, T):
             ref[b][c] = _rows(kv, shape, b, lens0[b], 1)
     assert any(not torch.equal(ref[0][0][0][0], ref[0][c][0][0]) for c in range(1, T))     # the rows do differ
     # lists of rows, at old lengths of every alignment (value groups of 4 rows, blocks of 32)
-    for lens in ([37, 50], [40, 63], [64, 31], [1, 127], [95, 98]):
-        W = int(rng.integers(1, min(Tp, 24) + 1))
+    for i, lens in enumerate(([37, 50], [40, 63], [64, 31], [1, 127], [95, 98], [48, 16])):
+        lens = lens[:B]
+        W = Tp if i in (1, 5) else min(Tp, 40) if i == 3 else int(rng.integers(1, min(Tp, 24) + 1))
         slots = rng.integers(T, size=(B, W)).astype(np.int32)
-        n_rows = np.array([W, int(rng.integers(0, W + 1))], np.int32)
+        n_rows = np.array([W, int(rng.integers(0, W + 1))][:B], np.int32)
         kv.set_len(lens)
         before = [_rows(kv, shape, b, max(lens[b] - 9, 0), min(9, lens[b])) for b in range(B)]
         after_keep = [_rows(kv, shape, b, lens[b] + int(n_rows[b]), 5) for b in range(B)]
@@ -92,7 +97,7 @@ def test_commit_stage_moves_rows_bit_exactly(sd, name, T):
     with pytest.raises(sd.SpecDecError) as e:
         sd.kv_commit_rows(model, kv, torch.zeros((B, Tp + 1), dtype=torch.int32, device="cuda"), one)
     assert e.value.name == "SD_ERR_SHAPE"
-    kv.set_len([cap - 3, 10])
+    kv.set_len([cap - 3, 10][:B])
     with pytest.raises(sd.SpecDecError) as e:
         sd.kv_commit_rows(model, kv, torch.zeros((B, 4), dtype=torch.int32, device="cuda"), one)
-    assert e.value.name == "SD_ERR_KV_FULL" and kv.len() == [cap - 3, 10]
+    assert e.value.name == "SD_ERR_KV_FULL" and kv.len() == [cap - 3, 10][:B]
