@@ -224,6 +224,16 @@ def test_7b_full_depth_one_step(sd):
     print(f"\n[7b L32] {rep}")
 
 
+@pytest.mark.timeout(900)
+def test_long_context_full_depth_one_step(sd):
+    """configs[2] at its full depth: all 32 layers, a 64-node tree over 16384 committed rows (eight split-KV attention
+    parts per head, the rotary stage as a launch of its own), one step on the model's own drafts."""
+    shape = dataclasses.replace(wl.preset("7b-long").model, dtype="bf16")
+    assert shape.n_layers == 32
+    rep = _run_batch_steps(sd, shape, 1, 64, [16384], 16896, n_steps=1, weights_device="cuda", plant=False)
+    print(f"\n[7b-long L32] {rep}")
+
+
 def _oracle_states(shape, lens, cap, roots, cand):
     """One oracle state per sequence over the synthetic rows of _fill_synthetic, made one at a time."""
     for b, n in enumerate(lens):
@@ -288,6 +298,16 @@ def test_13b_full_depth_one_step(sd):
     assert shape.n_layers == 40
     rep, sens = _full_depth_step_within_the_oracles_own_sensitivity(sd, shape, 128, [700], 1024)
     print(f"\n[13b L40] oracle's own sensitivity to K/V rounding {sens:.4f} {rep}")
+
+
+@pytest.mark.timeout(900)
+def test_ten_heads_256_node_tree_full_depth_one_step(sd):
+    """Ten draft heads and the largest tree (256 nodes = one 256-row pass, four query groups per head in attention,
+    eight ancestor words per row) at the 7B shape's full 32 layers."""
+    shape = dataclasses.replace(wl.preset("7b-h10").model, dtype="bf16")
+    assert shape.n_layers == 32 and shape.n_medusa == 10
+    rep, sens = _full_depth_step_within_the_oracles_own_sensitivity(sd, shape, 256, [700], 1024)
+    print(f"\n[7b-h10 L32 T=256] oracle's own sensitivity to K/V rounding {sens:.4f} {rep}")
 
 
 def test_ragged_batch_of_eight(sd):
