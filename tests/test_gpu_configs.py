@@ -158,7 +158,7 @@ def _run_batch_steps(sd, shape, B, T, lens, cap, n_steps, tree_np=None, plant=Tr
 
 
 def test_long_context_synthetic_cache(sd):
-    """configs[2] shape: 64-node tree over 16384 committed rows (split-KV attention, 52 parts)."""
+    """configs[2] shape: 64-node tree over 16384 committed rows (split-KV attention, eight parts per head)."""
     shape = _shape("7b-long")
     rep = _run_batch_steps(sd, shape, 1, 64, [16384], 16896, n_steps=2)
     print(f"\n[7b-long L2] {rep}")
