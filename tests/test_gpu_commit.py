@@ -69,9 +69,12 @@ def test_commit_stage_moves_rows_bit_exactly(sd, name, T):
             ref[b][c] = _rows(kv, shape, b, lens0[b], 1)
     assert any(not torch.equal(ref[0][0][0][0], ref[0][c][0][0]) for c in range(1, T))     # the rows do differ
     # lists of rows, at old lengths of every alignment (value groups of 4 rows, blocks of 32)
-    for i, lens in enumerate(([37, 50], [40, 63], [64, 31], [1, 127], [95, 98], [48, 16])):
+    cases = [(lens, Tp if i in (1, 5) else min(Tp, 40) if i == 3 else int(rng.integers(1, min(Tp, 24) + 1)))
+             for i, lens in enumerate(([37, 50], [40, 63], [64, 31], [1, 127], [95, 98], [48, 16]))]
+    # many more old lengths (every alignment in a 16-row half) and list lengths of 1 .. Tp rows
+    cases += [([int(x) for x in rng.integers(1, 121, size=2)], int(rng.integers(1, Tp + 1))) for _ in range(80)]
+    for lens, W in cases:
         lens = lens[:B]
-        W = Tp if i in (1, 5) else min(Tp, 40) if i == 3 else int(rng.integers(1, min(Tp, 24) + 1))
         slots = rng.integers(T, size=(B, W)).astype(np.int32)
         n_rows = np.array([W, int(rng.integers(0, W + 1))][:B], np.int32)
         kv.set_len(lens)
