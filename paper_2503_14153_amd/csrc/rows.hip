@@ -106,7 +106,12 @@ __global__ __launch_bounds__(NP_THREADS) void k_norm_pack(float* __restrict__ x,
                                                           bf16x8* __restrict__ xn, float* __restrict__ hf, int d,
                                                           int MB, const int32_t* __restrict__ gather) {
     __shared__ float red[NP_THREADS / 64];
-    const int m = blockIdx.x;
+    // Eight neighbouring rows share every 128-byte line of the packed operand (a row's 16-byte piece per lane), and
+    // workgroups go to the eight XCDs round-robin: workgroups b, b + 8, b + 16, .. take neighbouring rows, so that
+    // a line is put together in ONE L2 and leaves it whole instead of as eight masked pieces from eight L2s.
+    int m = blockIdx.x;
+    if ((gridDim.x & 63) == 0) m = (m & ~63) + (m & 7) * 8 + ((m & 63) >> 3);
+    else if ((gridDim.x & 31) == 0) m = (m & ~31) + (m & 7) * 4 + ((m & 31) >> 3);      // one row block: half lines
     norm_pack_row<false>(x, pv, gain, eps, xn, hf, d, MB, gather ? gather[m] : m, m, red);
 }
 
